@@ -1,0 +1,440 @@
+/*
+ * srm_oracle.c -- plain CPU oracle for the Structured Recurrent Mixer (SRM).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct
+ * statement of what the SRM decode path computes.  Only the tests, the smoke
+ * check and the benchmark's cpu_baseline leg may call it; the HIP library
+ * shares no code, header, table or helper with it.
+ *
+ * Compiled twice from this one source: -DREAL=double (the truth build that
+ * parity tests compare against) and -DREAL=float (the plain fp32 build that
+ * is timed as the CPU baseline).  Every arithmetic step is carried in REAL;
+ * libm calls (sqrt, erf, pow) are evaluated in double and rounded to REAL.
+ * The only parallelism is OpenMP over independent samples ("Recurrent
+ * Throughput and Concurrency": samples are independent).
+ *
+ * What follows the paper, and where:
+ *   - token mixing as Y = X M + B with a triangular, data-independent M
+ *     ("Masked Mixer Parameterization");
+ *   - row-repeat M (Eq. 1) and its recurrence (Eq. 2); column-repeat M and
+ *     its recurrence (Eq. 3); trainable decay lambda in (0.9, 1] per diagonal
+ *     ("Architecture");
+ *   - "mixed" heads: half the heads row-repeat, half column-repeat, each of
+ *     width d/h, concatenated before the out projection; per-head input
+ *     projections I_h stacked into one d x d matrix and P_out (Eq. 10);
+ *   - cache of d values per layer per sample ("SRM architecture optimization").
+ *
+ * What the paper leaves open and this oracle therefore DEFINES (each reading
+ * is listed in the design notes of this repository):
+ *   pre-LN residual blocks with affine LayerNorm (biased variance, eps given
+ *   by the caller), exact erf GELU, MLP expansion e, biased linears, untied
+ *   embedding / head with no head bias, a final LayerNorm before the head,
+ *   alpha and beta scalar per (layer, head, position), one lambda per
+ *   (layer, head), heads 0..H/2-1 row-repeat and H/2..H-1 column-repeat,
+ *   argmax ties resolved to the lowest index.  The structural part of that
+ *   reading (2 affine LNs per layer, biased linears, scalar alpha/beta,
+ *   expansion 4, untied embeddings) is pinned by the parameter counts printed
+ *   in Tables S1, S3 and S5; see orc_count_params.
+ *
+ * Pins (tests/test_oracle_pins.py): Eq. 1 worked example for n = 3; literal
+ * Eq. 2 / Eq. 3 closed forms; parallel == recurrent on brute-force inputs;
+ * cumsum / first-order IIR special cases checked against library routines;
+ * rank-1 generator; causality; constant state size; printed parameter counts.
+ * The numerical value of a whole-model logit has no printed example in the
+ * paper: for whole-model outputs "parity unpinned" beyond those structural
+ * pins and the cross-form identity.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifndef REAL
+#define REAL double
+#endif
+typedef REAL real;
+
+typedef struct {
+    real *ln1_g, *ln1_b, *w_in, *b_in, *alpha, *beta, *lam;
+    real *w_out, *b_out, *ln2_g, *ln2_b, *w_up, *b_up, *w_down, *b_down;
+} orc_layer;
+
+typedef struct {
+    int vocab, d, L, H, e, n_ctx;
+    double eps;
+    real *embed, *head, *lnf_g, *lnf_b;
+    orc_layer *layers;
+} orc_model;
+
+#define ORC_LAYER_TENSORS 15
+#define ORC_GLOBAL_TENSORS 4
+
+int orc_real_bytes(void) { return (int)sizeof(real); }
+
+static real *orc_copy(const float *src, size_t n)
+{
+    real *dst = (real *)malloc(n * sizeof(real));
+    for (size_t i = 0; i < n; ++i) dst[i] = (real)src[i];
+    return dst;
+}
+
+/*
+ * tensors: embed[V][d], head[V][d], lnf_g[d], lnf_b[d], then for each layer
+ * ln1_g[d] ln1_b[d] w_in[d][d] b_in[d] alpha[H][n_ctx] beta[H][n_ctx] lam[H]
+ * w_out[d][d] b_out[d] ln2_g[d] ln2_b[d] w_up[e*d][d] b_up[e*d]
+ * w_down[d][e*d] b_down[d].  All float32, row-major [out][in]; copied.
+ */
+orc_model *orc_create(int vocab, int d, int L, int H, int e, int n_ctx, double eps,
+                      const float *const *tensors)
+{
+    if (vocab <= 0 || d <= 0 || L <= 0 || H <= 0 || (H % 2) || (d % H) || e <= 0 || n_ctx <= 0)
+        return NULL;
+    orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
+    m->vocab = vocab; m->d = d; m->L = L; m->H = H; m->e = e; m->n_ctx = n_ctx; m->eps = eps;
+    size_t dd = (size_t)d * d, ff = (size_t)e * d;
+    m->embed = orc_copy(tensors[0], (size_t)vocab * d);
+    m->head  = orc_copy(tensors[1], (size_t)vocab * d);
+    m->lnf_g = orc_copy(tensors[2], d);
+    m->lnf_b = orc_copy(tensors[3], d);
+    m->layers = (orc_layer *)calloc(L, sizeof(orc_layer));
+    for (int l = 0; l < L; ++l) {
+        const float *const *t = tensors + ORC_GLOBAL_TENSORS + (size_t)l * ORC_LAYER_TENSORS;
+        orc_layer *y = &m->layers[l];
+        y->ln1_g = orc_copy(t[0], d);            y->ln1_b = orc_copy(t[1], d);
+        y->w_in  = orc_copy(t[2], dd);           y->b_in  = orc_copy(t[3], d);
+        y->alpha = orc_copy(t[4], (size_t)H * n_ctx);
+        y->beta  = orc_copy(t[5], (size_t)H * n_ctx);
+        y->lam   = orc_copy(t[6], H);
+        y->w_out = orc_copy(t[7], dd);           y->b_out = orc_copy(t[8], d);
+        y->ln2_g = orc_copy(t[9], d);            y->ln2_b = orc_copy(t[10], d);
+        y->w_up  = orc_copy(t[11], ff * d);      y->b_up  = orc_copy(t[12], ff);
+        y->w_down = orc_copy(t[13], (size_t)d * ff); y->b_down = orc_copy(t[14], d);
+    }
+    return m;
+}
+
+void orc_destroy(orc_model *m)
+{
+    if (!m) return;
+    for (int l = 0; l < m->L; ++l) {
+        orc_layer *y = &m->layers[l];
+        free(y->ln1_g); free(y->ln1_b); free(y->w_in); free(y->b_in); free(y->alpha);
+        free(y->beta); free(y->lam); free(y->w_out); free(y->b_out); free(y->ln2_g);
+        free(y->ln2_b); free(y->w_up); free(y->b_up); free(y->w_down); free(y->b_down);
+    }
+    free(m->layers); free(m->embed); free(m->head); free(m->lnf_g); free(m->lnf_b);
+    free(m);
+}
+
+/*
+ * Number of trainable scalars of the block structure above, obtained by adding
+ * up tensor shapes one by one (not from a closed formula).  with_projections=0
+ * drops the in/out projections (the "non-projected" variant of Table S3).
+ */
+long long orc_count_params(int vocab, int d, int L, int H, int e, int n_ctx, int with_projections)
+{
+    long long n = 0, ff = (long long)e * d;
+    n += (long long)vocab * d;           /* embedding              */
+    n += (long long)vocab * d;           /* head (untied, no bias) */
+    n += 2LL * d;                        /* final LayerNorm        */
+    for (int l = 0; l < L; ++l) {
+        n += 2LL * d;                    /* LN1 gain + bias        */
+        if (with_projections) {
+            n += (long long)d * d + d;   /* stacked I_h + bias     */
+            n += (long long)d * d + d;   /* P_out + bias           */
+        }
+        n += (long long)H * n_ctx;       /* alpha: scalar per head per position */
+        n += (long long)H * n_ctx;       /* beta                                */
+        n += H;                          /* lambda per head                     */
+        n += 2LL * d;                    /* LN2                    */
+        n += ff * d + ff;                /* MLP up                 */
+        n += (long long)d * ff + d;      /* MLP down               */
+    }
+    return n;
+}
+
+/* ---- per-token pieces ------------------------------------------------- */
+
+/* LayerNorm over d: biased variance, affine. */
+void orc_layernorm(const real *x, const real *g, const real *b, int d, double eps, real *out)
+{
+    real mean = 0;
+    for (int i = 0; i < d; ++i) mean += x[i];
+    mean /= (real)d;
+    real var = 0;
+    for (int i = 0; i < d; ++i) { real c = x[i] - mean; var += c * c; }
+    var /= (real)d;
+    real rstd = (real)(1.0 / sqrt((double)var + eps));
+    for (int i = 0; i < d; ++i) out[i] = (x[i] - mean) * rstd * g[i] + b[i];
+}
+
+/* y = W a (+ bias), W row-major [n_out][n_in]. */
+void orc_linear(const real *W, const real *bias, const real *a, int n_out, int n_in, real *y)
+{
+    for (int o = 0; o < n_out; ++o) {
+        const real *w = W + (size_t)o * n_in;
+        real acc = 0;
+        for (int k = 0; k < n_in; ++k) acc += w[k] * a[k];
+        y[o] = bias ? acc + bias[o] : acc;
+    }
+}
+
+/* exact GELU: x * Phi(x). */
+real orc_gelu(real x)
+{
+    return (real)(0.5 * (double)x * (1.0 + erf((double)x * 0.70710678118654752440)));
+}
+
+/* lowest index among maxima */
+int orc_argmax(const real *v, int n)
+{
+    int best = 0;
+    for (int i = 1; i < n; ++i) if (v[i] > v[best]) best = i;
+    return best;
+}
+
+/*
+ * One recurrent mixer update for one sample at one position (Eq. 2, Eq. 3).
+ * S[d] is the cache; it holds the running sum INCLUDING the current token:
+ *   row-repeat head:    S <- lam*S + alpha_t*u ;  m = S + beta_t
+ *   column-repeat head: S <- lam*S + u         ;  m = alpha_t*S + beta_t
+ * (the paper's cache C_n, the sum over m < n, equals lam*S_{n-1}; same size,
+ * same outputs).  alpha_t, beta_t, lam: [H] values for this position.
+ */
+void orc_mixer_step(real *S, const real *u, const real *alpha_t, const real *beta_t,
+                    const real *lam, int H, int d, real *m)
+{
+    int dh = d / H;
+    for (int h = 0; h < H; ++h) {
+        int row_repeat = h < H / 2;
+        for (int c = h * dh; c < (h + 1) * dh; ++c) {
+            if (row_repeat) {
+                S[c] = lam[h] * S[c] + alpha_t[h] * u[c];
+                m[c] = S[c] + beta_t[h];
+            } else {
+                S[c] = lam[h] * S[c] + u[c];
+                m[c] = alpha_t[h] * S[c] + beta_t[h];
+            }
+        }
+    }
+}
+
+/*
+ * Parallel mixer for one sample: the T x T matrix of each head is written out
+ * in full (Eq. 1 for row-repeat, Eq. 3 for column-repeat heads), each entry
+ * with pow(), and applied as a dense product.  Tokens are rows here
+ * (U[T][d]), i.e. the paper's Y = X M + B transposed: Y[j] = sum_i U[i] M[i][j].
+ * alpha, beta: [H][n_ctx]; pos0 is the absolute position of row 0.
+ */
+void orc_mixer_parallel(const real *U, const real *alpha, const real *beta, const real *lam,
+                        int H, int d, int T, int n_ctx, int pos0, real *Y)
+{
+    int dh = d / H;
+    real *M = (real *)malloc((size_t)T * T * sizeof(real));
+    for (int h = 0; h < H; ++h) {
+        int row_repeat = h < H / 2;
+        const real *a = alpha + (size_t)h * n_ctx + pos0;
+        const real *b = beta + (size_t)h * n_ctx + pos0;
+        for (int i = 0; i < T; ++i)
+            for (int j = 0; j < T; ++j) {
+                if (i > j) { M[(size_t)i * T + j] = 0; continue; }
+                real decay = (real)pow((double)lam[h], (double)(j - i));
+                M[(size_t)i * T + j] = decay * (row_repeat ? a[i] : a[j]);
+            }
+        for (int j = 0; j < T; ++j)
+            for (int c = h * dh; c < (h + 1) * dh; ++c) {
+                real acc = 0;
+                for (int i = 0; i < T; ++i) acc += U[(size_t)i * d + c] * M[(size_t)i * T + j];
+                Y[(size_t)j * d + c] = acc + b[j];
+            }
+    }
+    free(M);
+}
+
+/*
+ * The closed forms on the right of Eq. 2 and Eq. 3, evaluated literally for
+ * every position n (a third, independent statement used only as a pin):
+ *   row:    Y_n = alpha_n X_n + beta_n + sum_{m<n} lam^{n-m} alpha_m X_m
+ *   column: Y_n = alpha_n X_n + beta_n + alpha_n sum_{m<n} lam^{n-m} X_m
+ */
+void orc_mixer_closed_form(const real *U, const real *alpha, const real *beta, const real *lam,
+                           int H, int d, int T, int n_ctx, real *Y)
+{
+    int dh = d / H;
+    for (int h = 0; h < H; ++h) {
+        int row_repeat = h < H / 2;
+        const real *a = alpha + (size_t)h * n_ctx, *b = beta + (size_t)h * n_ctx;
+        for (int n = 0; n < T; ++n)
+            for (int c = h * dh; c < (h + 1) * dh; ++c) {
+                real sum = 0;
+                for (int m = 0; m < n; ++m) {
+                    real p = (real)pow((double)lam[h], (double)(n - m));
+                    sum += row_repeat ? p * a[m] * U[(size_t)m * d + c] : p * U[(size_t)m * d + c];
+                }
+                real y = a[n] * U[(size_t)n * d + c] + b[n];
+                Y[(size_t)n * d + c] = row_repeat ? y + sum : y + a[n] * sum;
+            }
+    }
+}
+
+/* ---- whole model, recurrent form --------------------------------------- */
+
+/*
+ * One token of one sample through the whole model in recurrent form.
+ * S: [L][d] cache, updated in place.  hidden (may be NULL): residual stream
+ * after the last block [d].  logits (may be NULL): [V].
+ */
+void orc_step(const orc_model *m, int tok, int pos, real *S, real *hidden, real *logits)
+{
+    int d = m->d, ff = m->e * m->d, H = m->H;
+    real *x = (real *)malloc(sizeof(real) * (size_t)(4 * d + 2 * ff + 3 * H));
+    real *a = x + d, *u = a + d, *mix = u + d, *g = mix + d, *t = g + ff;
+    real *al = t + ff, *be = al + H;
+    for (int i = 0; i < d; ++i) x[i] = m->embed[(size_t)tok * d + i];
+    for (int l = 0; l < m->L; ++l) {
+        const orc_layer *y = &m->layers[l];
+        orc_layernorm(x, y->ln1_g, y->ln1_b, d, m->eps, a);
+        orc_linear(y->w_in, y->b_in, a, d, d, u);
+        for (int h = 0; h < H; ++h) {
+            al[h] = y->alpha[(size_t)h * m->n_ctx + pos];
+            be[h] = y->beta[(size_t)h * m->n_ctx + pos];
+        }
+        orc_mixer_step(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
+        orc_linear(y->w_out, y->b_out, mix, d, d, t);
+        for (int i = 0; i < d; ++i) x[i] += t[i];
+        orc_layernorm(x, y->ln2_g, y->ln2_b, d, m->eps, a);
+        orc_linear(y->w_up, y->b_up, a, ff, d, g);
+        for (int i = 0; i < ff; ++i) g[i] = orc_gelu(g[i]);
+        orc_linear(y->w_down, y->b_down, g, d, ff, t);
+        for (int i = 0; i < d; ++i) x[i] += t[i];
+    }
+    if (hidden) memcpy(hidden, x, sizeof(real) * d);
+    if (logits) {
+        orc_layernorm(x, m->lnf_g, m->lnf_b, d, m->eps, a);
+        orc_linear(m->head, NULL, a, m->vocab, d, logits);
+    }
+    free(x);
+}
+
+/*
+ * Teacher-forced recurrent pass: tokens[B][T] at absolute positions
+ * pos0..pos0+T-1, starting from state[B][L][d] (updated in place; zero it for
+ * pos0 = 0).  Optional outputs: hidden[B][T][d], logits[B][T][V],
+ * greedy[B][T] (argmax of each position's logits).  Returns 0, or -1 on a
+ * bad argument.
+ */
+int orc_recurrent_forward(const orc_model *m, int B, int T, const int *tokens, int pos0,
+                          real *state, real *hidden, real *logits, int *greedy)
+{
+    if (pos0 < 0 || pos0 + T > m->n_ctx) return -1;
+    for (long long i = 0; i < (long long)B * T; ++i)
+        if (tokens[i] < 0 || tokens[i] >= m->vocab) return -1;
+    int d = m->d, V = m->vocab;
+    size_t Ld = (size_t)m->L * d;
+    int need_logits = logits || greedy;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        real *lg = need_logits && !logits ? (real *)malloc(sizeof(real) * V) : NULL;
+        for (int t = 0; t < T; ++t) {
+            size_t bt = (size_t)b * T + t;
+            real *lrow = logits ? logits + bt * V : lg;
+            orc_step(m, tokens[bt], pos0 + t, state + b * Ld,
+                     hidden ? hidden + bt * d : NULL, lrow);
+            if (greedy) greedy[bt] = orc_argmax(lrow, V);
+        }
+        free(lg);
+    }
+    return 0;
+}
+
+/*
+ * Greedy generation: consume prompts[B][P] from a zero state, then generate G
+ * tokens; out_tokens[b][0] is the argmax at the last prompt position and each
+ * generated token is fed back.  state[B][L][d] is overwritten.  Optional:
+ * logits[B][G][V] (the logits each generated token was chosen from) and
+ * margin[B][G] (top-1 minus top-2 of those logits).
+ */
+int orc_greedy(const orc_model *m, int B, int P, int G, const int *prompts, real *state,
+               int *out_tokens, real *logits, real *margin)
+{
+    if (P < 1 || G < 1 || P + G - 1 > m->n_ctx) return -1;
+    for (long long i = 0; i < (long long)B * P; ++i)
+        if (prompts[i] < 0 || prompts[i] >= m->vocab) return -1;
+    int d = m->d, V = m->vocab;
+    size_t Ld = (size_t)m->L * d;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        real *S = state + b * Ld;
+        real *lg = (real *)malloc(sizeof(real) * V);
+        for (size_t i = 0; i < Ld; ++i) S[i] = 0;
+        int tok = 0;
+        for (int t = 0; t < P + G - 1; ++t) {
+            int in = t < P ? prompts[(size_t)b * P + t] : tok;
+            int want = t >= P - 1;
+            orc_step(m, in, t, S, NULL, want ? lg : NULL);
+            if (!want) continue;
+            int g = t - (P - 1);
+            tok = orc_argmax(lg, V);
+            out_tokens[(size_t)b * G + g] = tok;
+            if (logits) memcpy(logits + ((size_t)b * G + g) * V, lg, sizeof(real) * V);
+            if (margin) {
+                real second = -INFINITY;
+                for (int v = 0; v < V; ++v) if (v != tok && lg[v] > second) second = lg[v];
+                margin[(size_t)b * G + g] = lg[tok] - second;
+            }
+        }
+        free(lg);
+    }
+    return 0;
+}
+
+/* ---- whole model, parallel (sequence) form ------------------------------ */
+
+/*
+ * The same model applied to whole sequences tokens[B][T] (positions 0..T-1),
+ * layer by layer, with the token mixer as the explicit structured triangular
+ * product (orc_mixer_parallel).  Outputs hidden[B][T][d] and, if not NULL,
+ * logits[B][T][V].  No cache is read or written.
+ */
+int orc_parallel_forward(const orc_model *m, int B, int T, const int *tokens,
+                         real *hidden, real *logits)
+{
+    if (T < 1 || T > m->n_ctx) return -1;
+    for (long long i = 0; i < (long long)B * T; ++i)
+        if (tokens[i] < 0 || tokens[i] >= m->vocab) return -1;
+    int d = m->d, ff = m->e * m->d, V = m->vocab;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        size_t Td = (size_t)T * d;
+        real *X = hidden + (size_t)b * Td;
+        real *A = (real *)malloc(sizeof(real) * (3 * Td + (size_t)ff + d));
+        real *U = A + Td, *Y = U + Td, *g = Y + Td, *tmp = g + ff;   /* g[ff], tmp[d] */
+        for (int s = 0; s < T; ++s)
+            for (int i = 0; i < d; ++i)
+                X[(size_t)s * d + i] = m->embed[(size_t)tokens[(size_t)b * T + s] * d + i];
+        for (int l = 0; l < m->L; ++l) {
+            const orc_layer *y = &m->layers[l];
+            for (int s = 0; s < T; ++s) {
+                orc_layernorm(X + (size_t)s * d, y->ln1_g, y->ln1_b, d, m->eps, A + (size_t)s * d);
+                orc_linear(y->w_in, y->b_in, A + (size_t)s * d, d, d, U + (size_t)s * d);
+            }
+            orc_mixer_parallel(U, y->alpha, y->beta, y->lam, m->H, d, T, m->n_ctx, 0, Y);
+            for (int s = 0; s < T; ++s) {
+                real *x = X + (size_t)s * d;
+                orc_linear(y->w_out, y->b_out, Y + (size_t)s * d, d, d, tmp);
+                for (int i = 0; i < d; ++i) x[i] += tmp[i];
+                orc_layernorm(x, y->ln2_g, y->ln2_b, d, m->eps, A + (size_t)s * d);
+                orc_linear(y->w_up, y->b_up, A + (size_t)s * d, ff, d, g);
+                for (int i = 0; i < ff; ++i) g[i] = orc_gelu(g[i]);
+                orc_linear(y->w_down, y->b_down, g, d, ff, tmp);
+                for (int i = 0; i < d; ++i) x[i] += tmp[i];
+            }
+        }
+        if (logits)
+            for (int s = 0; s < T; ++s) {
+                orc_layernorm(X + (size_t)s * d, m->lnf_g, m->lnf_b, d, m->eps, A);
+                orc_linear(m->head, NULL, A, V, d, logits + ((size_t)b * T + s) * V);
+            }
+        free(A);
+    }
+    return 0;
+}
