@@ -1,0 +1,190 @@
+/*
+ * srm.h -- C ABI of libsrm: batched autoregressive generation with the
+ * Structured Recurrent Mixer (SRM) in its recurrent form, plus the parallel
+ * (sequence) form of the same model, on one AMD MI355X (gfx950).
+ *
+ * Model (paper section "Method"): token embedding, then n_layers blocks of
+ *   [ LayerNorm -> per-head input projections I_h (stacked, d x d) ->
+ *     structured token mixer -> output projection P_out -> residual ]      (Eq. 10)
+ *   [ LayerNorm -> channel-mixing MLP (expansion e, exact GELU) -> residual ]
+ * then a final LayerNorm and an untied LM head; greedy next token = argmax,
+ * lowest index on ties.  The token mixer is the paper's causal mixing matrix
+ * restricted to row-repeat (Eq. 1) or column-repeat (Eq. 3) form with one
+ * decay factor lambda per diagonal; heads 0..H/2-1 are row-repeat, heads
+ * H/2..H-1 column-repeat ("mixed" heads).  Its recurrent form (Eq. 2, Eq. 3)
+ * keeps one fp32 value per channel per layer per sample (the cache):
+ *   row head:    S <- lambda_h S + alpha_{h,t} u ;  m = S + beta_{h,t}
+ *   column head: S <- lambda_h S + u             ;  m = alpha_{h,t} S + beta_{h,t}
+ * with u the projected input at absolute position t.  alpha and beta are
+ * scalars per (layer, head, position); positions are bounded by n_ctx.
+ *
+ * Conventions
+ *   - "d_" arguments are DEVICE pointers on the model's GPU; all other pointers
+ *     are HOST pointers.  The library owns only srm_model (device copies of the
+ *     weights).  State, workspace, token and output buffers belong to the caller.
+ *   - Matrices are row-major [out][in].  Tokens are int32.  The state is fp32,
+ *     laid out [n_layers][batch][d_model]; the caller zeroes it before position 0.
+ *   - Compute calls are asynchronous on the given hipStream_t (passed as void*,
+ *     NULL = the default stream); they never synchronise and never copy to host.
+ *   - Every call returns SRM_OK (0) or a negative srm_status; after a failure
+ *     srm_last_error() returns a message for the calling thread.  Arguments are
+ *     validated on the host before any kernel is launched.  Token ids outside
+ *     [0, vocab) are not checked on the device: the caller must not pass them.
+ *   - weight_dtype SRM_BF16: matrices (embed, head, w_in, w_out, w_up, w_down)
+ *     are stored in bf16 (host values are rounded to nearest-even), activations
+ *     entering a GEMM are bf16, accumulation, residual stream, LayerNorm,
+ *     mixer state and logits are fp32.  Requires d_model % 64 == 0.
+ *     weight_dtype SRM_FP32: everything fp32.  Both need d_model % (4*n_heads) == 0
+ *     and d_model <= 4096.
+ */
+#ifndef SRM_H
+#define SRM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct srm_model srm_model;
+
+typedef enum {
+    SRM_OK = 0,
+    SRM_EINVAL = -1,   /* bad argument (message says which)            */
+    SRM_ENOMEM = -2,   /* device or host allocation failed, or the workspace is too small */
+    SRM_EHIP = -3      /* a HIP runtime call failed (message has the HIP error) */
+} srm_status;
+
+enum { SRM_FP32 = 0, SRM_BF16 = 1 };
+
+typedef struct {
+    int32_t vocab;
+    int32_t d_model;
+    int32_t n_layers;
+    int32_t n_heads;        /* even; first half row-repeat, second half column-repeat */
+    int32_t mlp_expansion;
+    int32_t n_ctx;          /* number of positions alpha/beta are defined for */
+    int32_t weight_dtype;   /* SRM_FP32 | SRM_BF16 */
+    float ln_eps;
+} srm_config;
+
+/* HOST pointers, fp32, caller-owned, not retained after srm_init_weights. */
+typedef struct {
+    const float *ln1_g, *ln1_b;        /* [d], [d]                                  */
+    const float *w_in, *b_in;          /* [d][d] (rows h*d_h.. are I_h), [d]         */
+    const float *alpha, *beta;         /* [H][n_ctx], [H][n_ctx]                     */
+    const float *lambda;               /* [H], each in (0.9, 1]                      */
+    const float *w_out, *b_out;        /* [d][d] (P_out), [d]                        */
+    const float *ln2_g, *ln2_b;        /* [d], [d]                                   */
+    const float *w_up, *b_up;          /* [e*d][d], [e*d]                            */
+    const float *w_down, *b_down;      /* [d][e*d], [d]                              */
+} srm_host_layer;
+
+typedef struct {
+    const float *embed;                /* [vocab][d]                                 */
+    const float *head;                 /* [vocab][d], no bias                        */
+    const float *lnf_g, *lnf_b;        /* [d], [d]                                   */
+    const srm_host_layer *layers;      /* [n_layers]                                 */
+} srm_host_weights;
+
+/*
+ * Copy the weights to the current HIP device (casting matrices to bf16 when
+ * configured) and return an opaque model.  ("Method": one parameter set serves
+ * both the recurrent and the parallel form.)
+ * Errors: SRM_EINVAL for a null pointer, non-positive size, odd n_heads,
+ * d_model not divisible by 4*n_heads, d_model > 4096, bf16 with d_model % 64,
+ * or a lambda outside (0, 1]; SRM_ENOMEM; SRM_EHIP.
+ */
+int srm_init_weights(const srm_config *cfg, const srm_host_weights *w, srm_model **out);
+void srm_free(srm_model *m);
+
+/*
+ * Bytes of recurrent state for `batch` samples: n_layers * batch * d_model * 4,
+ * whatever the position ("Computational Complexity": O(d) space per sample).
+ * Returns 0 for a null model or batch <= 0.
+ */
+size_t srm_state_bytes(const srm_model *m, int64_t batch);
+
+/*
+ * Bytes of scratch a call needs for `rows` token rows processed at once
+ * (srm_decode_step: rows = B; srm_prefill / srm_parallel_forward: any multiple
+ * of the sequence length, at least one sequence; more rows = fewer passes).
+ */
+size_t srm_workspace_bytes(const srm_model *m, int64_t rows);
+
+/*
+ * One decode step for B samples that all sit at absolute position `pos`
+ * ("Recurrent Throughput and Concurrency": one token per sample per step,
+ * parallel over the batch).  Reads d_tok_in[B], updates d_state[L][B][d] in
+ * place (Eq. 2 / Eq. 3), writes the greedy next token d_tok_out[B].
+ * Optional outputs (NULL to skip): d_logits[B][vocab] fp32, d_hidden[B][d]
+ * fp32 (residual stream after the last block, before the final LayerNorm).
+ * d_tok_out may alias d_tok_in.  Errors: SRM_EINVAL (null pointer, B <= 0,
+ * pos outside [0, n_ctx)), SRM_ENOMEM (workspace_bytes < srm_workspace_bytes(m, B)).
+ */
+int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in,
+                    float *d_state, int32_t *d_tok_out, float *d_logits, float *d_hidden,
+                    void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Consume N prompts of P tokens (positions 0..P-1) from a zero state, layer by
+ * layer over all positions, with the mixer evaluated as the sequential
+ * recurrence (the result equals P decode steps), then replicate each prompt's
+ * state and first generated token to fanout_k consecutive samples:
+ * sample n*fanout_k + r takes prompt n.  Writes d_state[L][N*k][d] (every
+ * element), d_next_tok[N*k], and, if not NULL, d_logits[N][vocab] (last
+ * position).  Processes as many whole prompts per pass as the workspace holds.
+ * Errors: SRM_EINVAL (null pointer, N, P or fanout_k <= 0, P > n_ctx),
+ * SRM_ENOMEM (workspace smaller than srm_workspace_bytes(m, P)).
+ */
+int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, int32_t P, int32_t fanout_k,
+                float *d_state, int32_t *d_next_tok, float *d_logits,
+                void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Parallel (sequence) form over d_tok[B][T], positions 0..T-1: identical model,
+ * but the mixer is the explicit structured triangular product Y = U M + beta
+ * with M built from alpha and lambda as in Eq. 1 (row-repeat heads) and Eq. 3
+ * (column-repeat heads).  Reads and writes no state.  Writes d_hidden[B][T][d]
+ * fp32 and, if not NULL, d_logits[B][T][vocab] fp32.
+ * Errors: SRM_EINVAL (null pointer, B or T <= 0, T > n_ctx), SRM_ENOMEM
+ * (workspace smaller than srm_workspace_bytes(m, T)).
+ */
+int srm_parallel_forward(srm_model *m, const int32_t *d_tok, int32_t B, int32_t T,
+                         float *d_hidden, float *d_logits,
+                         void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Kernel-level entry points (the pieces of srm_decode_step, callable alone so
+ * each can be checked and timed by itself).
+ *
+ * srm_mixer_update: the recurrent state update of one layer (Eq. 2 / Eq. 3)
+ * for B samples at position pos.  d_u and d_m are [B][d] in the model's
+ * activation type (bf16 for SRM_BF16 models, fp32 otherwise); d_state_layer is
+ * that layer's [B][d] fp32 slab, updated in place.  d_m may alias d_u.
+ */
+int srm_mixer_update(srm_model *m, int32_t layer, int32_t pos, int64_t B, const void *d_u,
+                     float *d_state_layer, void *d_m, void *hip_stream);
+
+/*
+ * srm_linear: out = epilogue(A W^T + bias) with A [M][K] and W [N][K] device
+ * arrays of type `dtype` (SRM_BF16: bf16 operands on the matrix cores with fp32
+ * accumulation, K % 64 == 0; SRM_FP32: fp32).  d_bias [N] fp32 or NULL.
+ * epilogue: 0 = store (type `dtype`), 1 = exact GELU then store (type `dtype`),
+ * 2 = add into fp32 d_out (residual), 3 = store fp32 and also write the
+ * row-wise argmax (lowest index on ties) to d_argmax[M] (needs d_scratch of
+ * srm_linear_scratch_bytes(M, N) bytes); d_out may be NULL for epilogue 3.
+ */
+int srm_linear(int32_t dtype, int32_t epilogue, const void *d_A, const void *d_W,
+               const float *d_bias, int64_t M, int32_t N, int32_t K, void *d_out,
+               int32_t *d_argmax, void *d_scratch, void *hip_stream);
+size_t srm_linear_scratch_bytes(int64_t M, int32_t N);
+
+/* Message for the last failure on the calling thread ("" if none). */
+const char *srm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SRM_H */

@@ -1,0 +1,247 @@
+"""ctypes binding of libsrm.so: same names and argument order as include/srm.h.
+
+Argument marshalling only.  Device buffers are torch CUDA tensors; their
+dtype, contiguity and size are checked here, on the host, before a pointer is
+handed to the library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+SRM_FP32, SRM_BF16 = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsrm.so")
+_lib = None
+
+_LAYER_FIELDS = ("ln1_g", "ln1_b", "w_in", "b_in", "alpha", "beta", "lambda", "w_out", "b_out",
+                 "ln2_g", "ln2_b", "w_up", "b_up", "w_down", "b_down")
+_FP = C.POINTER(C.c_float)
+
+
+class SrmError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libsrm error {code}: {msg}")
+        self.code = code
+
+
+class srm_config(C.Structure):
+    _fields_ = [("vocab", C.c_int32), ("d_model", C.c_int32), ("n_layers", C.c_int32),
+                ("n_heads", C.c_int32), ("mlp_expansion", C.c_int32), ("n_ctx", C.c_int32),
+                ("weight_dtype", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class srm_host_layer(C.Structure):
+    _fields_ = [(n, _FP) for n in _LAYER_FIELDS]
+
+
+class srm_host_weights(C.Structure):
+    _fields_ = [("embed", _FP), ("head", _FP), ("lnf_g", _FP), ("lnf_b", _FP),
+                ("layers", C.POINTER(srm_host_layer))]
+
+
+def lib():
+    """Load libsrm.so; fails loudly if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`"
+                              " (there is no fallback path)")
+        L = C.CDLL(_LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        L.srm_init_weights.restype = C.c_int
+        L.srm_init_weights.argtypes = [C.POINTER(srm_config), C.POINTER(srm_host_weights), C.POINTER(vp)]
+        L.srm_free.restype = None
+        L.srm_free.argtypes = [vp]
+        L.srm_state_bytes.restype = sz
+        L.srm_state_bytes.argtypes = [vp, i64]
+        L.srm_workspace_bytes.restype = sz
+        L.srm_workspace_bytes.argtypes = [vp, i64]
+        L.srm_decode_step.restype = C.c_int
+        L.srm_decode_step.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.srm_prefill.restype = C.c_int
+        L.srm_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.srm_parallel_forward.restype = C.c_int
+        L.srm_parallel_forward.argtypes = [vp, vp, i32, i32, vp, vp, vp, sz, vp]
+        L.srm_mixer_update.restype = C.c_int
+        L.srm_mixer_update.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp]
+        L.srm_linear.restype = C.c_int
+        L.srm_linear.argtypes = [i32, i32, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp]
+        L.srm_linear_scratch_bytes.restype = sz
+        L.srm_linear_scratch_bytes.argtypes = [i64, i32]
+        L.srm_last_error.restype = C.c_char_p
+        L.srm_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SrmError(rc, lib().srm_last_error().decode())
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dev(t, dtype, numel: int, name: str) -> int:
+    """Device pointer of a tensor after host-side checks."""
+    if not t.is_cuda:
+        raise ValueError(f"{name}: must be a CUDA tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    if t.numel() < numel:
+        raise ValueError(f"{name}: {t.numel()} elements, need {numel}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+class Model:
+    """Owns one srm_model.  cfg needs vocab, d_model, n_layers, n_heads,
+    mlp_expansion, n_ctx, weight_dtype ("fp32"|"bf16") and ln_eps; weights is
+    {"embed","head","lnf_g","lnf_b": float32 ndarray, "layers": [{...}]} with
+    the layer tensor names of include/srm.h ("lam" for lambda)."""
+
+    def __init__(self, cfg, weights: dict):
+        L = lib()
+        self.vocab, self.d, self.L, self.H = cfg.vocab, cfg.d_model, cfg.n_layers, cfg.n_heads
+        self.ff = cfg.d_model * cfg.mlp_expansion
+        self.n_ctx = cfg.n_ctx
+        self.dtype = SRM_BF16 if cfg.weight_dtype == "bf16" else SRM_FP32
+        c = srm_config(cfg.vocab, cfg.d_model, cfg.n_layers, cfg.n_heads, cfg.mlp_expansion,
+                       cfg.n_ctx, self.dtype, cfg.ln_eps)
+        keep = []
+
+        def fp(a, shape):
+            a = np.ascontiguousarray(a, dtype=np.float32)
+            if a.shape != tuple(shape):
+                raise ValueError(f"weight shape {a.shape}, expected {tuple(shape)}")
+            keep.append(a)
+            return a.ctypes.data_as(_FP)
+
+        d, ff, H, n, V = self.d, self.ff, self.H, self.n_ctx, self.vocab
+        shapes = {"ln1_g": (d,), "ln1_b": (d,), "w_in": (d, d), "b_in": (d,), "alpha": (H, n),
+                  "beta": (H, n), "lambda": (H,), "w_out": (d, d), "b_out": (d,), "ln2_g": (d,),
+                  "ln2_b": (d,), "w_up": (ff, d), "b_up": (ff,), "w_down": (d, ff), "b_down": (d,)}
+        if len(weights["layers"]) != self.L:
+            raise ValueError("wrong number of layers")
+        layers = (srm_host_layer * self.L)()
+        for l, lw in enumerate(weights["layers"]):
+            for name in _LAYER_FIELDS:
+                src = lw["lam"] if name == "lambda" and "lam" in lw else lw[name]
+                setattr(layers[l], name, fp(src, shapes[name]))
+        hw = srm_host_weights(fp(weights["embed"], (V, d)), fp(weights["head"], (V, d)),
+                              fp(weights["lnf_g"], (d,)), fp(weights["lnf_b"], (d,)), layers)
+        h = C.c_void_p()
+        _check(L.srm_init_weights(C.byref(c), C.byref(hw), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().srm_free(self._h)
+            self._h = None
+
+    __del__ = close
+
+    @property
+    def act_dtype(self):
+        torch = _torch()
+        return torch.bfloat16 if self.dtype == SRM_BF16 else torch.float32
+
+    def state_bytes(self, batch: int) -> int:
+        return lib().srm_state_bytes(self._h, batch)
+
+    def workspace_bytes(self, rows: int) -> int:
+        return lib().srm_workspace_bytes(self._h, rows)
+
+    def new_state(self, batch: int):
+        torch = _torch()
+        return torch.zeros((self.L, batch, self.d), dtype=torch.float32, device="cuda")
+
+    def new_workspace(self, rows: int):
+        torch = _torch()
+        return torch.empty(self.workspace_bytes(rows), dtype=torch.uint8, device="cuda")
+
+    def decode_step(self, B, pos, tok_in, state, tok_out, logits=None, hidden=None, workspace=None,
+                    stream=None):
+        torch = _torch()
+        p_in = _dev(tok_in, torch.int32, B, "tok_in")
+        p_st = _dev(state, torch.float32, self.L * B * self.d, "state")
+        if state.numel() != self.L * B * self.d:
+            raise ValueError("state: must be exactly [L][B][d]")
+        p_out = _dev(tok_out, torch.int32, B, "tok_out")
+        p_lg = None if logits is None else _dev(logits, torch.float32, B * self.vocab, "logits")
+        p_hd = None if hidden is None else _dev(hidden, torch.float32, B * self.d, "hidden")
+        p_ws = _dev(workspace, torch.uint8, 1, "workspace")
+        _check(lib().srm_decode_step(self._h, B, pos, p_in, p_st, p_out, p_lg, p_hd, p_ws,
+                                     workspace.numel(), _stream(stream)))
+
+    def prefill(self, prompts, fanout_k, state, next_tok, logits=None, workspace=None, stream=None):
+        torch = _torch()
+        N, P = prompts.shape
+        Bt = N * fanout_k
+        p_pr = _dev(prompts, torch.int32, N * P, "prompts")
+        p_st = _dev(state, torch.float32, self.L * Bt * self.d, "state")
+        if state.numel() != self.L * Bt * self.d:
+            raise ValueError("state: must be exactly [L][N*k][d]")
+        p_nt = _dev(next_tok, torch.int32, Bt, "next_tok")
+        p_lg = None if logits is None else _dev(logits, torch.float32, N * self.vocab, "logits")
+        p_ws = _dev(workspace, torch.uint8, 1, "workspace")
+        _check(lib().srm_prefill(self._h, p_pr, N, P, fanout_k, p_st, p_nt, p_lg, p_ws,
+                                 workspace.numel(), _stream(stream)))
+
+    def parallel_forward(self, tok, hidden, logits=None, workspace=None, stream=None):
+        torch = _torch()
+        B, T = tok.shape
+        p_tk = _dev(tok, torch.int32, B * T, "tok")
+        p_hd = _dev(hidden, torch.float32, B * T * self.d, "hidden")
+        p_lg = None if logits is None else _dev(logits, torch.float32, B * T * self.vocab, "logits")
+        p_ws = _dev(workspace, torch.uint8, 1, "workspace")
+        _check(lib().srm_parallel_forward(self._h, p_tk, B, T, p_hd, p_lg, p_ws, workspace.numel(),
+                                          _stream(stream)))
+
+    def mixer_update(self, layer, pos, B, u, state_layer, m, stream=None):
+        torch = _torch()
+        n = B * self.d
+        p_u = _dev(u, self.act_dtype, n, "u")
+        p_s = _dev(state_layer, torch.float32, n, "state_layer")
+        p_m = _dev(m, self.act_dtype, n, "m")
+        _check(lib().srm_mixer_update(self._h, layer, pos, B, p_u, p_s, p_m, _stream(stream)))
+
+
+def linear_scratch_bytes(M: int, N: int) -> int:
+    return lib().srm_linear_scratch_bytes(M, N)
+
+
+def linear(dtype, epilogue, A, W, bias, out=None, argmax=None, scratch=None, stream=None, tile=None):
+    """srm_linear on torch tensors A [M][K], W [N][K].  tile (0|1|2) pins the
+    bf16 tile shape for sweeps."""
+    torch = _torch()
+    M, K = A.shape
+    N, K2 = W.shape
+    if K != K2:
+        raise ValueError("A and W disagree on K")
+    t = torch.bfloat16 if dtype == SRM_BF16 else torch.float32
+    p_a = _dev(A, t, M * K, "A")
+    p_w = _dev(W, t, N * K, "W")
+    p_b = None if bias is None else _dev(bias, torch.float32, N, "bias")
+    epi = epilogue % 100
+    out_t = torch.float32 if epi in (2, 3, 4) else t
+    p_o = None if out is None else _dev(out, out_t, M * N, "out")
+    p_am = None if argmax is None else _dev(argmax, torch.int32, M, "argmax")
+    p_sc = None
+    if epi == 3:
+        p_sc = _dev(scratch, torch.uint8, linear_scratch_bytes(M, N), "scratch")
+    code = epilogue if tile is None else (tile + 1) * 100 + epi
+    _check(lib().srm_linear(dtype, code, p_a, p_w, p_b, M, N, K, p_o, p_am, p_sc, _stream(stream)))

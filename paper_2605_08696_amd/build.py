@@ -1,0 +1,38 @@
+"""Build libsrm.so (the HIP library behind include/srm.h) for gfx950 with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+LIB = os.path.join(HERE, "libsrm.so")
+SOURCES = [os.path.join(HERE, "csrc", "srm.hip")]
+HEADERS = [os.path.join(HERE, "csrc", n) for n in ("common.hpp", "gemm.hpp", "mixer.hpp", "norm.hpp")]
+HEADERS.append(os.path.join(ROOT, "include", "srm.h"))
+
+
+def build_lib(verbose: bool = False) -> str:
+    """Compile unconditionally; returns the path of the shared library."""
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-I" + os.path.join(ROOT, "include"),
+           # packed-fp32 VALU forms are kept off for every kernel of this library
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           *SOURCES, "-o", LIB]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode:
+        print(res.stdout, res.stderr)
+    if res.returncode:
+        raise RuntimeError("hipcc failed:\n" + res.stderr)
+    return LIB
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
+
+
+if __name__ == "__main__":
+    print(build_lib(verbose=True))

@@ -1,0 +1,189 @@
+// The structured token mixer in its three evaluation orders.
+//
+//   state_update_kernel   one position for every sample (decode): Eq. 2 / Eq. 3
+//   mixer_scan_kernel     all prompt positions in sequence (prefill), state kept
+//                         in registers, same arithmetic as state_update_kernel
+//   mixer_parallel_kernel the explicit triangular product Y = U M + beta with M
+//                         built on the fly from alpha and lambda (Eq. 1, Eq. 3)
+//
+// Both head types share one update, S' = lam*S + p*u ; m = q*S' + beta, with
+// (p, q) = (alpha, 1) for row-repeat heads and (1, alpha) for column-repeat
+// heads; multiplying by the constant 1 is exact, so this is Eq. 2 / Eq. 3 as
+// written.  alpha, beta: [H][n_ctx] of this layer; lam: [H].
+#pragma once
+#include "common.hpp"
+
+constexpr int kMaxHeads = 64;
+
+// Streams u [B][d] (TAct), S [B][d] (fp32, in place) and m [B][d] (TAct), four
+// channels per thread.  The launch makes gridDim.x * 256 a multiple of d/4, so a
+// thread keeps one channel group, hence one head, for its whole loop; the per
+// head coefficients of this position are staged in LDS once per block.
+template <typename TAct, int UNROLL>
+__global__ void __launch_bounds__(256)
+state_update_kernel(const TAct *__restrict__ u, float *__restrict__ S, TAct *__restrict__ m,
+                    const float *__restrict__ alpha, const float *__restrict__ beta,
+                    const float *__restrict__ lam, int pos, int n_ctx, int H, int d, int64_t nvec)
+{
+    __shared__ float4 coef[kMaxHeads];      // (lam, p, q, beta) per head
+    if (threadIdx.x < H) {
+        const int h = threadIdx.x;
+        const float a = alpha[(size_t)h * n_ctx + pos];
+        const bool row_repeat = h < H / 2;
+        coef[h] = make_float4(lam[h], row_repeat ? a : 1.0f, row_repeat ? 1.0f : a,
+                              beta[(size_t)h * n_ctx + pos]);
+    }
+    __syncthreads();
+    const int dv = d >> 2, dhv = (d / H) >> 2;
+    const int64_t nthreads = (int64_t)gridDim.x * 256;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const float4 cf = coef[(int)(gid % dv) / dhv];
+    const float l = cf.x, p = cf.y, q = cf.z, be = cf.w;
+
+    for (int64_t i = gid; i < nvec; i += nthreads * UNROLL) {
+        float4 s[UNROLL], x[UNROLL];
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const int64_t j = i + k * nthreads;
+            if (j < nvec) {
+                const f32x4_t sv = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(S) + j);
+                s[k] = make_float4(sv[0], sv[1], sv[2], sv[3]);
+                x[k] = load4(u + j * 4);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const int64_t j = i + k * nthreads;
+            if (j < nvec) {
+                float4 n, o;
+                n.x = fmaf(l, s[k].x, p * x[k].x); o.x = fmaf(q, n.x, be);
+                n.y = fmaf(l, s[k].y, p * x[k].y); o.y = fmaf(q, n.y, be);
+                n.z = fmaf(l, s[k].z, p * x[k].z); o.z = fmaf(q, n.z, be);
+                n.w = fmaf(l, s[k].w, p * x[k].w); o.w = fmaf(q, n.w, be);
+                f32x4_t nv;
+                nv[0] = n.x; nv[1] = n.y; nv[2] = n.z; nv[3] = n.w;
+                __builtin_nontemporal_store(nv, reinterpret_cast<f32x4_t *>(S) + j);
+                store4(m + j * 4, o);
+            }
+        }
+    }
+}
+
+// Prefill: u, m are [nseq][P][d]; thread = (sequence, 4 channels), sequential in
+// t from a zero state (positions 0..P-1).  The final state is written to `rep`
+// consecutive samples: S[((seq0 + seq) * rep + r)][d] of this layer's slab.
+// Dynamic LDS: 2 * H * P floats (alpha then beta of the P positions).
+template <typename TAct>
+__global__ void __launch_bounds__(256)
+mixer_scan_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__restrict__ S,
+                  const float *__restrict__ alpha, const float *__restrict__ beta,
+                  const float *__restrict__ lam, int n_ctx, int H, int d, int nseq, int P,
+                  int64_t seq0, int rep)
+{
+    extern __shared__ float sc[];
+    float *sa = sc, *sb = sc + H * P;
+    for (int i = threadIdx.x; i < H * P; i += 256) {
+        const int h = i / P, t = i - h * P;
+        sa[i] = alpha[(size_t)h * n_ctx + t];
+        sb[i] = beta[(size_t)h * n_ctx + t];
+    }
+    __syncthreads();
+    const int dv = d >> 2, dhv = (d / H) >> 2;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t seq = gid / dv;
+    if (seq >= nseq) return;
+    const int cv = (int)(gid - seq * dv);
+    const int h = cv / dhv;
+    const bool row_repeat = h < H / 2;
+    const float l = lam[h];
+    const TAct *up = u + (seq * P) * (int64_t)d + cv * 4;
+    TAct *mp = m + (seq * P) * (int64_t)d + cv * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int t = 0; t < P; ++t) {
+        const float4 x = load4(up + (int64_t)t * d);
+        const float a = sa[h * P + t], be = sb[h * P + t];
+        const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
+        float4 o;
+        s.x = fmaf(l, s.x, p * x.x); o.x = fmaf(q, s.x, be);
+        s.y = fmaf(l, s.y, p * x.y); o.y = fmaf(q, s.y, be);
+        s.z = fmaf(l, s.z, p * x.z); o.z = fmaf(q, s.z, be);
+        s.w = fmaf(l, s.w, p * x.w); o.w = fmaf(q, s.w, be);
+        store4(mp + (int64_t)t * d, o);
+    }
+    float *dst = S + ((seq0 + seq) * rep) * (int64_t)d + cv * 4;
+    for (int r = 0; r < rep; ++r) store4(dst + (int64_t)r * d, s);
+}
+
+// Parallel form.  U, Y: [B][T][d].  grid = (ceil(T/64), H * ceil(d_h/64), B);
+// a block owns 64 output positions j x up to 64 channels c of one head and sums
+// over source positions i <= j in tiles of 64:
+//   Y[j][c] = sum_i U[i][c] * M[i][j] + beta_j,
+//   M[i][j] = lam^(j-i) * alpha_i (row-repeat) | lam^(j-i) * alpha_j (column-repeat), 0 for i > j.
+// lam^k comes from a per-block table computed with pow() in double, not from
+// running products, so this path shares no rounding with the recurrence.
+// Dynamic LDS: T floats (the power table).
+template <typename TAct>
+__global__ void __launch_bounds__(256)
+mixer_parallel_kernel(const TAct *__restrict__ U, TAct *__restrict__ Y,
+                      const float *__restrict__ alpha, const float *__restrict__ beta,
+                      const float *__restrict__ lam, int n_ctx, int H, int d, int T)
+{
+    extern __shared__ float pw[];            // [T]
+    __shared__ float Ms[64][64 + 4];         // [i][j]
+    __shared__ float Us[64][64 + 4];         // [i][c]
+    const int dh = d / H;
+    const int ctiles = (dh + 63) / 64;
+    const int h = blockIdx.y / ctiles, ct = blockIdx.y % ctiles;
+    const int jt = blockIdx.x, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const bool row_repeat = h < H / 2;
+    const float *al = alpha + (size_t)h * n_ctx;
+    const double lh = (double)lam[h];
+    for (int k = tid; k < T; k += 256) pw[k] = (float)pow(lh, (double)k);
+
+    const int j0 = jt * 64, c0 = h * dh + ct * 64, cw = min(64, dh - ct * 64);
+    const int tj = tid >> 4, tc = tid & 15;
+    const TAct *Ub = U + (size_t)b * T * d;
+    float acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[a][c] = 0.0f;
+
+    for (int it = 0; it <= jt; ++it) {
+        const int i0 = it * 64;
+        __syncthreads();                     // previous tile consumed; pw ready on the first pass
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const int e = tid + s * 256, ii = e >> 6, x = e & 63;
+            const int i = i0 + ii, j = j0 + x;
+            Ms[ii][x] = (i <= j && j < T) ? pw[j - i] * (row_repeat ? al[i] : al[j]) : 0.0f;
+            Us[ii][x] = (i < T && x < cw) ? (float)Ub[(size_t)i * d + c0 + x] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int ii = 0; ii < 64; ++ii) {
+            float mj[4], uc[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) mj[a] = Ms[ii][tj * 4 + a];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) uc[c] = Us[ii][tc * 4 + c];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[a][c] = fmaf(uc[c], mj[a], acc[a][c]);
+        }
+    }
+    TAct *Yb = Y + (size_t)b * T * d;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int j = j0 + tj * 4 + a;
+        if (j >= T) continue;
+        const float be = beta[(size_t)h * n_ctx + j];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int x = tc * 4 + c;
+            if (x < cw) store1(Yb + (size_t)j * d + c0 + x, acc[a][c] + be);
+        }
+    }
+}

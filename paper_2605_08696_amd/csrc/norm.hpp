@@ -1,0 +1,72 @@
+// Embedding gather and LayerNorm (one wavefront per token row).
+//
+// The residual stream is fp32; the normalised row is written in the type the
+// next GEMM consumes (bf16 or fp32).  Statistics are two-pass (mean, then the
+// biased variance of the centred values) over values held in registers, summed
+// with wavefront shuffles.
+#pragma once
+#include "common.hpp"
+
+// VPL = float4 vectors per lane: covers d <= 256 * VPL.
+//   GATHER: x = embed[tok[row]] is fetched, stored to x_out (fp32) and normalised.
+//   else:   x is read from x_in + row * in_stride.
+template <typename TW, typename TAct, int VPL, bool GATHER>
+__global__ void __launch_bounds__(256)
+ln_kernel(const float *__restrict__ x_in, int64_t in_stride, const int32_t *__restrict__ tok,
+          const TW *__restrict__ embed, int vocab, float *__restrict__ x_out,
+          const float *__restrict__ g, const float *__restrict__ b, TAct *__restrict__ out,
+          int64_t rows, int d, float eps)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+
+    float4 v[VPL];
+    float sum = 0.0f;
+    const TW *erow = nullptr;
+    if constexpr (GATHER) {
+        int t = tok[row];
+        t = min(max(t, 0), vocab - 1);          // never read outside the table
+        erow = embed + (size_t)t * d;
+    }
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) {
+            if constexpr (GATHER) {
+                v[i] = load4(erow + c);
+                store4(x_out + row * d + c, v[i]);
+            } else {
+                v[i] = load4(x_in + row * in_stride + c);
+            }
+            sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+        } else {
+            v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    const float mean = wave_sum(sum) / (float)d;
+    float sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) {
+            const float a = v[i].x - mean, bb = v[i].y - mean, cc = v[i].z - mean, dd = v[i].w - mean;
+            sq += (a * a + bb * bb) + (cc * cc + dd * dd);
+        }
+    }
+    const float var = wave_sum(sq) / (float)d;
+    const float rstd = 1.0f / sqrtf(var + eps);
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) {
+            const float4 gg = load4(g + c), bb = load4(b + c);
+            float4 o;
+            o.x = (v[i].x - mean) * rstd * gg.x + bb.x;
+            o.y = (v[i].y - mean) * rstd * gg.y + bb.y;
+            o.z = (v[i].z - mean) * rstd * gg.z + bb.z;
+            o.w = (v[i].w - mean) * rstd * gg.w + bb.w;
+            store4(out + row * d + c, o);
+        }
+    }
+}

@@ -1,0 +1,640 @@
+// libsrm: C ABI and step scheduler for SRM generation on gfx950.
+// The exported calls are declared and documented in include/srm.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "srm.h"
+#include "gemm.hpp"
+#include "mixer.hpp"
+#include "norm.hpp"
+
+// ------------------------------------------------------------------ errors
+static thread_local std::string g_err;
+
+static int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                       \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return fail(SRM_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_),    \
+                        __FILE__, __LINE__);                                                \
+    } while (0)
+
+#define SRM_TRY(expr)                 \
+    do {                              \
+        int rc_ = (expr);             \
+        if (rc_ != SRM_OK) return rc_; \
+    } while (0)
+
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ------------------------------------------------------------------ model
+struct LayerDev {
+    const float *ln1_g, *ln1_b, *b_in, *alpha, *beta, *lam, *b_out, *ln2_g, *ln2_b, *b_up, *b_down;
+    const void *w_in, *w_out, *w_up, *w_down;
+};
+
+struct srm_model {
+    srm_config cfg;
+    int device;
+    int d, ff, V, L, H;
+    size_t wsize;          // bytes per matrix element
+    void *slab;
+    const void *embed, *head;
+    const float *lnf_g, *lnf_b;
+    std::vector<LayerDev> layers;
+};
+
+static uint16_t host_f32_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+namespace {
+struct SlabBuilder {
+    std::vector<unsigned char> host;
+    size_t add(const float *src, size_t n, bool as_bf16)
+    {
+        size_t off = align_up(host.size(), 256);
+        size_t bytes = n * (as_bf16 ? 2 : 4);
+        host.resize(off + bytes);
+        if (as_bf16) {
+            uint16_t *dst = reinterpret_cast<uint16_t *>(host.data() + off);
+            for (size_t i = 0; i < n; ++i) dst[i] = host_f32_to_bf16(src[i]);
+        } else {
+            memcpy(host.data() + off, src, bytes);
+        }
+        return off;
+    }
+};
+}  // namespace
+
+extern "C" const char *srm_last_error(void) { return g_err.c_str(); }
+
+extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w, srm_model **out)
+{
+    if (!cfg || !w || !out) return fail(SRM_EINVAL, "srm_init_weights: null argument");
+    *out = nullptr;
+    if (cfg->vocab <= 0 || cfg->d_model <= 0 || cfg->n_layers <= 0 || cfg->n_heads <= 0 ||
+        cfg->mlp_expansion <= 0 || cfg->n_ctx <= 0)
+        return fail(SRM_EINVAL, "srm_init_weights: sizes must be positive");
+    if (cfg->n_heads % 2 || cfg->n_heads > kMaxHeads)
+        return fail(SRM_EINVAL, "srm_init_weights: n_heads must be even and <= %d", kMaxHeads);
+    if (cfg->d_model % (4 * cfg->n_heads))
+        return fail(SRM_EINVAL, "srm_init_weights: d_model must be a multiple of 4*n_heads");
+    if (cfg->d_model > 4096) return fail(SRM_EINVAL, "srm_init_weights: d_model > 4096 unsupported");
+    if (cfg->weight_dtype != SRM_FP32 && cfg->weight_dtype != SRM_BF16)
+        return fail(SRM_EINVAL, "srm_init_weights: unknown weight_dtype %d", cfg->weight_dtype);
+    if (cfg->weight_dtype == SRM_BF16 && cfg->d_model % 64)
+        return fail(SRM_EINVAL, "srm_init_weights: bf16 needs d_model %% 64 == 0");
+    if (!(cfg->ln_eps > 0.0f)) return fail(SRM_EINVAL, "srm_init_weights: ln_eps must be > 0");
+    if (!w->embed || !w->head || !w->lnf_g || !w->lnf_b || !w->layers)
+        return fail(SRM_EINVAL, "srm_init_weights: null weight pointer");
+    const int d = cfg->d_model, L = cfg->n_layers, H = cfg->n_heads, V = cfg->vocab;
+    const size_t ff = (size_t)cfg->mlp_expansion * d, nc = cfg->n_ctx;
+    for (int l = 0; l < L; ++l) {
+        const srm_host_layer &y = w->layers[l];
+        const float *ptrs[] = {y.ln1_g, y.ln1_b, y.w_in, y.b_in, y.alpha, y.beta, y.lambda, y.w_out,
+                               y.b_out, y.ln2_g, y.ln2_b, y.w_up, y.b_up, y.w_down, y.b_down};
+        for (const float *p : ptrs)
+            if (!p) return fail(SRM_EINVAL, "srm_init_weights: null weight pointer in layer %d", l);
+        for (int h = 0; h < H; ++h)
+            if (!(y.lambda[h] > 0.0f && y.lambda[h] <= 1.0f))
+                return fail(SRM_EINVAL, "srm_init_weights: lambda[%d][%d] = %g outside (0, 1]", l, h,
+                            (double)y.lambda[h]);
+    }
+
+    srm_model *m = new (std::nothrow) srm_model();
+    if (!m) return fail(SRM_ENOMEM, "srm_init_weights: host allocation failed");
+    m->cfg = *cfg;
+    m->d = d; m->ff = (int)ff; m->V = V; m->L = L; m->H = H;
+    const bool bf = cfg->weight_dtype == SRM_BF16;
+    m->wsize = bf ? 2 : 4;
+    m->slab = nullptr;
+
+    struct Offs { size_t v[15]; };
+    std::vector<Offs> lo(L);
+    size_t o_embed, o_head, o_lnfg, o_lnfb;
+    SlabBuilder sb;
+    try {
+        o_embed = sb.add(w->embed, (size_t)V * d, bf);
+        o_head = sb.add(w->head, (size_t)V * d, bf);
+        o_lnfg = sb.add(w->lnf_g, d, false);
+        o_lnfb = sb.add(w->lnf_b, d, false);
+        for (int l = 0; l < L; ++l) {
+            const srm_host_layer &y = w->layers[l];
+            size_t *o = lo[l].v;
+            o[0] = sb.add(y.ln1_g, d, false);          o[1] = sb.add(y.ln1_b, d, false);
+            o[2] = sb.add(y.w_in, (size_t)d * d, bf);   o[3] = sb.add(y.b_in, d, false);
+            o[4] = sb.add(y.alpha, H * nc, false);      o[5] = sb.add(y.beta, H * nc, false);
+            o[6] = sb.add(y.lambda, H, false);
+            o[7] = sb.add(y.w_out, (size_t)d * d, bf);  o[8] = sb.add(y.b_out, d, false);
+            o[9] = sb.add(y.ln2_g, d, false);           o[10] = sb.add(y.ln2_b, d, false);
+            o[11] = sb.add(y.w_up, ff * d, bf);         o[12] = sb.add(y.b_up, ff, false);
+            o[13] = sb.add(y.w_down, (size_t)d * ff, bf); o[14] = sb.add(y.b_down, d, false);
+        }
+    } catch (const std::bad_alloc &) {
+        delete m;
+        return fail(SRM_ENOMEM, "srm_init_weights: host staging allocation failed");
+    }
+    hipError_t e = hipGetDevice(&m->device);
+    if (e == hipSuccess) e = hipMalloc(&m->slab, align_up(sb.host.size(), 256));
+    if (e != hipSuccess) {
+        delete m;
+        return fail(e == hipErrorOutOfMemory ? SRM_ENOMEM : SRM_EHIP, "srm_init_weights: hipMalloc(%zu): %s",
+                    sb.host.size(), hipGetErrorString(e));
+    }
+    e = hipMemcpy(m->slab, sb.host.data(), sb.host.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(m->slab);
+        delete m;
+        return fail(SRM_EHIP, "srm_init_weights: hipMemcpy: %s", hipGetErrorString(e));
+    }
+    const unsigned char *base = static_cast<const unsigned char *>(m->slab);
+    auto F = [&](size_t off) { return reinterpret_cast<const float *>(base + off); };
+    m->embed = base + o_embed; m->head = base + o_head;
+    m->lnf_g = F(o_lnfg); m->lnf_b = F(o_lnfb);
+    m->layers.resize(L);
+    for (int l = 0; l < L; ++l) {
+        const size_t *o = lo[l].v;
+        LayerDev &y = m->layers[l];
+        y.ln1_g = F(o[0]); y.ln1_b = F(o[1]); y.w_in = base + o[2]; y.b_in = F(o[3]);
+        y.alpha = F(o[4]); y.beta = F(o[5]); y.lam = F(o[6]); y.w_out = base + o[7];
+        y.b_out = F(o[8]); y.ln2_g = F(o[9]); y.ln2_b = F(o[10]); y.w_up = base + o[11];
+        y.b_up = F(o[12]); y.w_down = base + o[13]; y.b_down = F(o[14]);
+    }
+    *out = m;
+    return SRM_OK;
+}
+
+extern "C" void srm_free(srm_model *m)
+{
+    if (!m) return;
+    if (m->slab) (void)hipFree(m->slab);
+    delete m;
+}
+
+extern "C" size_t srm_state_bytes(const srm_model *m, int64_t batch)
+{
+    if (!m || batch <= 0) return 0;
+    return (size_t)m->L * (size_t)batch * (size_t)m->d * sizeof(float);
+}
+
+// ------------------------------------------------------------------ workspace
+// Column-tile width that bounds the number of argmax partials per row.
+static int head_min_bn(const srm_model *m) { return m->cfg.weight_dtype == SRM_BF16 ? 128 : 64; }
+
+struct Workspace {
+    float *x;          // [rows][d]  residual stream
+    void *a, *u, *mx;  // [rows][d]  activation type
+    void *g;           // [rows][ff] activation type
+    float *pv;         // [rows][nparts]
+    int32_t *pi;       // [rows][nparts]
+    size_t bytes;
+};
+
+static Workspace carve(const srm_model *m, void *base, int64_t rows)
+{
+    Workspace w;
+    unsigned char *p = static_cast<unsigned char *>(base);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        unsigned char *r = p ? p + off : nullptr;
+        off += align_up(bytes, 256);
+        return r;
+    };
+    const size_t r = (size_t)rows, d = m->d, s = m->wsize;
+    const size_t nparts = cdiv(m->V, head_min_bn(m));
+    w.x = reinterpret_cast<float *>(take(r * d * 4));
+    w.a = take(r * d * s);
+    w.u = take(r * d * s);
+    w.mx = take(r * d * s);
+    w.g = take(r * (size_t)m->ff * s);
+    w.pv = reinterpret_cast<float *>(take(r * nparts * 4));
+    w.pi = reinterpret_cast<int32_t *>(take(r * nparts * 4));
+    w.bytes = off;
+    return w;
+}
+
+extern "C" size_t srm_workspace_bytes(const srm_model *m, int64_t rows)
+{
+    if (!m || rows <= 0) return 0;
+    return carve(m, nullptr, rows).bytes;
+}
+
+// ------------------------------------------------------------------ launchers
+template <int BM, int BN, int WM, int WN, int EPI, typename TAct>
+static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, const GemmEpi &ep,
+                            hipStream_t st)
+{
+    constexpr size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(bf16);
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI, TAct>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr_set = true;
+    }
+    const int64_t nb = cdiv(M, BM) * cdiv(N, BN);
+    hipLaunchKernelGGL(kern, dim3((unsigned)nb), dim3(WM * WN * 64), smem, st, A, W, M, N, K, ep);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
+// Tile choice for the bf16 GEMM: 0 = 256x256, 1 = 128x128, 2 = 64x64.  The big
+// tile needs enough blocks to fill 256 CUs; min_bn > 64 rules out the small one
+// (the LM head's partial buffers are sized for column tiles >= 128).
+static int choose_tile(int64_t M, int N, int min_bn)
+{
+    int tile;
+    if (cdiv(M, 256) * cdiv(N, 256) >= 200) tile = 0;
+    else if (cdiv(M, 128) * cdiv(N, 128) >= 128) tile = 1;
+    else tile = 2;
+    if (tile == 2 && min_bn > 64) tile = 1;
+    return tile;
+}
+static int tile_bn(int tile) { return tile == 0 ? 256 : tile == 1 ? 128 : 64; }
+
+static thread_local int g_force_tile = -1;   // test/bench hook of srm_linear only
+
+template <int EPI, typename TAct>
+static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, GemmEpi ep, hipStream_t st,
+                       int min_bn, int *nparts_out)
+{
+    if (K % 64) return fail(SRM_EINVAL, "bf16 GEMM needs K %% 64 == 0 (K = %d)", K);
+    if (M <= 0 || M >= (1 << 30) || N <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
+    const int tile = g_force_tile >= 0 ? g_force_tile : choose_tile(M, N, min_bn);
+    ep.nparts = (int)cdiv(N, tile_bn(tile));
+    if (nparts_out) *nparts_out = ep.nparts;
+    switch (tile) {
+    case 0: return launch_bf16_tile<256, 256, 2, 2, EPI, TAct>(A, W, (int)M, N, K, ep, st);
+    case 1: return launch_bf16_tile<128, 128, 2, 2, EPI, TAct>(A, W, (int)M, N, K, ep, st);
+    default: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct>(A, W, (int)M, N, K, ep, st);
+    }
+}
+
+template <int EPI>
+static int launch_f32(const float *A, const float *W, int64_t M, int N, int K, GemmEpi ep, hipStream_t st,
+                      int *nparts_out)
+{
+    if (M <= 0 || M >= (1 << 30) || N <= 0 || K <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
+    ep.nparts = (int)cdiv(N, 64);
+    if (nparts_out) *nparts_out = ep.nparts;
+    const int64_t nb = cdiv(M, 64) * cdiv(N, 64);
+    hipLaunchKernelGGL(gemm_f32_kernel<EPI>, dim3((unsigned)nb), dim3(256), 0, st, A, W, (int)M, N, K, ep);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
+// out = epilogue(A W^T + bias) with operands of type T (float or bf16)
+template <int EPI, typename T>
+static int linear(const void *A, const void *W, const float *bias, int64_t M, int N, int K, void *out,
+                  hipStream_t st, float *pv = nullptr, int32_t *pi = nullptr, int min_bn = 64,
+                  int *nparts_out = nullptr)
+{
+    GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0};
+    if constexpr (sizeof(T) == 2)
+        return launch_bf16<EPI, bf16>(static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), M, N, K, ep,
+                                      st, min_bn, nparts_out);
+    else
+        return launch_f32<EPI>(static_cast<const float *>(A), static_cast<const float *>(W), M, N, K, ep, st,
+                               nparts_out);
+}
+
+static int argmax_finalize(const float *pv, const int32_t *pi, int64_t rows, int nparts, int32_t *out,
+                           int64_t row0, int rep, int vocab, hipStream_t st)
+{
+    hipLaunchKernelGGL(argmax_finalize_kernel, dim3((unsigned)cdiv(rows, 4)), dim3(256), 0, st, pv, pi, rows,
+                       nparts, out, row0, rep, vocab);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
+template <typename T, bool GATHER>
+static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, const int32_t *tok,
+                     float *x_out, const float *g, const float *b, void *out, int64_t rows, hipStream_t st)
+{
+    const int d = m->d;
+    const unsigned nb = (unsigned)cdiv(rows, 4);
+    const T *emb = static_cast<const T *>(m->embed);
+    T *o = static_cast<T *>(out);
+#define LN_CASE(VPL)                                                                                     \
+    hipLaunchKernelGGL((ln_kernel<T, T, VPL, GATHER>), dim3(nb), dim3(256), 0, st, x_in, in_stride, tok, \
+                       emb, m->V, x_out, g, b, o, rows, d, m->cfg.ln_eps)
+    if (d <= 256) LN_CASE(1);
+    else if (d <= 512) LN_CASE(2);
+    else if (d <= 1024) LN_CASE(4);
+    else if (d <= 2048) LN_CASE(8);
+    else LN_CASE(16);
+#undef LN_CASE
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
+template <typename T>
+static int state_update(const srm_model *m, int layer, int pos, int64_t B, const void *u, float *S, void *mx,
+                        hipStream_t st)
+{
+    constexpr int UNROLL = 4;
+    const LayerDev &y = m->layers[layer];
+    const int dv = m->d / 4;
+    const int64_t nvec = B * dv;
+    // Enough blocks to cover the slab once with UNROLL vectors per thread, at
+    // most 8 per CU, rounded up so that gridDim * 256 is a multiple of d/4 (the
+    // kernel relies on it: a thread keeps one channel group).
+    int64_t nb = cdiv(nvec, 256 * UNROLL);
+    if (nb > 256 * 8) nb = 256 * 8;
+    int a = dv, b = 256;
+    while (b) { int t = a % b; a = b; b = t; }
+    const int step = dv / a;
+    nb = cdiv(nb, step) * step;
+    hipLaunchKernelGGL((state_update_kernel<T, UNROLL>), dim3((unsigned)nb), dim3(256), 0, st,
+                       static_cast<const T *>(u), S, static_cast<T *>(mx), y.alpha, y.beta, y.lam, pos,
+                       m->cfg.n_ctx, m->H, m->d, nvec);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
+static hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+
+static int check_device(const srm_model *m)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != m->device)
+        return fail(SRM_EINVAL, "model lives on device %d but device %d is current", m->device, dev);
+    return SRM_OK;
+}
+
+// One block (token mixing + channel mixing) on `rows` token rows.  On entry
+// w.a holds LayerNorm1(x) of this layer; mix(l) turns w.u into w.mx.  With
+// norm_next, w.a leaves holding the next layer's LayerNorm1(x), or the final
+// LayerNorm after the last layer.
+template <typename T, typename MIX>
+static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hipStream_t st, MIX &&mix,
+                 bool norm_next)
+{
+    const LayerDev &y = m->layers[l];
+    const int d = m->d, ff = m->ff;
+    SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, d, d, w.u, st)));
+    SRM_TRY(mix(l));
+    SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.x, st)));
+    SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
+    SRM_TRY((linear<EPI_GELU, T>(w.a, y.w_up, y.b_up, rows, ff, d, w.g, st)));
+    SRM_TRY((linear<EPI_RESID, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.x, st)));
+    if (norm_next) {
+        const float *g = l + 1 < m->L ? m->layers[l + 1].ln1_g : m->lnf_g;
+        const float *b = l + 1 < m->L ? m->layers[l + 1].ln1_b : m->lnf_b;
+        SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, g, b, w.a, rows, st)));
+    }
+    return SRM_OK;
+}
+
+// LM head on M normalised rows `a`: optional fp32 logits, greedy token written
+// `rep` times at d_tok[(row0 + row) * rep + r].
+template <typename T>
+static int head_argmax(const srm_model *m, const Workspace &w, const void *a, int64_t M, float *logits,
+                       int32_t *d_tok, int64_t row0, int rep, hipStream_t st)
+{
+    int nparts = 0;
+    SRM_TRY((linear<EPI_ARGMAX, T>(a, m->head, nullptr, M, m->V, m->d, logits, st, w.pv, w.pi, head_min_bn(m),
+                                   &nparts)));
+    return argmax_finalize(w.pv, w.pi, M, nparts, d_tok, row0, rep, m->V, st);
+}
+
+// ------------------------------------------------------------------ decode
+template <typename T>
+static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, float *state, int32_t *tok_out,
+                       float *logits, float *hidden, void *ws, hipStream_t st)
+{
+    const Workspace w = carve(m, ws, B);
+    const int d = m->d;
+    SRM_TRY((layernorm<T, true>(m, nullptr, 0, tok_in, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a, B, st)));
+    auto mix = [&](int l) { return state_update<T>(m, l, pos, B, w.u, state + (size_t)l * B * d, w.mx, st); };
+    for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true)));
+    if (hidden) HIP_TRY(hipMemcpyAsync(hidden, w.x, (size_t)B * d * 4, hipMemcpyDeviceToDevice, st));
+    return head_argmax<T>(m, w, w.a, B, logits, tok_out, 0, 1, st);
+}
+
+extern "C" int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
+                               int32_t *d_tok_out, float *d_logits, float *d_hidden, void *d_workspace,
+                               size_t workspace_bytes, void *hip_stream)
+{
+    if (!m || !d_tok_in || !d_state || !d_tok_out || !d_workspace)
+        return fail(SRM_EINVAL, "srm_decode_step: null argument");
+    if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "srm_decode_step: batch %lld out of range", (long long)B);
+    if (pos < 0 || pos >= m->cfg.n_ctx)
+        return fail(SRM_EINVAL, "srm_decode_step: pos %d outside [0, %d)", pos, m->cfg.n_ctx);
+    if (workspace_bytes < srm_workspace_bytes(m, B))
+        return fail(SRM_ENOMEM, "srm_decode_step: workspace %zu < %zu bytes", workspace_bytes,
+                    srm_workspace_bytes(m, B));
+    SRM_TRY(check_device(m));
+    hipStream_t st = as_stream(hip_stream);
+    return m->wsize == 2
+               ? decode_impl<bf16>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden, d_workspace, st)
+               : decode_impl<float>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden, d_workspace, st);
+}
+
+// ------------------------------------------------------------------ prefill
+// Whole sequences per pass that fit the workspace (0 if not even one does).
+static int64_t seqs_per_pass(const srm_model *m, size_t workspace_bytes, int T, int64_t nseq)
+{
+    if (srm_workspace_bytes(m, T) > workspace_bytes) return 0;
+    int64_t lo = 1, hi = nseq;       // largest n with bytes(n*T) <= workspace_bytes
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) / 2;
+        if (srm_workspace_bytes(m, mid * T) <= workspace_bytes) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+template <typename T>
+static int prefill_impl(srm_model *m, const int32_t *prompts, int N, int P, int k, float *state,
+                        int32_t *next_tok, float *logits, void *ws, int64_t per_pass, hipStream_t st)
+{
+    const int d = m->d;
+    const int64_t Btot = (int64_t)N * k;
+    const size_t scan_lds = (size_t)2 * m->H * P * sizeof(float);
+    for (int64_t n0 = 0; n0 < N; n0 += per_pass) {
+        const int64_t nc = std::min<int64_t>(per_pass, N - n0);
+        const int64_t rows = nc * P;
+        const Workspace w = carve(m, ws, rows);
+        SRM_TRY((layernorm<T, true>(m, nullptr, 0, prompts + n0 * P, w.x, m->layers[0].ln1_g,
+                                    m->layers[0].ln1_b, w.a, rows, st)));
+        auto mix = [&](int l) {
+            const LayerDev &y = m->layers[l];
+            const unsigned nb = (unsigned)cdiv(nc * (d / 4), 256);
+            hipLaunchKernelGGL((mixer_scan_kernel<T>), dim3(nb), dim3(256), scan_lds, st,
+                               static_cast<const T *>(w.u), static_cast<T *>(w.mx),
+                               state + (size_t)l * Btot * d, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d,
+                               (int)nc, P, n0, k);
+            HIP_TRY(hipGetLastError());
+            return (int)SRM_OK;
+        };
+        for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, rows, st, mix, l + 1 < m->L)));
+        // final LayerNorm of each prompt's last position only, packed [nc][d] into w.a
+        SRM_TRY((layernorm<T, false>(m, w.x + (size_t)(P - 1) * d, (int64_t)P * d, nullptr, nullptr, m->lnf_g,
+                                     m->lnf_b, w.a, nc, st)));
+        SRM_TRY((head_argmax<T>(m, w, w.a, nc, logits ? logits + (size_t)n0 * m->V : nullptr, next_tok, n0, k, st)));
+    }
+    return SRM_OK;
+}
+
+extern "C" int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, int32_t P, int32_t fanout_k,
+                           float *d_state, int32_t *d_next_tok, float *d_logits, void *d_workspace,
+                           size_t workspace_bytes, void *hip_stream)
+{
+    if (!m || !d_prompts || !d_state || !d_next_tok || !d_workspace)
+        return fail(SRM_EINVAL, "srm_prefill: null argument");
+    if (N <= 0 || P <= 0 || fanout_k <= 0) return fail(SRM_EINVAL, "srm_prefill: N, P and fanout_k must be positive");
+    if (P > m->cfg.n_ctx) return fail(SRM_EINVAL, "srm_prefill: P = %d exceeds n_ctx = %d", P, m->cfg.n_ctx);
+    if ((int64_t)N * fanout_k >= (1 << 30)) return fail(SRM_EINVAL, "srm_prefill: N * fanout_k too large");
+    if ((size_t)2 * m->H * P * sizeof(float) > 64 * 1024)
+        return fail(SRM_EINVAL, "srm_prefill: n_heads * P too large for the coefficient stage");
+    const int64_t max_seqs = std::max<int64_t>(1, ((1 << 30) - 1) / P);
+    int64_t per_pass = seqs_per_pass(m, workspace_bytes, P, std::min<int64_t>(N, max_seqs));
+    if (per_pass < 1)
+        return fail(SRM_ENOMEM, "srm_prefill: workspace %zu < %zu bytes (one prompt)", workspace_bytes,
+                    srm_workspace_bytes(m, P));
+    SRM_TRY(check_device(m));
+    hipStream_t st = as_stream(hip_stream);
+    return m->wsize == 2 ? prefill_impl<bf16>(m, d_prompts, N, P, fanout_k, d_state, d_next_tok, d_logits,
+                                              d_workspace, per_pass, st)
+                         : prefill_impl<float>(m, d_prompts, N, P, fanout_k, d_state, d_next_tok, d_logits,
+                                               d_workspace, per_pass, st);
+}
+
+// ------------------------------------------------------------------ parallel form
+template <typename T>
+static int parallel_impl(srm_model *m, const int32_t *tok, int B, int T_, float *hidden, float *logits, void *ws,
+                         int64_t per_pass, hipStream_t st)
+{
+    const int d = m->d, dh = d / m->H;
+    for (int64_t b0 = 0; b0 < B; b0 += per_pass) {
+        const int64_t nc = std::min<int64_t>(per_pass, B - b0);
+        const int64_t rows = nc * T_;
+        const Workspace w = carve(m, ws, rows);
+        SRM_TRY((layernorm<T, true>(m, nullptr, 0, tok + b0 * T_, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b,
+                                    w.a, rows, st)));
+        auto mix = [&](int l) {
+            const LayerDev &y = m->layers[l];
+            const dim3 grid((unsigned)cdiv(T_, 64), (unsigned)(m->H * cdiv(dh, 64)), (unsigned)nc);
+            hipLaunchKernelGGL((mixer_parallel_kernel<T>), grid, dim3(256), (size_t)T_ * sizeof(float), st,
+                               static_cast<const T *>(w.u), static_cast<T *>(w.mx), y.alpha, y.beta, y.lam,
+                               m->cfg.n_ctx, m->H, d, T_);
+            HIP_TRY(hipGetLastError());
+            return (int)SRM_OK;
+        };
+        for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, rows, st, mix, true)));
+        HIP_TRY(hipMemcpyAsync(hidden + (size_t)b0 * T_ * d, w.x, (size_t)rows * d * 4, hipMemcpyDeviceToDevice, st));
+        if (logits)
+            SRM_TRY((linear<EPI_F32, T>(w.a, m->head, nullptr, rows, m->V, d, logits + (size_t)b0 * T_ * m->V, st)));
+    }
+    return SRM_OK;
+}
+
+extern "C" int srm_parallel_forward(srm_model *m, const int32_t *d_tok, int32_t B, int32_t T, float *d_hidden,
+                                    float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!m || !d_tok || !d_hidden || !d_workspace) return fail(SRM_EINVAL, "srm_parallel_forward: null argument");
+    if (B <= 0 || T <= 0) return fail(SRM_EINVAL, "srm_parallel_forward: B and T must be positive");
+    if (T > m->cfg.n_ctx) return fail(SRM_EINVAL, "srm_parallel_forward: T = %d exceeds n_ctx = %d", T, m->cfg.n_ctx);
+    if ((size_t)T * sizeof(float) > 32 * 1024) return fail(SRM_EINVAL, "srm_parallel_forward: T too large");
+    if (B > 65535) return fail(SRM_EINVAL, "srm_parallel_forward: B > 65535");
+    const int64_t max_seqs = std::max<int64_t>(1, ((1 << 30) - 1) / T);
+    int64_t per_pass = seqs_per_pass(m, workspace_bytes, T, std::min<int64_t>(B, max_seqs));
+    if (per_pass < 1)
+        return fail(SRM_ENOMEM, "srm_parallel_forward: workspace %zu < %zu bytes (one sequence)", workspace_bytes,
+                    srm_workspace_bytes(m, T));
+    SRM_TRY(check_device(m));
+    hipStream_t st = as_stream(hip_stream);
+    return m->wsize == 2
+               ? parallel_impl<bf16>(m, d_tok, B, T, d_hidden, d_logits, d_workspace, per_pass, st)
+               : parallel_impl<float>(m, d_tok, B, T, d_hidden, d_logits, d_workspace, per_pass, st);
+}
+
+// ------------------------------------------------------------------ kernel-level entry points
+extern "C" int srm_mixer_update(srm_model *m, int32_t layer, int32_t pos, int64_t B, const void *d_u,
+                                float *d_state_layer, void *d_m, void *hip_stream)
+{
+    if (!m || !d_u || !d_state_layer || !d_m) return fail(SRM_EINVAL, "srm_mixer_update: null argument");
+    if (layer < 0 || layer >= m->L) return fail(SRM_EINVAL, "srm_mixer_update: layer %d outside [0, %d)", layer, m->L);
+    if (pos < 0 || pos >= m->cfg.n_ctx) return fail(SRM_EINVAL, "srm_mixer_update: pos %d outside [0, %d)", pos, m->cfg.n_ctx);
+    if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "srm_mixer_update: batch out of range");
+    SRM_TRY(check_device(m));
+    hipStream_t st = as_stream(hip_stream);
+    return m->wsize == 2 ? state_update<bf16>(m, layer, pos, B, d_u, d_state_layer, d_m, st)
+                         : state_update<float>(m, layer, pos, B, d_u, d_state_layer, d_m, st);
+}
+
+extern "C" size_t srm_linear_scratch_bytes(int64_t M, int32_t N)
+{
+    if (M <= 0 || N <= 0) return 0;
+    return align_up((size_t)M * cdiv(N, 64) * 4, 256) * 2;
+}
+
+template <typename T>
+static int linear_entry(int epilogue, const void *A, const void *W, const float *bias, int64_t M, int N, int K,
+                        void *out, int32_t *amax, void *scratch, hipStream_t st)
+{
+    switch (epilogue) {
+    case 0: return linear<EPI_STORE, T>(A, W, bias, M, N, K, out, st);
+    case 1: return linear<EPI_GELU, T>(A, W, bias, M, N, K, out, st);
+    case 2: return linear<EPI_RESID, T>(A, W, bias, M, N, K, out, st);
+    case 3: {
+        float *pv = static_cast<float *>(scratch);
+        int32_t *pi = reinterpret_cast<int32_t *>(static_cast<unsigned char *>(scratch) +
+                                                  align_up((size_t)M * cdiv(N, 64) * 4, 256));
+        int nparts = 0;
+        SRM_TRY((linear<EPI_ARGMAX, T>(A, W, bias, M, N, K, out, st, pv, pi, 64, &nparts)));
+        return argmax_finalize(pv, pi, M, nparts, amax, 0, 1, N, st);
+    }
+    case 4: return linear<EPI_F32, T>(A, W, bias, M, N, K, out, st);
+    default: return fail(SRM_EINVAL, "srm_linear: unknown epilogue %d", epilogue);
+    }
+}
+
+extern "C" int srm_linear(int32_t dtype, int32_t epilogue, const void *d_A, const void *d_W, const float *d_bias,
+                          int64_t M, int32_t N, int32_t K, void *d_out, int32_t *d_argmax, void *d_scratch,
+                          void *hip_stream)
+{
+    if (!d_A || !d_W) return fail(SRM_EINVAL, "srm_linear: null operand");
+    if (epilogue == 3 ? (!d_argmax || !d_scratch) : !d_out) return fail(SRM_EINVAL, "srm_linear: null output");
+    if (M <= 0 || N <= 0 || K <= 0) return fail(SRM_EINVAL, "srm_linear: sizes must be positive");
+    hipStream_t st = as_stream(hip_stream);
+    // epilogue codes >= 100 select a fixed bf16 tile (100*tile + epilogue) for tile sweeps
+    g_force_tile = -1;
+    if (epilogue >= 100 && dtype == SRM_BF16) {
+        g_force_tile = epilogue / 100 - 1;
+        epilogue %= 100;
+        if (g_force_tile > 2) return fail(SRM_EINVAL, "srm_linear: unknown tile");
+    }
+    int rc;
+    if (dtype == SRM_BF16) rc = linear_entry<bf16>(epilogue, d_A, d_W, d_bias, M, N, K, d_out, d_argmax, d_scratch, st);
+    else if (dtype == SRM_FP32) rc = linear_entry<float>(epilogue, d_A, d_W, d_bias, M, N, K, d_out, d_argmax, d_scratch, st);
+    else rc = fail(SRM_EINVAL, "srm_linear: unknown dtype %d", dtype);
+    g_force_tile = -1;
+    return rc;
+}
