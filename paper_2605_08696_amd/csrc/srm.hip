@@ -621,16 +621,17 @@ extern "C" int srm_linear(int32_t dtype, int32_t epilogue, const void *d_A, cons
                           void *hip_stream)
 {
     if (!d_A || !d_W) return fail(SRM_EINVAL, "srm_linear: null operand");
+    // epilogue codes >= 100 pin a bf16 tile, (tile + 1) * 100 + epilogue, for tile sweeps
+    int forced = -1;
+    if (epilogue >= 100) {
+        forced = epilogue / 100 - 1;
+        epilogue %= 100;
+        if (forced > 2 || dtype != SRM_BF16) return fail(SRM_EINVAL, "srm_linear: unknown tile code");
+    }
     if (epilogue == 3 ? (!d_argmax || !d_scratch) : !d_out) return fail(SRM_EINVAL, "srm_linear: null output");
     if (M <= 0 || N <= 0 || K <= 0) return fail(SRM_EINVAL, "srm_linear: sizes must be positive");
     hipStream_t st = as_stream(hip_stream);
-    // epilogue codes >= 100 select a fixed bf16 tile (100*tile + epilogue) for tile sweeps
-    g_force_tile = -1;
-    if (epilogue >= 100 && dtype == SRM_BF16) {
-        g_force_tile = epilogue / 100 - 1;
-        epilogue %= 100;
-        if (g_force_tile > 2) return fail(SRM_EINVAL, "srm_linear: unknown tile");
-    }
+    g_force_tile = forced;
     int rc;
     if (dtype == SRM_BF16) rc = linear_entry<bf16>(epilogue, d_A, d_W, d_bias, M, N, K, d_out, d_argmax, d_scratch, st);
     else if (dtype == SRM_FP32) rc = linear_entry<float>(epilogue, d_A, d_W, d_bias, M, N, K, d_out, d_argmax, d_scratch, st);

@@ -1,0 +1,163 @@
+"""Kernel-level GPU checks through the C ABI: the GEMM with each fused epilogue
+and each tile shape, the argmax tie rule, and the recurrent state update
+against the oracle's mixer step."""
+import numpy as np
+import pytest
+import torch
+
+import srm_synth
+from gpu_util import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def srm():
+    import paper_2605_08696_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+def _gelu(x):
+    import scipy.special
+    return x * scipy.special.ndtr(x)
+
+
+def _linear_case(srm, dtype, M, N, K, epi, tile, seed):
+    rng = np.random.default_rng(seed)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    W = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    if dtype == srm.SRM_BF16:
+        A, W = srm_synth.round_to_bf16(A), srm_synth.round_to_bf16(W)
+    tt = torch.bfloat16 if dtype == srm.SRM_BF16 else torch.float32
+    dA, dW, dB = to_dev(A, tt), to_dev(W, tt), to_dev(bias)
+    ref = A.astype(np.float64) @ W.astype(np.float64).T + bias
+    print(f"linear dtype={dtype} M={M} N={N} K={K} epi={epi} tile={tile}", flush=True)
+    if epi in (0, 1):
+        out = torch.full((M, N), 7.0, dtype=tt, device="cuda")
+        srm.linear(dtype, epi, dA, dW, dB, out=out, tile=tile)
+        want = ref if epi == 0 else _gelu(ref)
+        got = out.float().cpu().numpy()
+        tol = 2.0 ** -8 if dtype == srm.SRM_BF16 else 2e-6
+        assert np.abs(got - want).max() <= tol * max(1.0, np.abs(want).max())
+    elif epi == 2:
+        base = rng.standard_normal((M, N)).astype(np.float32)
+        out = to_dev(base)
+        srm.linear(dtype, 2, dA, dW, dB, out=out, tile=tile)
+        got = out.cpu().numpy()
+        assert np.abs(got - (ref + base)).max() <= 4e-6 * np.abs(ref).max() + 1e-6
+    elif epi == 4:
+        out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+        srm.linear(dtype, 4, dA, dW, dB, out=out, tile=tile)
+        assert np.abs(out.cpu().numpy() - ref).max() <= 4e-6 * np.abs(ref).max()
+    else:
+        out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+        am = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+        scratch = torch.empty(srm.linear_scratch_bytes(M, N), dtype=torch.uint8, device="cuda")
+        srm.linear(dtype, 3, dA, dW, dB, out=out, argmax=am, scratch=scratch, tile=tile)
+        got = out.cpu().numpy()
+        assert np.abs(got - ref).max() <= 4e-6 * np.abs(ref).max()
+        # argmax is decided on the kernel's own fp32 logits
+        np.testing.assert_array_equal(am.cpu().numpy(), got.argmax(axis=1))
+        am2 = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+        srm.linear(dtype, 3, dA, dW, dB, out=None, argmax=am2, scratch=scratch, tile=tile)
+        np.testing.assert_array_equal(am2.cpu().numpy(), got.argmax(axis=1))
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
+def test_linear_bf16_tiles_and_epilogues(srm, tile, epi):
+    # several tiles in both directions plus ragged edges in M and N
+    _linear_case(srm, srm.SRM_BF16, 300, 328, 192, epi, tile, seed=10 * tile + epi)
+
+
+@pytest.mark.parametrize("shape", [(1, 64, 64), (37, 130, 64), (513, 1000, 256), (1024, 512, 1024)])
+def test_linear_bf16_auto_tile_shapes(srm, shape):
+    M, N, K = shape
+    for epi in (0, 3):
+        _linear_case(srm, srm.SRM_BF16, M, N, K, epi, None, seed=M + N)
+
+
+@pytest.mark.parametrize("shape", [(1, 5, 3), (8, 256, 256), (70, 130, 37), (128, 64, 100)])
+@pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
+def test_linear_fp32(srm, shape, epi):
+    M, N, K = shape
+    _linear_case(srm, srm.SRM_FP32, M, N, K, epi, None, seed=M * 7 + epi)
+
+
+@pytest.mark.parametrize("dtype_name", ["fp32", "bf16"])
+def test_argmax_ties_go_to_the_lowest_index(srm, dtype_name):
+    dtype = srm.SRM_BF16 if dtype_name == "bf16" else srm.SRM_FP32
+    tt = torch.bfloat16 if dtype_name == "bf16" else torch.float32
+    M, N, K = 9, 700, 64
+    rng = np.random.default_rng(3)
+    A = srm_synth.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    W = srm_synth.round_to_bf16(rng.standard_normal((N, K)).astype(np.float32) * 0.1)
+    # plant identical rows far apart (different column tiles and lanes): exact ties
+    W[650] = W[17]; W[300] = W[17]
+    W[17] *= 0; W[300] *= 0; W[650] *= 0
+    bias = np.zeros(N, np.float32); bias[[17, 300, 650]] = 100.0     # all three tie at the top
+    am = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+    scratch = torch.empty(srm.linear_scratch_bytes(M, N), dtype=torch.uint8, device="cuda")
+    srm.linear(dtype, 3, to_dev(A, tt), to_dev(W, tt), to_dev(bias), out=None, argmax=am, scratch=scratch)
+    np.testing.assert_array_equal(am.cpu().numpy(), np.full(M, 17))
+
+
+@pytest.mark.parametrize("dtype_name", ["fp32", "bf16"])
+@pytest.mark.parametrize("B", [1, 5, 1000, 4099])
+def test_state_update_matches_oracle_step(srm, dtype_name, B):
+    from oracle import srm_oracle
+    d = 128 if dtype_name == "bf16" else 48
+    H = 4
+    cfg = srm_synth.tiny_config(vocab=16, d_model=d, n_layers=2, n_heads=H, n_ctx=8,
+                                weight_dtype=dtype_name, seed=31)
+    w = srm_synth.make_weights(cfg, stress=True)
+    orc = srm_oracle.Oracle(cfg, w, "f64")
+    model = srm.Model(cfg, w)
+    rng = np.random.default_rng(B)
+    u = rng.standard_normal((B, d)).astype(np.float32)
+    if dtype_name == "bf16":
+        u = srm_synth.round_to_bf16(u)
+    S0 = rng.standard_normal((B, d)).astype(np.float32)
+    layer, pos = 1, 5
+    lw = w["layers"][layer]
+    S_ref = S0.astype(np.float64)
+    m_ref = np.empty((B, d))
+    for b in range(B):
+        m_ref[b] = orc.mixer_step(S_ref[b], u[b], lw["alpha"][:, pos], lw["beta"][:, pos], lw["lam"])
+    print(f"state_update {dtype_name} B={B}", flush=True)
+    dS = to_dev(S0)
+    du = to_dev(u, model.act_dtype)
+    dm = torch.empty_like(du)
+    model.mixer_update(layer, pos, B, du, dS, dm)
+    torch.cuda.synchronize()
+    assert np.abs(dS.cpu().numpy() - S_ref).max() <= 4e-7 * np.abs(S_ref).max()
+    tol = 2.0 ** -8 if dtype_name == "bf16" else 4e-7
+    assert np.abs(dm.float().cpu().numpy() - m_ref).max() <= tol * np.abs(m_ref).max()
+    # second call continues from the updated state (in-place semantics)
+    for b in range(B):
+        orc.mixer_step(S_ref[b], u[b], lw["alpha"][:, pos + 1], lw["beta"][:, pos + 1], lw["lam"])
+    model.mixer_update(layer, pos + 1, B, du, dS, dm)
+    torch.cuda.synchronize()
+    assert np.abs(dS.cpu().numpy() - S_ref).max() <= 8e-7 * np.abs(S_ref).max()
+
+
+def test_error_codes_on_the_gpu(srm):
+    cfg = srm_synth.tiny_config(vocab=32, d_model=16, n_layers=1, n_heads=2, n_ctx=16)
+    model = srm.Model(cfg, srm_synth.make_weights(cfg))
+    B = 3
+    st = model.new_state(B)
+    ws = model.new_workspace(B)
+    tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    with pytest.raises(srm.SrmError) as e:
+        model.decode_step(B, 16, tok, st, tok, workspace=ws)          # pos == n_ctx
+    assert e.value.code == -1
+    with pytest.raises(srm.SrmError) as e:
+        model.decode_step(B, 0, tok, st, tok, workspace=ws[:64])      # workspace too small
+    assert e.value.code == -2
+    with pytest.raises(srm.SrmError):
+        model.prefill(torch.zeros((2, 17), dtype=torch.int32, device="cuda"), 1, model.new_state(2),
+                      torch.zeros(2, dtype=torch.int32, device="cuda"), workspace=model.new_workspace(64))
+    assert model.state_bytes(7) == cfg.n_layers * 7 * cfg.d_model * 4

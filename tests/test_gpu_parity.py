@@ -1,0 +1,240 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the five
+benchmark configurations, plus edge cases.
+
+Tolerances (relative to the largest |logit| of the row, as the benchmark
+definition states): fp32 configs 1e-4 and token-exact greedy; bf16-weight
+configs 2e-2 with the GPU teacher-forced on the oracle's tokens; parallel vs
+recurrent hidden states 1e-4.  The oracle build compared against is fp64.
+"""
+import numpy as np
+import pytest
+import torch
+
+import srm_synth
+from gpu_util import Generator, check_tokens, rel_err_rows, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def srm():
+    import paper_2605_08696_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def orc_mod():
+    from oracle import srm_oracle
+    srm_oracle.build()
+    return srm_oracle
+
+
+# ------------------------------------------------------------------ C1
+def test_c1_tiny_fp32_greedy_token_exact(srm, orc_mod):
+    cfg = srm_synth.CONFIGS["C1"]
+    w = srm_synth.make_weights(cfg)
+    prompts = srm_synth.make_prompts(cfg)
+    B, P, G = cfg.batch, cfg.prompt_len, cfg.gen_len
+    ref = orc_mod.Oracle(cfg, w, "f64").greedy(prompts, G, want_logits=True)
+    print("C1: oracle done", flush=True)
+    model = srm.Model(cfg, w)
+    gen = Generator(model, B, B * P)
+    logits = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    gen.prefill(to_dev(prompts), logits=logits)
+    toks, lgs = [gen.tok.cpu().numpy().copy()], [logits.cpu().numpy().copy()]
+    for g in range(1, G):
+        gen.step(P + g - 1, logits=logits)       # free running: feeds its own tokens back
+        toks.append(gen.tok.cpu().numpy().copy())
+        lgs.append(logits.cpu().numpy().copy())
+    toks, lgs = np.stack(toks, 1), np.stack(lgs, 1)
+    absmax = np.abs(ref["logits"]).max(axis=2)
+    ties = check_tokens(toks, ref["tokens"], ref["margin"], absmax)
+    assert ties == 0
+    err = rel_err_rows(lgs, ref["logits"])
+    print(f"C1: max relative logit error {err:.3e}", flush=True)
+    assert err <= 1e-4
+    # final state equals the oracle's (oracle layout [B][L][d], library [L][B][d])
+    st = gen.state.cpu().numpy().transpose(1, 0, 2)
+    # the oracle consumed P+G-1 tokens, the GPU likewise
+    assert np.abs(st - ref["state"]).max() <= 1e-4 * np.abs(ref["state"]).max()
+
+
+# ------------------------------------------------------------------ C2
+def test_c2_parallel_equals_recurrent(srm, orc_mod):
+    cfg = srm_synth.CONFIGS["C2"]
+    w = srm_synth.make_weights(cfg)
+    toks = srm_synth.make_prompts(cfg)           # [4][256]
+    B, T, V, d = toks.shape[0], toks.shape[1], cfg.vocab, cfg.d_model
+    orc = orc_mod.Oracle(cfg, w, "f64")
+    ref_p = orc.parallel_forward(toks)
+    ref_r = orc.recurrent_forward(toks)
+    print("C2: oracle done", flush=True)
+    assert rel_err_rows(ref_p["hidden"], ref_r["hidden"]) < 1e-10
+    model = srm.Model(cfg, w)
+    dtoks = to_dev(toks)
+    hid_p = torch.empty((B, T, d), dtype=torch.float32, device="cuda")
+    log_p = torch.empty((B, T, V), dtype=torch.float32, device="cuda")
+    ws = model.new_workspace(B * T)
+    model.parallel_forward(dtoks, hid_p, logits=log_p, workspace=ws)
+    # 256 decode steps, teacher forced
+    state = model.new_state(B)
+    hid_r = torch.empty((T, B, d), dtype=torch.float32, device="cuda")
+    log_r = torch.empty((T, B, V), dtype=torch.float32, device="cuda")
+    out_tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    tcol = dtoks.t().contiguous()
+    for t in range(T):
+        model.decode_step(B, t, tcol[t], state, out_tok, logits=log_r[t], hidden=hid_r[t], workspace=ws)
+    torch.cuda.synchronize()
+    hp, lp = hid_p.cpu().numpy(), log_p.cpu().numpy()
+    hr, lr = hid_r.cpu().numpy().transpose(1, 0, 2), log_r.cpu().numpy().transpose(1, 0, 2)
+    errs = {
+        "hidden par-vs-rec": rel_err_rows(hp, hr), "logits par-vs-rec": rel_err_rows(lp, lr),
+        "hidden par-vs-oracle": rel_err_rows(hp, ref_p["hidden"]),
+        "logits par-vs-oracle": rel_err_rows(lp, ref_p["logits"]),
+        "hidden rec-vs-oracle": rel_err_rows(hr, ref_r["hidden"]),
+        "logits rec-vs-oracle": rel_err_rows(lr, ref_r["logits"]),
+    }
+    print("C2:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    for k, v in errs.items():
+        assert v <= 1e-4, k
+    # causality on the GPU's parallel form: perturb position 100
+    pert = toks.copy(); pert[:, 100] = (pert[:, 100] + 1) % V
+    hid_q = torch.empty_like(hid_p)
+    model.parallel_forward(to_dev(pert), hid_q, workspace=ws)
+    hq = hid_q.cpu().numpy()
+    np.testing.assert_array_equal(hq[:, :100], hp[:, :100])
+    assert (np.abs(hq[:, 100:] - hp[:, 100:]).max(axis=2) > 0).all()
+
+
+# ------------------------------------------------------------------ C3 / C4 (bf16 weights)
+def _bf16_config_parity(srm, orc_mod, cfg, n_rows, n_gen, tol=2e-2):
+    """Full batch on the GPU; rows 0..n_rows-1 are also run by the oracle and the
+    GPU is teacher-forced on the oracle's tokens for those rows."""
+    w = srm_synth.make_weights(cfg)
+    prompts = srm_synth.make_prompts(cfg)
+    B, P, V = cfg.batch, cfg.prompt_len, cfg.vocab
+    ref = orc_mod.Oracle(cfg, w, "f64").greedy(prompts[:n_rows], n_gen, want_logits=True)
+    print(f"{cfg.name}: oracle done ({n_rows} rows x {P}+{n_gen})", flush=True)
+    model = srm.Model(cfg, w)
+    gen = Generator(model, B, min(B * P, 1 << 17))
+    logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    plog = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    gen.prefill(to_dev(prompts), logits=plog)
+    ref_tok = to_dev(ref["tokens"])
+    errs, agree, total = [], 0, 0
+    first = plog[:n_rows].cpu().numpy()
+    errs.append(rel_err_rows(first, ref["logits"][:, 0]))
+    agree += int((gen.tok[:n_rows].cpu().numpy() == ref["tokens"][:, 0]).sum()); total += n_rows
+    for g in range(1, n_gen):
+        gen.tok[:n_rows] = ref_tok[:, g - 1]                 # teacher forcing on the oracle's rows
+        gen.step(P + g - 1, logits=logits)
+        got = logits[:n_rows].cpu().numpy()
+        errs.append(rel_err_rows(got, ref["logits"][:, g]))
+        agree += int((gen.tok[:n_rows].cpu().numpy() == ref["tokens"][:, g]).sum()); total += n_rows
+    torch.cuda.synchronize()
+    print(f"{cfg.name}: max relative logit error {max(errs):.3e}; greedy agreement {agree}/{total}", flush=True)
+    assert max(errs) <= tol
+    assert agree >= 0.9 * total
+    # every row of the full batch produced a valid token and a finite state
+    tk = gen.tok.cpu().numpy()
+    assert ((tk >= 0) & (tk < V)).all()
+    assert torch.isfinite(gen.state).all()
+    return gen, model, prompts
+
+
+def test_c3_mid_bf16(srm, orc_mod):
+    cfg = srm_synth.CONFIGS["C3"]
+    _bf16_config_parity(srm, orc_mod, cfg, n_rows=8, n_gen=48)
+
+
+def test_c4_large_bf16(srm, orc_mod):
+    cfg = srm_synth.CONFIGS["C4"]
+    _bf16_config_parity(srm, orc_mod, cfg, n_rows=16, n_gen=12)
+
+
+# ------------------------------------------------------------------ C5 (fan-out)
+def test_c5_fanout_replicas_and_max_batch(srm, orc_mod):
+    cfg = srm_synth.CONFIGS["C5"]
+    w = srm_synth.make_weights(cfg)
+    prompts = srm_synth.make_prompts(cfg)                    # [256][128]
+    N, P, V, d, L = cfg.batch, cfg.prompt_len, cfg.vocab, cfg.d_model, cfg.n_layers
+    n_or, n_gen = 4, 3
+    ref = orc_mod.Oracle(cfg, w, "f64").greedy(prompts[:n_or], n_gen, want_logits=True)
+    print("C5: oracle done", flush=True)
+    model = srm.Model(cfg, w)
+    dprompts = to_dev(prompts)
+    for k in (64, 1024):
+        B = N * k
+        print(f"C5: fanout {k}, batch {B}", flush=True)
+        gen = Generator(model, B, N * P)
+        plog = torch.empty((N, V), dtype=torch.float32, device="cuda")
+        gen.prefill(dprompts, fanout=k, logits=plog)
+        assert rel_err_rows(plog[:n_or].cpu().numpy(), ref["logits"][:, 0]) <= 2e-2
+        toks = [gen.tok.view(N, k).cpu().numpy().copy()]
+        for g in range(1, n_gen):
+            gen.step(P + g - 1)
+            toks.append(gen.tok.view(N, k).cpu().numpy().copy())
+        torch.cuda.synchronize()
+        for t in toks:                                        # replicas of one prompt agree (greedy)
+            assert (t == t[:, :1]).all()
+        st = gen.state.view(L, N, k, d)
+        assert bool((st == st[:, :, :1]).all())
+        assert model.state_bytes(B) == L * B * d * 4          # 64 KiB per sequence
+        del gen, st
+        torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ semantics and edges
+@pytest.mark.parametrize("dtype_name", ["fp32", "bf16"])
+def test_prefill_equals_decode_steps(srm, dtype_name):
+    d = 64 if dtype_name == "bf16" else 32
+    cfg = srm_synth.tiny_config(vocab=96, d_model=d, n_layers=3, n_heads=4, n_ctx=40,
+                                weight_dtype=dtype_name, seed=41)
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    N, P = 5, 33
+    prompts = to_dev(srm_synth.make_prompts(cfg, batch=N, length=P))
+    ws = model.new_workspace(N * P)
+    st_a, tok_a = model.new_state(N), torch.empty(N, dtype=torch.int32, device="cuda")
+    lg_a = torch.empty((N, cfg.vocab), dtype=torch.float32, device="cuda")
+    model.prefill(prompts, 1, st_a, tok_a, logits=lg_a, workspace=ws)
+    # same thing with a workspace that only holds two prompts per pass
+    st_c, tok_c = model.new_state(N), torch.empty(N, dtype=torch.int32, device="cuda")
+    small = torch.empty(model.workspace_bytes(2 * P), dtype=torch.uint8, device="cuda")
+    model.prefill(prompts, 1, st_c, tok_c, workspace=small)
+    st_b, tok_b = model.new_state(N), torch.empty(N, dtype=torch.int32, device="cuda")
+    lg_b = torch.empty((N, cfg.vocab), dtype=torch.float32, device="cuda")
+    pc = prompts.t().contiguous()
+    for t in range(P):
+        model.decode_step(N, t, pc[t], st_b, tok_b, logits=lg_b, workspace=ws)
+    torch.cuda.synchronize()
+    tol = 2e-2 if dtype_name == "bf16" else 1e-5
+    assert (st_a - st_b).abs().max() <= tol * st_b.abs().max()
+    assert (lg_a - lg_b).abs().max() <= tol * lg_b.abs().max()
+    assert torch.equal(st_a, st_c) and torch.equal(tok_a, tok_c)
+    if dtype_name == "fp32":
+        assert torch.equal(tok_a, tok_b)
+
+
+@pytest.mark.parametrize("B", [1, 3, 67])
+def test_small_and_ragged_batches_match_oracle(srm, orc_mod, B):
+    cfg = srm_synth.tiny_config(vocab=200, d_model=48, n_layers=2, n_heads=6, n_ctx=12, seed=51)
+    w = srm_synth.make_weights(cfg, stress=True)
+    toks = srm_synth.make_prompts(cfg, batch=B, length=12)
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks, want_greedy=True)
+    model = srm.Model(cfg, w)
+    ws = model.new_workspace(B)
+    st = model.new_state(B)
+    out = torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    hd = torch.empty((B, cfg.d_model), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    for t in range(12):                                      # includes pos = n_ctx - 1
+        model.decode_step(B, t, tc[t], st, out, logits=lg, hidden=hd, workspace=ws)
+        assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, t]) <= 1e-4
+        assert rel_err_rows(hd.cpu().numpy(), ref["hidden"][:, t]) <= 1e-4
+    # single-token prompt through prefill
+    st1, t1 = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    model.prefill(to_dev(toks[:, :1]), 1, st1, t1, logits=lg, workspace=model.new_workspace(B))
+    assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, 0]) <= 1e-4
