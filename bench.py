@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the SRM recurrent decode path on one MI355X.
+
+A step is one pass of the whole hot path (embedding gather, L blocks of
+LayerNorm / in-projection / recurrent state update / out-projection /
+LayerNorm / MLP, final LayerNorm, LM head with fused argmax) over one batch:
+one new token for every sample.  Inputs (weights, prompts, prefilled state)
+are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4|C3|C1]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="C4", choices=["C1", "C3", "C4"])
+    ap.add_argument("--kernel-iters", type=int, default=20, help="launches per kernel leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-legs", action="store_true")
+    return ap.parse_args()
+
+
+def time_launches(torch, fn, iters, warm=3):
+    """Average duration (s) of fn() over `iters` back-to-back launches, timed with
+    events on the stream the kernels are launched on (torch's current stream)."""
+    for _ in range(warm):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / iters
+
+
+def kernel_legs(torch, srm, model, cfg, B, iters):
+    """Time each kernel of the step alone at the workload's shapes."""
+    d, ff, V, L = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.n_layers
+    bf = cfg.weight_dtype == "bf16"
+    dt = srm.SRM_BF16 if bf else srm.SRM_FP32
+    tt = torch.bfloat16 if bf else torch.float32
+    esz = 2 if bf else 4
+    g = torch.Generator(device="cuda").manual_seed(0)
+
+    def rnd(*shape, scale=1.0):
+        return (torch.randn(*shape, device="cuda", generator=g) * scale).to(tt)
+
+    legs = {}
+    a = rnd(B, d)
+    gact = rnd(B, ff)
+    shapes = {  # name: (A, N, K, epilogue, fp32 residual out?)
+        "gemm_in": (a, d, d, 0), "gemm_out": (a, d, d, 2),
+        "gemm_up": (a, ff, d, 1), "gemm_down": (gact, d, ff, 2),
+    }
+    for name, (A, N, K, epi) in shapes.items():
+        W = rnd(N, K, scale=0.02)
+        bias = torch.zeros(N, device="cuda")
+        out = torch.zeros((B, N), device="cuda", dtype=torch.float32 if epi == 2 else tt)
+        t = time_launches(torch, lambda: srm.linear(dt, epi, A, W, bias, out=out), iters)
+        fl = 2.0 * B * N * K
+        legs[name] = {"ms": t * 1e3, "tflops": fl / t * 1e-12, "M": B, "N": N, "K": K}
+        del W, out
+    W = rnd(V, d, scale=0.02)
+    am = torch.empty(B, dtype=torch.int32, device="cuda")
+    scratch = torch.empty(srm.linear_scratch_bytes(B, V), dtype=torch.uint8, device="cuda")
+    t = time_launches(torch, lambda: srm.linear(dt, 3, a, W, None, out=None, argmax=am, scratch=scratch), iters)
+    legs["gemm_head_argmax"] = {"ms": t * 1e3, "tflops": 2.0 * B * V * d / t * 1e-12, "M": B, "N": V, "K": d}
+    del W, scratch
+    # state update: cycle over the L layer slabs exactly as a step does
+    state = torch.zeros((L, B, d), dtype=torch.float32, device="cuda")
+    u = rnd(B, d)
+    m = torch.empty_like(u)
+    it = [0]
+
+    def su():
+        model.mixer_update(it[0] % L, 5, B, u, state[it[0] % L], m)
+        it[0] += 1
+
+    t = time_launches(torch, su, max(iters, 2 * L), warm=L)
+    nbytes = B * d * (8 + 2 * esz)
+    legs["state_update"] = {"ms": t * 1e3, "gbs": nbytes / t * 1e-9, "bytes": nbytes}
+    return legs
+
+
+def cpu_baseline(cfg, w, rows, T):
+    """The fp32 oracle, as it stands, on `rows` samples x T teacher-forced positions."""
+    import numpy as np
+    from oracle import srm_oracle
+    import srm_synth
+    orc = srm_oracle.Oracle(cfg, w, "f32")
+    toks = srm_synth.make_prompts(cfg, batch=rows, length=T, seed=99)
+    t0 = time.perf_counter()
+    orc.recurrent_forward(toks, pos0=cfg.prompt_len, want_hidden=False, want_logits=False, want_greedy=True)
+    dt = time.perf_counter() - t0
+    threads = min(rows, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+    return {"value": rows * T / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{rows} samples x {T} decode positions of {cfg.name} (fp32 build, OpenMP over samples), {dt:.1f} s"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (samples are independent; a multi-GPU run is "
+              "N copies of this one with the batch split); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2605_08696_amd as srm
+    import srm_synth
+
+    srm.lib()                                     # fails loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    cfg = srm_synth.CONFIGS[args.workload]
+    B, P = cfg.batch, cfg.prompt_len
+    t0 = time.perf_counter()
+    w = srm_synth.make_weights(cfg)
+    prompts = srm_synth.make_prompts(cfg)
+    model = srm.Model(cfg, w)
+    t_setup = time.perf_counter() - t0
+
+    state = model.new_state(B)
+    ws = model.new_workspace(max(B, min(B * P, 1 << 17)))
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    dprompts = torch.from_numpy(prompts).cuda()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    model.prefill(dprompts, 1, state, tok, workspace=ws)
+    e1.record()
+    e1.synchronize()
+    prefill_s = e0.elapsed_time(e1) * 1e-3
+
+    n_steps = args.warmup + args.steps
+    assert P + n_steps <= cfg.n_ctx, "steps + warmup exceed the model's positions"
+    pos = P
+    for _ in range(args.warmup):
+        model.decode_step(B, pos, tok, state, tok, workspace=ws)
+        pos += 1
+    torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        model.decode_step(B, pos, tok, state, tok, workspace=ws)
+        pos += 1
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_wall0
+    dev_s = e0.elapsed_time(e1) * 1e-3
+    step_s = max(wall, dev_s) / args.steps
+    tk = tok.cpu().numpy()
+    assert ((tk >= 0) & (tk < cfg.vocab)).all() and bool(torch.isfinite(state).all())
+
+    d, ff, V, L = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.n_layers
+    flops_step = B * (20.0 * L * d * d + 2.0 * V * d)
+    esz = 2 if cfg.weight_dtype == "bf16" else 4
+    bytes_step = (10.0 * L * d * d + V * d) * esz + 8.0 * B * L * d + B * d * esz
+    out = {
+        "metric": "generated tokens/sec on 1 MI355X at max batch",
+        "value": B / step_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": step_s * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: SRM d_model {d}, {L} layers, 4 mixed heads, MLP x4, vocab {V}, "
+                               f"{cfg.weight_dtype} weights / fp32 state, batch {B}, prompt {P}, greedy decode",
+                   "batch": B, "prompt_len": P, "state_bytes": model.state_bytes(B)},
+        "step": {"algorithmic_tflop": flops_step * 1e-12, "algorithmic_gb": bytes_step * 1e-9,
+                 "achieved_tflops": flops_step / step_s * 1e-12, "mfma_frac": flops_step / step_s * 1e-12 / PEAK_BF16_TFLOPS
+                 if esz == 2 else None,
+                 "device_ms_per_step": dev_s / args.steps * 1e3, "wall_ms_per_step": wall / args.steps * 1e3},
+        "prefill": {"seconds": prefill_s, "tokens_per_s": B * P / prefill_s},
+        "setup_seconds": t_setup,
+    }
+    if not args.no_kernel_legs:
+        legs = kernel_legs(torch, srm, model, cfg, B, args.kernel_iters)
+        out["kernels"] = legs
+        if esz == 2:
+            up = legs["gemm_up"]
+            out["roofline"] = {"kernel": "gemm_bf16_kernel (MLP up, GELU epilogue)", "bound": "mfma",
+                               "achieved": up["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                               "frac": up["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
+                               "avg_launch_ms": up["ms"], "flop_per_launch": 2.0 * B * ff * d}
+        else:
+            up = legs["gemm_up"]
+            out["roofline"] = {"kernel": "gemm_f32_kernel (MLP up)", "bound": "alu", "achieved": up["tflops"],
+                               "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": up["tflops"] / PEAK_FP32_TFLOPS,
+                               "traffic": None, "avg_launch_ms": up["ms"]}
+        su = legs["state_update"]
+        out["roofline_state_update"] = {"kernel": "state_update_kernel", "bound": "hbm", "achieved": su["gbs"],
+                                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": su["gbs"] / PEAK_HBM_GBS,
+                                        "traffic": None, "avg_launch_ms": su["ms"], "bytes_per_launch": su["bytes"]}
+    if not args.no_cpu_baseline:
+        rows = min(16, os.cpu_count() or 1)
+        T = {"C4": 12, "C3": 128, "C1": 240}[cfg.name]
+        out["cpu_baseline"] = cpu_baseline(cfg, w, rows, min(T, cfg.n_ctx - P))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
