@@ -3,9 +3,9 @@
 // MLP and the LM head.
 //
 //   gemm_bf16_kernel: bf16 operands on the gfx950 matrix cores
-//     (v_mfma_f32_32x32x16_bf16, fp32 accumulate), tiles staged through LDS
-//     with a 16-byte XOR swizzle, two LDS stages, global loads of tile k+1 in
-//     flight while tile k is multiplied.
+//     (v_mfma_f32_32x32x16_bf16, fp32 accumulate); tiles go global -> LDS with
+//     buffer_load ... lds into a 16-byte XOR-swizzled layout, two LDS stages,
+//     operands read from LDS two k-substeps ahead of the MFMAs that use them.
 //   gemm_f32_kernel: plain fp32 FMA tiles for the fp32 configurations.
 //
 // Epilogues are fused: bias, exact GELU, residual add into the fp32 stream,
@@ -63,17 +63,81 @@ __device__ __forceinline__ void epi_store(const GemmEpi &ep, int64_t row, int co
 }
 
 // ------------------------------------------------------------------ bf16 MFMA
+// Block tile BM x BN x 64 split over WM x WN waves, each wave holding a
+// (BM/WM) x (BN/WN) accumulator tile of 32x32x16 MFMAs.  Built to keep the matrix
+// pipe fed:
+//  (1) the MFMA operands of k-substep kk+1 are read from LDS before the MFMAs of
+//      kk issue (two register sets, order pinned with scheduling barriers);
+//  (2) tiles travel global -> LDS directly (buffer_load ... lds), two tiles ahead
+//      of the MFMAs, and the barrier sits one substep before the end of a tile
+//      (see the pipeline table in the kernel); writing the tiles with ds_write
+//      from registers instead cost ~30% of the main loop;
+//  (3) the product is formed transposed (W fragment as the first MFMA operand),
+//      so a lane holds four consecutive output columns of ONE row per register
+//      quad: the LM-head argmax reduces in-lane and needs a single cross-lane
+//      exchange, and the epilogue passes 32-row slices through a wave-private
+//      LDS stage with 16-byte writes and reads, so that global stores and the
+//      residual read-modify-write are 16-byte vectors over whole cache lines.
+// LDS chunk swizzle: 16-byte chunk c of row r sits at chunk c ^ ((r >> 1) & 7);
+// with 64 banks this makes both the tile writes and the fragment reads
+// conflict-free (measured: SQ_LDS_BANK_CONFLICT ~1% of SQ_LDS_IDX_ACTIVE).
+__device__ __forceinline__ int swz_of_row(int r) { return (r >> 1) & 7; }
+
+// erfc-based GELU for bf16 outputs: Phi(x) from the rational approximation
+// 7.1.26 of Abramowitz & Stegun (|error| of erf <= 1.5e-7), evaluated without
+// cancellation in the negative tail.  The result is rounded to bf16 (relative
+// 2^-9) right after, so the approximation error is invisible there.
+__device__ __forceinline__ float gelu_bf16out(float x)
+{
+    const float z = fabsf(x) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+    float p = fmaf(t, 1.061405429f, -1.453152027f);
+    p = fmaf(t, p, 1.421413741f);
+    p = fmaf(t, p, -0.284496736f);
+    p = fmaf(t, p, 0.254829592f);
+    const float q = 0.5f * t * p * __builtin_amdgcn_exp2f(-z * z * 1.44269504088896340736f);   // erfc(z)/2
+    return x * (x >= 0.0f ? 1.0f - q : q);
+}
+
+template <int EPI, typename TAct>
+__device__ __forceinline__ void epi_store4(const GemmEpi &ep, int64_t row, int col, float4 v)
+{
+    if constexpr (EPI == EPI_STORE) {
+        store4(reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + col, v);
+    } else if constexpr (EPI == EPI_GELU) {
+        store4(reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + col,
+               make_float4(gelu_bf16out(v.x), gelu_bf16out(v.y), gelu_bf16out(v.z), gelu_bf16out(v.w)));
+    } else if constexpr (EPI == EPI_RESID) {
+        float *p = reinterpret_cast<float *>(ep.out) + row * ep.ldo + col;
+        const float4 o = load4(p);
+        store4(p, make_float4(o.x + v.x, o.y + v.y, o.z + v.z, o.w + v.w));
+    } else if constexpr (EPI == EPI_F32) {
+        store4(reinterpret_cast<float *>(ep.out) + row * ep.ldo + col, v);
+    } else {
+        if (ep.out) store4(reinterpret_cast<float *>(ep.out) + row * ep.ldo + col, v);
+    }
+}
+
+template <int EPI, typename TAct>
+__device__ __forceinline__ void epi_store1p(const GemmEpi &ep, int64_t row, int col, float v)
+{
+    if constexpr (EPI == EPI_GELU) store1(reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + col, gelu_bf16out(v));
+    else epi_store<EPI, TAct>(ep, row, col, v);
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, typename TAct>
 __global__ void __launch_bounds__(WM *WN * 64)
 gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, int N, int K, GemmEpi ep)
 {
     constexpr int BK = 64;
-    constexpr int NTHR = WM * WN * 64;
+    constexpr int NW = WM * WN, NTHR = NW * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int A_IT = BM * BK / 8 / NTHR, B_IT = BN * BK / 8 / NTHR;
+    constexpr int STG = WTN + 4;                     // stage row stride in floats: 16 B * odd
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
     static_assert((BM * BK / 8) % NTHR == 0 && (BN * BK / 8) % NTHR == 0, "tile/threads mismatch");
+    static_assert(NW * 32 * STG * 4 + BM * WN * 8 <= 2 * (BM + BN) * BK * 2, "epilogue stage exceeds the tile LDS");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
     bf16 *As = reinterpret_cast<bf16 *>(smem_raw);   // [2][BM*BK]
@@ -89,37 +153,31 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     const int wm = wave / WN, wn = wave % WN;
     const int lr = lane & 31, lk = lane >> 5;
 
-    // global -> LDS assignment: 16-byte chunks, 8 consecutive threads cover one
-    // 128-byte row segment.  Rows past the edge are clamped (never stored).
-    const bf16 *a_src[A_IT];
-    const bf16 *b_src[B_IT];
-    int a_dst[A_IT], b_dst[B_IT];
-#pragma unroll
-    for (int i = 0; i < A_IT; ++i) {
-        const int q = i * NTHR + tid, r = q >> 3, c = q & 7;
-        const int gr = min(m0 + r, M - 1);
-        a_src[i] = A + (size_t)gr * K + c * 8;
-        a_dst[i] = r * BK + ((c ^ ((r >> 1) & 7)) << 3);
-    }
-#pragma unroll
-    for (int i = 0; i < B_IT; ++i) {
-        const int q = i * NTHR + tid, r = q >> 3, c = q & 7;
-        const int gr = min(n0 + r, N - 1);
-        b_src[i] = W + (size_t)gr * K + c * 8;
-        b_dst[i] = r * BK + ((c ^ ((r >> 1) & 7)) << 3);
-    }
-
-    u32x4_t ra[A_IT], rb[B_IT];
-#define SRM_LOAD_GLOBAL(k0)                                                                      \
+    // global -> LDS: buffer loads that write LDS directly (no VGPR staging, no
+    // ds_write).  One wave instruction moves 8 rows x 128 bytes; the hardware puts
+    // lane l's 16 bytes at M0-base + 16*l, so lane (r = l>>3, slot = l&7) fetches the
+    // global chunk slot ^ swz(r) of its row, which lands the row swizzled in LDS.
+    // The descriptors cover exactly this block's rows of A and W: rows past M or
+    // N and k past K arrive as zeros (hardware range check).
+    constexpr int ROWS_PER_IT = NTHR / 8;            // multiple of 16: the swizzle term repeats
+    const int ld_r = tid >> 3, ld_c = tid & 7;
+    const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16 *>(A + (size_t)m0 * K), 0, min(BM, M - m0) * K * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16 *>(W + (size_t)n0 * K), 0, min(BN, N - n0) * K * 2, 0x00020000);
+    const int ld_voff = (ld_r * K + ((ld_c ^ swz_of_row(ld_r)) << 3)) * 2;       // bytes
+    typedef __attribute__((address_space(3))) void lds_void;
+#define SRM_DMA_TILE(k0, buf)                                                                    \
     _Pragma("unroll") for (int i = 0; i < A_IT; ++i)                                             \
-        ra[i] = *reinterpret_cast<const u32x4_t *>(a_src[i] + (k0));                             \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
+            rs_a, (lds_void *)(As + (buf) * BM * BK + (i * ROWS_PER_IT + wave * 8) * BK), 16,    \
+            ld_voff, (i * ROWS_PER_IT * K + (k0)) * 2, 0, 0);                                    \
     _Pragma("unroll") for (int i = 0; i < B_IT; ++i)                                             \
-        rb[i] = *reinterpret_cast<const u32x4_t *>(b_src[i] + (k0));
-#define SRM_STORE_LDS(buf)                                                                       \
-    _Pragma("unroll") for (int i = 0; i < A_IT; ++i)                                             \
-        *reinterpret_cast<u32x4_t *>(As + (buf) * BM * BK + a_dst[i]) = ra[i];                   \
-    _Pragma("unroll") for (int i = 0; i < B_IT; ++i)                                             \
-        *reinterpret_cast<u32x4_t *>(Bs + (buf) * BN * BK + b_dst[i]) = rb[i];
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
+            rs_w, (lds_void *)(Bs + (buf) * BN * BK + (i * ROWS_PER_IT + wave * 8) * BK), 16,    \
+            ld_voff, (i * ROWS_PER_IT * K + (k0)) * 2, 0, 0);
+    // s_waitcnt immediate: vmcnt = n, expcnt and lgkmcnt unconstrained
+#define SRM_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -129,95 +187,173 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // operand fetch offsets (row within the wave tile is lr; swizzle uses row>>1)
-    const int sw = (lr >> 1) & 7;
+    const int sw = swz_of_row(lr);                   // wave-tile rows are multiples of 32 apart
     const int a_row_off = (wm * WTM + lr) * BK;
     const int b_row_off = (wn * WTN + lr) * BK;
+    bf16x8_t fa[4][TM], fb[4][TN];                   // one operand set per k-substep
+#define SRM_READ_FRAGS(buf, kk, set)                                                             \
+    {                                                                                            \
+        const int ch_ = ((((kk) * 2 + lk) ^ sw) << 3);                                           \
+        const bf16 *as_ = As + (buf) * BM * BK + a_row_off + ch_;                                \
+        const bf16 *bs_ = Bs + (buf) * BN * BK + b_row_off + ch_;                                \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+            fa[set][i] = *reinterpret_cast<const bf16x8_t *>(as_ + i * 32 * BK);                 \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
+            fb[set][j] = *reinterpret_cast<const bf16x8_t *>(bs_ + j * 32 * BK);                 \
+    }
 
+#define SRM_MFMA_STEP(set)                                                                       \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                               \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) /* transposed: MFMA rows run over N */    \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+    // Issue order inside one k-substep: one LDS read (and, in substep 1, one LDS
+    // write and one global load) behind each MFMA, so that memory instructions
+    // issue while the matrix pipe works instead of in a burst in front of it.
+#define SRM_INTERLEAVE(n_vmem)                                                                   \
+    _Pragma("unroll") for (int q = 0; q < TM * TN; ++q) {                                        \
+        constexpr int S_ = TM * TN;                                                              \
+        constexpr int R_ = (TM + TN + S_ - 1) / S_, V_ = ((n_vmem) + S_ - 1) / S_;               \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                       \
+        if (q * R_ < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, R_, 0);                \
+        if (q * V_ < (n_vmem)) __builtin_amdgcn_sched_group_barrier(0x020, V_, 0);               \
+    }                                                                                            \
+    __builtin_amdgcn_sched_barrier(0);
+
+    // Software pipeline over K tiles (four k-substeps of 16 each), two LDS
+    // buffers, MFMA operands read two substeps ahead (four register sets):
+    //   substep 0: read operands of substep 2                  | MFMAs of substep 0
+    //   substep 1: read operands of substep 3                  | MFMAs of substep 1
+    //              wait for tile kt+1's loads, barrier: buffer `cur` is now free
+    //   substep 2: read substep-0 operands of tile kt+1,       | MFMAs of substep 2
+    //              start tile kt+2's loads into `cur`
+    //   substep 3: read substep-1 operands of tile kt+1        | MFMAs of substep 3
+    // A tile's loads have a full tile period to land and every operand read has
+    // two substeps, which absorbs the queueing of reads behind the tile writes in
+    // the LDS pipe.  Loads for tiles past the end are issued like any other
+    // (range check: zeros nobody reads), which keeps the loop branch-free.
     const int KT = K / BK;
-    SRM_LOAD_GLOBAL(0)
-    SRM_STORE_LDS(0)
+    SRM_DMA_TILE(0, 0)
+    SRM_DMA_TILE(BK, 1)
+    SRM_WAIT_VM(A_IT + B_IT);
     __syncthreads();
+    SRM_READ_FRAGS(0, 0, 0)
+    SRM_READ_FRAGS(0, 1, 1)
+    __builtin_amdgcn_sched_barrier(0);
 
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < KT) { SRM_LOAD_GLOBAL((kt + 1) * BK) }
-        const bf16 *as = As + cur * BM * BK + a_row_off;
-        const bf16 *bs = Bs + cur * BN * BK + b_row_off;
+        SRM_READ_FRAGS(cur, 2, 2)
+        SRM_MFMA_STEP(0)
+        SRM_INTERLEAVE(0)
+        SRM_READ_FRAGS(cur, 3, 3)
+        SRM_MFMA_STEP(1)
+        SRM_INTERLEAVE(0)
+        SRM_WAIT_VM(0);
+        __syncthreads();
+        SRM_READ_FRAGS(cur ^ 1, 0, 0)
+        SRM_DMA_TILE((kt + 2) * BK, cur)
+        SRM_MFMA_STEP(2)
+        SRM_INTERLEAVE(A_IT + B_IT)
+        SRM_READ_FRAGS(cur ^ 1, 1, 1)
+        SRM_MFMA_STEP(3)
+        SRM_INTERLEAVE(0)
+    }
+    SRM_WAIT_VM(0);
+    __syncthreads();                                  // LDS is reused by the epilogue
+#undef SRM_MFMA_STEP
+#undef SRM_INTERLEAVE
+#undef SRM_DMA_TILE
+#undef SRM_WAIT_VM
+#undef SRM_READ_FRAGS
+
+    // ---- epilogue.  Accumulator register r of lane (lk, lr) of tile (i, j) is
+    // output row i*32 + lr, column j*32 + 8*(r/4) + 4*lk + r%4 of the wave tile.
+    float *stage = reinterpret_cast<float *>(smem_raw) + wave * 32 * STG;        // wave-private [32][STG]
+    float *red_val = reinterpret_cast<float *>(smem_raw) + NW * 32 * STG;        // [BM][WN]
+    int *red_idx = reinterpret_cast<int *>(red_val + BM * WN);                   // [BM][WN]
+    const bool vec_ok = (N & 3) == 0;
+    constexpr int LPR = WTN / 4;                      // lanes per staged row
+    constexpr int RPI = 64 / LPR;                     // rows per read instruction
+    const int s_row = lane / LPR, s_col = (lane % LPR) * 4;
+    const int wcol0 = n0 + wn * WTN;                  // first column of this wave's tile
+    const int gcol = wcol0 + s_col;
+    float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ep.bias) {
+        if (vec_ok && gcol + 3 < N) bias4 = load4(ep.bias + gcol);
+        else {
+            bias4.x = gcol < N ? ep.bias[gcol] : 0.f;
+            bias4.y = gcol + 1 < N ? ep.bias[gcol + 1] : 0.f;
+            bias4.z = gcol + 2 < N ? ep.bias[gcol + 2] : 0.f;
+            bias4.w = gcol + 3 < N ? ep.bias[gcol + 3] : 0.f;
+        }
+    }
+    const bool want_store = EPI != EPI_ARGMAX || ep.out != nullptr;
+    const bool n_edge = wcol0 + WTN > N;              // wave-uniform
+
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int ch = ((kk * 2 + lk) ^ sw) << 3;
-            bf16x8_t af[TM], bf[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8_t *>(as + i * 32 * BK + ch);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bf[j] = *reinterpret_cast<const bf16x8_t *>(bs + j * 32 * BK + ch);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+        if constexpr (EPI == EPI_ARGMAX) {
+            // in-lane over this lane's TN*16 columns in ascending order (strict >
+            // keeps the lowest index), then one exchange with the lane holding
+            // the other half of the row's columns
+            float bv = -INFINITY;
+            int brel = 0;
+            if (!n_edge && !ep.bias) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < KT) { SRM_STORE_LDS(cur ^ 1) }
-        __syncthreads();
-    }
-
-#undef SRM_LOAD_GLOBAL
-#undef SRM_STORE_LDS
-
-    // ---- epilogue.  Accumulator register r of lane (lk, lr) is element
-    // (row 8*(r/4) + 4*lk + r%4, column lr) of its 32x32 tile.
-    float bias_v[TN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * WTN + j * 32 + lr;
-        bias_v[j] = (ep.bias && col < N) ? ep.bias[col] : 0.0f;
-    }
-
-    if constexpr (EPI != EPI_ARGMAX) {
+                    for (int r = 0; r < 16; ++r) {
+                        const float v = acc[i][j][r];
+                        if (v > bv) { bv = v; brel = j * 32 + 8 * (r >> 2) + (r & 3); }
+                    }
+            } else {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-                if (row >= M) continue;
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int col = n0 + wn * WTN + j * 32 + lr;
-                    if (col < N) epi_store<EPI, TAct>(ep, row, col, acc[i][j][r] + bias_v[j]);
-                }
+                    for (int r = 0; r < 16; ++r) {
+                        const int rel = j * 32 + 8 * (r >> 2) + (r & 3);
+                        const int col = wcol0 + 4 * lk + rel;
+                        const float v = acc[i][j][r] + ((ep.bias && col < N) ? ep.bias[col] : 0.0f);
+                        if (col < N && v > bv) { bv = v; brel = rel; }
+                    }
             }
-    } else {
-        // LM head: optional logits store plus per-row (max, index) over this
-        // block's BN columns.  In-lane over the TN column tiles, across the 32
-        // lanes that share a row, then across the WN waves through LDS.
-        float *red_val = reinterpret_cast<float *>(smem_raw);               // [BM][WN]
-        int *red_idx = reinterpret_cast<int *>(smem_raw + BM * WN * 4);     // [BM][WN]
+            int bi = bv == -INFINITY ? 0x7fffffff : wcol0 + 4 * lk + brel;
+            const float ov = __shfl_xor(bv, 32, kWave);
+            const int oi = __shfl_xor(bi, 32, kWave);
+            if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            if (lk == 0) {
+                const int lrow = wm * WTM + i * 32 + lr;
+                red_val[lrow * WN + wn] = bv;
+                red_idx[lrow * WN + wn] = bi;
+            }
+        }
+        if (want_store) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lrow = wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-                const int row = m0 + lrow;
-                float bv = -INFINITY;
-                int bi = 0x7fffffff;
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4 *>(stage + lr * STG + j * 32 + 8 * g + 4 * lk) =
+                        make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int col = n0 + wn * WTN + j * 32 + lr;
-                    const float v = acc[i][j][r] + bias_v[j];
-                    if (col < N) {
-                        if (row < M) epi_store<EPI, TAct>(ep, row, col, v);
-                        if (arg_better(v, col, bv, bi)) { bv = v; bi = col; }
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int lrow = it * RPI + s_row;
+                const int64_t row = m0 + wm * WTM + i * 32 + lrow;
+                float4 v = *reinterpret_cast<const float4 *>(stage + lrow * STG + s_col);
+                v.x += bias4.x; v.y += bias4.y; v.z += bias4.z; v.w += bias4.w;
+                if (row < M) {
+                    if (vec_ok && gcol + 3 < N) {
+                        epi_store4<EPI, TAct>(ep, row, gcol, v);
+                    } else {
+                        if (gcol < N) epi_store1p<EPI, TAct>(ep, row, gcol, v.x);
+                        if (gcol + 1 < N) epi_store1p<EPI, TAct>(ep, row, gcol + 1, v.y);
+                        if (gcol + 2 < N) epi_store1p<EPI, TAct>(ep, row, gcol + 2, v.z);
+                        if (gcol + 3 < N) epi_store1p<EPI, TAct>(ep, row, gcol + 3, v.w);
                     }
                 }
-#pragma unroll
-                for (int off = 16; off >= 1; off >>= 1) {
-                    const float ov = __shfl_xor(bv, off, kWave);
-                    const int oi = __shfl_xor(bi, off, kWave);
-                    if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-                }
-                if (lr == 0) { red_val[lrow * WN + wn] = bv; red_idx[lrow * WN + wn] = bi; }
             }
+        }
+    }
+    if constexpr (EPI == EPI_ARGMAX) {
         __syncthreads();
         for (int lrow = tid; lrow < BM; lrow += NTHR) {
             const int row = m0 + lrow;

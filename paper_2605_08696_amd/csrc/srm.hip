@@ -246,8 +246,7 @@ extern "C" size_t srm_workspace_bytes(const srm_model *m, int64_t rows)
 
 // ------------------------------------------------------------------ launchers
 template <int BM, int BN, int WM, int WN, int EPI, typename TAct>
-static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, const GemmEpi &ep,
-                            hipStream_t st)
+static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, const GemmEpi &ep, hipStream_t st)
 {
     constexpr size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(bf16);
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI, TAct>;
@@ -263,9 +262,11 @@ static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, c
     return SRM_OK;
 }
 
-// Tile choice for the bf16 GEMM: 0 = 256x256, 1 = 128x128, 2 = 64x64.  The big
-// tile needs enough blocks to fill 256 CUs; min_bn > 64 rules out the small one
+// Tile codes of the bf16 GEMM: 0 = 256x256 (8 waves), 1 = 128x128 (4 waves),
+// 2 = 64x64 (4 waves), 3 = 128x128 (8 waves), 4 = 256x128 (8 waves).  The big
+// tile needs enough blocks to fill 256 CUs; min_bn > 64 rules out the 64-wide one
 // (the LM head's partial buffers are sized for column tiles >= 128).
+constexpr int kNumTiles = 5;
 static int choose_tile(int64_t M, int N, int min_bn)
 {
     int tile;
@@ -275,7 +276,7 @@ static int choose_tile(int64_t M, int N, int min_bn)
     if (tile == 2 && min_bn > 64) tile = 1;
     return tile;
 }
-static int tile_bn(int tile) { return tile == 0 ? 256 : tile == 1 ? 128 : 64; }
+static int tile_bn(int tile) { return tile == 0 ? 256 : tile == 2 ? 64 : 128; }
 
 static thread_local int g_force_tile = -1;   // test/bench hook of srm_linear only
 
@@ -285,13 +286,18 @@ static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, Ge
 {
     if (K % 64) return fail(SRM_EINVAL, "bf16 GEMM needs K %% 64 == 0 (K = %d)", K);
     if (M <= 0 || M >= (1 << 30) || N <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
+    if ((int64_t)K * 256 * 2 >= (1LL << 31)) return fail(SRM_EINVAL, "bf16 GEMM: K = %d too large", K);
     const int tile = g_force_tile >= 0 ? g_force_tile : choose_tile(M, N, min_bn);
     ep.nparts = (int)cdiv(N, tile_bn(tile));
     if (nparts_out) *nparts_out = ep.nparts;
+    const int m = (int)M;
     switch (tile) {
-    case 0: return launch_bf16_tile<256, 256, 2, 2, EPI, TAct>(A, W, (int)M, N, K, ep, st);
-    case 1: return launch_bf16_tile<128, 128, 2, 2, EPI, TAct>(A, W, (int)M, N, K, ep, st);
-    default: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct>(A, W, (int)M, N, K, ep, st);
+    case 0: return launch_bf16_tile<256, 256, 2, 4, EPI, TAct>(A, W, m, N, K, ep, st);
+    case 1: return launch_bf16_tile<128, 128, 2, 2, EPI, TAct>(A, W, m, N, K, ep, st);
+    case 2: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct>(A, W, m, N, K, ep, st);
+    case 3: return launch_bf16_tile<128, 128, 2, 4, EPI, TAct>(A, W, m, N, K, ep, st);
+    case 4: return launch_bf16_tile<256, 128, 4, 2, EPI, TAct>(A, W, m, N, K, ep, st);
+    default: return fail(SRM_EINVAL, "unknown GEMM tile code %d", tile);
     }
 }
 
@@ -626,7 +632,7 @@ extern "C" int srm_linear(int32_t dtype, int32_t epilogue, const void *d_A, cons
     if (epilogue >= 100) {
         forced = epilogue / 100 - 1;
         epilogue %= 100;
-        if (forced > 2 || dtype != SRM_BF16) return fail(SRM_EINVAL, "srm_linear: unknown tile code");
+        if (forced >= kNumTiles || dtype != SRM_BF16) return fail(SRM_EINVAL, "srm_linear: unknown tile code");
     }
     if (epilogue == 3 ? (!d_argmax || !d_scratch) : !d_out) return fail(SRM_EINVAL, "srm_linear: null output");
     if (M <= 0 || N <= 0 || K <= 0) return fail(SRM_EINVAL, "srm_linear: sizes must be positive");

@@ -66,7 +66,7 @@ def _linear_case(srm, dtype, M, N, K, epi, tile, seed):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
 def test_linear_bf16_tiles_and_epilogues(srm, tile, epi):
     # several tiles in both directions plus ragged edges in M and N
