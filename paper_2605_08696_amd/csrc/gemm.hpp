@@ -125,6 +125,126 @@ __device__ __forceinline__ void epi_store1p(const GemmEpi &ep, int64_t row, int 
     else epi_store<EPI, TAct>(ep, row, col, v);
 }
 
+// Epilogue shared by the bf16 kernels.  Accumulator register r of lane (lk, lr)
+// of tile (i, j) is output row i*32 + lr, column j*32 + 8*(r/4) + 4*lk + r%4 of
+// the wave tile.  smem_raw: the block's LDS, free for reuse (all tile reads and
+// loads have completed and a barrier has been passed); lds_bytes its size.
+template <int BM, int BN, int WM, int WN, int EPI, typename TAct>
+__device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN / WN / 32], unsigned char *smem_raw,
+                                              const GemmEpi &ep, int M, int N, int m0, int n0, int bn)
+{
+    constexpr int NW = WM * WN, NTHR = NW * 64;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int STG = WTN + 4;                     // stage row stride in floats: 16 B * odd
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int lr = lane & 31, lk = lane >> 5;
+    float *stage = reinterpret_cast<float *>(smem_raw) + wave * 32 * STG;        // wave-private [32][STG]
+    float *red_val = reinterpret_cast<float *>(smem_raw) + NW * 32 * STG;        // [BM][WN]
+    int *red_idx = reinterpret_cast<int *>(red_val + BM * WN);                   // [BM][WN]
+    const bool vec_ok = (N & 3) == 0;
+    constexpr int LPR = WTN / 4;                      // lanes per staged row
+    constexpr int RPI = 64 / LPR;                     // rows per read instruction
+    const int s_row = lane / LPR, s_col = (lane % LPR) * 4;
+    const int wcol0 = n0 + wn * WTN;                  // first column of this wave's tile
+    const int gcol = wcol0 + s_col;
+    float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ep.bias) {
+        if (vec_ok && gcol + 3 < N) bias4 = load4(ep.bias + gcol);
+        else {
+            bias4.x = gcol < N ? ep.bias[gcol] : 0.f;
+            bias4.y = gcol + 1 < N ? ep.bias[gcol + 1] : 0.f;
+            bias4.z = gcol + 2 < N ? ep.bias[gcol + 2] : 0.f;
+            bias4.w = gcol + 3 < N ? ep.bias[gcol + 3] : 0.f;
+        }
+    }
+    const bool want_store = EPI != EPI_ARGMAX || ep.out != nullptr;
+    const bool n_edge = wcol0 + WTN > N;              // wave-uniform
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        if constexpr (EPI == EPI_ARGMAX) {
+            // in-lane over this lane's TN*16 columns in ascending order (strict >
+            // keeps the lowest index), then one exchange with the lane holding
+            // the other half of the row's columns
+            float bv = -INFINITY;
+            int brel = 0;
+            if (!n_edge && !ep.bias) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float v = acc[i][j][r];
+                        if (v > bv) { bv = v; brel = j * 32 + 8 * (r >> 2) + (r & 3); }
+                    }
+            } else {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int rel = j * 32 + 8 * (r >> 2) + (r & 3);
+                        const int col = wcol0 + 4 * lk + rel;
+                        const float v = acc[i][j][r] + ((ep.bias && col < N) ? ep.bias[col] : 0.0f);
+                        if (col < N && v > bv) { bv = v; brel = rel; }
+                    }
+            }
+            int bi = bv == -INFINITY ? 0x7fffffff : wcol0 + 4 * lk + brel;
+            const float ov = __shfl_xor(bv, 32, kWave);
+            const int oi = __shfl_xor(bi, 32, kWave);
+            if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            if (lk == 0) {
+                const int lrow = wm * WTM + i * 32 + lr;
+                red_val[lrow * WN + wn] = bv;
+                red_idx[lrow * WN + wn] = bi;
+            }
+        }
+        if (want_store) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4 *>(stage + lr * STG + j * 32 + 8 * g + 4 * lk) =
+                        make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+#pragma unroll
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int lrow = it * RPI + s_row;
+                const int64_t row = m0 + wm * WTM + i * 32 + lrow;
+                float4 v = *reinterpret_cast<const float4 *>(stage + lrow * STG + s_col);
+                v.x += bias4.x; v.y += bias4.y; v.z += bias4.z; v.w += bias4.w;
+                if (row < M) {
+                    if (vec_ok && gcol + 3 < N) {
+                        epi_store4<EPI, TAct>(ep, row, gcol, v);
+                    } else {
+                        if (gcol < N) epi_store1p<EPI, TAct>(ep, row, gcol, v.x);
+                        if (gcol + 1 < N) epi_store1p<EPI, TAct>(ep, row, gcol + 1, v.y);
+                        if (gcol + 2 < N) epi_store1p<EPI, TAct>(ep, row, gcol + 2, v.z);
+                        if (gcol + 3 < N) epi_store1p<EPI, TAct>(ep, row, gcol + 3, v.w);
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (EPI == EPI_ARGMAX) {
+        __syncthreads();
+        for (int lrow = tid; lrow < BM; lrow += NTHR) {
+            const int row = m0 + lrow;
+            if (row >= M) continue;
+            float bv = red_val[lrow * WN];
+            int bi = red_idx[lrow * WN];
+#pragma unroll
+            for (int w = 1; w < WN; ++w) {
+                const float ov = red_val[lrow * WN + w];
+                const int oi = red_idx[lrow * WN + w];
+                if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            }
+            ep.part_val[(int64_t)row * ep.nparts + bn] = bv;
+            ep.part_idx[(int64_t)row * ep.nparts + bn] = bi;
+        }
+    }
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, typename TAct>
 __global__ void __launch_bounds__(WM *WN * 64)
 gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, int N, int K, GemmEpi ep)
@@ -266,110 +386,7 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
 #undef SRM_WAIT_VM
 #undef SRM_READ_FRAGS
 
-    // ---- epilogue.  Accumulator register r of lane (lk, lr) of tile (i, j) is
-    // output row i*32 + lr, column j*32 + 8*(r/4) + 4*lk + r%4 of the wave tile.
-    float *stage = reinterpret_cast<float *>(smem_raw) + wave * 32 * STG;        // wave-private [32][STG]
-    float *red_val = reinterpret_cast<float *>(smem_raw) + NW * 32 * STG;        // [BM][WN]
-    int *red_idx = reinterpret_cast<int *>(red_val + BM * WN);                   // [BM][WN]
-    const bool vec_ok = (N & 3) == 0;
-    constexpr int LPR = WTN / 4;                      // lanes per staged row
-    constexpr int RPI = 64 / LPR;                     // rows per read instruction
-    const int s_row = lane / LPR, s_col = (lane % LPR) * 4;
-    const int wcol0 = n0 + wn * WTN;                  // first column of this wave's tile
-    const int gcol = wcol0 + s_col;
-    float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (ep.bias) {
-        if (vec_ok && gcol + 3 < N) bias4 = load4(ep.bias + gcol);
-        else {
-            bias4.x = gcol < N ? ep.bias[gcol] : 0.f;
-            bias4.y = gcol + 1 < N ? ep.bias[gcol + 1] : 0.f;
-            bias4.z = gcol + 2 < N ? ep.bias[gcol + 2] : 0.f;
-            bias4.w = gcol + 3 < N ? ep.bias[gcol + 3] : 0.f;
-        }
-    }
-    const bool want_store = EPI != EPI_ARGMAX || ep.out != nullptr;
-    const bool n_edge = wcol0 + WTN > N;              // wave-uniform
-
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        if constexpr (EPI == EPI_ARGMAX) {
-            // in-lane over this lane's TN*16 columns in ascending order (strict >
-            // keeps the lowest index), then one exchange with the lane holding
-            // the other half of the row's columns
-            float bv = -INFINITY;
-            int brel = 0;
-            if (!n_edge && !ep.bias) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float v = acc[i][j][r];
-                        if (v > bv) { bv = v; brel = j * 32 + 8 * (r >> 2) + (r & 3); }
-                    }
-            } else {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int rel = j * 32 + 8 * (r >> 2) + (r & 3);
-                        const int col = wcol0 + 4 * lk + rel;
-                        const float v = acc[i][j][r] + ((ep.bias && col < N) ? ep.bias[col] : 0.0f);
-                        if (col < N && v > bv) { bv = v; brel = rel; }
-                    }
-            }
-            int bi = bv == -INFINITY ? 0x7fffffff : wcol0 + 4 * lk + brel;
-            const float ov = __shfl_xor(bv, 32, kWave);
-            const int oi = __shfl_xor(bi, 32, kWave);
-            if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-            if (lk == 0) {
-                const int lrow = wm * WTM + i * 32 + lr;
-                red_val[lrow * WN + wn] = bv;
-                red_idx[lrow * WN + wn] = bi;
-            }
-        }
-        if (want_store) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    *reinterpret_cast<float4 *>(stage + lr * STG + j * 32 + 8 * g + 4 * lk) =
-                        make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-#pragma unroll
-            for (int it = 0; it < 32 / RPI; ++it) {
-                const int lrow = it * RPI + s_row;
-                const int64_t row = m0 + wm * WTM + i * 32 + lrow;
-                float4 v = *reinterpret_cast<const float4 *>(stage + lrow * STG + s_col);
-                v.x += bias4.x; v.y += bias4.y; v.z += bias4.z; v.w += bias4.w;
-                if (row < M) {
-                    if (vec_ok && gcol + 3 < N) {
-                        epi_store4<EPI, TAct>(ep, row, gcol, v);
-                    } else {
-                        if (gcol < N) epi_store1p<EPI, TAct>(ep, row, gcol, v.x);
-                        if (gcol + 1 < N) epi_store1p<EPI, TAct>(ep, row, gcol + 1, v.y);
-                        if (gcol + 2 < N) epi_store1p<EPI, TAct>(ep, row, gcol + 2, v.z);
-                        if (gcol + 3 < N) epi_store1p<EPI, TAct>(ep, row, gcol + 3, v.w);
-                    }
-                }
-            }
-        }
-    }
-    if constexpr (EPI == EPI_ARGMAX) {
-        __syncthreads();
-        for (int lrow = tid; lrow < BM; lrow += NTHR) {
-            const int row = m0 + lrow;
-            if (row >= M) continue;
-            float bv = red_val[lrow * WN];
-            int bi = red_idx[lrow * WN];
-#pragma unroll
-            for (int w = 1; w < WN; ++w) {
-                const float ov = red_val[lrow * WN + w];
-                const int oi = red_idx[lrow * WN + w];
-                if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-            }
-            ep.part_val[(int64_t)row * ep.nparts + bn] = bv;
-            ep.part_idx[(int64_t)row * ep.nparts + bn] = bi;
-        }
-    }
+    gemm_epilogue<BM, BN, WM, WN, EPI, TAct>(acc, smem_raw, ep, M, N, m0, n0, bn);
 }
 
 // ------------------------------------------------------------------ fp32 FMA
