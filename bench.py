@@ -29,6 +29,14 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="C4", choices=["C1", "C3", "C4"])
+    ap.add_argument("--concurrency", action="store_true",
+                    help="instead of the timed step: the C5 sweep (256 prompts x k replicas) and the largest "
+                         "resident batch that still completes a decode step")
+    ap.add_argument("--no-prefill", action="store_true", help="start from a zero state and random tokens "
+                    "(for kernel traces that should hold decode kernels only)")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="only launch, a few times each: a plain 1 GiB copy, the state update over all layer slabs, "
+                         "the MLP-up GEMM and the LM-head GEMM (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--kernel-iters", type=int, default=20, help="launches per kernel leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-legs", action="store_true")
@@ -113,6 +121,77 @@ def cpu_baseline(cfg, w, rows, T):
             "sample": f"{rows} samples x {T} decode positions of {cfg.name} (fp32 build, OpenMP over samples), {dt:.1f} s"}
 
 
+def concurrency_sweep(torch, srm, srm_synth, steps):
+    """C5: 256 distinct prompts prefilled once, state fanned out to k replicas each, greedy decode;
+    then the largest batch (state + workspace resident) that completes one decode step."""
+    cfg = srm_synth.CONFIGS["C5"]
+    w = srm_synth.make_weights(cfg)
+    model = srm.Model(cfg, w)
+    prompts = torch.from_numpy(srm_synth.make_prompts(cfg)).cuda()
+    N, P = prompts.shape
+    out = {"metric": "generated tokens/sec on 1 MI355X at max batch", "unit": "tokens/s", "n_gpus": 1,
+           "data": "synthetic", "dtype": "bf16", "sweep": [], "config": {"workload": "C5: C4's model, 256 prompts x k"}}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for k in cfg.fanout:
+        B = N * k
+        state = model.new_state(B)
+        ws = model.new_workspace(max(B, N * P))
+        tok = torch.empty(B, dtype=torch.int32, device="cuda")
+        e0.record()
+        model.prefill(prompts, k, state, tok, workspace=ws)
+        e1.record(); e1.synchronize()
+        t_pre = e0.elapsed_time(e1) * 1e-3
+        for i in range(2):
+            model.decode_step(B, P + i, tok, state, tok, workspace=ws)
+        e0.record()
+        for i in range(steps):
+            model.decode_step(B, P + 2 + i, tok, state, tok, workspace=ws)
+        e1.record(); e1.synchronize()
+        t = e0.elapsed_time(e1) * 1e-3 / steps
+        out["sweep"].append({"k": k, "batch": B, "tokens_per_s": B / t, "ms_per_step": t * 1e3,
+                             "prefill_s": t_pre, "state_gib": model.state_bytes(B) / 2**30})
+        del state, ws, tok
+        torch.cuda.empty_cache()
+    # largest resident batch: state (64 KiB/sequence) + workspace, one successful step
+    free, total = torch.cuda.mem_get_info()
+    per_seq = model.state_bytes(1) + model.workspace_bytes(1 << 20) / (1 << 20)
+    hi = int((free - (2 << 30)) / per_seq) // 4096 * 4096
+    best = None
+    B = hi
+    while B > 0 and best is None:
+        try:
+            state = torch.zeros((cfg.n_layers, B, cfg.d_model), dtype=torch.float32, device="cuda")
+            ws = model.new_workspace(B)
+            tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+            e0.record()
+            model.decode_step(B, 0, tok, state, tok, workspace=ws)
+            e1.record(); e1.synchronize()
+            ok = bool(((tok >= 0) & (tok < cfg.vocab)).all())
+            if ok:
+                best = {"batch": B, "ms_per_step": e0.elapsed_time(e1), "tokens_per_s": B / (e0.elapsed_time(e1) * 1e-3),
+                        "state_gib": model.state_bytes(B) / 2**30, "workspace_gib": ws.numel() / 2**30,
+                        "hbm_total_gib": total / 2**30}
+            del state, ws, tok
+        except (RuntimeError, torch.cuda.OutOfMemoryError):
+            pass
+        torch.cuda.empty_cache()
+        B = int(B * 0.95) // 4096 * 4096
+    out["max_resident"] = best
+    out["value"] = max(r["tokens_per_s"] for r in out["sweep"])
+    print(json.dumps(out))
+
+
+def measured_traffic(kernel_key):
+    """HBM-side bytes per launch (read + written) of a kernel at the C4 shapes, from the committed
+    rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary (scaled by the copy-kernel factors stated there)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_C4_kernels.json.txt")
+    try:
+        t = json.load(open(path))[kernel_key]
+        return t["read_bytes"] + t["write_bytes"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -127,6 +206,9 @@ def main():
 
     srm.lib()                                     # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    if args.concurrency:
+        concurrency_sweep(torch, srm, srm_synth, min(args.steps, 8))
+        return
     cfg = srm_synth.CONFIGS[args.workload]
     B, P = cfg.batch, cfg.prompt_len
     t0 = time.perf_counter()
@@ -141,8 +223,20 @@ def main():
     dprompts = torch.from_numpy(prompts).cuda()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if args.pmc_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        kernel_legs(torch, srm, model, cfg, B, 4)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": "done", "copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
+        return
     e0.record()
-    model.prefill(dprompts, 1, state, tok, workspace=ws)
+    if args.no_prefill:
+        tok.copy_(dprompts[:, 0])
+    else:
+        model.prefill(dprompts, 1, state, tok, workspace=ws)
     e1.record()
     e1.synchronize()
     prefill_s = e0.elapsed_time(e1) * 1e-3
@@ -193,8 +287,10 @@ def main():
             up = legs["gemm_up"]
             out["roofline"] = {"kernel": "gemm_bf16_kernel (MLP up, GELU epilogue)", "bound": "mfma",
                                "achieved": up["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                               "frac": up["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
-                               "avg_launch_ms": up["ms"], "flop_per_launch": 2.0 * B * ff * d}
+                               "frac": up["tflops"] / PEAK_BF16_TFLOPS,
+                               "traffic": measured_traffic("gemm_bf16_kernel<256,256,2,4,EPI=GELU>") if cfg.name == "C4" else None,
+                               "avg_launch_ms": up["ms"], "flop_per_launch": 2.0 * B * ff * d,
+                               "algorithmic_bytes_per_launch": (B * d + ff * d + B * ff) * 2.0}
         else:
             up = legs["gemm_up"]
             out["roofline"] = {"kernel": "gemm_f32_kernel (MLP up)", "bound": "alu", "achieved": up["tflops"],
@@ -203,10 +299,11 @@ def main():
         su = legs["state_update"]
         out["roofline_state_update"] = {"kernel": "state_update_kernel", "bound": "hbm", "achieved": su["gbs"],
                                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": su["gbs"] / PEAK_HBM_GBS,
-                                        "traffic": None, "avg_launch_ms": su["ms"], "bytes_per_launch": su["bytes"]}
+                                        "traffic": measured_traffic("state_update_kernel<bf16,2>") if cfg.name == "C4" else None,
+                                        "avg_launch_ms": su["ms"], "bytes_per_launch": su["bytes"]}
     if not args.no_cpu_baseline:
         rows = min(16, os.cpu_count() or 1)
-        T = {"C4": 12, "C3": 128, "C1": 240}[cfg.name]
+        T = {"C4": 200, "C3": 256, "C1": 240}[cfg.name]      # about 10-20 s of host work
         out["cpu_baseline"] = cpu_baseline(cfg, w, rows, min(T, cfg.n_ctx - P))
     print(json.dumps(out))
 
