@@ -463,6 +463,79 @@ gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
     }
 }
 
+// ------------------------------------------------------------------ fp32, few rows
+// M <= a few dozen rows (small-batch decode): the work is streaming W once.  A
+// block of 256 threads owns 64 output columns; thread (c = tid & 63, q = tid >> 6)
+// accumulates, for MR rows at a time, the dot products of column c over the q-th
+// quarter of K.  The MR activation rows sit in LDS (every lane reads the same
+// address: a broadcast), each lane streams its own W row with 16-byte loads, and
+// the four K-quarters are added through LDS in a fixed order.  One argmax partial
+// per block, the layout gemm_f32_kernel uses.  Needs K % 16 == 0.
+// Dynamic LDS: (MR * K + 4 * MR * 64) floats.
+template <int EPI, int MR>
+__global__ void __launch_bounds__(256)
+gemv_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M, int N, int K, GemmEpi ep)
+{
+    extern __shared__ __align__(16) float gemv_sm[];
+    float *xs = gemv_sm;                   // [MR][K]
+    float *part = gemv_sm + MR * K;        // [4][MR][64]
+    const int tid = threadIdx.x, c = tid & 63, q = tid >> 6;
+    const int n = blockIdx.x * 64 + c;
+    const int Ks = K >> 2;
+    const float *wrow = W + (size_t)min(n, N - 1) * K + q * Ks;
+    for (int mg = 0; mg < M; mg += MR) {
+        __syncthreads();
+        for (int i = tid; i < MR * K / 4; i += 256) {
+            const int m = (i * 4) / K, k = (i * 4) - m * K;
+            const float4 v = mg + m < M ? load4(A + (size_t)(mg + m) * K + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            store4(xs + m * K + k, v);
+        }
+        __syncthreads();
+        float acc[MR];
+#pragma unroll
+        for (int m = 0; m < MR; ++m) acc[m] = 0.0f;
+        for (int k = 0; k < Ks; k += 4) {
+            const float4 w4 = load4(wrow + k);
+#pragma unroll
+            for (int m = 0; m < MR; ++m) {
+                const float4 x4 = load4(xs + m * K + q * Ks + k);
+                acc[m] = fmaf(w4.x, x4.x, acc[m]);
+                acc[m] = fmaf(w4.y, x4.y, acc[m]);
+                acc[m] = fmaf(w4.z, x4.z, acc[m]);
+                acc[m] = fmaf(w4.w, x4.w, acc[m]);
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < MR; ++m) part[(q * MR + m) * 64 + c] = acc[m];
+        __syncthreads();
+        // thread (c, q) finishes rows q, q + 4, ...; the lanes of wave q are the 64 columns
+        for (int m = q; m < MR; m += 4) {
+            const int row = mg + m;
+            float v = ((part[m * 64 + c] + part[(MR + m) * 64 + c]) + part[(2 * MR + m) * 64 + c]) +
+                      part[(3 * MR + m) * 64 + c];
+            const bool live = n < N && row < M;
+            if (live) {
+                v += ep.bias ? ep.bias[n] : 0.0f;
+                epi_store<EPI, float>(ep, row, n, v);
+            }
+            if constexpr (EPI == EPI_ARGMAX) {
+                float bv = live ? v : -INFINITY;
+                int bi = live ? n : 0x7fffffff;
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) {
+                    const float ov = __shfl_xor(bv, off, kWave);
+                    const int oi = __shfl_xor(bi, off, kWave);
+                    if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+                }
+                if (c == 0 && row < M) {
+                    ep.part_val[(int64_t)row * ep.nparts + blockIdx.x] = bv;
+                    ep.part_idx[(int64_t)row * ep.nparts + blockIdx.x] = bi;
+                }
+            }
+        }
+    }
+}
+
 // Reduce the per-tile partials of each row to one token; writes `rep`
 // consecutive copies starting at out[(row0 + row) * rep].  One wave per row.
 // A row without any ordered value (all NaN) yields token 0, so that the id is

@@ -309,8 +309,16 @@ static int launch_f32(const float *A, const float *W, int64_t M, int N, int K, G
     if (M <= 0 || M >= (1 << 30) || N <= 0 || K <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
     ep.nparts = (int)cdiv(N, 64);
     if (nparts_out) *nparts_out = ep.nparts;
-    const int64_t nb = cdiv(M, 64) * cdiv(N, 64);
-    hipLaunchKernelGGL(gemm_f32_kernel<EPI>, dim3((unsigned)nb), dim3(256), 0, st, A, W, (int)M, N, K, ep);
+    constexpr int MR = 8;
+    const size_t gemv_lds = ((size_t)MR * K + 4 * MR * 64) * sizeof(float);
+    if (M <= 32 && K % 16 == 0 && gemv_lds <= 64 * 1024) {
+        // few rows: stream W once per group of MR rows
+        hipLaunchKernelGGL((gemv_f32_kernel<EPI, MR>), dim3((unsigned)cdiv(N, 64)), dim3(256), gemv_lds, st, A, W,
+                           (int)M, N, K, ep);
+    } else {
+        const int64_t nb = cdiv(M, 64) * cdiv(N, 64);
+        hipLaunchKernelGGL(gemm_f32_kernel<EPI>, dim3((unsigned)nb), dim3(256), 0, st, A, W, (int)M, N, K, ep);
+    }
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }

@@ -80,7 +80,8 @@ def test_linear_bf16_auto_tile_shapes(srm, shape):
         _linear_case(srm, srm.SRM_BF16, M, N, K, epi, None, seed=M + N)
 
 
-@pytest.mark.parametrize("shape", [(1, 5, 3), (8, 256, 256), (70, 130, 37), (128, 64, 100)])
+@pytest.mark.parametrize("shape", [(1, 5, 3), (8, 256, 256), (70, 130, 37), (128, 64, 100), (5, 130, 64), (17, 70, 128),
+                                   (32, 4096, 256), (33, 64, 64)])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
 def test_linear_fp32(srm, shape, epi):
     M, N, K = shape
