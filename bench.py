@@ -32,6 +32,10 @@ def parse_args():
     ap.add_argument("--concurrency", action="store_true",
                     help="instead of the timed step: the C5 sweep (256 prompts x k replicas) and the largest "
                          "resident batch that still completes a decode step")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="sample with this temperature (fused Gumbel-max) instead of greedy argmax")
+    ap.add_argument("--per-step-calls", action="store_true",
+                    help="time K srm_decode_step calls instead of one srm_generate call of K steps")
     ap.add_argument("--no-prefill", action="store_true", help="start from a zero state and random tokens "
                     "(for kernel traces that should hold decode kernels only)")
     ap.add_argument("--pmc-probe", action="store_true",
@@ -243,19 +247,35 @@ def main():
 
     n_steps = args.warmup + args.steps
     assert P + n_steps <= cfg.n_ctx, "steps + warmup exceed the model's positions"
-    pos = P
-    for _ in range(args.warmup):
-        model.decode_step(B, pos, tok, state, tok, workspace=ws)
-        pos += 1
+    # All steps run on a side stream: srm_generate replays one captured step from a HIP graph there
+    # (the legacy default stream cannot be captured).
+    samp = {"temperature": args.temperature, "seed": 1} if args.temperature > 0 else {}
+    gsamp = {"temperature": args.temperature, "seed": 1}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    store = torch.empty((max(args.steps, args.warmup), B), dtype=torch.int32, device="cuda")
+    with torch.cuda.stream(side):
+        pos = P
+        if args.per_step_calls:
+            for _ in range(args.warmup):
+                model.decode_step(B, pos, tok, state, tok, workspace=ws, **samp)
+                pos += 1
+        elif args.warmup:
+            model.generate(B, pos, args.warmup, tok, state, store, workspace=ws, **gsamp)
+            pos += args.warmup
+        side.synchronize()
+        t_wall0 = time.perf_counter()
+        e0.record()
+        if args.per_step_calls:
+            for _ in range(args.steps):
+                model.decode_step(B, pos, tok, state, tok, workspace=ws, **samp)
+                pos += 1
+        else:
+            model.generate(B, pos, args.steps, tok, state, store, workspace=ws, **gsamp)
+        e1.record()
+        side.synchronize()
+        wall = time.perf_counter() - t_wall0
     torch.cuda.synchronize()
-    t_wall0 = time.perf_counter()
-    e0.record()
-    for _ in range(args.steps):
-        model.decode_step(B, pos, tok, state, tok, workspace=ws)
-        pos += 1
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t_wall0
     dev_s = e0.elapsed_time(e1) * 1e-3
     step_s = max(wall, dev_s) / args.steps
     tk = tok.cpu().numpy()
@@ -278,6 +298,8 @@ def main():
                  if esz == 2 else None,
                  "device_ms_per_step": dev_s / args.steps * 1e3, "wall_ms_per_step": wall / args.steps * 1e3},
         "prefill": {"seconds": prefill_s, "tokens_per_s": B * P / prefill_s},
+        "next_token": "greedy argmax" if args.temperature == 0 else f"sampled, temperature {args.temperature} (fused Gumbel-max)",
+        "driver": "K srm_decode_step calls" if args.per_step_calls else "one srm_generate call (HIP-graph replay of the step)",
         "setup_seconds": t_setup,
     }
     if not args.no_kernel_legs:

@@ -128,6 +128,48 @@ int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_i
                     void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * srm_decode_step with the next token SAMPLED from softmax(logits / temperature)
+ * instead of taken greedily (the paper's rollouts use temperature 0.7, "Training
+ * Details"; top-p truncation is not applied).  The sample is exact and needs no
+ * normalisation pass: tok = argmax_v(logit_v + temperature * g_v) with g_v
+ * independent standard Gumbel variates (the Gumbel-max rule), fused into the LM
+ * head like the greedy argmax.  g is a pure function of (seed, pos, sample index
+ * b, vocabulary index v), so a call can be reproduced exactly anywhere:
+ *   hash(x): x ^= x>>16; x *= 0x7feb352d; x ^= x>>15; x *= 0x846ca68b; x ^= x>>16   (uint32)
+ *   rowkey = hash(b ^ hash(pos + 0x9E3779B9 * (seed + 1)))
+ *   h      = hash(rowkey + v * 0x9E3779B9)
+ *   w      = ((h >> 9) + 0.5) * 2^-23 ;   g_v = -log(-log(1 - w))
+ * temperature = 0 gives srm_decode_step.  d_logits, if requested, are the raw
+ * logits.  Ties as in the greedy case.  Errors as srm_decode_step, plus
+ * SRM_EINVAL for a negative or NaN temperature.
+ */
+int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in,
+                            float *d_state, int32_t *d_tok_out, float temperature, uint32_t seed,
+                            float *d_logits, float *d_hidden, void *d_workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
+/*
+ * G decode steps in one call, for callers that only want the tokens
+ * ("MAX model details": looping forward passes and cache updates inside the
+ * compiled code instead of calling it once per token removed a per-call delay
+ * that dominated the paper's measurements).  Step g (0-based) consumes d_tok[B]
+ * at absolute position pos0 + g, updates d_state in place, overwrites d_tok with
+ * the greedy tokens and also stores them at d_tokens_out[g][B].  The position
+ * lives in device memory (the last 256 bytes of the workspace), so one step is
+ * captured into a HIP graph on the first call and replayed G - 1 times; the
+ * graph is cached in the model and reused while B and the four device pointers
+ * stay the same.  On the legacy default stream (NULL), which cannot be
+ * captured, the steps are launched one by one instead.  temperature = 0 is
+ * greedy; temperature > 0 samples as srm_decode_step_sampled does.  Results are
+ * identical to G srm_decode_step(_sampled) calls.  Not thread-safe per model.
+ * Errors: SRM_EINVAL (null pointer, B or G <= 0, pos0 + G > n_ctx), SRM_ENOMEM
+ * (workspace smaller than srm_workspace_bytes(m, B)), SRM_EHIP.
+ */
+int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+                 int32_t *d_tokens_out, float temperature, uint32_t seed, void *d_workspace,
+                 size_t workspace_bytes, void *hip_stream);
+
+/*
  * Consume N prompts of P tokens (positions 0..P-1) from a zero state, layer by
  * layer over all positions, with the mixer evaluated as the sequential
  * recurrence (the result equals P decode steps), then replicate each prompt's

@@ -276,6 +276,60 @@ void orc_mixer_closed_form(const real *U, const real *alpha, const real *beta, c
     }
 }
 
+/* ---- sampling ------------------------------------------------------------ */
+
+/*
+ * Counter-based Gumbel noise, a pure function of (seed, position, sample index b,
+ * vocabulary index v).  The paper only says that rollouts are sampled with a
+ * temperature ("Training Details"); the generator is this build's definition and
+ * is stated in full in the library's header so that both sides can implement it:
+ *   hash(x): x ^= x>>16; x *= 0x7feb352d; x ^= x>>15; x *= 0x846ca68b; x ^= x>>16  (uint32)
+ *   rowkey = hash(b ^ hash(pos + 0x9E3779B9 * (seed + 1)))
+ *   h      = hash(rowkey + v * 0x9E3779B9)
+ *   w      = ((h >> 9) + 0.5) * 2^-23        uniform in (0, 1)
+ *   g      = -log(-log(1 - w))               standard Gumbel
+ * Everything after the integer hash is evaluated in double here.
+ */
+#include <stdint.h>
+static uint32_t orc_hash32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+    return x;
+}
+
+double orc_uniform(uint32_t seed, uint32_t pos, uint32_t b, uint32_t v)
+{
+    uint32_t rowkey = orc_hash32(b ^ orc_hash32(pos + 0x9E3779B9U * (seed + 1U)));
+    uint32_t h = orc_hash32(rowkey + v * 0x9E3779B9U);
+    return ((double)(h >> 9) + 0.5) / 8388608.0;
+}
+
+double orc_gumbel(uint32_t seed, uint32_t pos, uint32_t b, uint32_t v)
+{
+    double w = orc_uniform(seed, pos, b, v);
+    return -log(-log1p(-w));
+}
+
+/*
+ * Next token from logits[V]: greedy for temperature == 0, otherwise the
+ * Gumbel-max rule argmax_v(logit_v + temperature * g_v), which draws from
+ * softmax(logits / temperature).  Lowest index on ties.  If margin is not NULL
+ * it receives best minus second-best of the scores the decision was taken on.
+ */
+int orc_pick(const real *logits, int V, double temperature, uint32_t seed, int pos, int b, real *margin)
+{
+    int best = -1;
+    real bs = -INFINITY, second = -INFINITY;
+    for (int v = 0; v < V; ++v) {
+        real sc = logits[v];
+        if (temperature > 0) sc += (real)(temperature * orc_gumbel(seed, (uint32_t)pos, (uint32_t)b, (uint32_t)v));
+        if (sc > bs) { second = bs; bs = sc; best = v; }
+        else if (sc > second) second = sc;
+    }
+    if (margin) *margin = bs - second;
+    return best < 0 ? 0 : best;
+}
+
 /* ---- whole model, recurrent form --------------------------------------- */
 
 /*
@@ -347,16 +401,18 @@ int orc_recurrent_forward(const orc_model *m, int B, int T, const int *tokens, i
 }
 
 /*
- * Greedy generation: consume prompts[B][P] from a zero state, then generate G
- * tokens; out_tokens[b][0] is the argmax at the last prompt position and each
- * generated token is fed back.  state[B][L][d] is overwritten.  Optional:
- * logits[B][G][V] (the logits each generated token was chosen from) and
- * margin[B][G] (top-1 minus top-2 of those logits).
+ * Generation: consume prompts[B][P] from a zero state, then generate G tokens;
+ * out_tokens[b][0] is chosen from the logits at the last prompt position and each
+ * generated token is fed back.  temperature == 0: greedy; otherwise sampled with
+ * orc_pick, the counter being (seed, position of the token just consumed, b0 + b).
+ * state[B][L][d] is overwritten.  Optional: logits[B][G][V] (the raw logits each
+ * generated token was chosen from) and margin[B][G] (top-1 minus top-2 of the
+ * scores the choice was made on).
  */
-int orc_greedy(const orc_model *m, int B, int P, int G, const int *prompts, real *state,
-               int *out_tokens, real *logits, real *margin)
+int orc_generate(const orc_model *m, int B, int P, int G, const int *prompts, real *state,
+                 int *out_tokens, real *logits, real *margin, double temperature, uint32_t seed, int b0)
 {
-    if (P < 1 || G < 1 || P + G - 1 > m->n_ctx) return -1;
+    if (P < 1 || G < 1 || P + G - 1 > m->n_ctx || temperature < 0) return -1;
     for (long long i = 0; i < (long long)B * P; ++i)
         if (prompts[i] < 0 || prompts[i] >= m->vocab) return -1;
     int d = m->d, V = m->vocab;
@@ -373,18 +429,21 @@ int orc_greedy(const orc_model *m, int B, int P, int G, const int *prompts, real
             orc_step(m, in, t, S, NULL, want ? lg : NULL);
             if (!want) continue;
             int g = t - (P - 1);
-            tok = orc_argmax(lg, V);
+            real mg;
+            tok = orc_pick(lg, V, temperature, seed, t, b0 + b, &mg);
             out_tokens[(size_t)b * G + g] = tok;
             if (logits) memcpy(logits + ((size_t)b * G + g) * V, lg, sizeof(real) * V);
-            if (margin) {
-                real second = -INFINITY;
-                for (int v = 0; v < V; ++v) if (v != tok && lg[v] > second) second = lg[v];
-                margin[(size_t)b * G + g] = lg[tok] - second;
-            }
+            if (margin) margin[(size_t)b * G + g] = mg;
         }
         free(lg);
     }
     return 0;
+}
+
+int orc_greedy(const orc_model *m, int B, int P, int G, const int *prompts, real *state,
+               int *out_tokens, real *logits, real *margin)
+{
+    return orc_generate(m, B, P, G, prompts, state, out_tokens, logits, margin, 0.0, 0, 0);
 }
 
 /* ---- whole model, parallel (sequence) form ------------------------------ */

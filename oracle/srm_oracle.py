@@ -48,6 +48,15 @@ def _load(kind: str):
         lib.orc_destroy.argtypes = [C.c_void_p]
         lib.orc_count_params.restype = C.c_longlong
         lib.orc_count_params.argtypes = [C.c_int] * 7
+        lib.orc_uniform.restype = C.c_double
+        lib.orc_uniform.argtypes = [C.c_uint32] * 4
+        lib.orc_gumbel.restype = C.c_double
+        lib.orc_gumbel.argtypes = [C.c_uint32] * 4
+        lib.orc_pick.restype = C.c_int
+        lib.orc_pick.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_uint32, C.c_int, C.c_int, C.c_void_p]
+        lib.orc_generate.restype = C.c_int
+        lib.orc_generate.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_double, C.c_uint32, C.c_int]
         lib.orc_gelu.restype = C.c_double if kind == "f64" else C.c_float
         lib.orc_gelu.argtypes = [C.c_double if kind == "f64" else C.c_float]
         _LIBS[kind] = lib
@@ -56,6 +65,20 @@ def _load(kind: str):
 
 def _p(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def uniform(seed, pos, b, v) -> float:
+    return float(_load("f64").orc_uniform(seed, pos, b, v))
+
+
+def gumbel(seed, pos, b, v) -> float:
+    return float(_load("f64").orc_gumbel(seed, pos, b, v))
+
+
+def pick(logits, temperature, seed, pos, b, kind="f64") -> int:
+    real = np.float64 if kind == "f64" else np.float32
+    lg = np.ascontiguousarray(logits, dtype=real)
+    return int(_load(kind).orc_pick(_p(lg), lg.size, float(temperature), seed, pos, b, None))
 
 
 def count_params(vocab, d, L, H=4, e=4, n_ctx=512, with_projections=True) -> int:
@@ -157,17 +180,18 @@ class Oracle:
             raise ValueError("orc_recurrent_forward: bad argument")
         return {"state": state, "hidden": hidden, "logits": logits, "greedy": greedy}
 
-    def greedy(self, prompts, G, want_logits=False):
+    def greedy(self, prompts, G, want_logits=False, temperature=0.0, seed=0, b0=0):
+        """Generate G tokens per prompt: greedy, or sampled when temperature > 0."""
         prompts = np.ascontiguousarray(prompts, dtype=np.int32)
         B, P = prompts.shape
         state = self.new_state(B)
         toks = np.empty((B, G), np.int32)
         logits = np.empty((B, G, self.V), self.real) if want_logits else None
         margin = np.empty((B, G), self.real)
-        rc = self.lib.orc_greedy(C.c_void_p(self.h), B, P, G, _p(prompts), _p(state), _p(toks),
-                                 _p(logits), _p(margin))
+        rc = self.lib.orc_generate(C.c_void_p(self.h), B, P, G, _p(prompts), _p(state), _p(toks),
+                                   _p(logits), _p(margin), float(temperature), seed, b0)
         if rc:
-            raise ValueError("orc_greedy: bad argument")
+            raise ValueError("orc_generate: bad argument")
         return {"tokens": toks, "logits": logits, "margin": margin, "state": state}
 
     def parallel_forward(self, tokens, want_logits=True):

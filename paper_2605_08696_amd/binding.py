@@ -62,6 +62,10 @@ def lib():
         L.srm_workspace_bytes.argtypes = [vp, i64]
         L.srm_decode_step.restype = C.c_int
         L.srm_decode_step.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.srm_generate.restype = C.c_int
+        L.srm_generate.argtypes = [vp, i64, i32, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, sz, vp]
+        L.srm_decode_step_sampled.restype = C.c_int
+        L.srm_decode_step_sampled.argtypes = [vp, i64, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, vp, vp, sz, vp]
         L.srm_prefill.restype = C.c_int
         L.srm_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
         L.srm_parallel_forward.restype = C.c_int
@@ -174,7 +178,8 @@ class Model:
         return torch.empty(self.workspace_bytes(rows), dtype=torch.uint8, device="cuda")
 
     def decode_step(self, B, pos, tok_in, state, tok_out, logits=None, hidden=None, workspace=None,
-                    stream=None):
+                    stream=None, temperature=None, seed=0):
+        """srm_decode_step, or srm_decode_step_sampled when a temperature is given."""
         torch = _torch()
         p_in = _dev(tok_in, torch.int32, B, "tok_in")
         p_st = _dev(state, torch.float32, self.L * B * self.d, "state")
@@ -184,8 +189,23 @@ class Model:
         p_lg = None if logits is None else _dev(logits, torch.float32, B * self.vocab, "logits")
         p_hd = None if hidden is None else _dev(hidden, torch.float32, B * self.d, "hidden")
         p_ws = _dev(workspace, torch.uint8, 1, "workspace")
-        _check(lib().srm_decode_step(self._h, B, pos, p_in, p_st, p_out, p_lg, p_hd, p_ws,
-                                     workspace.numel(), _stream(stream)))
+        if temperature is None:
+            _check(lib().srm_decode_step(self._h, B, pos, p_in, p_st, p_out, p_lg, p_hd, p_ws,
+                                         workspace.numel(), _stream(stream)))
+        else:
+            _check(lib().srm_decode_step_sampled(self._h, B, pos, p_in, p_st, p_out, temperature, seed, p_lg,
+                                                 p_hd, p_ws, workspace.numel(), _stream(stream)))
+
+    def generate(self, B, pos0, G, tok, state, tokens_out, workspace=None, stream=None, temperature=0.0, seed=0):
+        torch = _torch()
+        p_tk = _dev(tok, torch.int32, B, "tok")
+        p_st = _dev(state, torch.float32, self.L * B * self.d, "state")
+        if state.numel() != self.L * B * self.d:
+            raise ValueError("state: must be exactly [L][B][d]")
+        p_out = _dev(tokens_out, torch.int32, G * B, "tokens_out")
+        p_ws = _dev(workspace, torch.uint8, 1, "workspace")
+        _check(lib().srm_generate(self._h, B, pos0, G, p_tk, p_st, p_out, temperature, seed, p_ws,
+                                  workspace.numel(), _stream(stream)))
 
     def prefill(self, prompts, fanout_k, state, next_tok, logits=None, workspace=None, stream=None):
         torch = _torch()

@@ -48,3 +48,32 @@ __device__ __forceinline__ float gelu_erf(float x)
 {
     return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
 }
+
+// ---- counter-based random numbers for sampling ------------------------------------
+// Gumbel noise for (seed, position, sample b, vocabulary index v), a pure function
+// of its arguments (specified in include/srm.h):
+//   hash(x): x ^= x>>16; x *= 0x7feb352d; x ^= x>>15; x *= 0x846ca68b; x ^= x>>16
+//   rowkey  = hash(b ^ hash(pos + 0x9E3779B9 * (seed + 1)))          (mod 2^32)
+//   h       = hash(rowkey + v * 0x9E3779B9)
+//   w       = ((h >> 9) + 0.5) * 2^-23            uniform in (0, 1), exact in fp32
+//   E       = -log(1 - w)                          exponential variate
+//   g       = -log(E)                              standard Gumbel variate
+__device__ __forceinline__ uint32_t srm_hash32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ uint32_t srm_rowkey(uint32_t seed, uint32_t pos, uint32_t b)
+{
+    return srm_hash32(b ^ srm_hash32(pos + 0x9E3779B9u * (seed + 1u)));
+}
+__device__ __forceinline__ float srm_gumbel(uint32_t rowkey, uint32_t v)
+{
+    const uint32_t h = srm_hash32(rowkey + v * 0x9E3779B9u);
+    const float w = ((float)(h >> 9) + 0.5f) * (1.0f / 8388608.0f);
+    // -log(1 - w): series where 1 - w is too close to 1 for a fast logarithm
+    const float e_small = w * (1.0f + w * (0.5f + w * (1.0f / 3.0f)));
+    const float e_big = -0.69314718055994530942f * __builtin_amdgcn_logf(1.0f - w);
+    const float e = w < (1.0f / 64.0f) ? e_small : e_big;
+    return -0.69314718055994530942f * __builtin_amdgcn_logf(e);
+}

@@ -24,7 +24,15 @@ struct GemmEpi {
     float *part_val;     // EPI_ARGMAX: [M][nparts]
     int32_t *part_idx;   // EPI_ARGMAX: [M][nparts]
     int32_t nparts;      // number of column tiles
+    // EPI_ARGMAX with temp > 0: the decision is argmax_v(logit_v + temp * gumbel(seed, pos, row, v)),
+    // i.e. a sample from softmax(logits / temp); stored logits stay the raw ones.
+    float temp;
+    uint32_t seed;
+    int32_t pos;         // position of the counter, unless pos_dev is set
+    const int *pos_dev;
 };
+
+__device__ __forceinline__ uint32_t epi_pos(const GemmEpi &ep) { return (uint32_t)(ep.pos_dev ? *ep.pos_dev : ep.pos); }
 
 // Block -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs, each
 // with its own L2: give every XCD one contiguous run of tiles, and inside a run
@@ -171,7 +179,19 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
             // the other half of the row's columns
             float bv = -INFINITY;
             int brel = 0;
-            if (!n_edge && !ep.bias) {
+            if (ep.temp > 0.0f) {
+                const uint32_t rk = srm_rowkey(ep.seed, epi_pos(ep), (uint32_t)(m0 + wm * WTM + i * 32 + lr));
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int rel = j * 32 + 8 * (r >> 2) + (r & 3);
+                        const int col = wcol0 + 4 * lk + rel;
+                        const float v = acc[i][j][r] + ((ep.bias && col < N) ? ep.bias[col] : 0.0f) +
+                                        ep.temp * srm_gumbel(rk, (uint32_t)col);
+                        if (col < N && v > bv) { bv = v; brel = rel; }
+                    }
+            } else if (!n_edge && !ep.bias) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -444,8 +464,12 @@ gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
             if (col >= N) continue;
             const float v = acc[i][j] + (ep.bias ? ep.bias[col] : 0.0f);
             if (row < M) epi_store<EPI, float>(ep, row, col, v);
-            if constexpr (EPI == EPI_ARGMAX)
-                if (arg_better(v, col, bv, bi)) { bv = v; bi = col; }
+            if constexpr (EPI == EPI_ARGMAX) {
+                const float vs = ep.temp > 0.0f
+                                     ? v + ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep), (uint32_t)row), (uint32_t)col)
+                                     : v;
+                if (arg_better(vs, col, bv, bi)) { bv = vs; bi = col; }
+            }
         }
         if constexpr (EPI == EPI_ARGMAX) {
             // the 16 threads of a row are 16 consecutive lanes
@@ -519,6 +543,8 @@ gemv_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
                 epi_store<EPI, float>(ep, row, n, v);
             }
             if constexpr (EPI == EPI_ARGMAX) {
+                if (live && ep.temp > 0.0f)
+                    v += ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep), (uint32_t)row), (uint32_t)n);
                 float bv = live ? v : -INFINITY;
                 int bi = live ? n : 0x7fffffff;
 #pragma unroll
@@ -539,11 +565,13 @@ gemv_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
 // Reduce the per-tile partials of each row to one token; writes `rep`
 // consecutive copies starting at out[(row0 + row) * rep].  One wave per row.
 // A row without any ordered value (all NaN) yields token 0, so that the id is
-// always a valid embedding row.
+// always a valid embedding row.  If store is not null the token also goes to
+// store[step * store_stride + (row0 + row) * rep + r] with step = *step_dev.
 __global__ void __launch_bounds__(256)
 argmax_finalize_kernel(const float *__restrict__ part_val, const int32_t *__restrict__ part_idx,
                        int64_t rows, int nparts, int32_t *__restrict__ out, int64_t row0, int rep,
-                       int vocab)
+                       int vocab, int32_t *__restrict__ store, const int *__restrict__ step_dev,
+                       int64_t store_stride)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -563,4 +591,8 @@ argmax_finalize_kernel(const float *__restrict__ part_val, const int32_t *__rest
     }
     if (bi < 0 || bi >= vocab) bi = 0;
     for (int r = lane; r < rep; r += kWave) out[(row0 + row) * rep + r] = bi;
+    if (store) {
+        int32_t *dst = store + (int64_t)(*step_dev) * store_stride;
+        for (int r = lane; r < rep; r += kWave) dst[(row0 + row) * rep + r] = bi;
+    }
 }

@@ -18,14 +18,18 @@ constexpr int kMaxHeads = 64;
 // Streams u [B][d] (TAct), S [B][d] (fp32, in place) and m [B][d] (TAct), four
 // channels per thread.  The launch makes gridDim.x * 256 a multiple of d/4, so a
 // thread keeps one channel group, hence one head, for its whole loop; the per
-// head coefficients of this position are staged in LDS once per block.
+// head coefficients of this position are staged in LDS once per block.  If
+// pos_dev is not null the position is read from device memory (clamped to the
+// table), so that a captured graph of the step can be replayed as is.
 template <typename TAct, int UNROLL>
 __global__ void __launch_bounds__(256)
 state_update_kernel(const TAct *__restrict__ u, float *__restrict__ S, TAct *__restrict__ m,
                     const float *__restrict__ alpha, const float *__restrict__ beta,
-                    const float *__restrict__ lam, int pos, int n_ctx, int H, int d, int64_t nvec)
+                    const float *__restrict__ lam, int pos, const int *__restrict__ pos_dev, int n_ctx, int H,
+                    int d, int64_t nvec)
 {
     __shared__ float4 coef[kMaxHeads];      // (lam, p, q, beta) per head
+    if (pos_dev) pos = min(max(*pos_dev, 0), n_ctx - 1);
     if (threadIdx.x < H) {
         const int h = threadIdx.x;
         const float a = alpha[(size_t)h * n_ctx + pos];
@@ -187,3 +191,8 @@ mixer_parallel_kernel(const TAct *__restrict__ U, TAct *__restrict__ Y,
         }
     }
 }
+
+// Step counters of a multi-step generate call, kept in device memory so that the
+// captured step needs no host-side update: ctr[0] = position, ctr[1] = step.
+__global__ void counters_set_kernel(int *ctr, int pos, int step) { ctr[0] = pos; ctr[1] = step; }
+__global__ void counters_advance_kernel(int *ctr) { ctr[0] += 1; ctr[1] += 1; }

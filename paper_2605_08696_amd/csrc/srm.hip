@@ -62,6 +62,9 @@ struct srm_model {
     const void *embed, *head;
     const float *lnf_g, *lnf_b;
     std::vector<LayerDev> layers;
+    // cached graph of one decode step for srm_generate (see there)
+    hipGraphExec_t gexec;
+    struct { int64_t B; const void *tok, *state, *store, *ws; float temp; uint32_t seed; } gkey;
 };
 
 static uint16_t host_f32_to_bf16(float f)
@@ -134,6 +137,8 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     const bool bf = cfg->weight_dtype == SRM_BF16;
     m->wsize = bf ? 2 : 4;
     m->slab = nullptr;
+    m->gexec = nullptr;
+    m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0};
 
     struct Offs { size_t v[15]; };
     std::vector<Offs> lo(L);
@@ -193,6 +198,7 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
 extern "C" void srm_free(srm_model *m)
 {
     if (!m) return;
+    if (m->gexec) (void)hipGraphExecDestroy(m->gexec);
     if (m->slab) (void)hipFree(m->slab);
     delete m;
 }
@@ -213,6 +219,7 @@ struct Workspace {
     void *g;           // [rows][ff] activation type
     float *pv;         // [rows][nparts]
     int32_t *pi;       // [rows][nparts]
+    int *ctr;          // [2] position and step counters of srm_generate
     size_t bytes;
 };
 
@@ -235,6 +242,7 @@ static Workspace carve(const srm_model *m, void *base, int64_t rows)
     w.g = take(r * (size_t)m->ff * s);
     w.pv = reinterpret_cast<float *>(take(r * nparts * 4));
     w.pi = reinterpret_cast<int32_t *>(take(r * nparts * 4));
+    w.ctr = reinterpret_cast<int *>(take(256));
     w.bytes = off;
     return w;
 }
@@ -323,13 +331,20 @@ static int launch_f32(const float *A, const float *W, int64_t M, int N, int K, G
     return SRM_OK;
 }
 
+struct Sampling {          // temp == 0: greedy
+    float temp = 0.0f;
+    uint32_t seed = 0;
+    int pos = 0;
+    const int *pos_dev = nullptr;
+};
+
 // out = epilogue(A W^T + bias) with operands of type T (float or bf16)
 template <int EPI, typename T>
 static int linear(const void *A, const void *W, const float *bias, int64_t M, int N, int K, void *out,
                   hipStream_t st, float *pv = nullptr, int32_t *pi = nullptr, int min_bn = 64,
-                  int *nparts_out = nullptr)
+                  int *nparts_out = nullptr, Sampling sm = Sampling())
 {
-    GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0};
+    GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev};
     if constexpr (sizeof(T) == 2)
         return launch_bf16<EPI, bf16>(static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), M, N, K, ep,
                                       st, min_bn, nparts_out);
@@ -338,11 +353,17 @@ static int linear(const void *A, const void *W, const float *bias, int64_t M, in
                                nparts_out);
 }
 
+struct TokenStore {        // optional second destination of the greedy tokens (srm_generate)
+    int32_t *store = nullptr;
+    const int *step_dev = nullptr;
+    int64_t stride = 0;
+};
+
 static int argmax_finalize(const float *pv, const int32_t *pi, int64_t rows, int nparts, int32_t *out,
-                           int64_t row0, int rep, int vocab, hipStream_t st)
+                           int64_t row0, int rep, int vocab, hipStream_t st, TokenStore ts = TokenStore())
 {
     hipLaunchKernelGGL(argmax_finalize_kernel, dim3((unsigned)cdiv(rows, 4)), dim3(256), 0, st, pv, pi, rows,
-                       nparts, out, row0, rep, vocab);
+                       nparts, out, row0, rep, vocab, ts.store, ts.step_dev, ts.stride);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
@@ -370,7 +391,7 @@ static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, c
 
 template <typename T>
 static int state_update(const srm_model *m, int layer, int pos, int64_t B, const void *u, float *S, void *mx,
-                        hipStream_t st)
+                        hipStream_t st, const int *pos_dev = nullptr)
 {
     // Two 16-byte state vectors per thread and one pass over the slab (measured
     // best on MI355X: 6.15 TB/s at B = 16384, against 5.55 TB/s with four vectors
@@ -386,7 +407,7 @@ static int state_update(const srm_model *m, int layer, int pos, int64_t B, const
     const int step = dv / a;
     const int64_t nb = cdiv(cdiv(nvec, 256 * UNROLL), step) * step;
     hipLaunchKernelGGL((state_update_kernel<T, UNROLL>), dim3((unsigned)nb), dim3(256), 0, st,
-                       static_cast<const T *>(u), S, static_cast<T *>(mx), y.alpha, y.beta, y.lam, pos,
+                       static_cast<const T *>(u), S, static_cast<T *>(mx), y.alpha, y.beta, y.lam, pos, pos_dev,
                        m->cfg.n_ctx, m->H, m->d, nvec);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
@@ -431,45 +452,126 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
 // `rep` times at d_tok[(row0 + row) * rep + r].
 template <typename T>
 static int head_argmax(const srm_model *m, const Workspace &w, const void *a, int64_t M, float *logits,
-                       int32_t *d_tok, int64_t row0, int rep, hipStream_t st)
+                       int32_t *d_tok, int64_t row0, int rep, hipStream_t st, TokenStore ts = TokenStore(),
+                       Sampling sm = Sampling())
 {
     int nparts = 0;
     SRM_TRY((linear<EPI_ARGMAX, T>(a, m->head, nullptr, M, m->V, m->d, logits, st, w.pv, w.pi, head_min_bn(m),
-                                   &nparts)));
-    return argmax_finalize(w.pv, w.pi, M, nparts, d_tok, row0, rep, m->V, st);
+                                   &nparts, sm)));
+    return argmax_finalize(w.pv, w.pi, M, nparts, d_tok, row0, rep, m->V, st, ts);
 }
 
 // ------------------------------------------------------------------ decode
 template <typename T>
 static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, float *state, int32_t *tok_out,
-                       float *logits, float *hidden, void *ws, hipStream_t st)
+                       float *logits, float *hidden, void *ws, hipStream_t st, const int *pos_dev = nullptr,
+                       TokenStore ts = TokenStore(), float temperature = 0.0f, uint32_t seed = 0)
 {
     const Workspace w = carve(m, ws, B);
     const int d = m->d;
     SRM_TRY((layernorm<T, true>(m, nullptr, 0, tok_in, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a, B, st)));
-    auto mix = [&](int l) { return state_update<T>(m, l, pos, B, w.u, state + (size_t)l * B * d, w.mx, st); };
+    auto mix = [&](int l) {
+        return state_update<T>(m, l, pos, B, w.u, state + (size_t)l * B * d, w.mx, st, pos_dev);
+    };
     for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true)));
     if (hidden) HIP_TRY(hipMemcpyAsync(hidden, w.x, (size_t)B * d * 4, hipMemcpyDeviceToDevice, st));
-    return head_argmax<T>(m, w, w.a, B, logits, tok_out, 0, 1, st);
+    return head_argmax<T>(m, w, w.a, B, logits, tok_out, 0, 1, st, ts, Sampling{temperature, seed, pos, pos_dev});
+}
+
+static int decode_step_common(const char *who, srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in,
+                              float *d_state, int32_t *d_tok_out, float *d_logits, float *d_hidden,
+                              void *d_workspace, size_t workspace_bytes, void *hip_stream, float temperature,
+                              uint32_t seed)
+{
+    if (!m || !d_tok_in || !d_state || !d_tok_out || !d_workspace) return fail(SRM_EINVAL, "%s: null argument", who);
+    if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "%s: batch %lld out of range", who, (long long)B);
+    if (pos < 0 || pos >= m->cfg.n_ctx) return fail(SRM_EINVAL, "%s: pos %d outside [0, %d)", who, pos, m->cfg.n_ctx);
+    if (!(temperature >= 0.0f)) return fail(SRM_EINVAL, "%s: temperature must be >= 0", who);
+    if (workspace_bytes < srm_workspace_bytes(m, B))
+        return fail(SRM_ENOMEM, "%s: workspace %zu < %zu bytes", who, workspace_bytes, srm_workspace_bytes(m, B));
+    SRM_TRY(check_device(m));
+    hipStream_t st = as_stream(hip_stream);
+    return m->wsize == 2 ? decode_impl<bf16>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden, d_workspace,
+                                             st, nullptr, TokenStore(), temperature, seed)
+                         : decode_impl<float>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden,
+                                              d_workspace, st, nullptr, TokenStore(), temperature, seed);
 }
 
 extern "C" int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
                                int32_t *d_tok_out, float *d_logits, float *d_hidden, void *d_workspace,
                                size_t workspace_bytes, void *hip_stream)
 {
-    if (!m || !d_tok_in || !d_state || !d_tok_out || !d_workspace)
-        return fail(SRM_EINVAL, "srm_decode_step: null argument");
-    if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "srm_decode_step: batch %lld out of range", (long long)B);
-    if (pos < 0 || pos >= m->cfg.n_ctx)
-        return fail(SRM_EINVAL, "srm_decode_step: pos %d outside [0, %d)", pos, m->cfg.n_ctx);
+    return decode_step_common("srm_decode_step", m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden,
+                              d_workspace, workspace_bytes, hip_stream, 0.0f, 0);
+}
+
+extern "C" int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
+                                       int32_t *d_tok_out, float temperature, uint32_t seed, float *d_logits,
+                                       float *d_hidden, void *d_workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return decode_step_common("srm_decode_step_sampled", m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden,
+                              d_workspace, workspace_bytes, hip_stream, temperature, seed);
+}
+
+// ------------------------------------------------------------------ generate (G steps in one call)
+static int generate_step(srm_model *m, int64_t B, int32_t *tok, float *state, void *ws, const int *ctr,
+                         TokenStore ts, hipStream_t st, float temperature, uint32_t seed)
+{
+    SRM_TRY(m->wsize == 2
+                ? decode_impl<bf16>(m, B, 0, tok, state, tok, nullptr, nullptr, ws, st, ctr, ts, temperature, seed)
+                : decode_impl<float>(m, B, 0, tok, state, tok, nullptr, nullptr, ws, st, ctr, ts, temperature, seed));
+    hipLaunchKernelGGL(counters_advance_kernel, dim3(1), dim3(1), 0, st, const_cast<int *>(ctr));
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
+extern "C" int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+                            int32_t *d_tokens_out, float temperature, uint32_t seed, void *d_workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    if (!m || !d_tok || !d_state || !d_tokens_out || !d_workspace) return fail(SRM_EINVAL, "srm_generate: null argument");
+    if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "srm_generate: batch %lld out of range", (long long)B);
+    if (G <= 0) return fail(SRM_EINVAL, "srm_generate: G must be positive");
+    if (!(temperature >= 0.0f)) return fail(SRM_EINVAL, "srm_generate: temperature must be >= 0");
+    if (pos0 < 0 || (int64_t)pos0 + G > m->cfg.n_ctx)
+        return fail(SRM_EINVAL, "srm_generate: positions %d..%lld outside [0, %d)", pos0, (long long)pos0 + G - 1,
+                    m->cfg.n_ctx);
     if (workspace_bytes < srm_workspace_bytes(m, B))
-        return fail(SRM_ENOMEM, "srm_decode_step: workspace %zu < %zu bytes", workspace_bytes,
-                    srm_workspace_bytes(m, B));
+        return fail(SRM_ENOMEM, "srm_generate: workspace %zu < %zu bytes", workspace_bytes, srm_workspace_bytes(m, B));
     SRM_TRY(check_device(m));
     hipStream_t st = as_stream(hip_stream);
-    return m->wsize == 2
-               ? decode_impl<bf16>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden, d_workspace, st)
-               : decode_impl<float>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden, d_workspace, st);
+    const Workspace w = carve(m, d_workspace, B);
+    const TokenStore ts{d_tokens_out, w.ctr + 1, B};
+    hipLaunchKernelGGL(counters_set_kernel, dim3(1), dim3(1), 0, st, w.ctr, pos0, 0);
+    HIP_TRY(hipGetLastError());
+    // first step eagerly (it also performs every one-time kernel attribute set-up)
+    SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed));
+    if (G == 1) return SRM_OK;
+    // The legacy default stream cannot be captured: loop eagerly there.
+    if (st == nullptr) {
+        for (int g = 1; g < G; ++g)
+            SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed));
+        return SRM_OK;
+    }
+    const bool hit = m->gexec && m->gkey.B == B && m->gkey.tok == d_tok && m->gkey.state == d_state &&
+                     m->gkey.store == d_tokens_out && m->gkey.ws == d_workspace && m->gkey.temp == temperature &&
+                     m->gkey.seed == seed;
+    if (!hit) {
+        if (m->gexec) { (void)hipGraphExecDestroy(m->gexec); m->gexec = nullptr; }
+        hipGraph_t graph = nullptr;
+        HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+        const int rc = generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed);
+        const hipError_t e = hipStreamEndCapture(st, &graph);
+        if (rc != SRM_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+        if (e != hipSuccess) return fail(SRM_EHIP, "srm_generate: stream capture failed: %s", hipGetErrorString(e));
+        const hipError_t e2 = hipGraphInstantiate(&m->gexec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (e2 != hipSuccess) { m->gexec = nullptr; return fail(SRM_EHIP, "srm_generate: hipGraphInstantiate: %s", hipGetErrorString(e2)); }
+        m->gkey = {B, d_tok, d_state, d_tokens_out, d_workspace, temperature, seed};
+        // the captured step was recorded, not run: replay it G - 1 times below
+    }
+    for (int g = 1; g < G; ++g) HIP_TRY(hipGraphLaunch(m->gexec, st));
+    return SRM_OK;
 }
 
 // ------------------------------------------------------------------ prefill

@@ -238,3 +238,134 @@ def test_small_and_ragged_batches_match_oracle(srm, orc_mod, B):
     st1, t1 = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
     model.prefill(to_dev(toks[:, :1]), 1, st1, t1, logits=lg, workspace=model.new_workspace(B))
     assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, 0]) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype_name", ["fp32", "bf16"])
+def test_generate_equals_decode_steps(srm, dtype_name):
+    """srm_generate (one captured step replayed from a HIP graph, position in device memory) gives the
+    tokens and state of the same number of srm_decode_step calls: on a capturable stream (graph), again
+    with the cached graph after other work, and on the legacy default stream (eager loop)."""
+    d = 64 if dtype_name == "bf16" else 32
+    cfg = srm_synth.tiny_config(vocab=300, d_model=d, n_layers=3, n_heads=4, n_ctx=48,
+                                weight_dtype=dtype_name, seed=61)
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    B, P, G = 37, 5, 20
+    prompts = to_dev(srm_synth.make_prompts(cfg, batch=B, length=P))
+    ws = model.new_workspace(B * P)
+
+    def fresh():
+        st, tk = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+        model.prefill(prompts, 1, st, tk, workspace=ws)
+        return st, tk
+
+    st_ref, tk_ref = fresh()
+    ref = torch.empty((G, B), dtype=torch.int32, device="cuda")
+    for g in range(G):
+        model.decode_step(B, P + g, tk_ref, st_ref, tk_ref, workspace=ws)
+        ref[g] = tk_ref
+    torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    out = torch.full((G, B), -1, dtype=torch.int32, device="cuda")
+    st, tk = fresh()
+    for attempt in range(3):                      # 0: capture, 1 and 2: cached graph
+        if attempt:
+            st.copy_(st0); tk.copy_(tk0); out.fill_(-1)
+            junk = torch.randn(1 << 20, device="cuda").sum()      # unrelated eager work in between
+            torch.cuda.synchronize()
+        else:
+            st0, tk0 = st.clone(), tk.clone()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            model.generate(B, P, G, tk, st, out, workspace=ws)
+        side.synchronize()
+        assert torch.equal(out, ref), f"attempt {attempt}"
+        assert torch.equal(tk, tk_ref) and torch.equal(st, st_ref), f"attempt {attempt}"
+    # legacy default stream: eager loop inside the library
+    st.copy_(st0); tk.copy_(tk0); out.fill_(-1)
+    model.generate(B, P, G, tk, st, out, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref) and torch.equal(st, st_ref)
+    with pytest.raises(srm.SrmError):
+        model.generate(B, 40, 20, tk, st, out, workspace=ws)          # runs past n_ctx
+
+
+# ------------------------------------------------------------------ sampling (temperature, Gumbel-max)
+def _sampled_run(model, prompts_np, G, temperature, seed, use_generate):
+    """Prefill all but the last prompt token, then G sampled decode steps starting with the last one."""
+    B, P = prompts_np.shape
+    dp = to_dev(prompts_np)
+    ws = model.new_workspace(B * P)
+    st, tk = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    if P > 1:
+        model.prefill(dp[:, :P - 1].contiguous(), 1, st, tk, workspace=ws)
+    tk.copy_(dp[:, P - 1])
+    out = torch.empty((G, B), dtype=torch.int32, device="cuda")
+    if use_generate:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            model.generate(B, P - 1, G, tk, st, out, workspace=ws, temperature=temperature, seed=seed)
+        side.synchronize()
+    else:
+        for g in range(G):
+            model.decode_step(B, P - 1 + g, tk, st, tk, workspace=ws, temperature=temperature, seed=seed)
+            out[g] = tk
+    torch.cuda.synchronize()
+    return out.cpu().numpy().T
+
+
+@pytest.mark.parametrize("use_generate", [False, True])
+def test_sampled_decode_matches_oracle_fp32(srm, orc_mod, use_generate):
+    cfg = srm_synth.CONFIGS["C1"]
+    w = srm_synth.make_weights(cfg)
+    prompts = srm_synth.make_prompts(cfg)
+    prompts[1] = prompts[0]                                   # two replicas of one prompt
+    G, T, seed = 24, 0.7, 12345
+    ref = orc_mod.Oracle(cfg, w, "f64").greedy(prompts, G, want_logits=True, temperature=T, seed=seed)
+    model = srm.Model(cfg, w)
+    got = _sampled_run(model, prompts, G, T, seed, use_generate)
+    absmax = np.abs(ref["logits"]).max(axis=2)
+    ties = check_tokens(got, ref["tokens"], ref["margin"], absmax)
+    assert ties == 0
+    assert (got[0] != got[1]).any()                            # replicas diverge under sampling
+    # another seed gives another stream; temperature 0 reproduces greedy
+    other = _sampled_run(model, prompts, G, T, seed + 1, use_generate)
+    assert (other != got).any()
+    greedy = orc_mod.Oracle(cfg, w, "f64").greedy(prompts, G)
+    np.testing.assert_array_equal(_sampled_run(model, prompts, G, 0.0, seed, use_generate), greedy["tokens"])
+
+
+@pytest.mark.parametrize("dtype_name,B", [("fp32", 3), ("fp32", 70), ("bf16", 300)])
+def test_sampled_frequencies_follow_softmax(srm, orc_mod, dtype_name, B):
+    """Many replicas of one state at one position: the sampled tokens are distributed as
+    softmax(logits / T) of the oracle's logits (chi-square over the likeliest tokens), and each
+    single choice equals the oracle's choice from the GPU's own logits."""
+    import scipy.stats
+    d = 64 if dtype_name == "bf16" else 32
+    cfg = srm_synth.tiny_config(vocab=40, d_model=d, n_layers=2, n_heads=4, n_ctx=8, weight_dtype=dtype_name, seed=71)
+    w = srm_synth.make_weights(cfg, stress=True)
+    w["head"] *= 40.0                                          # spread the logits
+    if dtype_name == "bf16":
+        w["head"] = srm_synth.round_to_bf16(w["head"])
+    model = srm.Model(cfg, w)
+    R, T, seed = B * 400, 1.3, 99
+    tok = torch.full((R,), 7, dtype=torch.int32, device="cuda")
+    st = model.new_state(R)
+    ws = model.new_workspace(R)
+    lg = torch.empty((R, cfg.vocab), dtype=torch.float32, device="cuda")
+    out = torch.empty(R, dtype=torch.int32, device="cuda")
+    model.decode_step(R, 0, tok, st, out, logits=lg, workspace=ws, temperature=T, seed=seed)
+    torch.cuda.synchronize()
+    got, logits = out.cpu().numpy(), lg.cpu().numpy()
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(np.array([[7]], np.int32))["logits"][0, 0]
+    assert np.abs(logits[0] - ref).max() <= (2e-2 if dtype_name == "bf16" else 1e-4) * np.abs(ref).max()
+    p = np.exp((ref - ref.max()) / T); p /= p.sum()
+    keep = p * R >= 20
+    counts = np.bincount(got, minlength=cfg.vocab)
+    obs = np.append(counts[keep], counts[~keep].sum()); exp = np.append(p[keep], p[~keep].sum()) * R
+    assert scipy.stats.chisquare(obs, exp).pvalue > 1e-4
+    # per-row identity against the oracle's rule applied to the GPU's own logits (rows share logits)
+    for b in list(range(0, R, max(1, R // 64)))[:64]:
+        assert got[b] == orc_mod.pick(logits[b], T, seed, 0, b)

@@ -372,3 +372,68 @@ def test_bad_arguments_are_rejected(tiny):
         orc.recurrent_forward(np.full((1, 2), cfg.vocab, np.int32))       # token out of range
     with pytest.raises(ValueError):
         orc.parallel_forward(np.zeros((1, 17), np.int32))
+
+
+# ---- sampler: counter-based draws and the Gumbel-max rule --------------------------------
+def test_counter_draws_are_uniform_and_decorrelated(oracle_mod):
+    import scipy.stats
+    n = 40000
+    along_v = np.array([oracle_mod.uniform(3, 17, 5, v) for v in range(n)])
+    along_b = np.array([oracle_mod.uniform(3, 17, b, 9) for b in range(n)])
+    along_p = np.array([oracle_mod.uniform(3, p, 5, 9) for p in range(4000)])
+    for u in (along_v, along_b, along_p):
+        assert ((u > 0) & (u < 1)).all()
+        assert abs(u.mean() - 0.5) < 4 * np.sqrt(1 / 12 / u.size)
+        assert abs(u.var() - 1 / 12) < 0.004
+        assert scipy.stats.kstest(u, "uniform").pvalue > 1e-3
+        assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 5 / np.sqrt(u.size)
+    # the four counter fields are not interchangeable and every one matters
+    base = oracle_mod.uniform(1, 2, 3, 4)
+    assert len({base, oracle_mod.uniform(2, 1, 3, 4), oracle_mod.uniform(1, 3, 2, 4), oracle_mod.uniform(1, 2, 4, 3),
+                oracle_mod.uniform(0, 2, 3, 4), oracle_mod.uniform(1, 2, 3, 5)}) == 6
+    assert oracle_mod.uniform(1, 2, 3, 4) == base                      # pure function
+
+
+def test_gumbel_variates_have_gumbel_moments(oracle_mod):
+    g = np.array([oracle_mod.gumbel(11, 0, b, 0) for b in range(50000)])
+    assert abs(g.mean() - 0.5772156649) < 0.03                          # Euler-Mascheroni
+    assert abs(g.var() - np.pi ** 2 / 6) < 0.06
+    # transformation written out once more: g = -log(-log(1 - w))
+    w = oracle_mod.uniform(11, 0, 7, 0)
+    assert abs(oracle_mod.gumbel(11, 0, 7, 0) + np.log(-np.log1p(-w))) < 1e-12
+
+
+def test_gumbel_max_frequencies_follow_softmax(oracle_mod):
+    import scipy.stats
+    logits = np.array([1.2, -0.3, 0.4, 2.0, 0.0, -1.5])
+    T = 0.7
+    p = np.exp(logits / T); p /= p.sum()
+    n = 60000
+    counts = np.bincount([oracle_mod.pick(logits, T, 5, 3, b) for b in range(n)], minlength=6)
+    assert scipy.stats.chisquare(counts, p * n).pvalue > 1e-3
+    # temperature 0 is the plain argmax; a vanishing temperature agrees with it
+    assert oracle_mod.pick(logits, 0.0, 5, 3, 0) == 3
+    assert all(oracle_mod.pick(logits, 1e-9, 5, 3, b) == 3 for b in range(50))
+    # ties go to the lowest index in the greedy case
+    assert oracle_mod.pick(np.array([0.5, 2.0, 2.0]), 0.0, 0, 0, 0) == 1
+
+
+def test_sampled_generation_is_reproducible_and_seed_dependent(oracle_mod):
+    cfg = srm_synth.tiny_config(vocab=48, d_model=16, n_layers=2, n_heads=4, n_ctx=24, seed=21)
+    w = srm_synth.make_weights(cfg, stress=True)
+    orc = oracle_mod.Oracle(cfg, w, "f64")
+    prompts = np.repeat(srm_synth.make_prompts(cfg, batch=1, length=6), 8, axis=0)     # 8 replicas of one prompt
+    a = orc.greedy(prompts, 10, temperature=0.9, seed=4, want_logits=True)
+    b = orc.greedy(prompts, 10, temperature=0.9, seed=4)
+    c = orc.greedy(prompts, 10, temperature=0.9, seed=5)
+    np.testing.assert_array_equal(a["tokens"], b["tokens"])
+    assert (a["tokens"] != c["tokens"]).any()
+    assert len({tuple(r) for r in a["tokens"]}) > 1                   # replicas diverge under sampling
+    # every choice is the argmax of logit + T * gumbel with the documented counter (pos, b)
+    for bb in range(8):
+        for g in range(10):
+            sc = a["logits"][bb, g] + 0.9 * np.array([oracle_mod.gumbel(4, 5 + g, bb, v) for v in range(cfg.vocab)])
+            assert a["tokens"][bb, g] == int(np.argmax(sc))
+    # b0 shifts the sample index: rows 4..7 of a run equal a 4-row run started at b0 = 4
+    d4 = orc.greedy(prompts[4:], 10, temperature=0.9, seed=4, b0=4)
+    np.testing.assert_array_equal(d4["tokens"], a["tokens"][4:])
