@@ -185,6 +185,55 @@ int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, int32_t P, in
                 void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Decode step with one position per sample, for batches whose samples are at
+ * different positions (prompts of different lengths, slots that join and leave
+ * a running batch).  The recurrent form makes this free: a sample's cache has
+ * the same size at every position (Eq. 2, Eq. 3), so samples at different
+ * positions share one batch without padding; only alpha and beta are looked up
+ * per sample.  d_pos[B] (device, int32) holds each sample's absolute position.
+ * A sample whose position is outside [0, n_ctx) is inactive: its state is left
+ * untouched and d_tok_out gets -1 for it (its d_tok_in is still read and may be
+ * any value).  With advance != 0 the position of every active sample is
+ * incremented on the device at the end of the step, so a loop of calls needs no
+ * host-side update.  temperature = 0 is greedy; temperature > 0 samples as
+ * srm_decode_step_sampled does, keyed on the sample's own position.  For active
+ * samples the result equals srm_decode_step(_sampled) at that position.
+ * d_logits: optional [B][vocab].
+ * Errors: SRM_EINVAL (null pointer, B out of range, negative temperature),
+ * SRM_ENOMEM (workspace smaller than srm_workspace_bytes(m, B)), SRM_EHIP.
+ */
+int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, int32_t advance,
+                           const int32_t *d_tok_in, float *d_state, int32_t *d_tok_out,
+                           float temperature, uint32_t seed, float *d_logits,
+                           void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * srm_prefill for N prompts of different lengths, packed back to back in
+ * d_tokens: prompt n is d_tokens[offsets[n] .. offsets[n+1]-1], positions
+ * 0 .. length-1, from a zero state.  The offsets (N + 1 values, int32) are
+ * passed twice: h_offsets in host memory, which the call validates (every
+ * length in [1, n_ctx]) and uses to cut the work into passes of whole prompts
+ * that fit the workspace, and d_offsets, the same values in device memory, which
+ * the kernels read (clamped, so a mismatch cannot cause an access outside the
+ * workspace; results are then unspecified).
+ * Destination of prompt n in d_state[L][state_batch][d] (only the destination
+ * samples are written), d_next_tok[state_batch] and, if not NULL,
+ * d_pos[state_batch] (set to the prompt's length, the position of the next
+ * token): with d_slot == NULL the fanout_k consecutive samples
+ * n*fanout_k + r; with d_slot (device, int32 [N], fanout_k must be 1) sample
+ * d_slot[n], skipped if outside [0, state_batch) - this admits new prompts
+ * into free slots of a running batch.  d_logits: optional [N][vocab], last
+ * position of each prompt.  The first token is greedy.
+ * Errors: SRM_EINVAL (null pointer, N or fanout_k <= 0, a length outside
+ * [1, n_ctx], N*fanout_k > state_batch, slots with fanout_k != 1), SRM_ENOMEM
+ * (workspace smaller than srm_workspace_bytes(m, longest prompt)), SRM_EHIP.
+ */
+int srm_prefill_ragged(srm_model *m, const int32_t *d_tokens, const int32_t *h_offsets,
+                       const int32_t *d_offsets, int32_t N, int32_t fanout_k, const int32_t *d_slot,
+                       int64_t state_batch, float *d_state, int32_t *d_next_tok, int32_t *d_pos,
+                       float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Parallel (sequence) form over d_tok[B][T], positions 0..T-1: identical model,
  * but the mixer is the explicit structured triangular product Y = U M + beta
  * with M built from alpha and lambda as in Eq. 1 (row-repeat heads) and Eq. 3

@@ -68,6 +68,10 @@ def lib():
         L.srm_decode_step_sampled.argtypes = [vp, i64, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, vp, vp, sz, vp]
         L.srm_prefill.restype = C.c_int
         L.srm_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.srm_decode_step_ragged.restype = C.c_int
+        L.srm_decode_step_ragged.argtypes = [vp, i64, vp, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, vp, sz, vp]
+        L.srm_prefill_ragged.restype = C.c_int
+        L.srm_prefill_ragged.argtypes = [vp, vp, vp, vp, i32, i32, vp, i64, vp, vp, vp, vp, vp, sz, vp]
         L.srm_parallel_forward.restype = C.c_int
         L.srm_parallel_forward.argtypes = [vp, vp, i32, i32, vp, vp, vp, sz, vp]
         L.srm_mixer_update.restype = C.c_int
@@ -220,6 +224,47 @@ class Model:
         p_ws = _dev(workspace, torch.uint8, 1, "workspace")
         _check(lib().srm_prefill(self._h, p_pr, N, P, fanout_k, p_st, p_nt, p_lg, p_ws,
                                  workspace.numel(), _stream(stream)))
+
+    def decode_step_ragged(self, B, pos, tok_in, state, tok_out, advance=True, temperature=0.0, seed=0,
+                           logits=None, workspace=None, stream=None):
+        """One step with per-sample positions pos[B] (device int32, advanced in place if asked)."""
+        torch = _torch()
+        p_pos = _dev(pos, torch.int32, B, "pos")
+        p_in = _dev(tok_in, torch.int32, B, "tok_in")
+        p_st = _dev(state, torch.float32, self.L * B * self.d, "state")
+        if state.numel() != self.L * B * self.d:
+            raise ValueError("state: must be exactly [L][B][d]")
+        p_out = _dev(tok_out, torch.int32, B, "tok_out")
+        p_lg = None if logits is None else _dev(logits, torch.float32, B * self.vocab, "logits")
+        p_ws = _dev(workspace, torch.uint8, 1, "workspace")
+        _check(lib().srm_decode_step_ragged(self._h, B, p_pos, 1 if advance else 0, p_in, p_st, p_out,
+                                            float(temperature), int(seed), p_lg, p_ws, workspace.numel(),
+                                            _stream(stream)))
+
+    def prefill_ragged(self, tokens, offsets, state, next_tok, fanout_k=1, slot=None, pos=None, logits=None,
+                       workspace=None, stream=None):
+        """Packed prompts of different lengths; offsets: host int32 sequence of N + 1 boundaries."""
+        import numpy as np
+        torch = _torch()
+        h_off = np.ascontiguousarray(offsets, dtype=np.int32)
+        N = h_off.size - 1
+        if N < 1:
+            raise ValueError("offsets: need at least two boundaries")
+        d_off = torch.from_numpy(h_off).to(tokens.device)
+        Bt = state.numel() // (self.L * self.d)
+        if state.numel() != self.L * Bt * self.d:
+            raise ValueError("state: must be [L][state_batch][d]")
+        p_tk = _dev(tokens, torch.int32, int(h_off[-1]), "tokens")
+        p_st = _dev(state, torch.float32, self.L * Bt * self.d, "state")
+        p_nt = _dev(next_tok, torch.int32, Bt, "next_tok")
+        p_sl = None if slot is None else _dev(slot, torch.int32, N, "slot")
+        p_pos = None if pos is None else _dev(pos, torch.int32, Bt, "pos")
+        p_lg = None if logits is None else _dev(logits, torch.float32, N * self.vocab, "logits")
+        p_ws = _dev(workspace, torch.uint8, 1, "workspace")
+        _check(lib().srm_prefill_ragged(self._h, p_tk, h_off.ctypes.data, _dev(d_off, torch.int32, N + 1, "offsets"),
+                                        N, fanout_k, p_sl, Bt, p_st, p_nt, p_pos, p_lg, p_ws, workspace.numel(),
+                                        _stream(stream)))
+        return d_off      # kept alive by the caller until the stream has run the call
 
     def parallel_forward(self, tok, hidden, logits=None, workspace=None, stream=None):
         torch = _torch()

@@ -28,11 +28,17 @@ struct GemmEpi {
     // i.e. a sample from softmax(logits / temp); stored logits stay the raw ones.
     float temp;
     uint32_t seed;
-    int32_t pos;         // position of the counter, unless pos_dev is set
-    const int *pos_dev;
+    int32_t pos;         // position of the counter, unless pos_dev or pos_rows is set
+    const int *pos_dev;  // one position for all rows, in device memory
+    const int *pos_rows; // [M] one position per row, in device memory
 };
 
-__device__ __forceinline__ uint32_t epi_pos(const GemmEpi &ep) { return (uint32_t)(ep.pos_dev ? *ep.pos_dev : ep.pos); }
+// Position that keys the random numbers of output row `row` (rows >= M read nothing).
+__device__ __forceinline__ uint32_t epi_pos(const GemmEpi &ep, int64_t row, int M)
+{
+    if (ep.pos_rows) return row < M ? (uint32_t)ep.pos_rows[row] : 0u;
+    return (uint32_t)(ep.pos_dev ? *ep.pos_dev : ep.pos);
+}
 
 // Block -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs, each
 // with its own L2: give every XCD one contiguous run of tiles, and inside a run
@@ -180,7 +186,8 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
             float bv = -INFINITY;
             int brel = 0;
             if (ep.temp > 0.0f) {
-                const uint32_t rk = srm_rowkey(ep.seed, epi_pos(ep), (uint32_t)(m0 + wm * WTM + i * 32 + lr));
+                const int srow = m0 + wm * WTM + i * 32 + lr;
+                const uint32_t rk = srm_rowkey(ep.seed, epi_pos(ep, srow, M), (uint32_t)srow);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -466,7 +473,7 @@ gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
             if (row < M) epi_store<EPI, float>(ep, row, col, v);
             if constexpr (EPI == EPI_ARGMAX) {
                 const float vs = ep.temp > 0.0f
-                                     ? v + ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep), (uint32_t)row), (uint32_t)col)
+                                     ? v + ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep, row, M), (uint32_t)row), (uint32_t)col)
                                      : v;
                 if (arg_better(vs, col, bv, bi)) { bv = vs; bi = col; }
             }
@@ -544,7 +551,7 @@ gemv_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
             }
             if constexpr (EPI == EPI_ARGMAX) {
                 if (live && ep.temp > 0.0f)
-                    v += ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep), (uint32_t)row), (uint32_t)n);
+                    v += ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep, row, M), (uint32_t)row), (uint32_t)n);
                 float bv = live ? v : -INFINITY;
                 int bi = live ? n : 0x7fffffff;
 #pragma unroll
@@ -562,6 +569,17 @@ gemv_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
     }
 }
 
+// Optional behaviour of argmax_finalize_kernel for ragged batches.
+struct FinalizeRagged {
+    const int32_t *slot;      // destination index of sequence row0 + row (replaces the (row0 + row) * rep rule)
+    int64_t nslots;           // destinations outside [0, nslots) are skipped
+    int32_t *pos_rows;        // decode: position of each row; a row outside [0, n_ctx) is inactive -> token -1
+    int32_t advance;          // decode: add 1 to the position of every active row
+    int32_t n_ctx;
+    const int32_t *offsets;   // prefill: sequence boundaries, offsets[row0 + row + 1] - offsets[row0 + row] = length
+    int32_t *pos_set;         // prefill: pos_set[destination] = length of the sequence
+};
+
 // Reduce the per-tile partials of each row to one token; writes `rep`
 // consecutive copies starting at out[(row0 + row) * rep].  One wave per row.
 // A row without any ordered value (all NaN) yields token 0, so that the id is
@@ -571,7 +589,7 @@ __global__ void __launch_bounds__(256)
 argmax_finalize_kernel(const float *__restrict__ part_val, const int32_t *__restrict__ part_idx,
                        int64_t rows, int nparts, int32_t *__restrict__ out, int64_t row0, int rep,
                        int vocab, int32_t *__restrict__ store, const int *__restrict__ step_dev,
-                       int64_t store_stride)
+                       int64_t store_stride, FinalizeRagged rg)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -590,7 +608,24 @@ argmax_finalize_kernel(const float *__restrict__ part_val, const int32_t *__rest
         if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
     }
     if (bi < 0 || bi >= vocab) bi = 0;
-    for (int r = lane; r < rep; r += kWave) out[(row0 + row) * rep + r] = bi;
+    if (rg.pos_rows) {
+        const int p = rg.pos_rows[row0 + row];
+        const bool active = p >= 0 && p < rg.n_ctx;
+        if (!active) bi = -1;
+        else if (rg.advance && lane == 0) rg.pos_rows[row0 + row] = p + 1;
+    }
+    if (rg.slot) {
+        const int64_t dst = rg.slot[row0 + row];
+        if (lane == 0 && dst >= 0 && dst < rg.nslots) {
+            out[dst] = bi;
+            if (rg.pos_set) rg.pos_set[dst] = rg.offsets[row0 + row + 1] - rg.offsets[row0 + row];
+        }
+        return;
+    }
+    for (int r = lane; r < rep; r += kWave) {
+        out[(row0 + row) * rep + r] = bi;
+        if (rg.pos_set) rg.pos_set[(row0 + row) * rep + r] = rg.offsets[row0 + row + 1] - rg.offsets[row0 + row];
+    }
     if (store) {
         int32_t *dst = store + (int64_t)(*step_dev) * store_stride;
         for (int r = lane; r < rep; r += kWave) dst[(row0 + row) * rep + r] = bi;

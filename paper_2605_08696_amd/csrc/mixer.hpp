@@ -118,6 +118,101 @@ mixer_scan_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__res
     for (int r = 0; r < rep; ++r) store4(dst + (int64_t)r * d, s);
 }
 
+// Decode with one position per sample (ragged batches, continuous batching):
+// pos_rows[b] is sample b's position; a sample whose position is outside
+// [0, n_ctx) is inactive: its state is left as it is and its m row is zero.
+// Thread = (sample, 4 channels); alpha and beta come straight from the tables
+// (a few KB, cache resident).
+template <typename TAct>
+__global__ void __launch_bounds__(256)
+state_update_ragged_kernel(const TAct *__restrict__ u, float *__restrict__ S, TAct *__restrict__ m,
+                           const float *__restrict__ alpha, const float *__restrict__ beta,
+                           const float *__restrict__ lam, const int *__restrict__ pos_rows, int n_ctx, int H,
+                           int d, int64_t nvec)
+{
+    const int dv = d >> 2, dhv = (d / H) >> 2;
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= nvec) return;
+    const int64_t b = j / dv;
+    const int h = (int)(j - b * dv) / dhv;
+    const int pos = pos_rows[b];
+    if (pos < 0 || pos >= n_ctx) {
+        store4(m + j * 4, make_float4(0.f, 0.f, 0.f, 0.f));
+        return;
+    }
+    const float a = alpha[(size_t)h * n_ctx + pos], be = beta[(size_t)h * n_ctx + pos], l = lam[h];
+    const bool row_repeat = h < H / 2;
+    const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
+    const f32x4_t sv = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(S) + j);
+    const float4 x = load4(u + j * 4);
+    float4 o;
+    f32x4_t nv;
+    nv[0] = fmaf(l, sv[0], p * x.x); o.x = fmaf(q, nv[0], be);
+    nv[1] = fmaf(l, sv[1], p * x.y); o.y = fmaf(q, nv[1], be);
+    nv[2] = fmaf(l, sv[2], p * x.z); o.z = fmaf(q, nv[2], be);
+    nv[3] = fmaf(l, sv[3], p * x.w); o.w = fmaf(q, nv[3], be);
+    __builtin_nontemporal_store(nv, reinterpret_cast<f32x4_t *>(S) + j);
+    store4(m + j * 4, o);
+}
+
+// Prefill of packed sequences of different lengths: u, m are [rows][d] holding
+// the sequences back to back; sequence s (0 <= s < nseq) occupies rows
+// offsets[seq0 + s] - base .. offsets[seq0 + s + 1] - base - 1 (clamped to
+// [0, rows), so that no access depends on the array being well formed) and is
+// scanned from a zero state, positions 0.. (at most Pmax, the longest length of
+// the launch).  Its final state goes to sample slot[seq0 + s] if slot is given
+// (skipped when outside [0, nslots)), else to the `rep` samples
+// (seq0 + s) * rep + r.  Dynamic LDS: 2 * H * Pmax floats.
+template <typename TAct>
+__global__ void __launch_bounds__(256)
+mixer_scan_ragged_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__restrict__ S,
+                         const float *__restrict__ alpha, const float *__restrict__ beta,
+                         const float *__restrict__ lam, int n_ctx, int H, int d, int nseq, int Pmax,
+                         const int32_t *__restrict__ offsets, int64_t base, int64_t rows, int64_t seq0, int rep,
+                         const int32_t *__restrict__ slot, int64_t nslots)
+{
+    extern __shared__ float sc[];
+    float *sa = sc, *sb = sc + H * Pmax;
+    for (int i = threadIdx.x; i < H * Pmax; i += 256) {
+        const int h = i / Pmax, t = i - h * Pmax;
+        sa[i] = alpha[(size_t)h * n_ctx + t];
+        sb[i] = beta[(size_t)h * n_ctx + t];
+    }
+    __syncthreads();
+    const int dv = d >> 2, dhv = (d / H) >> 2;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t seq = gid / dv;
+    if (seq >= nseq) return;
+    const int cv = (int)(gid - seq * dv);
+    const int h = cv / dhv;
+    const bool row_repeat = h < H / 2;
+    const float l = lam[h];
+    const int64_t r0 = min(max((int64_t)offsets[seq0 + seq] - base, (int64_t)0), rows);
+    const int64_t r1 = min(max((int64_t)offsets[seq0 + seq + 1] - base, r0), rows);
+    const int len = (int)min(r1 - r0, (int64_t)Pmax);
+    const TAct *up = u + r0 * (int64_t)d + cv * 4;
+    TAct *mp = m + r0 * (int64_t)d + cv * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int t = 0; t < len; ++t) {
+        const float4 x = load4(up + (int64_t)t * d);
+        const float a = sa[h * Pmax + t], be = sb[h * Pmax + t];
+        const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
+        float4 o;
+        s.x = fmaf(l, s.x, p * x.x); o.x = fmaf(q, s.x, be);
+        s.y = fmaf(l, s.y, p * x.y); o.y = fmaf(q, s.y, be);
+        s.z = fmaf(l, s.z, p * x.z); o.z = fmaf(q, s.z, be);
+        s.w = fmaf(l, s.w, p * x.w); o.w = fmaf(q, s.w, be);
+        store4(mp + (int64_t)t * d, o);
+    }
+    if (slot) {
+        const int64_t dst = slot[seq0 + seq];
+        if (dst >= 0 && dst < nslots) store4(S + dst * (int64_t)d + cv * 4, s);
+    } else {
+        float *dst = S + ((seq0 + seq) * rep) * (int64_t)d + cv * 4;
+        for (int r = 0; r < rep; ++r) store4(dst + (int64_t)r * d, s);
+    }
+}
+
 // Parallel form.  U, Y: [B][T][d].  grid = (ceil(T/64), H * ceil(d_h/64), B);
 // a block owns 64 output positions j x up to 64 channels c of one head and sums
 // over source positions i <= j in tiles of 64:

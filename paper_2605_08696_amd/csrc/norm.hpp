@@ -9,13 +9,16 @@
 
 // VPL = float4 vectors per lane: covers d <= 256 * VPL.
 //   GATHER: x = embed[tok[row]] is fetched, stored to x_out (fp32) and normalised.
-//   else:   x is read from x_in + row * in_stride.
+//   else:   x is read from x_in + row * in_stride, or, if seq_end is given, from
+//           the last row of packed sequence `row`: source row seq_end[row + 1] - 1 - base,
+//           clamped to [0, src_rows).
 template <typename TW, typename TAct, int VPL, bool GATHER>
 __global__ void __launch_bounds__(256)
 ln_kernel(const float *__restrict__ x_in, int64_t in_stride, const int32_t *__restrict__ tok,
           const TW *__restrict__ embed, int vocab, float *__restrict__ x_out,
           const float *__restrict__ g, const float *__restrict__ b, TAct *__restrict__ out,
-          int64_t rows, int d, float eps)
+          int64_t rows, int d, float eps, const int32_t *__restrict__ seq_end = nullptr, int64_t base = 0,
+          int64_t src_rows = 0)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -24,6 +27,8 @@ ln_kernel(const float *__restrict__ x_in, int64_t in_stride, const int32_t *__re
     float4 v[VPL];
     float sum = 0.0f;
     const TW *erow = nullptr;
+    int64_t src = row;
+    if (!GATHER && seq_end) src = min(max((int64_t)seq_end[row + 1] - 1 - base, (int64_t)0), src_rows - 1);
     if constexpr (GATHER) {
         int t = tok[row];
         t = min(max(t, 0), vocab - 1);          // never read outside the table
@@ -37,7 +42,7 @@ ln_kernel(const float *__restrict__ x_in, int64_t in_stride, const int32_t *__re
                 v[i] = load4(erow + c);
                 store4(x_out + row * d + c, v[i]);
             } else {
-                v[i] = load4(x_in + row * in_stride + c);
+                v[i] = load4(x_in + src * in_stride + c);
             }
             sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
         } else {

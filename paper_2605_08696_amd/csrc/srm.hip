@@ -336,6 +336,7 @@ struct Sampling {          // temp == 0: greedy
     uint32_t seed = 0;
     int pos = 0;
     const int *pos_dev = nullptr;
+    const int *pos_rows = nullptr;
 };
 
 // out = epilogue(A W^T + bias) with operands of type T (float or bf16)
@@ -344,7 +345,7 @@ static int linear(const void *A, const void *W, const float *bias, int64_t M, in
                   hipStream_t st, float *pv = nullptr, int32_t *pi = nullptr, int min_bn = 64,
                   int *nparts_out = nullptr, Sampling sm = Sampling())
 {
-    GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev};
+    GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows};
     if constexpr (sizeof(T) == 2)
         return launch_bf16<EPI, bf16>(static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), M, N, K, ep,
                                       st, min_bn, nparts_out);
@@ -360,17 +361,19 @@ struct TokenStore {        // optional second destination of the greedy tokens (
 };
 
 static int argmax_finalize(const float *pv, const int32_t *pi, int64_t rows, int nparts, int32_t *out,
-                           int64_t row0, int rep, int vocab, hipStream_t st, TokenStore ts = TokenStore())
+                           int64_t row0, int rep, int vocab, hipStream_t st, TokenStore ts = TokenStore(),
+                           FinalizeRagged rg = FinalizeRagged{})
 {
     hipLaunchKernelGGL(argmax_finalize_kernel, dim3((unsigned)cdiv(rows, 4)), dim3(256), 0, st, pv, pi, rows,
-                       nparts, out, row0, rep, vocab, ts.store, ts.step_dev, ts.stride);
+                       nparts, out, row0, rep, vocab, ts.store, ts.step_dev, ts.stride, rg);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
 
 template <typename T, bool GATHER>
 static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, const int32_t *tok,
-                     float *x_out, const float *g, const float *b, void *out, int64_t rows, hipStream_t st)
+                     float *x_out, const float *g, const float *b, void *out, int64_t rows, hipStream_t st,
+                     const int32_t *seq_end = nullptr, int64_t base = 0, int64_t src_rows = 0)
 {
     const int d = m->d;
     const unsigned nb = (unsigned)cdiv(rows, 4);
@@ -378,7 +381,7 @@ static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, c
     T *o = static_cast<T *>(out);
 #define LN_CASE(VPL)                                                                                     \
     hipLaunchKernelGGL((ln_kernel<T, T, VPL, GATHER>), dim3(nb), dim3(256), 0, st, x_in, in_stride, tok, \
-                       emb, m->V, x_out, g, b, o, rows, d, m->cfg.ln_eps)
+                       emb, m->V, x_out, g, b, o, rows, d, m->cfg.ln_eps, seq_end, base, src_rows)
     if (d <= 256) LN_CASE(1);
     else if (d <= 512) LN_CASE(2);
     else if (d <= 1024) LN_CASE(4);
@@ -453,12 +456,12 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
 template <typename T>
 static int head_argmax(const srm_model *m, const Workspace &w, const void *a, int64_t M, float *logits,
                        int32_t *d_tok, int64_t row0, int rep, hipStream_t st, TokenStore ts = TokenStore(),
-                       Sampling sm = Sampling())
+                       Sampling sm = Sampling(), FinalizeRagged rg = FinalizeRagged{})
 {
     int nparts = 0;
     SRM_TRY((linear<EPI_ARGMAX, T>(a, m->head, nullptr, M, m->V, m->d, logits, st, w.pv, w.pi, head_min_bn(m),
                                    &nparts, sm)));
-    return argmax_finalize(w.pv, w.pi, M, nparts, d_tok, row0, rep, m->V, st, ts);
+    return argmax_finalize(w.pv, w.pi, M, nparts, d_tok, row0, rep, m->V, st, ts, rg);
 }
 
 // ------------------------------------------------------------------ decode
@@ -511,6 +514,53 @@ extern "C" int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, con
 {
     return decode_step_common("srm_decode_step_sampled", m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden,
                               d_workspace, workspace_bytes, hip_stream, temperature, seed);
+}
+
+// ------------------------------------------------------------------ decode, one position per sample
+template <typename T>
+static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int advance, const int32_t *tok_in,
+                              float *state, int32_t *tok_out, float *logits, void *ws, hipStream_t st,
+                              float temperature, uint32_t seed)
+{
+    const Workspace w = carve(m, ws, B);
+    const int d = m->d;
+    SRM_TRY((layernorm<T, true>(m, nullptr, 0, tok_in, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a, B, st)));
+    auto mix = [&](int l) {
+        const LayerDev &y = m->layers[l];
+        const int64_t nvec = B * (d / 4);
+        hipLaunchKernelGGL((state_update_ragged_kernel<T>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
+                           static_cast<const T *>(w.u), state + (size_t)l * B * d, static_cast<T *>(w.mx), y.alpha,
+                           y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
+        HIP_TRY(hipGetLastError());
+        return (int)SRM_OK;
+    };
+    for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true)));
+    FinalizeRagged rg{};
+    rg.pos_rows = pos_rows;
+    rg.advance = advance;
+    rg.n_ctx = m->cfg.n_ctx;
+    return head_argmax<T>(m, w, w.a, B, logits, tok_out, 0, 1, st, TokenStore(),
+                          Sampling{temperature, seed, 0, nullptr, pos_rows}, rg);
+}
+
+extern "C" int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, int32_t advance,
+                                      const int32_t *d_tok_in, float *d_state, int32_t *d_tok_out,
+                                      float temperature, uint32_t seed, float *d_logits, void *d_workspace,
+                                      size_t workspace_bytes, void *hip_stream)
+{
+    const char *who = "srm_decode_step_ragged";
+    if (!m || !d_pos || !d_tok_in || !d_state || !d_tok_out || !d_workspace)
+        return fail(SRM_EINVAL, "%s: null argument", who);
+    if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "%s: batch %lld out of range", who, (long long)B);
+    if (!(temperature >= 0.0f)) return fail(SRM_EINVAL, "%s: temperature must be >= 0", who);
+    if (workspace_bytes < srm_workspace_bytes(m, B))
+        return fail(SRM_ENOMEM, "%s: workspace %zu < %zu bytes", who, workspace_bytes, srm_workspace_bytes(m, B));
+    SRM_TRY(check_device(m));
+    hipStream_t st = as_stream(hip_stream);
+    return m->wsize == 2 ? decode_ragged_impl<bf16>(m, B, d_pos, advance != 0, d_tok_in, d_state, d_tok_out, d_logits,
+                                                    d_workspace, st, temperature, seed)
+                         : decode_ragged_impl<float>(m, B, d_pos, advance != 0, d_tok_in, d_state, d_tok_out,
+                                                     d_logits, d_workspace, st, temperature, seed);
 }
 
 // ------------------------------------------------------------------ generate (G steps in one call)
@@ -641,6 +691,99 @@ extern "C" int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, in
                                               d_workspace, per_pass, st)
                          : prefill_impl<float>(m, d_prompts, N, P, fanout_k, d_state, d_next_tok, d_logits,
                                                d_workspace, per_pass, st);
+}
+
+// ------------------------------------------------------------------ prefill of packed ragged prompts
+template <typename T>
+static int prefill_ragged_impl(srm_model *m, const int32_t *tokens, const int32_t *h_off, const int32_t *d_off, int N,
+                               int k, const int32_t *slot, int64_t state_batch, float *state, int32_t *next_tok,
+                               int32_t *pos_out, float *logits, void *ws, int64_t max_rows, hipStream_t st)
+{
+    const int d = m->d;
+    int n0 = 0;
+    while (n0 < N) {
+        // as many whole prompts as the workspace holds
+        int n1 = n0;
+        int pmax = 0;
+        while (n1 < N && (int64_t)h_off[n1 + 1] - h_off[n0] <= max_rows) {
+            pmax = std::max(pmax, h_off[n1 + 1] - h_off[n1]);
+            ++n1;
+        }
+        const int nc = n1 - n0;
+        const int64_t base = h_off[n0], rows = (int64_t)h_off[n1] - base;
+        const Workspace w = carve(m, ws, rows);
+        SRM_TRY((layernorm<T, true>(m, nullptr, 0, tokens + base, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a,
+                                    rows, st)));
+        const size_t scan_lds = (size_t)2 * m->H * pmax * sizeof(float);
+        auto mix = [&](int l) {
+            const LayerDev &y = m->layers[l];
+            const unsigned nb = (unsigned)cdiv((int64_t)nc * (d / 4), 256);
+            hipLaunchKernelGGL((mixer_scan_ragged_kernel<T>), dim3(nb), dim3(256), scan_lds, st,
+                               static_cast<const T *>(w.u), static_cast<T *>(w.mx),
+                               state + (size_t)l * state_batch * d, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc,
+                               pmax, d_off, base, rows, (int64_t)n0, k, slot, state_batch);
+            HIP_TRY(hipGetLastError());
+            return (int)SRM_OK;
+        };
+        for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, rows, st, mix, l + 1 < m->L)));
+        // final LayerNorm of each prompt's last row, packed [nc][d] into w.a
+        SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, m->lnf_g, m->lnf_b, w.a, nc, st, d_off + n0, base,
+                                     rows)));
+        FinalizeRagged rg{};
+        rg.slot = slot;
+        rg.nslots = state_batch;
+        rg.offsets = d_off;
+        rg.pos_set = pos_out;
+        SRM_TRY((head_argmax<T>(m, w, w.a, nc, logits ? logits + (size_t)n0 * m->V : nullptr, next_tok, n0, k, st,
+                                TokenStore(), Sampling(), rg)));
+        n0 = n1;
+    }
+    return SRM_OK;
+}
+
+extern "C" int srm_prefill_ragged(srm_model *m, const int32_t *d_tokens, const int32_t *h_offsets,
+                                  const int32_t *d_offsets, int32_t N, int32_t fanout_k, const int32_t *d_slot,
+                                  int64_t state_batch, float *d_state, int32_t *d_next_tok, int32_t *d_pos,
+                                  float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const char *who = "srm_prefill_ragged";
+    if (!m || !d_tokens || !h_offsets || !d_offsets || !d_state || !d_next_tok || !d_workspace)
+        return fail(SRM_EINVAL, "%s: null argument", who);
+    if (N <= 0 || fanout_k <= 0) return fail(SRM_EINVAL, "%s: N and fanout_k must be positive", who);
+    if (d_slot && fanout_k != 1) return fail(SRM_EINVAL, "%s: a slot list needs fanout_k = 1", who);
+    if (state_batch <= 0 || state_batch >= (1 << 30)) return fail(SRM_EINVAL, "%s: state_batch out of range", who);
+    if (!d_slot && (int64_t)N * fanout_k > state_batch)
+        return fail(SRM_EINVAL, "%s: N * fanout_k = %lld exceeds state_batch = %lld", who, (long long)N * fanout_k,
+                    (long long)state_batch);
+    if (h_offsets[0] < 0) return fail(SRM_EINVAL, "%s: offsets[0] is negative", who);
+    // rows the workspace holds (largest r with srm_workspace_bytes(r) <= workspace_bytes)
+    int64_t lo = 0, hi = (1 << 30) - 1;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) / 2;
+        if (srm_workspace_bytes(m, mid) <= workspace_bytes) lo = mid; else hi = mid - 1;
+    }
+    const int64_t max_rows = lo;
+    int pmax = 0;
+    for (int n = 0; n < N; ++n) {
+        const int64_t len = (int64_t)h_offsets[n + 1] - h_offsets[n];
+        if (len < 1 || len > m->cfg.n_ctx)
+            return fail(SRM_EINVAL, "%s: prompt %d has length %lld outside [1, n_ctx = %d]", who, n, (long long)len,
+                        m->cfg.n_ctx);
+        if (len > max_rows)
+            return fail(SRM_ENOMEM, "%s: workspace %zu < %zu bytes (prompt %d of %lld tokens)", who, workspace_bytes,
+                        srm_workspace_bytes(m, len), n, (long long)len);
+        pmax = std::max(pmax, (int)len);
+    }
+    if ((size_t)2 * m->H * pmax * sizeof(float) > 64 * 1024)
+        return fail(SRM_EINVAL, "%s: n_heads * longest prompt too large for the coefficient stage", who);
+    SRM_TRY(check_device(m));
+    hipStream_t st = as_stream(hip_stream);
+    return m->wsize == 2 ? prefill_ragged_impl<bf16>(m, d_tokens, h_offsets, d_offsets, N, fanout_k, d_slot,
+                                                     state_batch, d_state, d_next_tok, d_pos, d_logits, d_workspace,
+                                                     max_rows, st)
+                         : prefill_ragged_impl<float>(m, d_tokens, h_offsets, d_offsets, N, fanout_k, d_slot,
+                                                      state_batch, d_state, d_next_tok, d_pos, d_logits, d_workspace,
+                                                      max_rows, st);
 }
 
 // ------------------------------------------------------------------ parallel form

@@ -1,0 +1,267 @@
+"""Ragged batches through the C ABI: prompts of different lengths packed back to
+back, decode with one position per sample, slots that join and leave a running
+batch.  Samples are independent, so the oracle's answer for a ragged batch is
+simply each sample run alone on its own prompt."""
+import numpy as np
+import pytest
+import torch
+
+import srm_synth
+from gpu_util import to_dev, rel_err_rows, check_tokens
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def srm():
+    import paper_2605_08696_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def orc_mod(oracle_mod):
+    return oracle_mod
+
+
+@pytest.fixture(scope="module")
+def c1(srm, orc_mod):
+    cfg = srm_synth.CONFIGS["C1"]
+    w = srm_synth.make_weights(cfg)
+    return cfg, w, srm.Model(cfg, w), orc_mod.Oracle(cfg, w, "f64")
+
+
+def _pack(prompts, lengths):
+    toks = np.concatenate([prompts[i, :n] for i, n in enumerate(lengths)]).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    return toks, off
+
+
+def _oracle_streams(orc, prompts, lengths, G, temperature=0.0, seed=0, slots=None):
+    """Per sample: G tokens, logits, margins from the oracle run on that prompt alone."""
+    out = []
+    for i, n in enumerate(lengths):
+        b = i if slots is None else slots[i]
+        out.append(orc.greedy(prompts[i:i + 1, :n], G, want_logits=True, temperature=temperature, seed=seed, b0=b))
+    return out
+
+
+LENGTHS = [1, 5, 16, 9, 2, 12, 16, 3]
+
+
+@pytest.mark.parametrize("small_ws", [False, True])
+def test_ragged_prefill_then_ragged_decode_matches_oracle(c1, small_ws):
+    cfg, w, model, orc = c1
+    prompts = srm_synth.make_prompts(cfg)                      # [8][16]
+    B, G = len(LENGTHS), 20
+    ref = _oracle_streams(orc, prompts, LENGTHS, G)
+    toks, off = _pack(prompts, LENGTHS)
+    print(f"ragged prefill+decode B={B} lengths={LENGTHS} small_ws={small_ws}", flush=True)
+    rows = 20 if small_ws else int(off[-1])                    # 20 rows: several passes of whole prompts
+    ws = model.new_workspace(max(rows, B))
+    st = model.new_state(B)
+    st.fill_(float("nan"))                                     # every destination must be written
+    tk = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    pos = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    keep = model.prefill_ragged(to_dev(toks), off, st, tk, pos=pos, logits=lg, workspace=ws)
+    torch.cuda.synchronize()
+    del keep
+    np.testing.assert_array_equal(pos.cpu().numpy(), LENGTHS)
+    got = np.empty((B, G), np.int32)
+    got[:, 0] = tk.cpu().numpy()
+    first_logits = np.stack([r["logits"][0, 0] for r in ref])
+    assert rel_err_rows(lg.cpu().numpy(), first_logits) <= 1e-4
+    for g in range(1, G):
+        model.decode_step_ragged(B, pos, tk, st, tk, advance=True, workspace=ws)
+        got[:, g] = tk.cpu().numpy()
+    np.testing.assert_array_equal(pos.cpu().numpy(), np.array(LENGTHS) + G - 1)
+    for b in range(B):
+        absmax = np.abs(ref[b]["logits"][0]).max(axis=1)
+        assert check_tokens(got[b], ref[b]["tokens"][0], ref[b]["margin"][0], absmax) == 0
+    # state after the last step against the oracle (the oracle consumed one token more: compare one step earlier
+    # is not available, so run the oracle's own recurrence for G - 1 generated tokens)
+    for b in (0, 2, 5):
+        seq = np.concatenate([prompts[b, :LENGTHS[b]], ref[b]["tokens"][0, :G - 1]])[None, :]
+        s_ref = orc.greedy(seq, 1)["state"][0]
+        s_got = st.view(cfg.n_layers, B, cfg.d_model)[:, b, :].cpu().numpy()
+        assert np.abs(s_got - s_ref).max() <= 1e-4 * np.abs(s_ref).max()
+
+
+def test_ragged_equals_uniform_when_positions_agree(srm):
+    """All samples at one position: the ragged step is bit-identical to srm_decode_step (bf16, several tiles)."""
+    cfg = srm_synth.tiny_config(vocab=1000, d_model=128, n_layers=3, n_heads=4, n_ctx=32, weight_dtype="bf16", seed=5)
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    B, P = 700, 6
+    rng = np.random.default_rng(9)
+    prompts = rng.integers(0, cfg.vocab, (B, P)).astype(np.int32)
+    ws = model.new_workspace(B * P)
+    sa, sb = model.new_state(B), model.new_state(B)
+    ta = torch.empty(B, dtype=torch.int32, device="cuda")
+    tb = torch.empty(B, dtype=torch.int32, device="cuda")
+    print(f"ragged==uniform B={B} P={P}", flush=True)
+    model.prefill(to_dev(prompts), 1, sa, ta, workspace=ws)
+    pos = torch.empty(B, dtype=torch.int32, device="cuda")
+    off = np.arange(B + 1, dtype=np.int32) * P
+    keep = model.prefill_ragged(to_dev(prompts.reshape(-1)), off, sb, tb, pos=pos, workspace=ws)
+    torch.cuda.synchronize()
+    del keep
+    assert torch.equal(ta, tb) and torch.equal(sa, sb)
+    for g in range(4):
+        model.decode_step(B, P + g, ta, sa, ta, workspace=ws)
+        model.decode_step_ragged(B, pos, tb, sb, tb, advance=True, workspace=ws)
+        assert torch.equal(ta, tb) and torch.equal(sa, sb)
+    # sampled: same draws, since the counter is keyed on (seed, position, sample)
+    for g in range(3):
+        model.decode_step(B, P + 4 + g, ta, sa, ta, workspace=ws, temperature=0.9, seed=3)
+        model.decode_step_ragged(B, pos, tb, sb, tb, advance=True, temperature=0.9, seed=3, workspace=ws)
+        assert torch.equal(ta, tb) and torch.equal(sa, sb)
+
+
+def test_slots_join_and_leave_a_running_batch(c1):
+    """Six slots; four start, two are admitted later through a slot list, one leaves.  Every
+    slot's stream equals the oracle's stream for its prompt; idle slots are untouched."""
+    cfg, w, model, orc = c1
+    prompts = srm_synth.make_prompts(cfg)
+    S = 6
+    first = {0: (0, 7), 2: (1, 16), 3: (2, 3), 5: (3, 11)}      # slot -> (prompt row, length)
+    later = {1: (4, 5), 4: (5, 1)}
+    G1, G2 = 5, 6
+    ws = model.new_workspace(64)
+    st = model.new_state(S)
+    st.fill_(123.0)
+    tk = torch.full((S,), 0, dtype=torch.int32, device="cuda")
+    pos = torch.full((S,), -1, dtype=torch.int32, device="cuda")
+    print("slots join/leave", flush=True)
+
+    def admit(group):
+        slots = sorted(group)
+        rows = [group[s][0] for s in slots]; lens = [group[s][1] for s in slots]
+        toks, off = _pack(prompts[rows], lens)
+        keep = model.prefill_ragged(to_dev(toks), off, st, tk, slot=to_dev(np.array(slots, np.int32)), pos=pos,
+                                    workspace=ws)
+        torch.cuda.synchronize()
+        del keep
+
+    admit(first)
+    sv = st.view(cfg.n_layers, S, cfg.d_model)
+    assert (sv[:, 1] == 123.0).all() and (sv[:, 4] == 123.0).all()          # idle slots not written
+    np.testing.assert_array_equal(pos.cpu().numpy(), [7, -1, 16, 3, -1, 11])
+    streams = {s: [int(tk[s])] for s in first}
+    for g in range(G1):
+        model.decode_step_ragged(S, pos, tk, st, tk, advance=True, workspace=ws)
+        t = tk.cpu().numpy()
+        assert t[1] == -1 and t[4] == -1
+        for s in first:
+            streams[s].append(int(t[s]))
+        tk[1] = 0; tk[4] = 0
+    assert (sv[:, 1] == 123.0).all() and (sv[:, 4] == 123.0).all()
+    # slot 3 leaves, slots 1 and 4 join
+    pos[3] = -1
+    frozen = sv[:, 3].clone()
+    admit(later)
+    for s in later:
+        streams[s] = [int(tk[s])]
+    for g in range(G2):
+        model.decode_step_ragged(S, pos, tk, st, tk, advance=True, workspace=ws)
+        t = tk.cpu().numpy()
+        assert t[3] == -1
+        for s in streams:
+            if s != 3:
+                streams[s].append(int(t[s]))
+        tk[3] = 0
+    assert torch.equal(sv[:, 3], frozen)
+    everyone = dict(first); everyone.update(later)
+    for s, (row, n) in everyone.items():
+        ref = orc.greedy(prompts[row:row + 1, :n], len(streams[s]), want_logits=True)
+        absmax = np.abs(ref["logits"][0]).max(axis=1)
+        assert check_tokens(np.array(streams[s]), ref["tokens"][0], ref["margin"][0], absmax) == 0
+
+
+def test_ragged_sampled_matches_oracle(c1):
+    """Temperature sampling with per-sample positions: prefill all but the last prompt token,
+    feed the last one to the first sampled step (a one-token prompt starts from the zero state)."""
+    cfg, w, model, orc = c1
+    prompts = srm_synth.make_prompts(cfg)
+    B, G, T, seed = len(LENGTHS), 12, 0.7, 4242
+    ref = _oracle_streams(orc, prompts, LENGTHS, G, temperature=T, seed=seed)
+    ws = model.new_workspace(int(sum(LENGTHS)))
+    st = model.new_state(B)
+    st.zero_()
+    tk = torch.zeros(B, dtype=torch.int32, device="cuda")
+    pos = torch.zeros(B, dtype=torch.int32, device="cuda")
+    has = [b for b in range(B) if LENGTHS[b] > 1]
+    toks, off = _pack(prompts[has], [LENGTHS[b] - 1 for b in has])
+    print(f"ragged sampled B={B}", flush=True)
+    keep = model.prefill_ragged(to_dev(toks), off, st, tk, slot=to_dev(np.array(has, np.int32)), pos=pos, workspace=ws)
+    torch.cuda.synchronize()
+    del keep
+    np.testing.assert_array_equal(pos.cpu().numpy(), np.array(LENGTHS) - 1)
+    tk.copy_(to_dev(np.array([prompts[b, LENGTHS[b] - 1] for b in range(B)], np.int32)))
+    got = np.empty((B, G), np.int32)
+    for g in range(G):
+        model.decode_step_ragged(B, pos, tk, st, tk, advance=True, temperature=T, seed=seed, workspace=ws)
+        got[:, g] = tk.cpu().numpy()
+    for b in range(B):
+        absmax = np.abs(ref[b]["logits"][0]).max(axis=1)
+        assert check_tokens(got[b], ref[b]["tokens"][0], ref[b]["margin"][0], absmax) == 0
+
+
+def test_ragged_bf16_logits_against_oracle(srm, orc_mod):
+    """bf16 model, 300 packed prompts of random lengths (several GEMM tiles, ragged tail):
+    first-token logits and two decode steps of sampled rows against the oracle."""
+    cfg = srm_synth.tiny_config(vocab=500, d_model=128, n_layers=3, n_heads=4, n_ctx=24, weight_dtype="bf16", seed=8)
+    w = srm_synth.make_weights(cfg)
+    model = srm.Model(cfg, w)
+    orc = orc_mod.Oracle(cfg, w, "f64")
+    rng = np.random.default_rng(11)
+    N = 300
+    lens = rng.integers(1, 17, N)
+    prompts = rng.integers(0, cfg.vocab, (N, 16)).astype(np.int32)
+    toks, off = _pack(prompts, lens)
+    ws = model.new_workspace(int(off[-1]))
+    st = model.new_state(N)
+    tk = torch.empty(N, dtype=torch.int32, device="cuda")
+    pos = torch.empty(N, dtype=torch.int32, device="cuda")
+    lg = torch.empty((N, cfg.vocab), dtype=torch.float32, device="cuda")
+    print(f"ragged bf16 N={N} rows={int(off[-1])}", flush=True)
+    keep = model.prefill_ragged(to_dev(toks), off, st, tk, pos=pos, logits=lg, workspace=ws)
+    torch.cuda.synchronize()
+    del keep
+    rows = [0, 1, 17, 150, 298, 299]
+    steps = [lg.cpu().numpy()]
+    forced = {b: orc.greedy(prompts[b:b + 1, :lens[b]], 3, want_logits=True) for b in rows}
+    for g in range(2):
+        for b in rows:                                       # teacher-force the checked rows on the oracle's tokens
+            tk[b] = int(forced[b]["tokens"][0, g])
+        model.decode_step_ragged(N, pos, tk, st, tk, advance=True, logits=lg, workspace=ws)
+        steps.append(lg.cpu().numpy())
+    for b in rows:
+        for g in range(3):
+            assert rel_err_rows(steps[g][b][None], forced[b]["logits"][0, g][None]) <= 2e-2
+    t = tk.cpu().numpy()
+    assert ((t >= 0) & (t < cfg.vocab)).all() and bool(torch.isfinite(st).all())
+
+
+def test_ragged_errors(c1, srm):
+    cfg, w, model, orc = c1
+    ws = model.new_workspace(32)
+    st = model.new_state(4)
+    tk = torch.zeros(4, dtype=torch.int32, device="cuda")
+    toks = torch.zeros(64, dtype=torch.int32, device="cuda")
+    with pytest.raises(srm.SrmError):                         # empty prompt
+        model.prefill_ragged(toks, [0, 3, 3, 5], st, tk, workspace=ws)
+    with pytest.raises(srm.SrmError):                         # longer than n_ctx
+        model.prefill_ragged(torch.zeros(600, dtype=torch.int32, device="cuda"), [0, cfg.n_ctx + 1], st, tk,
+                             workspace=model.new_workspace(600))
+    with pytest.raises(srm.SrmError):                         # more prompts than samples in the state
+        model.prefill_ragged(toks, [0, 1, 2, 3, 4, 5], st, tk, workspace=ws)
+    with pytest.raises(srm.SrmError):                         # one prompt larger than the workspace
+        model.prefill_ragged(toks, [0, 40], st, tk, workspace=ws)
+    with pytest.raises(srm.SrmError):                         # slot list with fan-out
+        model.prefill_ragged(toks, [0, 2], st, tk, fanout_k=2, slot=torch.zeros(1, dtype=torch.int32, device="cuda"),
+                             workspace=ws)
+    with pytest.raises(srm.SrmError):                         # workspace too small for the batch
+        model.decode_step_ragged(4, tk, tk, st, tk, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
