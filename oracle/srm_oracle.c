@@ -330,6 +330,87 @@ int orc_pick(const real *logits, int V, double temperature, uint32_t seed, int p
     return best < 0 ? 0 : best;
 }
 
+/*
+ * Nucleus (top-p) truncation, the sampling rule of the paper's rollouts
+ * ("Reasoning Experiments details": top-p 0.9 at temperature 0.7; the method is
+ * the nucleus sampling the "Reinforcement Learning" paragraph cites).  With
+ * p_v = softmax(logits / temperature): order the tokens by descending
+ * probability (equal values by ascending index), take the shortest prefix whose
+ * cumulative probability reaches top_p, and keep every token whose logit is at
+ * least the last prefix element's (so equal values are kept or dropped
+ * together).  keep[V] receives 0/1.  top_p >= 1 keeps everything.  Returns the
+ * number kept.  mass_margin (may be NULL): distance of the deciding cumulative
+ * sums from top_p, min(cum_k - top_p, top_p - cum_{k-1}), as a probability.
+ */
+typedef struct { double l; int v; } orc_lv;
+static int orc_lv_desc(const void *a, const void *b)
+{
+    const orc_lv *x = (const orc_lv *)a, *y = (const orc_lv *)b;
+    if (x->l > y->l) return -1;
+    if (x->l < y->l) return 1;
+    return x->v < y->v ? -1 : (x->v > y->v ? 1 : 0);
+}
+
+int orc_nucleus(const real *logits, int V, double temperature, double top_p, unsigned char *keep,
+                double *mass_margin)
+{
+    if (mass_margin) *mass_margin = 1.0;
+    if (!(top_p < 1.0) || !(temperature > 0)) {
+        for (int v = 0; v < V; ++v) keep[v] = 1;
+        return V;
+    }
+    orc_lv *o = (orc_lv *)malloc(sizeof(orc_lv) * (size_t)V);
+    double mx = -INFINITY, Z = 0;
+    for (int v = 0; v < V; ++v) { o[v].l = (double)logits[v]; o[v].v = v; if (o[v].l > mx) mx = o[v].l; }
+    qsort(o, (size_t)V, sizeof(orc_lv), orc_lv_desc);
+    for (int v = 0; v < V; ++v) Z += exp((o[v].l - mx) / temperature);
+    double cum = 0, prev = 0;
+    int k = 0;
+    for (; k < V; ++k) {
+        prev = cum;
+        cum += exp((o[k].l - mx) / temperature) / Z;
+        if (cum >= top_p) break;
+    }
+    if (k == V) k = V - 1;                       /* rounding left the total just below top_p */
+    if (mass_margin) {
+        double a = cum - top_p, b = top_p - prev;
+        *mass_margin = a < b ? a : b;
+    }
+    const double cut = o[k].l;
+    int n = 0;
+    for (int v = 0; v < V; ++v) { keep[v] = (double)logits[v] >= cut; n += keep[v]; }
+    free(o);
+    return n;
+}
+
+/*
+ * orc_pick restricted to the nucleus: argmax over the kept tokens of
+ * logit_v + temperature * g_v, the Gumbel-max draw from the renormalised
+ * truncated distribution, with the same counter as orc_pick (so for top_p >= 1
+ * the two agree).  temperature == 0 is greedy whatever top_p.
+ */
+int orc_pick_topp(const real *logits, int V, double temperature, double top_p, uint32_t seed, int pos, int b,
+                  real *margin, double *mass_margin)
+{
+    if (!(temperature > 0) || !(top_p < 1.0)) {
+        if (mass_margin) *mass_margin = 1.0;
+        return orc_pick(logits, V, temperature, seed, pos, b, margin);
+    }
+    unsigned char *keep = (unsigned char *)malloc((size_t)V);
+    orc_nucleus(logits, V, temperature, top_p, keep, mass_margin);
+    int best = -1;
+    real bs = -INFINITY, second = -INFINITY;
+    for (int v = 0; v < V; ++v) {
+        if (!keep[v]) continue;
+        real sc = logits[v] + (real)(temperature * orc_gumbel(seed, (uint32_t)pos, (uint32_t)b, (uint32_t)v));
+        if (sc > bs) { second = bs; bs = sc; best = v; }
+        else if (sc > second) second = sc;
+    }
+    free(keep);
+    if (margin) *margin = bs - second;
+    return best < 0 ? 0 : best;
+}
+
 /* ---- whole model, recurrent form --------------------------------------- */
 
 /*
@@ -404,15 +485,17 @@ int orc_recurrent_forward(const orc_model *m, int B, int T, const int *tokens, i
  * Generation: consume prompts[B][P] from a zero state, then generate G tokens;
  * out_tokens[b][0] is chosen from the logits at the last prompt position and each
  * generated token is fed back.  temperature == 0: greedy; otherwise sampled with
- * orc_pick, the counter being (seed, position of the token just consumed, b0 + b).
+ * orc_pick_topp (nucleus truncation when top_p < 1), the counter being (seed,
+ * position of the token just consumed, b0 + b).
  * state[B][L][d] is overwritten.  Optional: logits[B][G][V] (the raw logits each
  * generated token was chosen from) and margin[B][G] (top-1 minus top-2 of the
  * scores the choice was made on).
  */
-int orc_generate(const orc_model *m, int B, int P, int G, const int *prompts, real *state,
-                 int *out_tokens, real *logits, real *margin, double temperature, uint32_t seed, int b0)
+int orc_generate_topp(const orc_model *m, int B, int P, int G, const int *prompts, real *state,
+                      int *out_tokens, real *logits, real *margin, double temperature, uint32_t seed, int b0,
+                      double top_p, double *mass_margin)
 {
-    if (P < 1 || G < 1 || P + G - 1 > m->n_ctx || temperature < 0) return -1;
+    if (P < 1 || G < 1 || P + G - 1 > m->n_ctx || temperature < 0 || !(top_p > 0)) return -1;
     for (long long i = 0; i < (long long)B * P; ++i)
         if (prompts[i] < 0 || prompts[i] >= m->vocab) return -1;
     int d = m->d, V = m->vocab;
@@ -430,14 +513,23 @@ int orc_generate(const orc_model *m, int B, int P, int G, const int *prompts, re
             if (!want) continue;
             int g = t - (P - 1);
             real mg;
-            tok = orc_pick(lg, V, temperature, seed, t, b0 + b, &mg);
+            double mm;
+            tok = orc_pick_topp(lg, V, temperature, top_p, seed, t, b0 + b, &mg, &mm);
             out_tokens[(size_t)b * G + g] = tok;
             if (logits) memcpy(logits + ((size_t)b * G + g) * V, lg, sizeof(real) * V);
             if (margin) margin[(size_t)b * G + g] = mg;
+            if (mass_margin) mass_margin[(size_t)b * G + g] = mm;
         }
         free(lg);
     }
     return 0;
+}
+
+int orc_generate(const orc_model *m, int B, int P, int G, const int *prompts, real *state,
+                 int *out_tokens, real *logits, real *margin, double temperature, uint32_t seed, int b0)
+{
+    return orc_generate_topp(m, B, P, G, prompts, state, out_tokens, logits, margin, temperature, seed, b0, 1.0,
+                             NULL);
 }
 
 int orc_greedy(const orc_model *m, int B, int P, int G, const int *prompts, real *state,

@@ -54,6 +54,15 @@ def _load(kind: str):
         lib.orc_gumbel.argtypes = [C.c_uint32] * 4
         lib.orc_pick.restype = C.c_int
         lib.orc_pick.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_uint32, C.c_int, C.c_int, C.c_void_p]
+        lib.orc_nucleus.restype = C.c_int
+        lib.orc_nucleus.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_double, C.c_void_p, C.c_void_p]
+        lib.orc_pick_topp.restype = C.c_int
+        lib.orc_pick_topp.argtypes = [C.c_void_p, C.c_int, C.c_double, C.c_double, C.c_uint32, C.c_int, C.c_int,
+                                      C.c_void_p, C.c_void_p]
+        lib.orc_generate_topp.restype = C.c_int
+        lib.orc_generate_topp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_double, C.c_uint32, C.c_int, C.c_double,
+                                          C.c_void_p]
         lib.orc_generate.restype = C.c_int
         lib.orc_generate.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_double, C.c_uint32, C.c_int]
@@ -79,6 +88,26 @@ def pick(logits, temperature, seed, pos, b, kind="f64") -> int:
     real = np.float64 if kind == "f64" else np.float32
     lg = np.ascontiguousarray(logits, dtype=real)
     return int(_load(kind).orc_pick(_p(lg), lg.size, float(temperature), seed, pos, b, None))
+
+
+def nucleus(logits, temperature, top_p, kind="f64"):
+    """(keep mask [V] of bool, mass margin) of the top-p truncation of softmax(logits / temperature)."""
+    real = np.float64 if kind == "f64" else np.float32
+    lg = np.ascontiguousarray(logits, dtype=real)
+    keep = np.zeros(lg.size, np.uint8)
+    mm = C.c_double(0.0)
+    _load(kind).orc_nucleus(_p(lg), lg.size, float(temperature), float(top_p), _p(keep), C.byref(mm))
+    return keep.astype(bool), mm.value
+
+
+def pick_topp(logits, temperature, top_p, seed, pos, b, kind="f64", want_margins=False):
+    real = np.float64 if kind == "f64" else np.float32
+    lg = np.ascontiguousarray(logits, dtype=real)
+    mg = (C.c_double if kind == "f64" else C.c_float)(0.0)
+    mm = C.c_double(0.0)
+    tok = int(_load(kind).orc_pick_topp(_p(lg), lg.size, float(temperature), float(top_p), seed, pos, b,
+                                        C.byref(mg), C.byref(mm)))
+    return (tok, float(mg.value), mm.value) if want_margins else tok
 
 
 def count_params(vocab, d, L, H=4, e=4, n_ctx=512, with_projections=True) -> int:
@@ -180,19 +209,22 @@ class Oracle:
             raise ValueError("orc_recurrent_forward: bad argument")
         return {"state": state, "hidden": hidden, "logits": logits, "greedy": greedy}
 
-    def greedy(self, prompts, G, want_logits=False, temperature=0.0, seed=0, b0=0):
-        """Generate G tokens per prompt: greedy, or sampled when temperature > 0."""
+    def greedy(self, prompts, G, want_logits=False, temperature=0.0, seed=0, b0=0, top_p=1.0):
+        """Generate G tokens per prompt: greedy, or sampled when temperature > 0 (from the
+        top-p nucleus when top_p < 1)."""
         prompts = np.ascontiguousarray(prompts, dtype=np.int32)
         B, P = prompts.shape
         state = self.new_state(B)
         toks = np.empty((B, G), np.int32)
         logits = np.empty((B, G, self.V), self.real) if want_logits else None
         margin = np.empty((B, G), self.real)
-        rc = self.lib.orc_generate(C.c_void_p(self.h), B, P, G, _p(prompts), _p(state), _p(toks),
-                                   _p(logits), _p(margin), float(temperature), seed, b0)
+        mass = np.ones((B, G), np.float64)
+        rc = self.lib.orc_generate_topp(C.c_void_p(self.h), B, P, G, _p(prompts), _p(state), _p(toks),
+                                        _p(logits), _p(margin), float(temperature), seed, b0, float(top_p),
+                                        _p(mass))
         if rc:
             raise ValueError("orc_generate: bad argument")
-        return {"tokens": toks, "logits": logits, "margin": margin, "state": state}
+        return {"tokens": toks, "logits": logits, "margin": margin, "state": state, "mass_margin": mass}
 
     def parallel_forward(self, tokens, want_logits=True):
         tokens = np.ascontiguousarray(tokens, dtype=np.int32)

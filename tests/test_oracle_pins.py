@@ -437,3 +437,75 @@ def test_sampled_generation_is_reproducible_and_seed_dependent(oracle_mod):
     # b0 shifts the sample index: rows 4..7 of a run equal a 4-row run started at b0 = 4
     d4 = orc.greedy(prompts[4:], 10, temperature=0.9, seed=4, b0=4)
     np.testing.assert_array_equal(d4["tokens"], a["tokens"][4:])
+
+
+# ---- nucleus (top-p) truncation: "Reasoning Experiments details" (top-p 0.9, temperature 0.7) ----
+def test_nucleus_worked_examples(oracle_mod):
+    # probabilities 0.5, 0.3, 0.15, 0.05: cumulative 0.5, 0.8, 0.95, 1.0
+    lg = np.log([0.5, 0.3, 0.15, 0.05])
+    keep, margin = oracle_mod.nucleus(lg, 1.0, 0.9)
+    assert keep.tolist() == [True, True, True, False] and abs(margin - 0.05) < 1e-12
+    assert oracle_mod.nucleus(lg, 1.0, 0.79)[0].tolist() == [True, True, False, False]
+    assert oracle_mod.nucleus(lg, 1.0, 0.45)[0].tolist() == [True, False, False, False]
+    assert oracle_mod.nucleus(lg, 1.0, 0.96)[0].all() and oracle_mod.nucleus(lg, 1.0, 1.0)[0].all()
+    # order of the tokens does not matter, only their probabilities
+    perm = [3, 0, 2, 1]
+    assert oracle_mod.nucleus(lg[perm], 1.0, 0.9)[0].tolist() == [False, True, True, True]
+    # temperature acts before the truncation: at T = 0.5 the probabilities are ~ p^2 = .25, .09, .0225, .0025 / .365
+    assert oracle_mod.nucleus(lg, 0.5, 0.9)[0].tolist() == [True, True, False, False]      # .685, .932
+    # equal values are kept or dropped together
+    assert oracle_mod.nucleus(np.log([0.4, 0.2, 0.2, 0.2]), 1.0, 0.5)[0].all()
+
+
+def test_nucleus_is_the_smallest_top_set_reaching_top_p(oracle_mod):
+    rng = np.random.default_rng(3)
+    for trial in range(200):
+        V = int(rng.integers(2, 200))
+        T = float(rng.uniform(0.3, 2.0)); top_p = float(rng.uniform(0.05, 0.999))
+        lg = rng.standard_normal(V) * rng.uniform(0.1, 6.0)
+        keep, _ = oracle_mod.nucleus(lg, T, top_p)
+        p = np.exp((lg - lg.max()) / T); p /= p.sum()
+        assert p[keep].sum() >= top_p - 1e-12                       # reaches top_p
+        assert lg[keep].min() > lg[~keep].max() if (~keep).any() else True      # a top set
+        assert p[keep].sum() - p[keep].min() < top_p + 1e-12        # dropping its smallest member falls short
+
+
+def test_nucleus_sampling_frequencies_and_limits(oracle_mod):
+    import scipy.stats
+    logits = np.array([1.2, -0.3, 0.4, 2.0, 0.0, -1.5, 0.9])
+    T, top_p = 0.7, 0.9
+    keep, _ = oracle_mod.nucleus(logits, T, top_p)
+    p = np.exp(logits / T) * keep; p /= p.sum()
+    assert 1 < keep.sum() < logits.size
+    n = 60000
+    counts = np.bincount([oracle_mod.pick_topp(logits, T, top_p, 5, 3, b) for b in range(n)], minlength=logits.size)
+    assert counts[~keep].sum() == 0                                  # never a truncated token
+    assert scipy.stats.chisquare(counts[keep], p[keep] * n).pvalue > 1e-3      # renormalised truncated softmax
+    # top_p = 1 is plain sampling with the same draws; a tiny top_p or temperature 0 is greedy
+    for b in range(200):
+        assert oracle_mod.pick_topp(logits, T, 1.0, 5, 3, b) == oracle_mod.pick(logits, T, 5, 3, b)
+        assert oracle_mod.pick_topp(logits, T, 1e-6, 5, 3, b) == 3
+        assert oracle_mod.pick_topp(logits, 0.0, 0.5, 5, 3, b) == 3
+    # whenever the untruncated draw falls inside the nucleus, truncation does not change it
+    for b in range(500):
+        free = oracle_mod.pick(logits, T, 5, 3, b)
+        if keep[free]:
+            assert oracle_mod.pick_topp(logits, T, top_p, 5, 3, b) == free
+
+
+def test_generation_with_top_p(oracle_mod):
+    cfg = srm_synth.tiny_config(vocab=48, d_model=16, n_layers=2, n_heads=4, n_ctx=24, seed=21)
+    w = srm_synth.make_weights(cfg, stress=True)
+    w["head"] = w["head"] * 30.0
+    orc = oracle_mod.Oracle(cfg, w, "f64")
+    prompts = np.repeat(srm_synth.make_prompts(cfg, batch=1, length=6), 16, axis=0)
+    a = orc.greedy(prompts, 8, temperature=0.8, seed=4, want_logits=True, top_p=0.6)
+    full = orc.greedy(prompts, 8, temperature=0.8, seed=4, top_p=1.0)
+    plain = orc.greedy(prompts, 8, temperature=0.8, seed=4)
+    np.testing.assert_array_equal(full["tokens"], plain["tokens"])
+    assert (a["tokens"] != plain["tokens"]).any()
+    for bb in range(16):
+        for g in range(8):
+            keep, _ = oracle_mod.nucleus(a["logits"][bb, g], 0.8, 0.6)
+            assert keep[a["tokens"][bb, g]]
+            assert a["tokens"][bb, g] == oracle_mod.pick_topp(a["logits"][bb, g], 0.8, 0.6, 4, 5 + g, bb)
