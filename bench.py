@@ -34,6 +34,8 @@ def parse_args():
                          "resident batch that still completes a decode step")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="sample with this temperature (fused Gumbel-max) instead of greedy argmax")
+    ap.add_argument("--top-p", type=float, default=1.0,
+                    help="with --temperature: nucleus truncation (the paper's rollouts use 0.9 at temperature 0.7)")
     ap.add_argument("--per-step-calls", action="store_true",
                     help="time K srm_decode_step calls instead of one srm_generate call of K steps")
     ap.add_argument("--no-prefill", action="store_true", help="start from a zero state and random tokens "
@@ -251,6 +253,10 @@ def main():
     # (the legacy default stream cannot be captured).
     samp = {"temperature": args.temperature, "seed": 1} if args.temperature > 0 else {}
     gsamp = {"temperature": args.temperature, "seed": 1}
+    if args.temperature > 0 and args.top_p < 1.0:
+        scratch_logits = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+        samp.update(top_p=args.top_p, logits=scratch_logits)
+        gsamp.update(top_p=args.top_p, logits=scratch_logits)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     store = torch.empty((max(args.steps, args.warmup), B), dtype=torch.int32, device="cuda")
@@ -298,7 +304,9 @@ def main():
                  if esz == 2 else None,
                  "device_ms_per_step": dev_s / args.steps * 1e3, "wall_ms_per_step": wall / args.steps * 1e3},
         "prefill": {"seconds": prefill_s, "tokens_per_s": B * P / prefill_s},
-        "next_token": "greedy argmax" if args.temperature == 0 else f"sampled, temperature {args.temperature} (fused Gumbel-max)",
+        "next_token": "greedy argmax" if args.temperature == 0 else
+                      f"sampled, temperature {args.temperature} (fused Gumbel-max)" +
+                      (f", top-p {args.top_p} (nucleus pass over materialised logits)" if args.top_p < 1.0 else ""),
         "driver": "K srm_decode_step calls" if args.per_step_calls else "one srm_generate call (HIP-graph replay of the step)",
         "setup_seconds": t_setup,
     }

@@ -185,6 +185,44 @@ int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, int32_t P, in
                 void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Decode step with nucleus (top-p) sampling, the rule of the paper's rollouts
+ * ("Reasoning Experiments details": top-p 0.9, temperature 0.7).  With
+ * p = softmax(logits / temperature), the nucleus is the smallest set of most
+ * probable tokens whose probability reaches top_p (tokens with equal logits are
+ * kept or dropped together); the token is drawn from the renormalised nucleus
+ * by the Gumbel-max rule with the noise of srm_decode_step_sampled, restricted
+ * to the nucleus: whenever the unrestricted draw lies inside the nucleus the two
+ * calls return the same token.  The truncation needs the whole row, so
+ * d_logits[B][vocab] is required when top_p < 1 and temperature > 0 (it is left
+ * holding the raw logits); top_p >= 1 or temperature = 0 behave as
+ * srm_decode_step_sampled.  Sums of probabilities are formed in fp32 by a fixed
+ * reduction tree, so results are reproducible from run to run.
+ * Errors: as srm_decode_step_sampled, plus SRM_EINVAL for top_p <= 0 or a
+ * missing logits buffer.
+ */
+int srm_decode_step_topp(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
+                         int32_t *d_tok_out, float temperature, float top_p, uint32_t seed,
+                         float *d_logits, float *d_hidden,
+                         void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/* srm_generate with nucleus sampling; d_logits[B][vocab] is scratch for the truncation
+ * (required when top_p < 1 and temperature > 0).  Otherwise as srm_generate. */
+int srm_generate_topp(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+                      int32_t *d_tokens_out, float temperature, float top_p, uint32_t seed,
+                      float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The sampler alone, on logits that are already in device memory:
+ * d_logits[rows][vocab] fp32 -> d_tok_out[rows], drawn from
+ * softmax(logits / temperature) truncated to the top_p nucleus (top_p >= 1: no
+ * truncation), with the counter (seed, pos, row).  Same kernel as in
+ * srm_decode_step_topp.  Needs no model.
+ * Errors: SRM_EINVAL (null pointer, sizes <= 0, temperature <= 0, top_p <= 0).
+ */
+int srm_sample_logits(const float *d_logits, int64_t rows, int32_t vocab, float temperature, float top_p,
+                      uint32_t seed, int32_t pos, int32_t *d_tok_out, void *hip_stream);
+
+/*
  * Decode step with one position per sample, for batches whose samples are at
  * different positions (prompts of different lengths, slots that join and leave
  * a running batch).  The recurrent form makes this free: a sample's cache has
@@ -196,15 +234,16 @@ int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, int32_t P, in
  * any value).  With advance != 0 the position of every active sample is
  * incremented on the device at the end of the step, so a loop of calls needs no
  * host-side update.  temperature = 0 is greedy; temperature > 0 samples as
- * srm_decode_step_sampled does, keyed on the sample's own position.  For active
- * samples the result equals srm_decode_step(_sampled) at that position.
- * d_logits: optional [B][vocab].
- * Errors: SRM_EINVAL (null pointer, B out of range, negative temperature),
- * SRM_ENOMEM (workspace smaller than srm_workspace_bytes(m, B)), SRM_EHIP.
+ * srm_decode_step_topp does (top_p >= 1: no truncation), keyed on the sample's
+ * own position.  For active samples the result equals the uniform-position call
+ * at that position.  d_logits: [B][vocab], optional unless top_p < 1.
+ * Errors: SRM_EINVAL (null pointer, B out of range, negative temperature,
+ * top_p <= 0, top_p < 1 without d_logits), SRM_ENOMEM (workspace smaller than
+ * srm_workspace_bytes(m, B)), SRM_EHIP.
  */
 int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, int32_t advance,
                            const int32_t *d_tok_in, float *d_state, int32_t *d_tok_out,
-                           float temperature, uint32_t seed, float *d_logits,
+                           float temperature, float top_p, uint32_t seed, float *d_logits,
                            void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*

@@ -4,4 +4,5 @@ Every step of the path runs in the HIP library; this package only marshals
 arguments.  PyTorch is used for device memory and streams.  There is no CPU
 fallback: if the library is missing, loading fails.
 """
-from .binding import (SRM_BF16, SRM_FP32, Model, SrmError, lib, linear, linear_scratch_bytes)  # noqa: F401
+from .binding import (SRM_BF16, SRM_FP32, Model, SrmError, lib, linear, linear_scratch_bytes,
+                      sample_logits)  # noqa: F401

@@ -69,7 +69,16 @@ def lib():
         L.srm_prefill.restype = C.c_int
         L.srm_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
         L.srm_decode_step_ragged.restype = C.c_int
-        L.srm_decode_step_ragged.argtypes = [vp, i64, vp, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, vp, sz, vp]
+        L.srm_decode_step_ragged.argtypes = [vp, i64, vp, i32, vp, vp, vp, C.c_float, C.c_float, C.c_uint32, vp, vp,
+                                             sz, vp]
+        L.srm_decode_step_topp.restype = C.c_int
+        L.srm_decode_step_topp.argtypes = [vp, i64, i32, vp, vp, vp, C.c_float, C.c_float, C.c_uint32, vp, vp, vp, sz,
+                                           vp]
+        L.srm_generate_topp.restype = C.c_int
+        L.srm_generate_topp.argtypes = [vp, i64, i32, i32, vp, vp, vp, C.c_float, C.c_float, C.c_uint32, vp, vp, sz,
+                                        vp]
+        L.srm_sample_logits.restype = C.c_int
+        L.srm_sample_logits.argtypes = [vp, i64, i32, C.c_float, C.c_float, C.c_uint32, i32, vp, vp]
         L.srm_prefill_ragged.restype = C.c_int
         L.srm_prefill_ragged.argtypes = [vp, vp, vp, vp, i32, i32, vp, i64, vp, vp, vp, vp, vp, sz, vp]
         L.srm_parallel_forward.restype = C.c_int
@@ -182,8 +191,9 @@ class Model:
         return torch.empty(self.workspace_bytes(rows), dtype=torch.uint8, device="cuda")
 
     def decode_step(self, B, pos, tok_in, state, tok_out, logits=None, hidden=None, workspace=None,
-                    stream=None, temperature=None, seed=0):
-        """srm_decode_step, or srm_decode_step_sampled when a temperature is given."""
+                    stream=None, temperature=None, seed=0, top_p=None):
+        """srm_decode_step; srm_decode_step_sampled when a temperature is given; srm_decode_step_topp
+        when top_p is given too."""
         torch = _torch()
         p_in = _dev(tok_in, torch.int32, B, "tok_in")
         p_st = _dev(state, torch.float32, self.L * B * self.d, "state")
@@ -196,11 +206,15 @@ class Model:
         if temperature is None:
             _check(lib().srm_decode_step(self._h, B, pos, p_in, p_st, p_out, p_lg, p_hd, p_ws,
                                          workspace.numel(), _stream(stream)))
-        else:
+        elif top_p is None:
             _check(lib().srm_decode_step_sampled(self._h, B, pos, p_in, p_st, p_out, temperature, seed, p_lg,
                                                  p_hd, p_ws, workspace.numel(), _stream(stream)))
+        else:
+            _check(lib().srm_decode_step_topp(self._h, B, pos, p_in, p_st, p_out, temperature, top_p, seed, p_lg,
+                                              p_hd, p_ws, workspace.numel(), _stream(stream)))
 
-    def generate(self, B, pos0, G, tok, state, tokens_out, workspace=None, stream=None, temperature=0.0, seed=0):
+    def generate(self, B, pos0, G, tok, state, tokens_out, workspace=None, stream=None, temperature=0.0, seed=0,
+                 top_p=None, logits=None):
         torch = _torch()
         p_tk = _dev(tok, torch.int32, B, "tok")
         p_st = _dev(state, torch.float32, self.L * B * self.d, "state")
@@ -208,8 +222,13 @@ class Model:
             raise ValueError("state: must be exactly [L][B][d]")
         p_out = _dev(tokens_out, torch.int32, G * B, "tokens_out")
         p_ws = _dev(workspace, torch.uint8, 1, "workspace")
-        _check(lib().srm_generate(self._h, B, pos0, G, p_tk, p_st, p_out, temperature, seed, p_ws,
-                                  workspace.numel(), _stream(stream)))
+        if top_p is None:
+            _check(lib().srm_generate(self._h, B, pos0, G, p_tk, p_st, p_out, temperature, seed, p_ws,
+                                      workspace.numel(), _stream(stream)))
+        else:
+            p_lg = None if logits is None else _dev(logits, torch.float32, B * self.vocab, "logits")
+            _check(lib().srm_generate_topp(self._h, B, pos0, G, p_tk, p_st, p_out, temperature, top_p, seed, p_lg,
+                                           p_ws, workspace.numel(), _stream(stream)))
 
     def prefill(self, prompts, fanout_k, state, next_tok, logits=None, workspace=None, stream=None):
         torch = _torch()
@@ -226,7 +245,7 @@ class Model:
                                  workspace.numel(), _stream(stream)))
 
     def decode_step_ragged(self, B, pos, tok_in, state, tok_out, advance=True, temperature=0.0, seed=0,
-                           logits=None, workspace=None, stream=None):
+                           logits=None, workspace=None, stream=None, top_p=1.0):
         """One step with per-sample positions pos[B] (device int32, advanced in place if asked)."""
         torch = _torch()
         p_pos = _dev(pos, torch.int32, B, "pos")
@@ -238,8 +257,8 @@ class Model:
         p_lg = None if logits is None else _dev(logits, torch.float32, B * self.vocab, "logits")
         p_ws = _dev(workspace, torch.uint8, 1, "workspace")
         _check(lib().srm_decode_step_ragged(self._h, B, p_pos, 1 if advance else 0, p_in, p_st, p_out,
-                                            float(temperature), int(seed), p_lg, p_ws, workspace.numel(),
-                                            _stream(stream)))
+                                            float(temperature), float(top_p), int(seed), p_lg, p_ws,
+                                            workspace.numel(), _stream(stream)))
 
     def prefill_ragged(self, tokens, offsets, state, next_tok, fanout_k=1, slot=None, pos=None, logits=None,
                        workspace=None, stream=None):
@@ -283,6 +302,15 @@ class Model:
         p_s = _dev(state_layer, torch.float32, n, "state_layer")
         p_m = _dev(m, self.act_dtype, n, "m")
         _check(lib().srm_mixer_update(self._h, layer, pos, B, p_u, p_s, p_m, _stream(stream)))
+
+
+def sample_logits(logits, temperature, top_p, seed, pos, tok_out, stream=None):
+    """srm_sample_logits on a torch tensor logits [rows][vocab] (fp32)."""
+    torch = _torch()
+    rows, V = logits.shape
+    _check(lib().srm_sample_logits(_dev(logits, torch.float32, rows * V, "logits"), rows, V, float(temperature),
+                                   float(top_p), int(seed), int(pos), _dev(tok_out, torch.int32, rows, "tok_out"),
+                                   _stream(stream)))
 
 
 def linear_scratch_bytes(M: int, N: int) -> int:

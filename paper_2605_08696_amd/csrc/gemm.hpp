@@ -578,6 +578,7 @@ struct FinalizeRagged {
     int32_t n_ctx;
     const int32_t *offsets;   // prefill: sequence boundaries, offsets[row0 + row + 1] - offsets[row0 + row] = length
     int32_t *pos_set;         // prefill: pos_set[destination] = length of the sequence
+    int32_t *zero_counter;    // set to 0 (the row list of the nucleus pass that follows)
 };
 
 // Reduce the per-tile partials of each row to one token; writes `rep`
@@ -593,6 +594,7 @@ argmax_finalize_kernel(const float *__restrict__ part_val, const int32_t *__rest
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (rg.zero_counter && blockIdx.x == 0 && threadIdx.x == 0) *rg.zero_counter = 0;
     if (row >= rows) return;
     float bv = -INFINITY;
     int bi = 0x7fffffff;

@@ -15,6 +15,7 @@
 #include "gemm.hpp"
 #include "mixer.hpp"
 #include "norm.hpp"
+#include "sample.hpp"
 
 // ------------------------------------------------------------------ errors
 static thread_local std::string g_err;
@@ -64,7 +65,7 @@ struct srm_model {
     std::vector<LayerDev> layers;
     // cached graph of one decode step for srm_generate (see there)
     hipGraphExec_t gexec;
-    struct { int64_t B; const void *tok, *state, *store, *ws; float temp; uint32_t seed; } gkey;
+    struct { int64_t B; const void *tok, *state, *store, *ws; float temp; uint32_t seed; float top_p; const void *logits; } gkey;
 };
 
 static uint16_t host_f32_to_bf16(float f)
@@ -138,7 +139,7 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     m->wsize = bf ? 2 : 4;
     m->slab = nullptr;
     m->gexec = nullptr;
-    m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0};
+    m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, 1.0f, nullptr};
 
     struct Offs { size_t v[15]; };
     std::vector<Offs> lo(L);
@@ -220,6 +221,7 @@ struct Workspace {
     float *pv;         // [rows][nparts]
     int32_t *pi;       // [rows][nparts]
     int *ctr;          // [2] position and step counters of srm_generate
+    int *slow;         // [64 + rows] nucleus pass: count, then (from slow + 64) the rows that need the search
     size_t bytes;
 };
 
@@ -242,6 +244,7 @@ static Workspace carve(const srm_model *m, void *base, int64_t rows)
     w.g = take(r * (size_t)m->ff * s);
     w.pv = reinterpret_cast<float *>(take(r * nparts * 4));
     w.pi = reinterpret_cast<int32_t *>(take(r * nparts * 4));
+    w.slow = reinterpret_cast<int *>(take(256 + r * 4));
     w.ctr = reinterpret_cast<int *>(take(256));
     w.bytes = off;
     return w;
@@ -337,7 +340,34 @@ struct Sampling {          // temp == 0: greedy
     int pos = 0;
     const int *pos_dev = nullptr;
     const int *pos_rows = nullptr;
+    float top_p = 1.0f;    // < 1 (with temp > 0): nucleus truncation, needs the logits in memory
 };
+
+// Nucleus pass over the logits the LM head has just written; tok holds the
+// unrestricted Gumbel-max winners and *slow (the row-list counter) is zero.
+static int nucleus(const float *logits, int64_t rows, int V, const Sampling &sm, int32_t *tok, int32_t *store,
+                   const int *step_dev, int64_t store_stride, int32_t *pos_advance, int *slow, hipStream_t st)
+{
+    constexpr int NT = 512, EPT = 64;
+    if (V > NT * EPT) {
+        // vocabulary too large for the register-resident search: one kernel, searching from memory
+        hipLaunchKernelGGL((nucleus_kernel<256, false, false>), dim3((unsigned)rows), dim3(256), 0, st, logits,
+                           (int64_t)V, V, sm.temp, sm.top_p, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, tok, store,
+                           step_dev, store_stride, pos_advance, nullptr, nullptr);
+        HIP_TRY(hipGetLastError());
+        return SRM_OK;
+    }
+    hipLaunchKernelGGL((nucleus_kernel<256, false, true>), dim3((unsigned)rows), dim3(256), 0, st, logits, (int64_t)V,
+                       V, sm.temp, sm.top_p, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, tok, store, step_dev,
+                       store_stride, pos_advance, slow, slow + 64);
+    HIP_TRY(hipGetLastError());
+    const unsigned nb = (unsigned)std::min<int64_t>(rows, 256);
+    hipLaunchKernelGGL((nucleus_slow_kernel<NT, EPT>), dim3(nb), dim3(NT), 0, st, logits, (int64_t)V, V, sm.temp,
+                       sm.top_p, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, tok, store, step_dev, store_stride,
+                       pos_advance, slow, slow + 64);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
 
 // out = epilogue(A W^T + bias) with operands of type T (float or bf16)
 template <int EPI, typename T>
@@ -468,7 +498,7 @@ static int head_argmax(const srm_model *m, const Workspace &w, const void *a, in
 template <typename T>
 static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, float *state, int32_t *tok_out,
                        float *logits, float *hidden, void *ws, hipStream_t st, const int *pos_dev = nullptr,
-                       TokenStore ts = TokenStore(), float temperature = 0.0f, uint32_t seed = 0)
+                       TokenStore ts = TokenStore(), float temperature = 0.0f, uint32_t seed = 0, float top_p = 1.0f)
 {
     const Workspace w = carve(m, ws, B);
     const int d = m->d;
@@ -478,26 +508,35 @@ static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, 
     };
     for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true)));
     if (hidden) HIP_TRY(hipMemcpyAsync(hidden, w.x, (size_t)B * d * 4, hipMemcpyDeviceToDevice, st));
-    return head_argmax<T>(m, w, w.a, B, logits, tok_out, 0, 1, st, ts, Sampling{temperature, seed, pos, pos_dev});
+    const Sampling sm{temperature, seed, pos, pos_dev, nullptr, top_p};
+    const bool topp = temperature > 0.0f && top_p < 1.0f;
+    FinalizeRagged rg{};
+    if (topp) rg.zero_counter = w.slow;
+    SRM_TRY((head_argmax<T>(m, w, w.a, B, logits, tok_out, 0, 1, st, ts, sm, rg)));
+    if (topp) SRM_TRY(nucleus(logits, B, m->V, sm, tok_out, ts.store, ts.step_dev, ts.stride, nullptr, w.slow, st));
+    return SRM_OK;
 }
 
 static int decode_step_common(const char *who, srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in,
                               float *d_state, int32_t *d_tok_out, float *d_logits, float *d_hidden,
                               void *d_workspace, size_t workspace_bytes, void *hip_stream, float temperature,
-                              uint32_t seed)
+                              uint32_t seed, float top_p = 1.0f)
 {
     if (!m || !d_tok_in || !d_state || !d_tok_out || !d_workspace) return fail(SRM_EINVAL, "%s: null argument", who);
     if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "%s: batch %lld out of range", who, (long long)B);
     if (pos < 0 || pos >= m->cfg.n_ctx) return fail(SRM_EINVAL, "%s: pos %d outside [0, %d)", who, pos, m->cfg.n_ctx);
     if (!(temperature >= 0.0f)) return fail(SRM_EINVAL, "%s: temperature must be >= 0", who);
+    if (!(top_p > 0.0f)) return fail(SRM_EINVAL, "%s: top_p must be > 0", who);
+    if (temperature > 0.0f && top_p < 1.0f && !d_logits)
+        return fail(SRM_EINVAL, "%s: top_p < 1 needs a logits buffer", who);
     if (workspace_bytes < srm_workspace_bytes(m, B))
         return fail(SRM_ENOMEM, "%s: workspace %zu < %zu bytes", who, workspace_bytes, srm_workspace_bytes(m, B));
     SRM_TRY(check_device(m));
     hipStream_t st = as_stream(hip_stream);
     return m->wsize == 2 ? decode_impl<bf16>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden, d_workspace,
-                                             st, nullptr, TokenStore(), temperature, seed)
+                                             st, nullptr, TokenStore(), temperature, seed, top_p)
                          : decode_impl<float>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden,
-                                              d_workspace, st, nullptr, TokenStore(), temperature, seed);
+                                              d_workspace, st, nullptr, TokenStore(), temperature, seed, top_p);
 }
 
 extern "C" int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
@@ -516,11 +555,20 @@ extern "C" int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, con
                               d_workspace, workspace_bytes, hip_stream, temperature, seed);
 }
 
+extern "C" int srm_decode_step_topp(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
+                                    int32_t *d_tok_out, float temperature, float top_p, uint32_t seed,
+                                    float *d_logits, float *d_hidden, void *d_workspace, size_t workspace_bytes,
+                                    void *hip_stream)
+{
+    return decode_step_common("srm_decode_step_topp", m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden,
+                              d_workspace, workspace_bytes, hip_stream, temperature, seed, top_p);
+}
+
 // ------------------------------------------------------------------ decode, one position per sample
 template <typename T>
 static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int advance, const int32_t *tok_in,
                               float *state, int32_t *tok_out, float *logits, void *ws, hipStream_t st,
-                              float temperature, uint32_t seed)
+                              float temperature, uint32_t seed, float top_p)
 {
     const Workspace w = carve(m, ws, B);
     const int d = m->d;
@@ -535,51 +583,64 @@ static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int ad
         return (int)SRM_OK;
     };
     for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true)));
+    const bool topp = temperature > 0.0f && top_p < 1.0f;
     FinalizeRagged rg{};
     rg.pos_rows = pos_rows;
-    rg.advance = advance;
+    rg.advance = advance && !topp;        // with a nucleus pass the positions move after it
     rg.n_ctx = m->cfg.n_ctx;
-    return head_argmax<T>(m, w, w.a, B, logits, tok_out, 0, 1, st, TokenStore(),
-                          Sampling{temperature, seed, 0, nullptr, pos_rows}, rg);
+    if (topp) rg.zero_counter = w.slow;
+    const Sampling sm{temperature, seed, 0, nullptr, pos_rows, top_p};
+    SRM_TRY((head_argmax<T>(m, w, w.a, B, logits, tok_out, 0, 1, st, TokenStore(), sm, rg)));
+    if (topp)
+        SRM_TRY(nucleus(logits, B, m->V, sm, tok_out, nullptr, nullptr, 0, advance ? pos_rows : nullptr, w.slow, st));
+    return SRM_OK;
 }
 
 extern "C" int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, int32_t advance,
                                       const int32_t *d_tok_in, float *d_state, int32_t *d_tok_out,
-                                      float temperature, uint32_t seed, float *d_logits, void *d_workspace,
-                                      size_t workspace_bytes, void *hip_stream)
+                                      float temperature, float top_p, uint32_t seed, float *d_logits,
+                                      void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
     const char *who = "srm_decode_step_ragged";
     if (!m || !d_pos || !d_tok_in || !d_state || !d_tok_out || !d_workspace)
         return fail(SRM_EINVAL, "%s: null argument", who);
     if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "%s: batch %lld out of range", who, (long long)B);
     if (!(temperature >= 0.0f)) return fail(SRM_EINVAL, "%s: temperature must be >= 0", who);
+    if (!(top_p > 0.0f)) return fail(SRM_EINVAL, "%s: top_p must be > 0", who);
+    if (temperature > 0.0f && top_p < 1.0f && !d_logits)
+        return fail(SRM_EINVAL, "%s: top_p < 1 needs a logits buffer", who);
     if (workspace_bytes < srm_workspace_bytes(m, B))
         return fail(SRM_ENOMEM, "%s: workspace %zu < %zu bytes", who, workspace_bytes, srm_workspace_bytes(m, B));
     SRM_TRY(check_device(m));
     hipStream_t st = as_stream(hip_stream);
     return m->wsize == 2 ? decode_ragged_impl<bf16>(m, B, d_pos, advance != 0, d_tok_in, d_state, d_tok_out, d_logits,
-                                                    d_workspace, st, temperature, seed)
+                                                    d_workspace, st, temperature, seed, top_p)
                          : decode_ragged_impl<float>(m, B, d_pos, advance != 0, d_tok_in, d_state, d_tok_out,
-                                                     d_logits, d_workspace, st, temperature, seed);
+                                                     d_logits, d_workspace, st, temperature, seed, top_p);
 }
 
 // ------------------------------------------------------------------ generate (G steps in one call)
 static int generate_step(srm_model *m, int64_t B, int32_t *tok, float *state, void *ws, const int *ctr,
-                         TokenStore ts, hipStream_t st, float temperature, uint32_t seed)
+                         TokenStore ts, hipStream_t st, float temperature, uint32_t seed, float top_p, float *logits)
 {
-    SRM_TRY(m->wsize == 2
-                ? decode_impl<bf16>(m, B, 0, tok, state, tok, nullptr, nullptr, ws, st, ctr, ts, temperature, seed)
-                : decode_impl<float>(m, B, 0, tok, state, tok, nullptr, nullptr, ws, st, ctr, ts, temperature, seed));
+    SRM_TRY(m->wsize == 2 ? decode_impl<bf16>(m, B, 0, tok, state, tok, logits, nullptr, ws, st, ctr, ts, temperature,
+                                              seed, top_p)
+                          : decode_impl<float>(m, B, 0, tok, state, tok, logits, nullptr, ws, st, ctr, ts,
+                                               temperature, seed, top_p));
     hipLaunchKernelGGL(counters_advance_kernel, dim3(1), dim3(1), 0, st, const_cast<int *>(ctr));
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
 
-extern "C" int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
-                            int32_t *d_tokens_out, float temperature, uint32_t seed, void *d_workspace,
-                            size_t workspace_bytes, void *hip_stream)
+static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+                           int32_t *d_tokens_out, float temperature, uint32_t seed, float top_p, float *d_logits,
+                           void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!m || !d_tok || !d_state || !d_tokens_out || !d_workspace) return fail(SRM_EINVAL, "srm_generate: null argument");
+    if (!(top_p > 0.0f)) return fail(SRM_EINVAL, "srm_generate: top_p must be > 0");
+    const bool topp = temperature > 0.0f && top_p < 1.0f;
+    if (topp && !d_logits) return fail(SRM_EINVAL, "srm_generate: top_p < 1 needs a logits buffer");
+    if (!topp) { d_logits = nullptr; top_p = 1.0f; }
     if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "srm_generate: batch %lld out of range", (long long)B);
     if (G <= 0) return fail(SRM_EINVAL, "srm_generate: G must be positive");
     if (!(temperature >= 0.0f)) return fail(SRM_EINVAL, "srm_generate: temperature must be >= 0");
@@ -595,33 +656,50 @@ extern "C" int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, in
     hipLaunchKernelGGL(counters_set_kernel, dim3(1), dim3(1), 0, st, w.ctr, pos0, 0);
     HIP_TRY(hipGetLastError());
     // first step eagerly (it also performs every one-time kernel attribute set-up)
-    SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed));
+    SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed, top_p, d_logits));
     if (G == 1) return SRM_OK;
     // The legacy default stream cannot be captured: loop eagerly there.
     if (st == nullptr) {
         for (int g = 1; g < G; ++g)
-            SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed));
+            SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed, top_p, d_logits));
         return SRM_OK;
     }
     const bool hit = m->gexec && m->gkey.B == B && m->gkey.tok == d_tok && m->gkey.state == d_state &&
                      m->gkey.store == d_tokens_out && m->gkey.ws == d_workspace && m->gkey.temp == temperature &&
-                     m->gkey.seed == seed;
+                     m->gkey.seed == seed && m->gkey.top_p == top_p && m->gkey.logits == d_logits;
     if (!hit) {
         if (m->gexec) { (void)hipGraphExecDestroy(m->gexec); m->gexec = nullptr; }
         hipGraph_t graph = nullptr;
         HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-        const int rc = generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed);
+        const int rc = generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed, top_p,
+                                     d_logits);
         const hipError_t e = hipStreamEndCapture(st, &graph);
         if (rc != SRM_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
         if (e != hipSuccess) return fail(SRM_EHIP, "srm_generate: stream capture failed: %s", hipGetErrorString(e));
         const hipError_t e2 = hipGraphInstantiate(&m->gexec, graph, nullptr, nullptr, 0);
         (void)hipGraphDestroy(graph);
         if (e2 != hipSuccess) { m->gexec = nullptr; return fail(SRM_EHIP, "srm_generate: hipGraphInstantiate: %s", hipGetErrorString(e2)); }
-        m->gkey = {B, d_tok, d_state, d_tokens_out, d_workspace, temperature, seed};
+        m->gkey = {B, d_tok, d_state, d_tokens_out, d_workspace, temperature, seed, top_p, d_logits};
         // the captured step was recorded, not run: replay it G - 1 times below
     }
     for (int g = 1; g < G; ++g) HIP_TRY(hipGraphLaunch(m->gexec, st));
     return SRM_OK;
+}
+
+extern "C" int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+                            int32_t *d_tokens_out, float temperature, uint32_t seed, void *d_workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    return generate_common(m, B, pos0, G, d_tok, d_state, d_tokens_out, temperature, seed, 1.0f, nullptr, d_workspace,
+                           workspace_bytes, hip_stream);
+}
+
+extern "C" int srm_generate_topp(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+                                 int32_t *d_tokens_out, float temperature, float top_p, uint32_t seed,
+                                 float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return generate_common(m, B, pos0, G, d_tok, d_state, d_tokens_out, temperature, seed, top_p, d_logits,
+                           d_workspace, workspace_bytes, hip_stream);
 }
 
 // ------------------------------------------------------------------ prefill
@@ -847,6 +925,20 @@ extern "C" int srm_mixer_update(srm_model *m, int32_t layer, int32_t pos, int64_
     hipStream_t st = as_stream(hip_stream);
     return m->wsize == 2 ? state_update<bf16>(m, layer, pos, B, d_u, d_state_layer, d_m, st)
                          : state_update<float>(m, layer, pos, B, d_u, d_state_layer, d_m, st);
+}
+
+extern "C" int srm_sample_logits(const float *d_logits, int64_t rows, int32_t vocab, float temperature, float top_p,
+                                 uint32_t seed, int32_t pos, int32_t *d_tok_out, void *hip_stream)
+{
+    if (!d_logits || !d_tok_out) return fail(SRM_EINVAL, "srm_sample_logits: null argument");
+    if (rows <= 0 || rows >= (1 << 30) || vocab <= 0) return fail(SRM_EINVAL, "srm_sample_logits: sizes out of range");
+    if (!(temperature > 0.0f)) return fail(SRM_EINVAL, "srm_sample_logits: temperature must be > 0");
+    if (!(top_p > 0.0f)) return fail(SRM_EINVAL, "srm_sample_logits: top_p must be > 0");
+    hipLaunchKernelGGL((nucleus_kernel<256, true, false>), dim3((unsigned)rows), dim3(256), 0, as_stream(hip_stream),
+                       d_logits, (int64_t)vocab, vocab, temperature, top_p, seed, pos, nullptr, nullptr, d_tok_out,
+                       nullptr, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
 }
 
 extern "C" size_t srm_linear_scratch_bytes(int64_t M, int32_t N)
