@@ -3,6 +3,8 @@
 //   state_update_kernel   one position for every sample (decode): Eq. 2 / Eq. 3
 //   mixer_scan_kernel     all prompt positions in sequence (prefill), state kept
 //                         in registers, same arithmetic as state_update_kernel
+//   scan_chunk_*_kernel   the same scan cut into chunks that run side by side
+//                         (prefill of few sequences)
 //   mixer_parallel_kernel the explicit triangular product Y = U M + beta with M
 //                         built on the fly from alpha and lambda (Eq. 1, Eq. 3)
 //
@@ -210,6 +212,127 @@ mixer_scan_ragged_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float
     } else {
         float *dst = S + ((seq0 + seq) * rep) * (int64_t)d + cv * 4;
         for (int r = 0; r < rep; ++r) store4(dst + (int64_t)r * d, s);
+    }
+}
+
+// Chunked scan for prefill with few sequences, where the sequential kernels leave
+// most of the chip idle (the "parallel scan for recurrent prefill" the paper's
+// "MAX model details" name as unexplored).  The recurrence S_t = lam S_{t-1} + p_t u_t
+// is linear, so the state entering chunk j (positions j*c ..) is
+//   C_j = lam^c C_{j-1} + F_{j-1},   C_0 = 0,
+// with F_j the state chunk j reaches from zero.  Two launches:
+//   scan_chunk_partials_kernel  F_j for every chunk but the last  (thread = sequence x chunk x 4 channels)
+//   scan_chunk_apply_kernel     each thread folds the F_i, i < j, into C_j (a short loop), then
+//                               scans its chunk from C_j, writing m; the last chunk writes the state
+// The sums are the sequential ones in another association: results agree with
+// mixer_scan_kernel to fp32 rounding, not bit for bit.  u, m: [rows][d];
+// sequence s occupies rows s*P .. s*P+P-1, or, with offsets, rows
+// offsets[seq0+s]-base .. offsets[seq0+s+1]-base-1 (clamped as in
+// mixer_scan_ragged_kernel).  F: [nseq][nchunks][d] fp32 scratch.
+template <typename TAct>
+__device__ __forceinline__ void scan_chunk_range(int64_t seq, int P, const int32_t *offsets, int64_t base,
+                                                 int64_t rows, int64_t seq0, int n_ctx, int64_t &r0, int &len)
+{
+    if (offsets) {
+        r0 = min(max((int64_t)offsets[seq0 + seq] - base, (int64_t)0), rows);
+        const int64_t r1 = min(max((int64_t)offsets[seq0 + seq + 1] - base, r0), rows);
+        len = (int)min(r1 - r0, (int64_t)n_ctx);
+    } else {
+        r0 = seq * P;
+        len = P;
+    }
+}
+
+template <typename TAct>
+__global__ void __launch_bounds__(256)
+scan_chunk_partials_kernel(const TAct *__restrict__ u, float *__restrict__ F, const float *__restrict__ alpha,
+                           const float *__restrict__ lam, int n_ctx, int H, int d, int nseq, int P, int c,
+                           int nchunks, const int32_t *__restrict__ offsets, int64_t base, int64_t rows,
+                           int64_t seq0)
+{
+    const int dv = d >> 2, dhv = (d / H) >> 2;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int cv = (int)(gid % dv);
+    const int64_t sj = gid / dv;
+    const int j = (int)(sj % nchunks);
+    const int64_t seq = sj / nchunks;
+    if (seq >= nseq || j >= nchunks - 1) return;
+    int64_t r0;
+    int len;
+    scan_chunk_range<TAct>(seq, P, offsets, base, rows, seq0, n_ctx, r0, len);
+    const int t0 = j * c, t1 = min(t0 + c, len);
+    if (t0 >= len) return;
+    const int h = cv / dhv;
+    const bool row_repeat = h < H / 2;
+    const float l = lam[h];
+    const TAct *up = u + r0 * (int64_t)d + cv * 4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int t = t0; t < t1; ++t) {
+        const float4 x = load4(up + (int64_t)t * d);
+        const float p = row_repeat ? alpha[(size_t)h * n_ctx + t] : 1.0f;
+        s.x = fmaf(l, s.x, p * x.x);
+        s.y = fmaf(l, s.y, p * x.y);
+        s.z = fmaf(l, s.z, p * x.z);
+        s.w = fmaf(l, s.w, p * x.w);
+    }
+    store4(F + (seq * nchunks + j) * (int64_t)d + cv * 4, s);
+}
+
+template <typename TAct>
+__global__ void __launch_bounds__(256)
+scan_chunk_apply_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__restrict__ S,
+                        const float *__restrict__ F, const float *__restrict__ alpha,
+                        const float *__restrict__ beta, const float *__restrict__ lam, int n_ctx, int H, int d,
+                        int nseq, int P, int c, int nchunks, const int32_t *__restrict__ offsets, int64_t base,
+                        int64_t rows, int64_t seq0, int rep, const int32_t *__restrict__ slot, int64_t nslots)
+{
+    const int dv = d >> 2, dhv = (d / H) >> 2;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int cv = (int)(gid % dv);
+    const int64_t sj = gid / dv;
+    const int j = (int)(sj % nchunks);
+    const int64_t seq = sj / nchunks;
+    if (seq >= nseq) return;
+    int64_t r0;
+    int len;
+    scan_chunk_range<TAct>(seq, P, offsets, base, rows, seq0, n_ctx, r0, len);
+    const int t0 = j * c, t1 = min(t0 + c, len);
+    if (t0 >= len) return;
+    const int h = cv / dhv;
+    const bool row_repeat = h < H / 2;
+    const float l = lam[h];
+    float lc = 1.0f;                               // lam^c
+    for (int i = 0; i < c; ++i) lc *= l;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float *Fp = F + (seq * nchunks) * (int64_t)d + cv * 4;
+    for (int i = 0; i < j; ++i) {
+        const float4 f = load4(Fp + (int64_t)i * d);
+        s.x = fmaf(lc, s.x, f.x);
+        s.y = fmaf(lc, s.y, f.y);
+        s.z = fmaf(lc, s.z, f.z);
+        s.w = fmaf(lc, s.w, f.w);
+    }
+    const TAct *up = u + r0 * (int64_t)d + cv * 4;
+    TAct *mp = m + r0 * (int64_t)d + cv * 4;
+    for (int t = t0; t < t1; ++t) {
+        const float4 x = load4(up + (int64_t)t * d);
+        const float a = alpha[(size_t)h * n_ctx + t], be = beta[(size_t)h * n_ctx + t];
+        const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
+        float4 o;
+        s.x = fmaf(l, s.x, p * x.x); o.x = fmaf(q, s.x, be);
+        s.y = fmaf(l, s.y, p * x.y); o.y = fmaf(q, s.y, be);
+        s.z = fmaf(l, s.z, p * x.z); o.z = fmaf(q, s.z, be);
+        s.w = fmaf(l, s.w, p * x.w); o.w = fmaf(q, s.w, be);
+        store4(mp + (int64_t)t * d, o);
+    }
+    if (t1 == len) {                               // this chunk ends the sequence: its state is the result
+        if (slot) {
+            const int64_t dst = slot[seq0 + seq];
+            if (dst >= 0 && dst < nslots) store4(S + dst * (int64_t)d + cv * 4, s);
+        } else {
+            float *dst = S + ((seq0 + seq) * rep) * (int64_t)d + cv * 4;
+            for (int r = 0; r < rep; ++r) store4(dst + (int64_t)r * d, s);
+        }
     }
 }
 

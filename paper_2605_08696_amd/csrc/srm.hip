@@ -715,13 +715,65 @@ static int64_t seqs_per_pass(const srm_model *m, size_t workspace_bytes, int T, 
     return lo;
 }
 
+// Chunk length of the chunked scan for a call with nseq sequences of up to P
+// positions, or 0 for the sequential kernel.  Chunks are used only while the
+// sequential kernel (one thread per sequence and 4 channels) would leave the
+// chip mostly idle; the choice depends on the whole call, not on how the
+// workspace cuts it into passes, so results do not depend on the workspace size.
+static int scan_chunk_len(const srm_model *m, int64_t nseq, int P)
+{
+    const int64_t dv = m->d / 4;
+    if (P < 64 || nseq * dv >= 65536) return 0;
+    for (int c : {16, 32, 64, 128}) {
+        const int64_t nch = cdiv(P, c);
+        if (nch < 2) break;
+        if (nseq * dv * nch <= 262144) return c;
+    }
+    return 0;
+}
+
+// The mixer of one prefill pass: nc sequences in rows of w.u -> w.mx, final states to S_layer.
+template <typename T>
+static int prefill_mixer(const srm_model *m, int l, const Workspace &w, float *S_layer, int nc, int P, int chunk,
+                         int nchunks, const int32_t *offsets, int64_t base, int64_t rows, int64_t seq0, int rep,
+                         const int32_t *slot, int64_t nslots, hipStream_t st)
+{
+    const LayerDev &y = m->layers[l];
+    const int d = m->d;
+    if (chunk > 0) {
+        float *F = static_cast<float *>(w.g);       // free until the MLP of this layer
+        const unsigned nb = (unsigned)cdiv((int64_t)nc * nchunks * (d / 4), 256);
+        hipLaunchKernelGGL((scan_chunk_partials_kernel<T>), dim3(nb), dim3(256), 0, st, static_cast<const T *>(w.u), F,
+                           y.alpha, y.lam, m->cfg.n_ctx, m->H, d, nc, P, chunk, nchunks, offsets, base, rows, seq0);
+        HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL((scan_chunk_apply_kernel<T>), dim3(nb), dim3(256), 0, st, static_cast<const T *>(w.u),
+                           static_cast<T *>(w.mx), S_layer, F, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc, P,
+                           chunk, nchunks, offsets, base, rows, seq0, rep, slot, nslots);
+        HIP_TRY(hipGetLastError());
+        return SRM_OK;
+    }
+    const unsigned nb = (unsigned)cdiv((int64_t)nc * (d / 4), 256);
+    const size_t scan_lds = (size_t)2 * m->H * P * sizeof(float);
+    if (offsets)
+        hipLaunchKernelGGL((mixer_scan_ragged_kernel<T>), dim3(nb), dim3(256), scan_lds, st,
+                           static_cast<const T *>(w.u), static_cast<T *>(w.mx), S_layer, y.alpha, y.beta, y.lam,
+                           m->cfg.n_ctx, m->H, d, nc, P, offsets, base, rows, seq0, rep, slot, nslots);
+    else
+        hipLaunchKernelGGL((mixer_scan_kernel<T>), dim3(nb), dim3(256), scan_lds, st, static_cast<const T *>(w.u),
+                           static_cast<T *>(w.mx), S_layer, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc, P, seq0,
+                           rep);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
 template <typename T>
 static int prefill_impl(srm_model *m, const int32_t *prompts, int N, int P, int k, float *state,
                         int32_t *next_tok, float *logits, void *ws, int64_t per_pass, hipStream_t st)
 {
     const int d = m->d;
     const int64_t Btot = (int64_t)N * k;
-    const size_t scan_lds = (size_t)2 * m->H * P * sizeof(float);
+    const int chunk = scan_chunk_len(m, N, P);
+    const int nchunks = chunk ? (int)cdiv(P, chunk) : 1;
     for (int64_t n0 = 0; n0 < N; n0 += per_pass) {
         const int64_t nc = std::min<int64_t>(per_pass, N - n0);
         const int64_t rows = nc * P;
@@ -729,14 +781,8 @@ static int prefill_impl(srm_model *m, const int32_t *prompts, int N, int P, int 
         SRM_TRY((layernorm<T, true>(m, nullptr, 0, prompts + n0 * P, w.x, m->layers[0].ln1_g,
                                     m->layers[0].ln1_b, w.a, rows, st)));
         auto mix = [&](int l) {
-            const LayerDev &y = m->layers[l];
-            const unsigned nb = (unsigned)cdiv(nc * (d / 4), 256);
-            hipLaunchKernelGGL((mixer_scan_kernel<T>), dim3(nb), dim3(256), scan_lds, st,
-                               static_cast<const T *>(w.u), static_cast<T *>(w.mx),
-                               state + (size_t)l * Btot * d, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d,
-                               (int)nc, P, n0, k);
-            HIP_TRY(hipGetLastError());
-            return (int)SRM_OK;
+            return prefill_mixer<T>(m, l, w, state + (size_t)l * Btot * d, (int)nc, P, chunk, nchunks, nullptr, 0, rows,
+                                    n0, k, nullptr, 0, st);
         };
         for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, rows, st, mix, l + 1 < m->L)));
         // final LayerNorm of each prompt's last position only, packed [nc][d] into w.a
@@ -775,9 +821,12 @@ extern "C" int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, in
 template <typename T>
 static int prefill_ragged_impl(srm_model *m, const int32_t *tokens, const int32_t *h_off, const int32_t *d_off, int N,
                                int k, const int32_t *slot, int64_t state_batch, float *state, int32_t *next_tok,
-                               int32_t *pos_out, float *logits, void *ws, int64_t max_rows, hipStream_t st)
+                               int32_t *pos_out, float *logits, void *ws, int64_t max_rows, int pmax_call,
+                               hipStream_t st)
 {
     const int d = m->d;
+    const int chunk = scan_chunk_len(m, N, pmax_call);
+    const int nchunks = chunk ? (int)cdiv(pmax_call, chunk) : 1;
     int n0 = 0;
     while (n0 < N) {
         // as many whole prompts as the workspace holds
@@ -792,16 +841,9 @@ static int prefill_ragged_impl(srm_model *m, const int32_t *tokens, const int32_
         const Workspace w = carve(m, ws, rows);
         SRM_TRY((layernorm<T, true>(m, nullptr, 0, tokens + base, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a,
                                     rows, st)));
-        const size_t scan_lds = (size_t)2 * m->H * pmax * sizeof(float);
         auto mix = [&](int l) {
-            const LayerDev &y = m->layers[l];
-            const unsigned nb = (unsigned)cdiv((int64_t)nc * (d / 4), 256);
-            hipLaunchKernelGGL((mixer_scan_ragged_kernel<T>), dim3(nb), dim3(256), scan_lds, st,
-                               static_cast<const T *>(w.u), static_cast<T *>(w.mx),
-                               state + (size_t)l * state_batch * d, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc,
-                               pmax, d_off, base, rows, (int64_t)n0, k, slot, state_batch);
-            HIP_TRY(hipGetLastError());
-            return (int)SRM_OK;
+            return prefill_mixer<T>(m, l, w, state + (size_t)l * state_batch * d, nc, chunk ? pmax_call : pmax, chunk,
+                                    nchunks, d_off, base, rows, (int64_t)n0, k, slot, state_batch, st);
         };
         for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, rows, st, mix, l + 1 < m->L)));
         // final LayerNorm of each prompt's last row, packed [nc][d] into w.a
@@ -858,10 +900,10 @@ extern "C" int srm_prefill_ragged(srm_model *m, const int32_t *d_tokens, const i
     hipStream_t st = as_stream(hip_stream);
     return m->wsize == 2 ? prefill_ragged_impl<bf16>(m, d_tokens, h_offsets, d_offsets, N, fanout_k, d_slot,
                                                      state_batch, d_state, d_next_tok, d_pos, d_logits, d_workspace,
-                                                     max_rows, st)
+                                                     max_rows, pmax, st)
                          : prefill_ragged_impl<float>(m, d_tokens, h_offsets, d_offsets, N, fanout_k, d_slot,
                                                       state_batch, d_state, d_next_tok, d_pos, d_logits, d_workspace,
-                                                      max_rows, st);
+                                                      max_rows, pmax, st);
 }
 
 // ------------------------------------------------------------------ parallel form

@@ -265,3 +265,82 @@ def test_ragged_errors(c1, srm):
     with pytest.raises(srm.SrmError):                         # workspace too small for the batch
         model.decode_step_ragged(4, tk, tk, st, tk, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     torch.cuda.synchronize()
+
+
+# ---- chunked scan: prefill of few, long prompts ------------------------------------------------
+@pytest.mark.parametrize("N,P", [(1, 256), (2, 200), (3, 65)])
+def test_chunked_scan_prefill_matches_oracle_and_decode_steps(c1, N, P):
+    """Few long prompts take the chunked mixer scan; it must agree with the oracle's recurrence
+    and, to fp32 rounding, with P single decode steps."""
+    cfg, w, model, orc = c1
+    rng = np.random.default_rng(100 + P)
+    prompts = rng.integers(0, cfg.vocab, (N, P)).astype(np.int32)
+    ref = orc.greedy(prompts, 1, want_logits=True)
+    print(f"chunked scan prefill N={N} P={P}", flush=True)
+    ws = model.new_workspace(N * P)
+    st, tk = model.new_state(N), torch.empty(N, dtype=torch.int32, device="cuda")
+    lg = torch.empty((N, cfg.vocab), dtype=torch.float32, device="cuda")
+    st.fill_(float("nan"))
+    model.prefill(to_dev(prompts), 1, st, tk, logits=lg, workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, 0]) <= 1e-4
+    s_got = st.view(cfg.n_layers, N, cfg.d_model).permute(1, 0, 2).cpu().numpy()
+    assert np.abs(s_got - ref["state"]).max() <= 1e-4 * np.abs(ref["state"]).max()
+    absmax = np.abs(ref["logits"][:, 0]).max(axis=1)
+    assert check_tokens(tk.cpu().numpy(), ref["tokens"][:, 0], ref["margin"][:, 0], absmax) == 0
+    # against the step-by-step path
+    st_b, tk_b = model.new_state(N), torch.empty(N, dtype=torch.int32, device="cuda")
+    st_b.zero_()
+    pc = to_dev(prompts).t().contiguous()
+    for t in range(P):
+        model.decode_step(N, t, pc[t], st_b, tk_b, workspace=ws)
+    torch.cuda.synchronize()
+    assert (st - st_b).abs().max() <= 1e-5 * st_b.abs().max()
+    # a workspace that holds one prompt per pass gives the same bits (the chunking depends on the call only)
+    st_c, tk_c = model.new_state(N), torch.empty(N, dtype=torch.int32, device="cuda")
+    model.prefill(to_dev(prompts), 1, st_c, tk_c, workspace=torch.empty(model.workspace_bytes(P), dtype=torch.uint8,
+                                                                         device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(st, st_c) and torch.equal(tk, tk_c)
+
+
+def test_chunked_scan_ragged_prompts(c1):
+    cfg, w, model, orc = c1
+    lens = [200, 77, 1, 130, 16]
+    rng = np.random.default_rng(7)
+    prompts = rng.integers(0, cfg.vocab, (len(lens), 200)).astype(np.int32)
+    toks, off = _pack(prompts, lens)
+    N = len(lens)
+    ws = model.new_workspace(int(off[-1]))
+    st, tk = model.new_state(N), torch.empty(N, dtype=torch.int32, device="cuda")
+    st.fill_(float("nan"))
+    lg = torch.empty((N, cfg.vocab), dtype=torch.float32, device="cuda")
+    print(f"chunked scan ragged lens={lens}", flush=True)
+    keep = model.prefill_ragged(to_dev(toks), off, st, tk, logits=lg, workspace=ws)
+    torch.cuda.synchronize()
+    del keep
+    sv = st.view(cfg.n_layers, N, cfg.d_model)
+    for b, n in enumerate(lens):
+        ref = orc.greedy(prompts[b:b + 1, :n], 1, want_logits=True)
+        assert rel_err_rows(lg[b:b + 1].cpu().numpy(), ref["logits"][:, 0]) <= 1e-4
+        assert np.abs(sv[:, b].cpu().numpy() - ref["state"][0]).max() <= 1e-4 * np.abs(ref["state"][0]).max()
+        assert int(tk[b]) == int(ref["tokens"][0, 0])
+
+
+def test_chunked_scan_bf16(srm, orc_mod):
+    cfg = srm_synth.tiny_config(vocab=300, d_model=128, n_layers=3, n_heads=4, n_ctx=160, weight_dtype="bf16", seed=13)
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    orc = orc_mod.Oracle(cfg, w, "f64")
+    N, P = 4, 150
+    prompts = np.random.default_rng(3).integers(0, cfg.vocab, (N, P)).astype(np.int32)
+    ref = orc.greedy(prompts, 1, want_logits=True)
+    ws = model.new_workspace(N * P)
+    st, tk = model.new_state(N), torch.empty(N, dtype=torch.int32, device="cuda")
+    lg = torch.empty((N, cfg.vocab), dtype=torch.float32, device="cuda")
+    print(f"chunked scan bf16 N={N} P={P}", flush=True)
+    model.prefill(to_dev(prompts), 1, st, tk, logits=lg, workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, 0]) <= 2e-2
+    s_got = st.view(cfg.n_layers, N, cfg.d_model).permute(1, 0, 2).cpu().numpy()
+    assert np.abs(s_got - ref["state"]).max() <= 2e-2 * np.abs(ref["state"]).max()
