@@ -97,19 +97,22 @@ __device__ __forceinline__ void epi_store(const GemmEpi &ep, int64_t row, int co
 // conflict-free (measured: SQ_LDS_BANK_CONFLICT ~1% of SQ_LDS_IDX_ACTIVE).
 __device__ __forceinline__ int swz_of_row(int r) { return (r >> 1) & 7; }
 
-// erfc-based GELU for bf16 outputs: Phi(x) from the rational approximation
-// 7.1.26 of Abramowitz & Stegun (|error| of erf <= 1.5e-7), evaluated without
-// cancellation in the negative tail.  The result is rounded to bf16 (relative
+// Exact (erf) GELU for bf16 outputs: x * Phi(x) with erfc(z) / 2 = 2^-P(z),
+// z = |x| / sqrt(2) clamped to 4.3 (beyond it Phi is 0 or 1 to 1e-9), P a degree-6
+// polynomial fitted to -log2(erfc(z) / 2) (minimax in the absolute error of
+// erfc: 2.2e-7; |error| of the GELU value <= 6.5e-7 in fp32 evaluation), so one
+// exp2 and six FMAs, no reciprocal.  The result is rounded to bf16 (relative
 // 2^-9) right after, so the approximation error is invisible there.
 __device__ __forceinline__ float gelu_bf16out(float x)
 {
-    const float z = fabsf(x) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-    float p = fmaf(t, 1.061405429f, -1.453152027f);
-    p = fmaf(t, p, 1.421413741f);
-    p = fmaf(t, p, -0.284496736f);
-    p = fmaf(t, p, 0.254829592f);
-    const float q = 0.5f * t * p * __builtin_amdgcn_exp2f(-z * z * 1.44269504088896340736f);   // erfc(z)/2
+    const float z = fminf(fabsf(x) * 0.70710678118654752440f, 4.3f);
+    float p = fmaf(z, -0.00015339720622212807f, 0.003725629992140978f);
+    p = fmaf(z, p, -0.031017635167076434f);
+    p = fmaf(z, p, 0.1498087523043019f);
+    p = fmaf(z, p, 0.9181205081101346f);
+    p = fmaf(z, p, 1.6279324177979881f);
+    p = fmaf(z, p, 0.9999996936263803f);
+    const float q = __builtin_amdgcn_exp2f(-p);                  // erfc(z) / 2
     return x * (x >= 0.0f ? 1.0f - q : q);
 }
 
@@ -290,6 +293,17 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     bf16 *As = reinterpret_cast<bf16 *>(smem_raw);   // [2][BM*BK]
     bf16 *Bs = As + 2 * BM * BK;                     // [2][BN*BK]
 
+    // Split K (gridDim.y > 1, EPI_F32 only): block row y of the grid contracts k in
+    // [y * K / gridDim.y, (y + 1) * K / gridDim.y) and writes its own output slab
+    // out + y * M * ldo; slab 0 carries the bias.  The consumer adds the slabs in
+    // a fixed order, so the result does not depend on scheduling.
+    const int ksplit = gridDim.y;
+    const int kbeg = blockIdx.y * (K / ksplit);
+    if (ksplit > 1) {
+        ep.out = reinterpret_cast<float *>(ep.out) + (int64_t)blockIdx.y * M * ep.ldo;
+        if (blockIdx.y) ep.bias = nullptr;
+    }
+
     const int nbm = (M + BM - 1) / BM, nbn = (N + BN - 1) / BN;
     int bm, bn;
     tile_of_block(nbm, nbn, bm, bn);
@@ -318,11 +332,11 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     _Pragma("unroll") for (int i = 0; i < A_IT; ++i)                                             \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
             rs_a, (lds_void *)(As + (buf) * BM * BK + (i * ROWS_PER_IT + wave * 8) * BK), 16,    \
-            ld_voff, (i * ROWS_PER_IT * K + (k0)) * 2, 0, 0);                                    \
+            ld_voff, (i * ROWS_PER_IT * K + kbeg + (k0)) * 2, 0, 0);                             \
     _Pragma("unroll") for (int i = 0; i < B_IT; ++i)                                             \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
             rs_w, (lds_void *)(Bs + (buf) * BN * BK + (i * ROWS_PER_IT + wave * 8) * BK), 16,    \
-            ld_voff, (i * ROWS_PER_IT * K + (k0)) * 2, 0, 0);
+            ld_voff, (i * ROWS_PER_IT * K + kbeg + (k0)) * 2, 0, 0);
     // s_waitcnt immediate: vmcnt = n, expcnt and lgkmcnt unconstrained
 #define SRM_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
@@ -378,7 +392,7 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     // two substeps, which absorbs the queueing of reads behind the tile writes in
     // the LDS pipe.  Loads for tiles past the end are issued like any other
     // (range check: zeros nobody reads), which keeps the loop branch-free.
-    const int KT = K / BK;
+    const int KT = K / ksplit / BK;
     SRM_DMA_TILE(0, 0)
     SRM_DMA_TILE(BK, 1)
     SRM_WAIT_VM(A_IT + B_IT);

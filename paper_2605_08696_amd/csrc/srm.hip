@@ -222,8 +222,16 @@ struct Workspace {
     int32_t *pi;       // [rows][nparts]
     int *ctr;          // [2] position and step counters of srm_generate
     int *slow;         // [64 + rows] nucleus pass: count, then (from slow + 64) the rows that need the search
+    float *part;       // [kSplitK][rows][d] split-K slabs of the down projection (rows <= kSplitMaxRows), else null
     size_t bytes;
 };
+
+// Split-K of the MLP down projection for small batches: with few token rows the
+// GEMM has too few tiles to fill the chip and a long serial k loop, so K is cut
+// into kSplitK slices whose fp32 slabs the following LayerNorm kernel adds to the
+// residual stream (in slab order: deterministic).
+constexpr int kSplitK = 4;
+constexpr int64_t kSplitMaxRows = 2048;
 
 static Workspace carve(const srm_model *m, void *base, int64_t rows)
 {
@@ -245,6 +253,7 @@ static Workspace carve(const srm_model *m, void *base, int64_t rows)
     w.pv = reinterpret_cast<float *>(take(r * nparts * 4));
     w.pi = reinterpret_cast<int32_t *>(take(r * nparts * 4));
     w.slow = reinterpret_cast<int *>(take(256 + r * 4));
+    w.part = rows <= kSplitMaxRows ? reinterpret_cast<float *>(take((size_t)kSplitK * r * d * 4)) : nullptr;
     w.ctr = reinterpret_cast<int *>(take(256));
     w.bytes = off;
     return w;
@@ -258,7 +267,8 @@ extern "C" size_t srm_workspace_bytes(const srm_model *m, int64_t rows)
 
 // ------------------------------------------------------------------ launchers
 template <int BM, int BN, int WM, int WN, int EPI, typename TAct>
-static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, const GemmEpi &ep, hipStream_t st)
+static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, const GemmEpi &ep, hipStream_t st,
+                            int ksplit = 1)
 {
     constexpr size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(bf16);
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI, TAct>;
@@ -269,7 +279,7 @@ static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, c
         attr_set = true;
     }
     const int64_t nb = cdiv(M, BM) * cdiv(N, BN);
-    hipLaunchKernelGGL(kern, dim3((unsigned)nb), dim3(WM * WN * 64), smem, st, A, W, M, N, K, ep);
+    hipLaunchKernelGGL(kern, dim3((unsigned)nb, (unsigned)ksplit), dim3(WM * WN * 64), smem, st, A, W, M, N, K, ep);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
@@ -294,9 +304,16 @@ static thread_local int g_force_tile = -1;   // test/bench hook of srm_linear on
 
 template <int EPI, typename TAct>
 static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, GemmEpi ep, hipStream_t st,
-                       int min_bn, int *nparts_out)
+                       int min_bn, int *nparts_out, int ksplit = 1)
 {
     if (K % 64) return fail(SRM_EINVAL, "bf16 GEMM needs K %% 64 == 0 (K = %d)", K);
+    if (ksplit > 1) {
+        // slices of whole 64-wide k tiles, fp32 slabs, small tiles (the point is to fill the chip)
+        if (EPI != EPI_F32 || K % (64 * ksplit)) return fail(SRM_EINVAL, "bf16 GEMM: bad split of K = %d", K);
+        if (M <= 0 || M >= (1 << 30) || N <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
+        ep.nparts = 0;
+        return launch_bf16_tile<64, 64, 2, 2, EPI, TAct>(A, W, (int)M, N, K, ep, st, ksplit);
+    }
     if (M <= 0 || M >= (1 << 30) || N <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
     if ((int64_t)K * 256 * 2 >= (1LL << 31)) return fail(SRM_EINVAL, "bf16 GEMM: K = %d too large", K);
     const int tile = g_force_tile >= 0 ? g_force_tile : choose_tile(M, N, min_bn);
@@ -373,12 +390,12 @@ static int nucleus(const float *logits, int64_t rows, int V, const Sampling &sm,
 template <int EPI, typename T>
 static int linear(const void *A, const void *W, const float *bias, int64_t M, int N, int K, void *out,
                   hipStream_t st, float *pv = nullptr, int32_t *pi = nullptr, int min_bn = 64,
-                  int *nparts_out = nullptr, Sampling sm = Sampling())
+                  int *nparts_out = nullptr, Sampling sm = Sampling(), int ksplit = 1)
 {
     GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows};
     if constexpr (sizeof(T) == 2)
         return launch_bf16<EPI, bf16>(static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), M, N, K, ep,
-                                      st, min_bn, nparts_out);
+                                      st, min_bn, nparts_out, ksplit);
     else
         return launch_f32<EPI>(static_cast<const float *>(A), static_cast<const float *>(W), M, N, K, ep, st,
                                nparts_out);
@@ -403,7 +420,8 @@ static int argmax_finalize(const float *pv, const int32_t *pi, int64_t rows, int
 template <typename T, bool GATHER>
 static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, const int32_t *tok,
                      float *x_out, const float *g, const float *b, void *out, int64_t rows, hipStream_t st,
-                     const int32_t *seq_end = nullptr, int64_t base = 0, int64_t src_rows = 0)
+                     const int32_t *seq_end = nullptr, int64_t base = 0, int64_t src_rows = 0,
+                     const float *part = nullptr, int nsplit = 0)
 {
     const int d = m->d;
     const unsigned nb = (unsigned)cdiv(rows, 4);
@@ -411,7 +429,8 @@ static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, c
     T *o = static_cast<T *>(out);
 #define LN_CASE(VPL)                                                                                     \
     hipLaunchKernelGGL((ln_kernel<T, T, VPL, GATHER>), dim3(nb), dim3(256), 0, st, x_in, in_stride, tok, \
-                       emb, m->V, x_out, g, b, o, rows, d, m->cfg.ln_eps, seq_end, base, src_rows)
+                       emb, m->V, x_out, g, b, o, rows, d, m->cfg.ln_eps, seq_end, base, src_rows, part, nsplit,       \
+                       (int64_t)rows * d)
     if (d <= 256) LN_CASE(1);
     else if (d <= 512) LN_CASE(2);
     else if (d <= 1024) LN_CASE(4);
@@ -463,20 +482,30 @@ static int check_device(const srm_model *m)
 // LayerNorm after the last layer.
 template <typename T, typename MIX>
 static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hipStream_t st, MIX &&mix,
-                 bool norm_next)
+                 bool norm_next, bool allow_split = false)
 {
     const LayerDev &y = m->layers[l];
     const int d = m->d, ff = m->ff;
+    // split-K down projection (decode with few rows, bf16): see kSplitK
+    const bool split = allow_split && norm_next && sizeof(T) == 2 && w.part && ff >= 1024 &&
+                       ff % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 256;
     SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, d, d, w.u, st)));
     SRM_TRY(mix(l));
     SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.x, st)));
     SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
     SRM_TRY((linear<EPI_GELU, T>(w.a, y.w_up, y.b_up, rows, ff, d, w.g, st)));
-    SRM_TRY((linear<EPI_RESID, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.x, st)));
+    if (split)
+        SRM_TRY((linear<EPI_F32, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.part, st, nullptr, nullptr, 64, nullptr,
+                                    Sampling(), kSplitK)));
+    else
+        SRM_TRY((linear<EPI_RESID, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.x, st)));
     if (norm_next) {
         const float *g = l + 1 < m->L ? m->layers[l + 1].ln1_g : m->lnf_g;
         const float *b = l + 1 < m->L ? m->layers[l + 1].ln1_b : m->lnf_b;
-        SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, g, b, w.a, rows, st)));
+        if (split)      // x += slabs, then normalise
+            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, g, b, w.a, rows, st, nullptr, 0, 0, w.part, kSplitK)));
+        else
+            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, g, b, w.a, rows, st)));
     }
     return SRM_OK;
 }
@@ -506,7 +535,7 @@ static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, 
     auto mix = [&](int l) {
         return state_update<T>(m, l, pos, B, w.u, state + (size_t)l * B * d, w.mx, st, pos_dev);
     };
-    for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true)));
+    for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true, true)));
     if (hidden) HIP_TRY(hipMemcpyAsync(hidden, w.x, (size_t)B * d * 4, hipMemcpyDeviceToDevice, st));
     const Sampling sm{temperature, seed, pos, pos_dev, nullptr, top_p};
     const bool topp = temperature > 0.0f && top_p < 1.0f;
@@ -582,7 +611,7 @@ static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int ad
         HIP_TRY(hipGetLastError());
         return (int)SRM_OK;
     };
-    for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true)));
+    for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true, true)));
     const bool topp = temperature > 0.0f && top_p < 1.0f;
     FinalizeRagged rg{};
     rg.pos_rows = pos_rows;

@@ -369,3 +369,29 @@ def test_sampled_frequencies_follow_softmax(srm, orc_mod, dtype_name, B):
     # per-row identity against the oracle's rule applied to the GPU's own logits (rows share logits)
     for b in list(range(0, R, max(1, R // 64)))[:64]:
         assert got[b] == orc_mod.pick(logits[b], T, seed, 0, b)
+
+
+@pytest.mark.parametrize("B", [1, 77, 300])
+def test_small_batch_bf16_decode_with_split_k_down_projection(srm, orc_mod, B):
+    """Few rows, bf16, MLP width >= 1024: the down projection runs split over K with the
+    LayerNorm kernel adding the slabs to the residual stream.  Logits and hidden state of
+    every step against the oracle, ragged row counts."""
+    cfg = srm_synth.tiny_config(vocab=300, d_model=256, n_layers=2, n_heads=4, n_ctx=8, weight_dtype="bf16", seed=77)
+    w = srm_synth.make_weights(cfg, stress=True)
+    assert cfg.d_ff >= 1024
+    T = 5
+    toks = srm_synth.make_prompts(cfg, batch=B, length=T)
+    rows = list(range(min(B, 3))) + ([B - 1] if B > 3 else [])
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks[rows])
+    model = srm.Model(cfg, w)
+    ws, st = model.new_workspace(B), model.new_state(B)
+    out = torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    hd = torch.empty((B, cfg.d_model), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    print(f"split-K small batch B={B}", flush=True)
+    for t in range(T):
+        model.decode_step(B, t, tc[t], st, out, logits=lg, hidden=hd, workspace=ws)
+        assert rel_err_rows(lg[rows].cpu().numpy(), ref["logits"][:, t]) <= 2e-2
+        assert rel_err_rows(hd[rows].cpu().numpy(), ref["hidden"][:, t]) <= 2e-2
+    assert bool(torch.isfinite(st).all())
