@@ -300,6 +300,7 @@ def main():
                                f"{cfg.weight_dtype} weights / fp32 state, batch {B}, prompt {P}, greedy decode",
                    "batch": B, "prompt_len": P, "state_bytes": model.state_bytes(B)},
         "step": {"algorithmic_tflop": flops_step * 1e-12, "algorithmic_gb": bytes_step * 1e-9,
+                 "achieved_gbs": bytes_step / step_s * 1e-9, "hbm_frac": bytes_step / step_s * 1e-9 / PEAK_HBM_GBS,
                  "achieved_tflops": flops_step / step_s * 1e-12, "mfma_frac": flops_step / step_s * 1e-12 / PEAK_BF16_TFLOPS
                  if esz == 2 else None,
                  "device_ms_per_step": dev_s / args.steps * 1e3, "wall_ms_per_step": wall / args.steps * 1e3},

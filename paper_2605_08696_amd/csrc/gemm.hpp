@@ -14,7 +14,7 @@
 #pragma once
 #include "common.hpp"
 
-enum { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_ARGMAX = 3, EPI_F32 = 4 };
+enum { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_ARGMAX = 3, EPI_F32 = 4, EPI_MIX = 5 };
 
 struct GemmEpi {
     const float *bias;   // [N] or nullptr
@@ -31,6 +31,13 @@ struct GemmEpi {
     int32_t pos;         // position of the counter, unless pos_dev or pos_rows is set
     const int *pos_dev;  // one position for all rows, in device memory
     const int *pos_rows; // [M] one position per row, in device memory
+    // EPI_MIX: the recurrent state update (Eq. 2 / Eq. 3) applied to the product, which is the
+    // stacked head projection u: S <- lam*S + p*u, out = q*S + beta at the row's position
+    // (pos / pos_dev / pos_rows as above; a position outside [0, n_ctx) leaves S alone and
+    // writes zeros).  state: fp32 [M][ldo]; alpha, beta: [H][n_ctx]; lam: [H]; dh = ldo / H.
+    float *state;
+    const float *alpha, *beta, *lam;
+    int32_t n_ctx, H, dh;
 };
 
 // Position that keys the random numbers of output row `row` (rows >= M read nothing).
@@ -71,6 +78,19 @@ __device__ __forceinline__ void epi_store(const GemmEpi &ep, int64_t row, int co
         *p += v;
     } else if constexpr (EPI == EPI_F32) {
         reinterpret_cast<float *>(ep.out)[row * ep.ldo + col] = v;
+    } else if constexpr (EPI == EPI_MIX) {
+        const int pos = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row] : (ep.pos_dev ? (uint32_t)*ep.pos_dev : (uint32_t)ep.pos));
+        TAct *o = reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + col;
+        if (pos < 0 || pos >= ep.n_ctx) { store1(o, 0.0f); return; }
+        const int h = col / ep.dh;
+        const float a = ep.alpha[(size_t)h * ep.n_ctx + pos], be = ep.beta[(size_t)h * ep.n_ctx + pos], l = ep.lam[h];
+        const bool row_repeat = h < ep.H / 2;
+        const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
+        const float u = (float)(TAct)v;                 // u in the activation type, as the unfused path stores it
+        float *sp = ep.state + row * ep.ldo + col;
+        const float n = fmaf(l, *sp, p * u);
+        *sp = n;
+        store1(o, fmaf(q, n, be));
     } else {
         if (ep.out) reinterpret_cast<float *>(ep.out)[row * ep.ldo + col] = v;
     }
@@ -130,6 +150,24 @@ __device__ __forceinline__ void epi_store4(const GemmEpi &ep, int64_t row, int c
         store4(p, make_float4(o.x + v.x, o.y + v.y, o.z + v.z, o.w + v.w));
     } else if constexpr (EPI == EPI_F32) {
         store4(reinterpret_cast<float *>(ep.out) + row * ep.ldo + col, v);
+    } else if constexpr (EPI == EPI_MIX) {
+        // four consecutive channels lie in one head (dh is a multiple of 4)
+        const int pos = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row] : (ep.pos_dev ? (uint32_t)*ep.pos_dev : (uint32_t)ep.pos));
+        TAct *o = reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + col;
+        if (pos < 0 || pos >= ep.n_ctx) { store4(o, make_float4(0.f, 0.f, 0.f, 0.f)); return; }
+        const int h = col / ep.dh;
+        const float a = ep.alpha[(size_t)h * ep.n_ctx + pos], be = ep.beta[(size_t)h * ep.n_ctx + pos], l = ep.lam[h];
+        const bool row_repeat = h < ep.H / 2;
+        const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
+        float *sp = ep.state + row * ep.ldo + col;
+        const float4 s0 = load4(sp);
+        float4 n, m;
+        n.x = fmaf(l, s0.x, p * (float)(TAct)v.x); m.x = fmaf(q, n.x, be);
+        n.y = fmaf(l, s0.y, p * (float)(TAct)v.y); m.y = fmaf(q, n.y, be);
+        n.z = fmaf(l, s0.z, p * (float)(TAct)v.z); m.z = fmaf(q, n.z, be);
+        n.w = fmaf(l, s0.w, p * (float)(TAct)v.w); m.w = fmaf(q, n.w, be);
+        store4(sp, n);
+        store4(o, m);
     } else {
         if (ep.out) store4(reinterpret_cast<float *>(ep.out) + row * ep.ldo + col, v);
     }

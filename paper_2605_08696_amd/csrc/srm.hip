@@ -293,7 +293,7 @@ static int choose_tile(int64_t M, int N, int min_bn)
 {
     int tile;
     if (cdiv(M, 256) * cdiv(N, 256) >= 200) tile = 0;
-    else if (cdiv(M, 128) * cdiv(N, 128) >= 128) tile = 1;
+    else if (cdiv(M, 128) * cdiv(N, 128) >= 256) tile = 1;   // measured: below a full wave of 128x128 tiles, 64x64 wins
     else tile = 2;
     if (tile == 2 && min_bn > 64) tile = 1;
     return tile;
@@ -386,13 +386,20 @@ static int nucleus(const float *logits, int64_t rows, int V, const Sampling &sm,
     return SRM_OK;
 }
 
+struct MixArgs {           // EPI_MIX: state slab of the layer and its coefficient tables
+    float *state = nullptr;
+    const float *alpha = nullptr, *beta = nullptr, *lam = nullptr;
+    int n_ctx = 0, H = 0, dh = 0;
+};
+
 // out = epilogue(A W^T + bias) with operands of type T (float or bf16)
 template <int EPI, typename T>
 static int linear(const void *A, const void *W, const float *bias, int64_t M, int N, int K, void *out,
                   hipStream_t st, float *pv = nullptr, int32_t *pi = nullptr, int min_bn = 64,
-                  int *nparts_out = nullptr, Sampling sm = Sampling(), int ksplit = 1)
+                  int *nparts_out = nullptr, Sampling sm = Sampling(), int ksplit = 1, MixArgs mx = MixArgs())
 {
-    GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows};
+    GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows,
+               mx.state, mx.alpha, mx.beta, mx.lam, mx.n_ctx, mx.H, mx.dh};
     if constexpr (sizeof(T) == 2)
         return launch_bf16<EPI, bf16>(static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), M, N, K, ep,
                                       st, min_bn, nparts_out, ksplit);
@@ -476,21 +483,34 @@ static int check_device(const srm_model *m)
     return SRM_OK;
 }
 
+// Decode with few rows is bound by the number of dependent kernels, not by their
+// work: below this many state elements per layer the state update is fused into
+// the in-projection.  Above it the separate streaming kernel (HBM-bound, two
+// state vectors per thread) is the faster arrangement.
+static bool fuse_mixer(const srm_model *m, int64_t rows) { return rows * m->d <= (1 << 20); }
+
 // One block (token mixing + channel mixing) on `rows` token rows.  On entry
 // w.a holds LayerNorm1(x) of this layer; mix(l) turns w.u into w.mx.  With
 // norm_next, w.a leaves holding the next layer's LayerNorm1(x), or the final
 // LayerNorm after the last layer.
 template <typename T, typename MIX>
 static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hipStream_t st, MIX &&mix,
-                 bool norm_next, bool allow_split = false)
+                 bool norm_next, bool allow_split = false, float *fuse_state = nullptr, Sampling fuse_pos = Sampling())
 {
     const LayerDev &y = m->layers[l];
     const int d = m->d, ff = m->ff;
     // split-K down projection (decode with few rows, bf16): see kSplitK
     const bool split = allow_split && norm_next && sizeof(T) == 2 && w.part && ff >= 1024 &&
                        ff % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 256;
-    SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, d, d, w.u, st)));
-    SRM_TRY(mix(l));
+    if (fuse_state) {
+        // few rows: the state update rides in the in-projection's epilogue (one kernel less per layer)
+        const MixArgs mx{fuse_state, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d / m->H};
+        SRM_TRY((linear<EPI_MIX, T>(w.a, y.w_in, y.b_in, rows, d, d, w.mx, st, nullptr, nullptr, 64, nullptr, fuse_pos,
+                                    1, mx)));
+    } else {
+        SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, d, d, w.u, st)));
+        SRM_TRY(mix(l));
+    }
     SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.x, st)));
     SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
     SRM_TRY((linear<EPI_GELU, T>(w.a, y.w_up, y.b_up, rows, ff, d, w.g, st)));
@@ -535,7 +555,10 @@ static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, 
     auto mix = [&](int l) {
         return state_update<T>(m, l, pos, B, w.u, state + (size_t)l * B * d, w.mx, st, pos_dev);
     };
-    for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true, true)));
+    const bool fuse = fuse_mixer(m, B);
+    const Sampling where{0.0f, 0, pos, pos_dev, nullptr, 1.0f};
+    for (int l = 0; l < m->L; ++l)
+        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? state + (size_t)l * B * d : nullptr, where)));
     if (hidden) HIP_TRY(hipMemcpyAsync(hidden, w.x, (size_t)B * d * 4, hipMemcpyDeviceToDevice, st));
     const Sampling sm{temperature, seed, pos, pos_dev, nullptr, top_p};
     const bool topp = temperature > 0.0f && top_p < 1.0f;
@@ -611,7 +634,10 @@ static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int ad
         HIP_TRY(hipGetLastError());
         return (int)SRM_OK;
     };
-    for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, B, st, mix, true, true)));
+    const bool fuse = fuse_mixer(m, B);
+    const Sampling where{0.0f, 0, 0, nullptr, pos_rows, 1.0f};
+    for (int l = 0; l < m->L; ++l)
+        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? state + (size_t)l * B * d : nullptr, where)));
     const bool topp = temperature > 0.0f && top_p < 1.0f;
     FinalizeRagged rg{};
     rg.pos_rows = pos_rows;
