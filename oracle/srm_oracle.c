@@ -60,6 +60,7 @@ typedef struct {
 
 typedef struct {
     int vocab, d, L, H, e, n_ctx;
+    int no_proj;        /* 1: non-projected ("head-parallel") mixer layers, see orc_set_projections */
     double eps;
     real *embed, *head, *lnf_g, *lnf_b;
     orc_layer *layers;
@@ -111,6 +112,18 @@ orc_model *orc_create(int vocab, int d, int L, int H, int e, int n_ctx, double e
     }
     return m;
 }
+
+/*
+ * Non-projected SRM ("Method": the input projection "may or may not be applied,
+ * heads are sliced ... and outputs concatenated and optionally projected back";
+ * "SRM architecture optimization" and Tables S2-S4 call these parallel heads /
+ * non-projected models).  With on = 0 the mixer of every layer reads the
+ * LayerNorm output directly, head h being channels h*d_h .. (h+1)*d_h - 1, and
+ * its output is added to the residual stream as it is; w_in, b_in, w_out, b_out
+ * are unused.  orc_count_params(..., with_projections = 0) is this model's size
+ * (pinned to Table S3).
+ */
+void orc_set_projections(orc_model *m, int on) { m->no_proj = !on; }
 
 void orc_destroy(orc_model *m)
 {
@@ -428,13 +441,15 @@ void orc_step(const orc_model *m, int tok, int pos, real *S, real *hidden, real 
     for (int l = 0; l < m->L; ++l) {
         const orc_layer *y = &m->layers[l];
         orc_layernorm(x, y->ln1_g, y->ln1_b, d, m->eps, a);
-        orc_linear(y->w_in, y->b_in, a, d, d, u);
+        if (m->no_proj) memcpy(u, a, sizeof(real) * d);
+        else orc_linear(y->w_in, y->b_in, a, d, d, u);
         for (int h = 0; h < H; ++h) {
             al[h] = y->alpha[(size_t)h * m->n_ctx + pos];
             be[h] = y->beta[(size_t)h * m->n_ctx + pos];
         }
         orc_mixer_step(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
-        orc_linear(y->w_out, y->b_out, mix, d, d, t);
+        if (m->no_proj) memcpy(t, mix, sizeof(real) * d);
+        else orc_linear(y->w_out, y->b_out, mix, d, d, t);
         for (int i = 0; i < d; ++i) x[i] += t[i];
         orc_layernorm(x, y->ln2_g, y->ln2_b, d, m->eps, a);
         orc_linear(y->w_up, y->b_up, a, ff, d, g);
@@ -566,12 +581,14 @@ int orc_parallel_forward(const orc_model *m, int B, int T, const int *tokens,
             const orc_layer *y = &m->layers[l];
             for (int s = 0; s < T; ++s) {
                 orc_layernorm(X + (size_t)s * d, y->ln1_g, y->ln1_b, d, m->eps, A + (size_t)s * d);
-                orc_linear(y->w_in, y->b_in, A + (size_t)s * d, d, d, U + (size_t)s * d);
+                if (m->no_proj) memcpy(U + (size_t)s * d, A + (size_t)s * d, sizeof(real) * d);
+                else orc_linear(y->w_in, y->b_in, A + (size_t)s * d, d, d, U + (size_t)s * d);
             }
             orc_mixer_parallel(U, y->alpha, y->beta, y->lam, m->H, d, T, m->n_ctx, 0, Y);
             for (int s = 0; s < T; ++s) {
                 real *x = X + (size_t)s * d;
-                orc_linear(y->w_out, y->b_out, Y + (size_t)s * d, d, d, tmp);
+                if (m->no_proj) memcpy(tmp, Y + (size_t)s * d, sizeof(real) * d);
+                else orc_linear(y->w_out, y->b_out, Y + (size_t)s * d, d, d, tmp);
                 for (int i = 0; i < d; ++i) x[i] += tmp[i];
                 orc_layernorm(x, y->ln2_g, y->ln2_b, d, m->eps, A + (size_t)s * d);
                 orc_linear(y->w_up, y->b_up, A + (size_t)s * d, ff, d, g);

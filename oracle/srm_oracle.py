@@ -63,6 +63,8 @@ def _load(kind: str):
         lib.orc_generate_topp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_double, C.c_uint32, C.c_int, C.c_double,
                                           C.c_void_p]
+        lib.orc_set_projections.restype = None
+        lib.orc_set_projections.argtypes = [C.c_void_p, C.c_int]
         lib.orc_generate.restype = C.c_int
         lib.orc_generate.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_double, C.c_uint32, C.c_int]
@@ -135,6 +137,8 @@ class Oracle:
         if not self.h:
             raise ValueError("orc_create rejected the configuration")
         self._keep = None  # the C side copied everything
+        if not getattr(cfg, "use_projections", True):
+            self.lib.orc_set_projections(C.c_void_p(self.h), 0)
 
     def close(self):
         if getattr(self, "h", None):

@@ -47,6 +47,7 @@ class SRMConfig:
     ln_eps: float = LN_EPS
     fanout: tuple = (1,)
     n_ctx_fixed: int = 0    # 0: prompt_len + gen_len rounded up to a multiple of 64
+    use_projections: bool = True   # False: non-projected mixer layers (w_in / w_out are drawn but unused)
 
     @property
     def n_ctx(self) -> int:
@@ -78,11 +79,11 @@ CONFIGS: Dict[str, SRMConfig] = {
 
 
 def tiny_config(name="T", vocab=32, d_model=8, n_layers=2, n_heads=2, n_ctx=16,
-                weight_dtype="fp32", seed=7, mlp_expansion=4) -> SRMConfig:
+                weight_dtype="fp32", seed=7, mlp_expansion=4, use_projections=True) -> SRMConfig:
     """A brute-force sized config for unit tests."""
     return SRMConfig(name, vocab, d_model, n_layers, weight_dtype, seed, seed + 1,
                      2, n_ctx, 0, n_heads=n_heads, mlp_expansion=mlp_expansion,
-                     n_ctx_fixed=n_ctx)
+                     n_ctx_fixed=n_ctx, use_projections=use_projections)
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:

@@ -509,3 +509,72 @@ def test_generation_with_top_p(oracle_mod):
             keep, _ = oracle_mod.nucleus(a["logits"][bb, g], 0.8, 0.6)
             assert keep[a["tokens"][bb, g]]
             assert a["tokens"][bb, g] == oracle_mod.pick_topp(a["logits"][bb, g], 0.8, 0.6, 4, 5 + g, bb)
+
+
+# ---- non-projected ("parallel heads") mixer layers: "Method" last paragraph, Tables S2-S4 ------------
+def _np_model(oracle_mod, **kw):
+    cfg = srm_synth.tiny_config(vocab=40, d_model=16, n_layers=2, n_heads=4, n_ctx=24, seed=33,
+                                use_projections=False, **kw)
+    w = srm_synth.make_weights(cfg, stress=True)
+    return cfg, w, oracle_mod.Oracle(cfg, w, "f64")
+
+
+def test_non_projected_block_against_numpy_restatement(oracle_mod):
+    """Two tokens through hand-wired numpy blocks without head projections: the mixer reads the
+    LayerNorm output sliced into heads and its output joins the residual stream directly."""
+    cfg, w, orc = _np_model(oracle_mod)
+    d, H = cfg.d_model, cfg.n_heads
+    dh = d // H
+    toks = [5, 17]
+
+    def ln(x, g, b):
+        return (x - x.mean()) / np.sqrt(x.var() + cfg.ln_eps) * g + b
+
+    S = [np.zeros(d) for _ in w["layers"]]
+    hidden = []
+    for t, tok in enumerate(toks):
+        x = w["embed"][tok].astype(np.float64)
+        for li, lw in enumerate(w["layers"]):
+            lw = {k: v.astype(np.float64) for k, v in lw.items()}
+            u = ln(x, lw["ln1_g"], lw["ln1_b"])
+            m = np.empty(d)
+            for h in range(H):
+                sl = slice(h * dh, (h + 1) * dh)
+                a, b, lam = lw["alpha"][h, t], lw["beta"][h, t], lw["lam"][h]
+                if h < H // 2:                                  # row repeat, Eq. 2
+                    S[li][sl] = lam * S[li][sl] + a * u[sl]
+                    m[sl] = S[li][sl] + b
+                else:                                           # column repeat, Eq. 3
+                    S[li][sl] = lam * S[li][sl] + u[sl]
+                    m[sl] = a * S[li][sl] + b
+            x = x + m
+            z = lw["w_up"] @ ln(x, lw["ln2_g"], lw["ln2_b"]) + lw["b_up"]
+            x = x + lw["w_down"] @ (z * scipy.special.ndtr(z)) + lw["b_down"]
+        hidden.append(x)
+    r = orc.recurrent_forward(np.array([toks], np.int32))
+    np.testing.assert_allclose(r["hidden"][0], np.stack(hidden), rtol=1e-12, atol=1e-12)
+    # the projection weights play no part: scrambling them changes nothing
+    w2 = {k: v for k, v in w.items()}
+    w2["layers"] = [dict(lw, w_in=lw["w_in"] * 3.0, b_out=lw["b_out"] + 1.0) for lw in w["layers"]]
+    r2 = oracle_mod.Oracle(cfg, w2, "f64").recurrent_forward(np.array([toks], np.int32))
+    np.testing.assert_array_equal(r2["hidden"], r["hidden"])
+    # and the projected model on the same weights differs
+    cfg_p = srm_synth.tiny_config(vocab=40, d_model=16, n_layers=2, n_heads=4, n_ctx=24, seed=33)
+    rp = oracle_mod.Oracle(cfg_p, w, "f64").recurrent_forward(np.array([toks], np.int32))
+    assert np.abs(rp["hidden"] - r["hidden"]).max() > 1e-3
+
+
+def test_non_projected_parallel_equals_recurrent_and_is_causal(oracle_mod):
+    cfg, w, orc = _np_model(oracle_mod)
+    toks = srm_synth.make_prompts(cfg, batch=3, length=24)
+    rec = orc.recurrent_forward(toks)
+    par = orc.parallel_forward(toks)
+    np.testing.assert_allclose(par["hidden"], rec["hidden"], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(par["logits"], rec["logits"], rtol=1e-10, atol=1e-12)
+    t2 = toks.copy(); t2[:, 15] = (t2[:, 15] + 1) % cfg.vocab
+    par2 = orc.parallel_forward(t2)
+    np.testing.assert_array_equal(par2["hidden"][:, :15], par["hidden"][:, :15])
+    assert (par2["hidden"][:, 15:] != par["hidden"][:, 15:]).any()
+    # generation works and replicas agree
+    g = orc.greedy(np.repeat(toks[:1, :6], 3, axis=0), 8)
+    assert (g["tokens"] == g["tokens"][0]).all()
