@@ -34,6 +34,8 @@ def parse_args():
                          "resident batch that still completes a decode step")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="sample with this temperature (fused Gumbel-max) instead of greedy argmax")
+    ap.add_argument("--no-projections", action="store_true",
+                    help="the non-projected model variant (mixer layers without in/out head projections)")
     ap.add_argument("--top-p", type=float, default=1.0,
                     help="with --temperature: nucleus truncation (the paper's rollouts use 0.9 at temperature 0.7)")
     ap.add_argument("--per-step-calls", action="store_true",
@@ -216,6 +218,9 @@ def main():
         concurrency_sweep(torch, srm, srm_synth, min(args.steps, 8))
         return
     cfg = srm_synth.CONFIGS[args.workload]
+    if args.no_projections:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, use_projections=False)
     B, P = cfg.batch, cfg.prompt_len
     t0 = time.perf_counter()
     w = srm_synth.make_weights(cfg)
@@ -288,16 +293,18 @@ def main():
     assert ((tk >= 0) & (tk < cfg.vocab)).all() and bool(torch.isfinite(state).all())
 
     d, ff, V, L = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.n_layers
-    flops_step = B * (20.0 * L * d * d + 2.0 * V * d)
+    gemm_dd = 20.0 if cfg.use_projections else 16.0         # flop / d^2 per token per layer
+    flops_step = B * (gemm_dd * L * d * d + 2.0 * V * d)
     esz = 2 if cfg.weight_dtype == "bf16" else 4
-    bytes_step = (10.0 * L * d * d + V * d) * esz + 8.0 * B * L * d + B * d * esz
+    bytes_step = (gemm_dd / 2 * L * d * d + V * d) * esz + 8.0 * B * L * d + B * d * esz
     out = {
         "metric": "generated tokens/sec on 1 MI355X at max batch",
         "value": B / step_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": step_s * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: SRM d_model {d}, {L} layers, 4 mixed heads, MLP x4, vocab {V}, "
-                               f"{cfg.weight_dtype} weights / fp32 state, batch {B}, prompt {P}, greedy decode",
+                               f"{cfg.weight_dtype} weights / fp32 state, batch {B}, prompt {P}, greedy decode" +
+                               ("" if cfg.use_projections else ", non-projected mixer layers"),
                    "batch": B, "prompt_len": P, "state_bytes": model.state_bytes(B)},
         "step": {"algorithmic_tflop": flops_step * 1e-12, "algorithmic_gb": bytes_step * 1e-9,
                  "achieved_gbs": bytes_step / step_s * 1e-9, "hbm_frac": bytes_step / step_s * 1e-9 / PEAK_HBM_GBS,

@@ -67,6 +67,10 @@ typedef struct {
     int32_t n_ctx;          /* number of positions alpha/beta are defined for */
     int32_t weight_dtype;   /* SRM_FP32 | SRM_BF16 */
     float ln_eps;
+    int32_t no_projections; /* 0: in/out head projections (the default model); 1: non-projected mixer
+                               layers ("Method", last paragraph; Tables S2-S4): head h is channels
+                               h*d_h .. of the LayerNorm output, the mixer output joins the residual
+                               stream directly; w_in, b_in, w_out, b_out are ignored and may be NULL */
 } srm_config;
 
 /* HOST pointers, fp32, caller-owned, not retained after srm_init_weights. */

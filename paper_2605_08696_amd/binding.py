@@ -31,7 +31,7 @@ class SrmError(RuntimeError):
 class srm_config(C.Structure):
     _fields_ = [("vocab", C.c_int32), ("d_model", C.c_int32), ("n_layers", C.c_int32),
                 ("n_heads", C.c_int32), ("mlp_expansion", C.c_int32), ("n_ctx", C.c_int32),
-                ("weight_dtype", C.c_int32), ("ln_eps", C.c_float)]
+                ("weight_dtype", C.c_int32), ("ln_eps", C.c_float), ("no_projections", C.c_int32)]
 
 
 class srm_host_layer(C.Structure):
@@ -137,7 +137,7 @@ class Model:
         self.n_ctx = cfg.n_ctx
         self.dtype = SRM_BF16 if cfg.weight_dtype == "bf16" else SRM_FP32
         c = srm_config(cfg.vocab, cfg.d_model, cfg.n_layers, cfg.n_heads, cfg.mlp_expansion,
-                       cfg.n_ctx, self.dtype, cfg.ln_eps)
+                       cfg.n_ctx, self.dtype, cfg.ln_eps, 0 if getattr(cfg, "use_projections", True) else 1)
         keep = []
 
         def fp(a, shape):

@@ -5,6 +5,8 @@
 //                         in registers, same arithmetic as state_update_kernel
 //   scan_chunk_*_kernel   the same scan cut into chunks that run side by side
 //                         (prefill of few sequences)
+//   np_token_mix_kernel   decode of a non-projected layer: both LayerNorms, the
+//                         update and the residual add in one pass
 //   mixer_parallel_kernel the explicit triangular product Y = U M + beta with M
 //                         built on the fly from alpha and lambda (Eq. 1, Eq. 3)
 //
@@ -118,6 +120,112 @@ mixer_scan_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__res
     }
     float *dst = S + ((seq0 + seq) * rep) * (int64_t)d + cv * 4;
     for (int r = 0; r < rep; ++r) store4(dst + (int64_t)r * d, s);
+}
+
+// Token mixing of a non-projected layer in one pass over the row (decode): LayerNorm1,
+// the state update on its output (head h = channels h*d_h ..), the residual add
+// and LayerNorm2, one wavefront per sample, the row held in registers:
+//   u = LN1(x) ; S <- lam*S + p*u ; m = q*S + beta ; x <- x + m ; out = LN2(x)
+// u and m pass through the activation type TAct exactly where the separate
+// kernels (ln_kernel, state_update_kernel, ln_kernel with add_act) store them, so
+// the results are bit-identical to that sequence.  Reads x and S, writes S, x and
+// out: 16d + 2d bytes per sample for bf16 activations.  VPL = float4 vectors per
+// lane (d <= 256 * VPL).  Position: pos_rows[row], else *pos_dev, else pos; a
+// position outside [0, n_ctx) leaves S alone and adds nothing.
+template <typename TAct, int VPL>
+__global__ void __launch_bounds__(256)
+np_token_mix_kernel(float *x, float *__restrict__ S, TAct *__restrict__ out, const float *__restrict__ g1,
+                    const float *__restrict__ b1, const float *__restrict__ g2, const float *__restrict__ b2,
+                    const float *__restrict__ alpha, const float *__restrict__ beta,
+                    const float *__restrict__ lam, int pos, const int *__restrict__ pos_dev,
+                    const int *__restrict__ pos_rows, int n_ctx, int H, int d, int64_t rows, float eps)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int p = pos_rows ? pos_rows[row] : (pos_dev ? *pos_dev : pos);
+    const bool active = p >= 0 && p < n_ctx;
+    const int dh = d / H;
+
+    float4 v[VPL];
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) {
+            v[i] = load4(x + row * d + c);
+            sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+        } else {
+            v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    float mean = wave_sum(sum) / (float)d;
+    float sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) {
+            const float a = v[i].x - mean, bb = v[i].y - mean, cc = v[i].z - mean, dd = v[i].w - mean;
+            sq += (a * a + bb * bb) + (cc * cc + dd * dd);
+        }
+    }
+    float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)d + eps);
+    sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) {
+            if (active) {
+                const float4 gg = load4(g1 + c), bb = load4(b1 + c);
+                // LN1 output as the activation type holds it
+                const float u0 = (float)(TAct)((v[i].x - mean) * rstd * gg.x + bb.x);
+                const float u1 = (float)(TAct)((v[i].y - mean) * rstd * gg.y + bb.y);
+                const float u2 = (float)(TAct)((v[i].z - mean) * rstd * gg.z + bb.z);
+                const float u3 = (float)(TAct)((v[i].w - mean) * rstd * gg.w + bb.w);
+                const int h = c / dh;
+                const float a = alpha[(size_t)h * n_ctx + p], be = beta[(size_t)h * n_ctx + p], l = lam[h];
+                const bool row_repeat = h < H / 2;
+                const float pp = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
+                const f32x4_t sv = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(S + row * d + c));
+                f32x4_t nv;
+                nv[0] = fmaf(l, sv[0], pp * u0);
+                nv[1] = fmaf(l, sv[1], pp * u1);
+                nv[2] = fmaf(l, sv[2], pp * u2);
+                nv[3] = fmaf(l, sv[3], pp * u3);
+                __builtin_nontemporal_store(nv, reinterpret_cast<f32x4_t *>(S + row * d + c));
+                v[i].x += (float)(TAct)fmaf(q, nv[0], be);
+                v[i].y += (float)(TAct)fmaf(q, nv[1], be);
+                v[i].z += (float)(TAct)fmaf(q, nv[2], be);
+                v[i].w += (float)(TAct)fmaf(q, nv[3], be);
+                store4(x + row * d + c, v[i]);
+            }
+            sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+        }
+    }
+    mean = wave_sum(sum) / (float)d;
+    sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) {
+            const float a = v[i].x - mean, bb = v[i].y - mean, cc = v[i].z - mean, dd = v[i].w - mean;
+            sq += (a * a + bb * bb) + (cc * cc + dd * dd);
+        }
+    }
+    rstd = 1.0f / sqrtf(wave_sum(sq) / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        const int c = (i * 64 + lane) * 4;
+        if (c < d) {
+            const float4 gg = load4(g2 + c), bb = load4(b2 + c);
+            float4 o;
+            o.x = (v[i].x - mean) * rstd * gg.x + bb.x;
+            o.y = (v[i].y - mean) * rstd * gg.y + bb.y;
+            o.z = (v[i].z - mean) * rstd * gg.z + bb.z;
+            o.w = (v[i].w - mean) * rstd * gg.w + bb.w;
+            store4(out + row * d + c, o);
+        }
+    }
 }
 
 // Decode with one position per sample (ragged batches, continuous batching):

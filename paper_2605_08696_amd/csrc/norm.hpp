@@ -15,13 +15,16 @@
 //   part:   nsplit slabs [rows][d] (slab stride part_stride floats) of a split-K
 //           GEMM are added to x first, in slab order, and the updated x is written
 //           back to x_out: the residual add of that GEMM, done here.
+//   add_act: [rows][d] in the activation type, added to x first (x_out gets the
+//           sum): the residual add of a non-projected mixer layer.
 template <typename TW, typename TAct, int VPL, bool GATHER>
 __global__ void __launch_bounds__(256)
 ln_kernel(const float *x_in, int64_t in_stride, const int32_t *__restrict__ tok,
           const TW *__restrict__ embed, int vocab, float *x_out,
           const float *__restrict__ g, const float *__restrict__ b, TAct *__restrict__ out,
           int64_t rows, int d, float eps, const int32_t *__restrict__ seq_end = nullptr, int64_t base = 0,
-          int64_t src_rows = 0, const float *__restrict__ part = nullptr, int nsplit = 0, int64_t part_stride = 0)
+          int64_t src_rows = 0, const float *__restrict__ part = nullptr, int nsplit = 0, int64_t part_stride = 0,
+          const TAct *__restrict__ add_act = nullptr)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -51,6 +54,11 @@ ln_kernel(const float *x_in, int64_t in_stride, const int32_t *__restrict__ tok,
                         const float4 t = load4(part + sp * part_stride + row * d + c);
                         v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
                     }
+                    store4(x_out + row * d + c, v[i]);
+                }
+                if (add_act) {
+                    const float4 t = load4(add_act + row * d + c);
+                    v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
                     store4(x_out + row * d + c, v[i]);
                 }
             }

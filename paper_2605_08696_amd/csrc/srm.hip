@@ -58,6 +58,7 @@ struct srm_model {
     srm_config cfg;
     int device;
     int d, ff, V, L, H;
+    bool noproj;           // non-projected mixer layers
     size_t wsize;          // bytes per matrix element
     void *slab;
     const void *embed, *head;
@@ -121,10 +122,12 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     const size_t ff = (size_t)cfg->mlp_expansion * d, nc = cfg->n_ctx;
     for (int l = 0; l < L; ++l) {
         const srm_host_layer &y = w->layers[l];
-        const float *ptrs[] = {y.ln1_g, y.ln1_b, y.w_in, y.b_in, y.alpha, y.beta, y.lambda, y.w_out,
-                               y.b_out, y.ln2_g, y.ln2_b, y.w_up, y.b_up, y.w_down, y.b_down};
+        const float *ptrs[] = {y.ln1_g, y.ln1_b, y.alpha, y.beta, y.lambda, y.ln2_g, y.ln2_b, y.w_up, y.b_up,
+                               y.w_down, y.b_down};
         for (const float *p : ptrs)
             if (!p) return fail(SRM_EINVAL, "srm_init_weights: null weight pointer in layer %d", l);
+        if (!cfg->no_projections && (!y.w_in || !y.b_in || !y.w_out || !y.b_out))
+            return fail(SRM_EINVAL, "srm_init_weights: null projection weights in layer %d", l);
         for (int h = 0; h < H; ++h)
             if (!(y.lambda[h] > 0.0f && y.lambda[h] <= 1.0f))
                 return fail(SRM_EINVAL, "srm_init_weights: lambda[%d][%d] = %g outside (0, 1]", l, h,
@@ -135,6 +138,7 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     if (!m) return fail(SRM_ENOMEM, "srm_init_weights: host allocation failed");
     m->cfg = *cfg;
     m->d = d; m->ff = (int)ff; m->V = V; m->L = L; m->H = H;
+    m->noproj = cfg->no_projections != 0;
     const bool bf = cfg->weight_dtype == SRM_BF16;
     m->wsize = bf ? 2 : 4;
     m->slab = nullptr;
@@ -154,10 +158,11 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
             const srm_host_layer &y = w->layers[l];
             size_t *o = lo[l].v;
             o[0] = sb.add(y.ln1_g, d, false);          o[1] = sb.add(y.ln1_b, d, false);
-            o[2] = sb.add(y.w_in, (size_t)d * d, bf);   o[3] = sb.add(y.b_in, d, false);
+            const bool pj = !m->noproj;
+            o[2] = pj ? sb.add(y.w_in, (size_t)d * d, bf) : 0;   o[3] = pj ? sb.add(y.b_in, d, false) : 0;
             o[4] = sb.add(y.alpha, H * nc, false);      o[5] = sb.add(y.beta, H * nc, false);
             o[6] = sb.add(y.lambda, H, false);
-            o[7] = sb.add(y.w_out, (size_t)d * d, bf);  o[8] = sb.add(y.b_out, d, false);
+            o[7] = pj ? sb.add(y.w_out, (size_t)d * d, bf) : 0;  o[8] = pj ? sb.add(y.b_out, d, false) : 0;
             o[9] = sb.add(y.ln2_g, d, false);           o[10] = sb.add(y.ln2_b, d, false);
             o[11] = sb.add(y.w_up, ff * d, bf);         o[12] = sb.add(y.b_up, ff, false);
             o[13] = sb.add(y.w_down, (size_t)d * ff, bf); o[14] = sb.add(y.b_down, d, false);
@@ -247,7 +252,7 @@ static Workspace carve(const srm_model *m, void *base, int64_t rows)
     const size_t nparts = cdiv(m->V, head_min_bn(m));
     w.x = reinterpret_cast<float *>(take(r * d * 4));
     w.a = take(r * d * s);
-    w.u = take(r * d * s);
+    w.u = m->noproj ? w.a : take(r * d * s);      // without projections the mixer reads the LayerNorm output
     w.mx = take(r * d * s);
     w.g = take(r * (size_t)m->ff * s);
     w.pv = reinterpret_cast<float *>(take(r * nparts * 4));
@@ -428,7 +433,7 @@ template <typename T, bool GATHER>
 static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, const int32_t *tok,
                      float *x_out, const float *g, const float *b, void *out, int64_t rows, hipStream_t st,
                      const int32_t *seq_end = nullptr, int64_t base = 0, int64_t src_rows = 0,
-                     const float *part = nullptr, int nsplit = 0)
+                     const float *part = nullptr, int nsplit = 0, const void *add_act = nullptr)
 {
     const int d = m->d;
     const unsigned nb = (unsigned)cdiv(rows, 4);
@@ -437,7 +442,7 @@ static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, c
 #define LN_CASE(VPL)                                                                                     \
     hipLaunchKernelGGL((ln_kernel<T, T, VPL, GATHER>), dim3(nb), dim3(256), 0, st, x_in, in_stride, tok, \
                        emb, m->V, x_out, g, b, o, rows, d, m->cfg.ln_eps, seq_end, base, src_rows, part, nsplit,       \
-                       (int64_t)rows * d)
+                       (int64_t)rows * d, static_cast<const T *>(add_act))
     if (d <= 256) LN_CASE(1);
     else if (d <= 512) LN_CASE(2);
     else if (d <= 1024) LN_CASE(4);
@@ -487,7 +492,7 @@ static int check_device(const srm_model *m)
 // work: below this many state elements per layer the state update is fused into
 // the in-projection.  Above it the separate streaming kernel (HBM-bound, two
 // state vectors per thread) is the faster arrangement.
-static bool fuse_mixer(const srm_model *m, int64_t rows) { return rows * m->d <= (1 << 20); }
+static bool fuse_mixer(const srm_model *m, int64_t rows) { return !m->noproj && rows * m->d <= (1 << 20); }
 
 // One block (token mixing + channel mixing) on `rows` token rows.  On entry
 // w.a holds LayerNorm1(x) of this layer; mix(l) turns w.u into w.mx.  With
@@ -495,14 +500,34 @@ static bool fuse_mixer(const srm_model *m, int64_t rows) { return rows * m->d <=
 // LayerNorm after the last layer.
 template <typename T, typename MIX>
 static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hipStream_t st, MIX &&mix,
-                 bool norm_next, bool allow_split = false, float *fuse_state = nullptr, Sampling fuse_pos = Sampling())
+                 bool norm_next, bool allow_split = false, float *fuse_state = nullptr, Sampling fuse_pos = Sampling(),
+                 float *np_state = nullptr)
 {
     const LayerDev &y = m->layers[l];
     const int d = m->d, ff = m->ff;
     // split-K down projection (decode with few rows, bf16): see kSplitK
     const bool split = allow_split && norm_next && sizeof(T) == 2 && w.part && ff >= 1024 &&
                        ff % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 256;
-    if (fuse_state) {
+    if (m->noproj && np_state) {
+        // non-projected layer, decode: LayerNorm1, state update, residual add and LayerNorm2 in one kernel
+        const unsigned nb = (unsigned)cdiv(rows, 4);
+#define NP_CASE(VPL)                                                                                          \
+    hipLaunchKernelGGL((np_token_mix_kernel<T, VPL>), dim3(nb), dim3(256), 0, st, w.x, np_state,               \
+                       static_cast<T *>(w.a), y.ln1_g, y.ln1_b, y.ln2_g, y.ln2_b, y.alpha, y.beta, y.lam,      \
+                       fuse_pos.pos, fuse_pos.pos_dev, fuse_pos.pos_rows, m->cfg.n_ctx, m->H, d, rows, m->cfg.ln_eps)
+        if (d <= 256) NP_CASE(1);
+        else if (d <= 512) NP_CASE(2);
+        else if (d <= 1024) NP_CASE(4);
+        else if (d <= 2048) NP_CASE(8);
+        else NP_CASE(16);
+#undef NP_CASE
+        HIP_TRY(hipGetLastError());
+    } else if (m->noproj) {
+        // non-projected layer: mixer on the LayerNorm output, its result added to x by the LayerNorm kernel
+        SRM_TRY(mix(l));
+        SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, y.ln2_g, y.ln2_b, w.a, rows, st, nullptr, 0, 0, nullptr,
+                                     0, w.mx)));
+    } else if (fuse_state) {
         // few rows: the state update rides in the in-projection's epilogue (one kernel less per layer)
         const MixArgs mx{fuse_state, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d / m->H};
         SRM_TRY((linear<EPI_MIX, T>(w.a, y.w_in, y.b_in, rows, d, d, w.mx, st, nullptr, nullptr, 64, nullptr, fuse_pos,
@@ -511,15 +536,17 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
         SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, d, d, w.u, st)));
         SRM_TRY(mix(l));
     }
-    SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.x, st)));
-    SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
+    if (!m->noproj) {
+        SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.x, st)));
+        SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
+    }
     SRM_TRY((linear<EPI_GELU, T>(w.a, y.w_up, y.b_up, rows, ff, d, w.g, st)));
     if (split)
         SRM_TRY((linear<EPI_F32, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.part, st, nullptr, nullptr, 64, nullptr,
                                     Sampling(), kSplitK)));
     else
         SRM_TRY((linear<EPI_RESID, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.x, st)));
-    if (norm_next) {
+    if (norm_next && !(m->noproj && np_state && l + 1 < m->L)) {   // the fused kernel does its own LayerNorm1
         const float *g = l + 1 < m->L ? m->layers[l + 1].ln1_g : m->lnf_g;
         const float *b = l + 1 < m->L ? m->layers[l + 1].ln1_b : m->lnf_b;
         if (split)      // x += slabs, then normalise
@@ -558,7 +585,8 @@ static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, 
     const bool fuse = fuse_mixer(m, B);
     const Sampling where{0.0f, 0, pos, pos_dev, nullptr, 1.0f};
     for (int l = 0; l < m->L; ++l)
-        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? state + (size_t)l * B * d : nullptr, where)));
+        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? state + (size_t)l * B * d : nullptr, where,
+                          state + (size_t)l * B * d)));
     if (hidden) HIP_TRY(hipMemcpyAsync(hidden, w.x, (size_t)B * d * 4, hipMemcpyDeviceToDevice, st));
     const Sampling sm{temperature, seed, pos, pos_dev, nullptr, top_p};
     const bool topp = temperature > 0.0f && top_p < 1.0f;
@@ -637,7 +665,8 @@ static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int ad
     const bool fuse = fuse_mixer(m, B);
     const Sampling where{0.0f, 0, 0, nullptr, pos_rows, 1.0f};
     for (int l = 0; l < m->L; ++l)
-        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? state + (size_t)l * B * d : nullptr, where)));
+        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? state + (size_t)l * B * d : nullptr, where,
+                          state + (size_t)l * B * d)));
     const bool topp = temperature > 0.0f && top_p < 1.0f;
     FinalizeRagged rg{};
     rg.pos_rows = pos_rows;

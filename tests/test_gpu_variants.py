@@ -1,0 +1,110 @@
+"""Architectural variants through the C ABI, against the oracle run with the same switch."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import srm_synth
+from gpu_util import to_dev, rel_err_rows, check_tokens
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def srm():
+    import paper_2605_08696_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def orc_mod(oracle_mod):
+    return oracle_mod
+
+
+# ---- non-projected mixer layers ("Method", last paragraph; Tables S2-S4) -----------------------
+def test_non_projected_fp32_all_paths_match_oracle(srm, orc_mod):
+    cfg = dataclasses.replace(srm_synth.CONFIGS["C1"], use_projections=False)
+    w = srm_synth.make_weights(cfg)
+    orc = orc_mod.Oracle(cfg, w, "f64")
+    model = srm.Model(cfg, w)
+    prompts = srm_synth.make_prompts(cfg)                      # [8][16]
+    B, P = prompts.shape
+    G = 24
+    ref = orc.greedy(prompts, G, want_logits=True)
+    print("non-projected fp32: prefill + generate", flush=True)
+    ws = model.new_workspace(B * P)
+    st, tk = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    model.prefill(to_dev(prompts), 1, st, tk, logits=lg, workspace=ws)
+    assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, 0]) <= 1e-4
+    out = torch.empty((G - 1, B), dtype=torch.int32, device="cuda")
+    first = tk.cpu().numpy().copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        model.generate(B, P, G - 1, tk, st, out, workspace=ws)
+    side.synchronize()
+    got = np.concatenate([first[:, None], out.cpu().numpy().T], axis=1)
+    absmax = np.abs(ref["logits"]).max(axis=2)
+    assert check_tokens(got, ref["tokens"], ref["margin"], absmax) == 0
+    # step by step from scratch, with logits and hidden state of every position
+    toks = srm_synth.make_prompts(cfg, batch=3, length=20)
+    rf = orc.recurrent_forward(toks)
+    st3 = model.new_state(3); st3.zero_()
+    o3 = torch.empty(3, dtype=torch.int32, device="cuda")
+    l3 = torch.empty((3, cfg.vocab), dtype=torch.float32, device="cuda")
+    h3 = torch.empty((3, cfg.d_model), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    for t in range(20):
+        model.decode_step(3, t, tc[t], st3, o3, logits=l3, hidden=h3, workspace=ws)
+        assert rel_err_rows(l3.cpu().numpy(), rf["logits"][:, t]) <= 1e-4
+        assert rel_err_rows(h3.cpu().numpy(), rf["hidden"][:, t]) <= 1e-4
+    # parallel form
+    hid = torch.empty((3, 20, cfg.d_model), dtype=torch.float32, device="cuda")
+    lgp = torch.empty((3, 20, cfg.vocab), dtype=torch.float32, device="cuda")
+    model.parallel_forward(to_dev(toks), hid, logits=lgp, workspace=model.new_workspace(60))
+    torch.cuda.synchronize()
+    assert rel_err_rows(hid.cpu().numpy().reshape(60, -1), rf["hidden"].reshape(60, -1)) <= 1e-4
+    assert rel_err_rows(lgp.cpu().numpy().reshape(60, -1), rf["logits"].reshape(60, -1)) <= 1e-4
+    # ragged entry points
+    lens = [3, 20, 11]
+    pk = np.concatenate([toks[i, :n] for i, n in enumerate(lens)]).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    str_, tkr = model.new_state(3), torch.empty(3, dtype=torch.int32, device="cuda")
+    pos = torch.empty(3, dtype=torch.int32, device="cuda")
+    keep = model.prefill_ragged(to_dev(pk), off, str_, tkr, pos=pos, logits=l3, workspace=ws)
+    torch.cuda.synchronize()
+    del keep
+    for b, n in enumerate(lens):
+        assert rel_err_rows(l3[b:b + 1].cpu().numpy(), rf["logits"][b:b + 1, n - 1]) <= 1e-4
+
+
+@pytest.mark.parametrize("B", [5, 300])
+def test_non_projected_bf16_decode_matches_oracle(srm, orc_mod, B):
+    cfg = srm_synth.tiny_config(vocab=400, d_model=128, n_layers=3, n_heads=4, n_ctx=12, weight_dtype="bf16", seed=61,
+                                use_projections=False)
+    w = srm_synth.make_weights(cfg, stress=True)
+    T = 8
+    toks = srm_synth.make_prompts(cfg, batch=B, length=T)
+    rows = sorted({0, 1, B // 2, B - 1})
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks[rows])
+    model = srm.Model(cfg, w)
+    ws, st = model.new_workspace(B * T), model.new_state(B)
+    st.zero_()
+    out = torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    print(f"non-projected bf16 B={B}", flush=True)
+    for t in range(T):
+        model.decode_step(B, t, tc[t], st, out, logits=lg, workspace=ws)
+        assert rel_err_rows(lg[rows].cpu().numpy(), ref["logits"][:, t]) <= 2e-2
+    # prefill of the same tokens reaches the same state
+    st2, tk2 = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    model.prefill(to_dev(toks), 1, st2, tk2, workspace=ws)
+    torch.cuda.synchronize()
+    assert (st - st2).abs().max() <= 2e-2 * st.abs().max()
+    s_ref = ref["state"]                                       # [rows][L][d]
+    s_got = st.view(cfg.n_layers, B, cfg.d_model)[:, rows].permute(1, 0, 2).cpu().numpy()
+    assert np.abs(s_got - s_ref).max() <= 2e-2 * np.abs(s_ref).max()
