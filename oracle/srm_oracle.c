@@ -61,6 +61,7 @@ typedef struct {
 typedef struct {
     int vocab, d, L, H, e, n_ctx;
     int no_proj;        /* 1: non-projected ("head-parallel") mixer layers, see orc_set_projections */
+    int half_state;     /* 1: cache and decay constants in half precision, see orc_set_state_half */
     double eps;
     real *embed, *head, *lnf_g, *lnf_b;
     orc_layer *layers;
@@ -124,6 +125,38 @@ orc_model *orc_create(int vocab, int d, int L, int H, int e, int n_ctx, double e
  * (pinned to Table S3).
  */
 void orc_set_projections(orc_model *m, int on) { m->no_proj = !on; }
+
+/*
+ * Round to the nearest IEEE binary16 value (ties to even), result kept in `real`:
+ * 11 significant bits, normal exponents -14..15, subnormals in steps of 2^-24,
+ * overflow to infinity from 65520 on.
+ */
+real orc_round_half(real v)
+{
+    double a = fabs((double)v);
+    if (!(a == a) || a == 0.0) return v;
+    if (a >= 65520.0) return (real)(v < 0 ? -INFINITY : INFINITY);
+    int e;
+    (void)frexp(a, &e);                 /* a = f * 2^e, f in [0.5, 1): exponent of the leading bit is e - 1 */
+    int lead = e - 1;
+    if (lead < -14) lead = -14;         /* subnormal range: fixed step */
+    double q = ldexp(1.0, lead - 10);   /* spacing of binary16 values in this binade */
+    double r = rint(a / q) * q;         /* rint: ties to even in the default rounding mode */
+    return (real)(v < 0 ? -r : r);
+}
+
+/*
+ * Half-precision cache ("SRM architecture optimization": the recurrent form stays
+ * stable with cache values and decay constants in half precision).  With on = 1
+ * the stored sum S and lambda are binary16 values: each update computes
+ * lam_h * S + p * u in the build's precision from the stored S, rounds the
+ * result to binary16, stores it, and forms the layer output from the stored
+ * value, so that the output is a function of the cache as it is kept.
+ */
+void orc_set_state_half(orc_model *m, int on) { m->half_state = on != 0; }
+
+void orc_mixer_step_half(real *S, const real *u, const real *alpha_t, const real *beta_t,
+                         const real *lam, int H, int d, real *m);
 
 void orc_destroy(orc_model *m)
 {
@@ -225,6 +258,26 @@ void orc_mixer_step(real *S, const real *u, const real *alpha_t, const real *bet
                 m[c] = S[c] + beta_t[h];
             } else {
                 S[c] = lam[h] * S[c] + u[c];
+                m[c] = alpha_t[h] * S[c] + beta_t[h];
+            }
+        }
+    }
+}
+
+/* orc_mixer_step with the cache and lambda held as binary16 values (see orc_set_state_half). */
+void orc_mixer_step_half(real *S, const real *u, const real *alpha_t, const real *beta_t,
+                         const real *lam, int H, int d, real *m)
+{
+    int dh = d / H;
+    for (int h = 0; h < H; ++h) {
+        int row_repeat = h < H / 2;
+        real lh = orc_round_half(lam[h]);
+        for (int c = h * dh; c < (h + 1) * dh; ++c) {
+            if (row_repeat) {
+                S[c] = orc_round_half(lh * S[c] + alpha_t[h] * u[c]);
+                m[c] = S[c] + beta_t[h];
+            } else {
+                S[c] = orc_round_half(lh * S[c] + u[c]);
                 m[c] = alpha_t[h] * S[c] + beta_t[h];
             }
         }
@@ -447,7 +500,8 @@ void orc_step(const orc_model *m, int tok, int pos, real *S, real *hidden, real 
             al[h] = y->alpha[(size_t)h * m->n_ctx + pos];
             be[h] = y->beta[(size_t)h * m->n_ctx + pos];
         }
-        orc_mixer_step(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
+        if (m->half_state) orc_mixer_step_half(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
+        else orc_mixer_step(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
         if (m->no_proj) memcpy(t, mix, sizeof(real) * d);
         else orc_linear(y->w_out, y->b_out, mix, d, d, t);
         for (int i = 0; i < d; ++i) x[i] += t[i];

@@ -63,6 +63,10 @@ def _load(kind: str):
         lib.orc_generate_topp.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_double, C.c_uint32, C.c_int, C.c_double,
                                           C.c_void_p]
+        lib.orc_set_state_half.restype = None
+        lib.orc_set_state_half.argtypes = [C.c_void_p, C.c_int]
+        lib.orc_round_half.restype = C.c_double if kind == "f64" else C.c_float
+        lib.orc_round_half.argtypes = [C.c_double if kind == "f64" else C.c_float]
         lib.orc_set_projections.restype = None
         lib.orc_set_projections.argtypes = [C.c_void_p, C.c_int]
         lib.orc_generate.restype = C.c_int
@@ -112,6 +116,10 @@ def pick_topp(logits, temperature, top_p, seed, pos, b, kind="f64", want_margins
     return (tok, float(mg.value), mm.value) if want_margins else tok
 
 
+def round_half(v: float) -> float:
+    return float(_load("f64").orc_round_half(float(v)))
+
+
 def count_params(vocab, d, L, H=4, e=4, n_ctx=512, with_projections=True) -> int:
     return int(_load("f64").orc_count_params(vocab, d, L, H, e, n_ctx, int(with_projections)))
 
@@ -139,6 +147,8 @@ class Oracle:
         self._keep = None  # the C side copied everything
         if not getattr(cfg, "use_projections", True):
             self.lib.orc_set_projections(C.c_void_p(self.h), 0)
+        if getattr(cfg, "state_dtype", "fp32") == "fp16":
+            self.lib.orc_set_state_half(C.c_void_p(self.h), 1)
 
     def close(self):
         if getattr(self, "h", None):

@@ -48,6 +48,7 @@ class SRMConfig:
     fanout: tuple = (1,)
     n_ctx_fixed: int = 0    # 0: prompt_len + gen_len rounded up to a multiple of 64
     use_projections: bool = True   # False: non-projected mixer layers (w_in / w_out are drawn but unused)
+    state_dtype: str = "fp32"      # "fp16": recurrent cache and decay constants in half precision
 
     @property
     def n_ctx(self) -> int:
@@ -79,11 +80,12 @@ CONFIGS: Dict[str, SRMConfig] = {
 
 
 def tiny_config(name="T", vocab=32, d_model=8, n_layers=2, n_heads=2, n_ctx=16,
-                weight_dtype="fp32", seed=7, mlp_expansion=4, use_projections=True) -> SRMConfig:
+                weight_dtype="fp32", seed=7, mlp_expansion=4, use_projections=True,
+                state_dtype="fp32") -> SRMConfig:
     """A brute-force sized config for unit tests."""
     return SRMConfig(name, vocab, d_model, n_layers, weight_dtype, seed, seed + 1,
                      2, n_ctx, 0, n_heads=n_heads, mlp_expansion=mlp_expansion,
-                     n_ctx_fixed=n_ctx, use_projections=use_projections)
+                     n_ctx_fixed=n_ctx, use_projections=use_projections, state_dtype=state_dtype)
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:

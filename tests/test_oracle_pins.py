@@ -578,3 +578,50 @@ def test_non_projected_parallel_equals_recurrent_and_is_causal(oracle_mod):
     # generation works and replicas agree
     g = orc.greedy(np.repeat(toks[:1, :6], 3, axis=0), 8)
     assert (g["tokens"] == g["tokens"][0]).all()
+
+
+# ---- half-precision cache: "SRM architecture optimization", last sentence --------------------------
+def test_round_half_against_numpy_float16(oracle_mod):
+    rng = np.random.default_rng(12)
+    vals = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-9, 5, 4000),
+                           [0.0, 1.0, -1.0, 65504.0, 65519.9, 65520.0, 1e9, -1e9, 2.0 ** -24, 2.0 ** -25,
+                            1.5 * 2.0 ** -25, 2.0 ** -14, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 2047.5, 2048.5]])
+    with np.errstate(over="ignore"):
+        want = vals.astype(np.float16).astype(np.float64)      # numpy's own converter: nearest, ties to even
+    got = np.array([oracle_mod.round_half(v) for v in vals])
+    np.testing.assert_array_equal(got, want)
+
+
+def test_half_state_recurrence_against_float16_emulation(oracle_mod):
+    """The cache holds binary16 values: the oracle's recurrence equals a step-by-step numpy
+    emulation that stores S (and lambda) as float16, and stays close to the fp32-cache model."""
+    cfg = srm_synth.tiny_config(vocab=40, d_model=16, n_layers=1, n_heads=4, n_ctx=64, seed=35,
+                                use_projections=False, state_dtype="fp16")
+    w = srm_synth.make_weights(cfg, stress=True)
+    orc = oracle_mod.Oracle(cfg, w, "f64")
+    toks = srm_synth.make_prompts(cfg, batch=1, length=64)
+    r = orc.recurrent_forward(toks)
+    S = r["state"][0, 0]
+    np.testing.assert_array_equal(S, S.astype(np.float16).astype(np.float64))      # representable
+    lw = {k: v.astype(np.float64) for k, v in w["layers"][0].items()}
+    d, H = cfg.d_model, cfg.n_heads
+    dh = d // H
+
+    def ln(x, g, b):
+        return (x - x.mean()) / np.sqrt(x.var() + cfg.ln_eps) * g + b
+
+    # one layer, non-projected: the mixer input of position t depends only on the token, so the
+    # whole cache trajectory can be emulated without the rest of the model
+    Sh = np.zeros(d, np.float16)
+    lam16 = lw["lam"].astype(np.float16).astype(np.float64)
+    for t in range(64):
+        u = ln(w["embed"][toks[0, t]].astype(np.float64), lw["ln1_g"], lw["ln1_b"])
+        for h in range(H):
+            sl = slice(h * dh, (h + 1) * dh)
+            p = lw["alpha"][h, t] if h < H // 2 else 1.0
+            Sh[sl] = (lam16[h] * Sh[sl].astype(np.float64) + p * u[sl]).astype(np.float16)
+    np.testing.assert_array_equal(S, Sh.astype(np.float64))
+    cfg32 = srm_synth.tiny_config(vocab=40, d_model=16, n_layers=1, n_heads=4, n_ctx=64, seed=35, use_projections=False)
+    r32 = oracle_mod.Oracle(cfg32, w, "f64").recurrent_forward(toks)
+    rel = np.abs(r["logits"] - r32["logits"]).max() / np.abs(r32["logits"]).max()
+    assert 0 < rel < 2e-2                                          # different, and close
