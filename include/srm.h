@@ -56,7 +56,7 @@ typedef enum {
     SRM_EHIP = -3      /* a HIP runtime call failed (message has the HIP error) */
 } srm_status;
 
-enum { SRM_FP32 = 0, SRM_BF16 = 1 };
+enum { SRM_FP32 = 0, SRM_BF16 = 1, SRM_FP16 = 2 };
 
 typedef struct {
     int32_t vocab;
@@ -67,6 +67,12 @@ typedef struct {
     int32_t n_ctx;          /* number of positions alpha/beta are defined for */
     int32_t weight_dtype;   /* SRM_FP32 | SRM_BF16 */
     float ln_eps;
+    int32_t state_dtype;    /* SRM_FP32 (default, 0): fp32 recurrent state; SRM_FP16: the cache and the decay
+                               constants as IEEE binary16 values ("SRM architecture optimization": the
+                               recurrent form stays stable with both in half precision).  Each update
+                               computes lam*S + p*u in fp32 from the stored S, rounds it to binary16
+                               (nearest, ties to even), stores it and forms the output from the stored
+                               value; d_state arrays then hold binary16 elements. */
     int32_t no_projections; /* 0: in/out head projections (the default model); 1: non-projected mixer
                                layers ("Method", last paragraph; Tables S2-S4): head h is channels
                                h*d_h .. of the LayerNorm output, the mixer output joins the residual
@@ -104,8 +110,8 @@ int srm_init_weights(const srm_config *cfg, const srm_host_weights *w, srm_model
 void srm_free(srm_model *m);
 
 /*
- * Bytes of recurrent state for `batch` samples: n_layers * batch * d_model * 4,
- * whatever the position ("Computational Complexity": O(d) space per sample).
+ * Bytes of recurrent state for `batch` samples: n_layers * batch * d_model * 4
+ * (* 2 with a binary16 state), whatever the position ("Computational Complexity": O(d) space per sample).
  * Returns 0 for a null model or batch <= 0.
  */
 size_t srm_state_bytes(const srm_model *m, int64_t batch);
@@ -128,7 +134,7 @@ size_t srm_workspace_bytes(const srm_model *m, int64_t rows);
  * pos outside [0, n_ctx)), SRM_ENOMEM (workspace_bytes < srm_workspace_bytes(m, B)).
  */
 int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in,
-                    float *d_state, int32_t *d_tok_out, float *d_logits, float *d_hidden,
+                    void *d_state, int32_t *d_tok_out, float *d_logits, float *d_hidden,
                     void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
@@ -148,7 +154,7 @@ int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_i
  * SRM_EINVAL for a negative or NaN temperature.
  */
 int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in,
-                            float *d_state, int32_t *d_tok_out, float temperature, uint32_t seed,
+                            void *d_state, int32_t *d_tok_out, float temperature, uint32_t seed,
                             float *d_logits, float *d_hidden, void *d_workspace,
                             size_t workspace_bytes, void *hip_stream);
 
@@ -169,7 +175,7 @@ int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, const int32_t 
  * Errors: SRM_EINVAL (null pointer, B or G <= 0, pos0 + G > n_ctx), SRM_ENOMEM
  * (workspace smaller than srm_workspace_bytes(m, B)), SRM_EHIP.
  */
-int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, void *d_state,
                  int32_t *d_tokens_out, float temperature, uint32_t seed, void *d_workspace,
                  size_t workspace_bytes, void *hip_stream);
 
@@ -185,7 +191,7 @@ int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_to
  * SRM_ENOMEM (workspace smaller than srm_workspace_bytes(m, P)).
  */
 int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, int32_t P, int32_t fanout_k,
-                float *d_state, int32_t *d_next_tok, float *d_logits,
+                void *d_state, int32_t *d_next_tok, float *d_logits,
                 void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
@@ -204,14 +210,14 @@ int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, int32_t P, in
  * Errors: as srm_decode_step_sampled, plus SRM_EINVAL for top_p <= 0 or a
  * missing logits buffer.
  */
-int srm_decode_step_topp(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
+int srm_decode_step_topp(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, void *d_state,
                          int32_t *d_tok_out, float temperature, float top_p, uint32_t seed,
                          float *d_logits, float *d_hidden,
                          void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /* srm_generate with nucleus sampling; d_logits[B][vocab] is scratch for the truncation
  * (required when top_p < 1 and temperature > 0).  Otherwise as srm_generate. */
-int srm_generate_topp(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+int srm_generate_topp(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, void *d_state,
                       int32_t *d_tokens_out, float temperature, float top_p, uint32_t seed,
                       float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
@@ -246,7 +252,7 @@ int srm_sample_logits(const float *d_logits, int64_t rows, int32_t vocab, float 
  * srm_workspace_bytes(m, B)), SRM_EHIP.
  */
 int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, int32_t advance,
-                           const int32_t *d_tok_in, float *d_state, int32_t *d_tok_out,
+                           const int32_t *d_tok_in, void *d_state, int32_t *d_tok_out,
                            float temperature, float top_p, uint32_t seed, float *d_logits,
                            void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
@@ -273,7 +279,7 @@ int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, int32_t adva
  */
 int srm_prefill_ragged(srm_model *m, const int32_t *d_tokens, const int32_t *h_offsets,
                        const int32_t *d_offsets, int32_t N, int32_t fanout_k, const int32_t *d_slot,
-                       int64_t state_batch, float *d_state, int32_t *d_next_tok, int32_t *d_pos,
+                       int64_t state_batch, void *d_state, int32_t *d_next_tok, int32_t *d_pos,
                        float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
@@ -299,7 +305,7 @@ int srm_parallel_forward(srm_model *m, const int32_t *d_tok, int32_t B, int32_t 
  * that layer's [B][d] fp32 slab, updated in place.  d_m may alias d_u.
  */
 int srm_mixer_update(srm_model *m, int32_t layer, int32_t pos, int64_t B, const void *d_u,
-                     float *d_state_layer, void *d_m, void *hip_stream);
+                     void *d_state_layer, void *d_m, void *hip_stream);
 
 /*
  * srm_linear: out = epilogue(A W^T + bias) with A [M][K] and W [N][K] device

@@ -12,7 +12,7 @@ from typing import Optional
 
 import numpy as np
 
-SRM_FP32, SRM_BF16 = 0, 1
+SRM_FP32, SRM_BF16, SRM_FP16 = 0, 1, 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsrm.so")
 _lib = None
@@ -31,7 +31,8 @@ class SrmError(RuntimeError):
 class srm_config(C.Structure):
     _fields_ = [("vocab", C.c_int32), ("d_model", C.c_int32), ("n_layers", C.c_int32),
                 ("n_heads", C.c_int32), ("mlp_expansion", C.c_int32), ("n_ctx", C.c_int32),
-                ("weight_dtype", C.c_int32), ("ln_eps", C.c_float), ("no_projections", C.c_int32)]
+                ("weight_dtype", C.c_int32), ("ln_eps", C.c_float), ("state_dtype", C.c_int32),
+                ("no_projections", C.c_int32)]
 
 
 class srm_host_layer(C.Structure):
@@ -137,7 +138,10 @@ class Model:
         self.n_ctx = cfg.n_ctx
         self.dtype = SRM_BF16 if cfg.weight_dtype == "bf16" else SRM_FP32
         c = srm_config(cfg.vocab, cfg.d_model, cfg.n_layers, cfg.n_heads, cfg.mlp_expansion,
-                       cfg.n_ctx, self.dtype, cfg.ln_eps, 0 if getattr(cfg, "use_projections", True) else 1)
+                       cfg.n_ctx, self.dtype, cfg.ln_eps,
+                       SRM_FP16 if getattr(cfg, "state_dtype", "fp32") == "fp16" else SRM_FP32,
+                       0 if getattr(cfg, "use_projections", True) else 1)
+        self.state_half = getattr(cfg, "state_dtype", "fp32") == "fp16"
         keep = []
 
         def fp(a, shape):
@@ -176,6 +180,11 @@ class Model:
         torch = _torch()
         return torch.bfloat16 if self.dtype == SRM_BF16 else torch.float32
 
+    @property
+    def state_torch_dtype(self):
+        torch = _torch()
+        return torch.float16 if self.state_half else torch.float32
+
     def state_bytes(self, batch: int) -> int:
         return lib().srm_state_bytes(self._h, batch)
 
@@ -184,7 +193,7 @@ class Model:
 
     def new_state(self, batch: int):
         torch = _torch()
-        return torch.zeros((self.L, batch, self.d), dtype=torch.float32, device="cuda")
+        return torch.zeros((self.L, batch, self.d), dtype=self.state_torch_dtype, device="cuda")
 
     def new_workspace(self, rows: int):
         torch = _torch()
@@ -196,7 +205,7 @@ class Model:
         when top_p is given too."""
         torch = _torch()
         p_in = _dev(tok_in, torch.int32, B, "tok_in")
-        p_st = _dev(state, torch.float32, self.L * B * self.d, "state")
+        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.d, "state")
         if state.numel() != self.L * B * self.d:
             raise ValueError("state: must be exactly [L][B][d]")
         p_out = _dev(tok_out, torch.int32, B, "tok_out")
@@ -217,7 +226,7 @@ class Model:
                  top_p=None, logits=None):
         torch = _torch()
         p_tk = _dev(tok, torch.int32, B, "tok")
-        p_st = _dev(state, torch.float32, self.L * B * self.d, "state")
+        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.d, "state")
         if state.numel() != self.L * B * self.d:
             raise ValueError("state: must be exactly [L][B][d]")
         p_out = _dev(tokens_out, torch.int32, G * B, "tokens_out")
@@ -235,7 +244,7 @@ class Model:
         N, P = prompts.shape
         Bt = N * fanout_k
         p_pr = _dev(prompts, torch.int32, N * P, "prompts")
-        p_st = _dev(state, torch.float32, self.L * Bt * self.d, "state")
+        p_st = _dev(state, self.state_torch_dtype, self.L * Bt * self.d, "state")
         if state.numel() != self.L * Bt * self.d:
             raise ValueError("state: must be exactly [L][N*k][d]")
         p_nt = _dev(next_tok, torch.int32, Bt, "next_tok")
@@ -250,7 +259,7 @@ class Model:
         torch = _torch()
         p_pos = _dev(pos, torch.int32, B, "pos")
         p_in = _dev(tok_in, torch.int32, B, "tok_in")
-        p_st = _dev(state, torch.float32, self.L * B * self.d, "state")
+        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.d, "state")
         if state.numel() != self.L * B * self.d:
             raise ValueError("state: must be exactly [L][B][d]")
         p_out = _dev(tok_out, torch.int32, B, "tok_out")
@@ -274,7 +283,7 @@ class Model:
         if state.numel() != self.L * Bt * self.d:
             raise ValueError("state: must be [L][state_batch][d]")
         p_tk = _dev(tokens, torch.int32, int(h_off[-1]), "tokens")
-        p_st = _dev(state, torch.float32, self.L * Bt * self.d, "state")
+        p_st = _dev(state, self.state_torch_dtype, self.L * Bt * self.d, "state")
         p_nt = _dev(next_tok, torch.int32, Bt, "next_tok")
         p_sl = None if slot is None else _dev(slot, torch.int32, N, "slot")
         p_pos = None if pos is None else _dev(pos, torch.int32, Bt, "pos")
@@ -299,7 +308,7 @@ class Model:
         torch = _torch()
         n = B * self.d
         p_u = _dev(u, self.act_dtype, n, "u")
-        p_s = _dev(state_layer, torch.float32, n, "state_layer")
+        p_s = _dev(state_layer, self.state_torch_dtype, n, "state_layer")
         p_m = _dev(m, self.act_dtype, n, "m")
         _check(lib().srm_mixer_update(self._h, layer, pos, B, p_u, p_s, p_m, _stream(stream)))
 

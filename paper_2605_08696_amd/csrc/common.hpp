@@ -10,6 +10,9 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
+typedef _Float16 f16;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+
 constexpr int kWave = 64;
 
 // ---- activation-type load / store of 4 consecutive channels -----------------
@@ -28,6 +31,34 @@ __device__ __forceinline__ void store4(bf16 *p, float4 v)
 }
 __device__ __forceinline__ void store1(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store1(bf16 *p, float v) { *p = (bf16)v; }
+
+// ---- recurrent state: fp32, or binary16 when the model keeps a half-precision cache --------
+// Vector j = channels 4j .. 4j+3 of the slab.  The state is touched once per step:
+// streaming (nontemporal) accesses.  to_state() is the value as the cache keeps it.
+__device__ __forceinline__ float4 load_state4(const float *S, int64_t j)
+{
+    const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(S) + j);
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ float4 load_state4(const f16 *S, int64_t j)
+{
+    const f16x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f16x4_t *>(S) + j);
+    return make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+}
+__device__ __forceinline__ void store_state4(float *S, int64_t j, float4 v)
+{
+    f32x4_t o;
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t *>(S) + j);
+}
+__device__ __forceinline__ void store_state4(f16 *S, int64_t j, float4 v)
+{
+    f16x4_t o;
+    o[0] = (f16)v.x; o[1] = (f16)v.y; o[2] = (f16)v.z; o[3] = (f16)v.w;   // already binary16 values
+    __builtin_nontemporal_store(o, reinterpret_cast<f16x4_t *>(S) + j);
+}
+__device__ __forceinline__ float to_state(float v, const float *) { return v; }
+__device__ __forceinline__ float to_state(float v, const f16 *) { return (float)(f16)v; }   // nearest, ties to even
 
 // ---- wavefront reductions ------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v)

@@ -34,10 +34,11 @@ struct GemmEpi {
     // EPI_MIX: the recurrent state update (Eq. 2 / Eq. 3) applied to the product, which is the
     // stacked head projection u: S <- lam*S + p*u, out = q*S + beta at the row's position
     // (pos / pos_dev / pos_rows as above; a position outside [0, n_ctx) leaves S alone and
-    // writes zeros).  state: fp32 [M][ldo]; alpha, beta: [H][n_ctx]; lam: [H]; dh = ldo / H.
-    float *state;
+    // writes zeros).  state: [M][ldo], fp32 or (state_half) binary16; alpha, beta: [H][n_ctx];
+    // lam: [H]; dh = ldo / H.
+    void *state;
     const float *alpha, *beta, *lam;
-    int32_t n_ctx, H, dh;
+    int32_t n_ctx, H, dh, state_half;
 };
 
 // Position that keys the random numbers of output row `row` (rows >= M read nothing).
@@ -87,9 +88,16 @@ __device__ __forceinline__ void epi_store(const GemmEpi &ep, int64_t row, int co
         const bool row_repeat = h < ep.H / 2;
         const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
         const float u = (float)(TAct)v;                 // u in the activation type, as the unfused path stores it
-        float *sp = ep.state + row * ep.ldo + col;
-        const float n = fmaf(l, *sp, p * u);
-        *sp = n;
+        float n;
+        if (ep.state_half) {
+            f16 *sp = static_cast<f16 *>(ep.state) + row * ep.ldo + col;
+            n = to_state(fmaf(l, (float)*sp, p * u), sp);
+            *sp = (f16)n;
+        } else {
+            float *sp = static_cast<float *>(ep.state) + row * ep.ldo + col;
+            n = fmaf(l, *sp, p * u);
+            *sp = n;
+        }
         store1(o, fmaf(q, n, be));
     } else {
         if (ep.out) reinterpret_cast<float *>(ep.out)[row * ep.ldo + col] = v;
@@ -159,14 +167,29 @@ __device__ __forceinline__ void epi_store4(const GemmEpi &ep, int64_t row, int c
         const float a = ep.alpha[(size_t)h * ep.n_ctx + pos], be = ep.beta[(size_t)h * ep.n_ctx + pos], l = ep.lam[h];
         const bool row_repeat = h < ep.H / 2;
         const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
-        float *sp = ep.state + row * ep.ldo + col;
-        const float4 s0 = load4(sp);
+        const int64_t sj = (row * ep.ldo + col) >> 2;
         float4 n, m;
-        n.x = fmaf(l, s0.x, p * (float)(TAct)v.x); m.x = fmaf(q, n.x, be);
-        n.y = fmaf(l, s0.y, p * (float)(TAct)v.y); m.y = fmaf(q, n.y, be);
-        n.z = fmaf(l, s0.z, p * (float)(TAct)v.z); m.z = fmaf(q, n.z, be);
-        n.w = fmaf(l, s0.w, p * (float)(TAct)v.w); m.w = fmaf(q, n.w, be);
-        store4(sp, n);
+        if (ep.state_half) {
+            f16 *sp = static_cast<f16 *>(ep.state);
+            const float4 s0 = load_state4(sp, sj);
+            n.x = to_state(fmaf(l, s0.x, p * (float)(TAct)v.x), sp);
+            n.y = to_state(fmaf(l, s0.y, p * (float)(TAct)v.y), sp);
+            n.z = to_state(fmaf(l, s0.z, p * (float)(TAct)v.z), sp);
+            n.w = to_state(fmaf(l, s0.w, p * (float)(TAct)v.w), sp);
+            store_state4(sp, sj, n);
+        } else {
+            float *sp = static_cast<float *>(ep.state);
+            const float4 s0 = load_state4(sp, sj);
+            n.x = fmaf(l, s0.x, p * (float)(TAct)v.x);
+            n.y = fmaf(l, s0.y, p * (float)(TAct)v.y);
+            n.z = fmaf(l, s0.z, p * (float)(TAct)v.z);
+            n.w = fmaf(l, s0.w, p * (float)(TAct)v.w);
+            store_state4(sp, sj, n);
+        }
+        m.x = fmaf(q, n.x, be);
+        m.y = fmaf(q, n.y, be);
+        m.z = fmaf(q, n.z, be);
+        m.w = fmaf(q, n.w, be);
         store4(o, m);
     } else {
         if (ep.out) store4(reinterpret_cast<float *>(ep.out) + row * ep.ldo + col, v);

@@ -25,9 +25,9 @@ constexpr int kMaxHeads = 64;
 // head coefficients of this position are staged in LDS once per block.  If
 // pos_dev is not null the position is read from device memory (clamped to the
 // table), so that a captured graph of the step can be replayed as is.
-template <typename TAct, int UNROLL>
+template <typename TAct, int UNROLL, typename TState = float>
 __global__ void __launch_bounds__(256)
-state_update_kernel(const TAct *__restrict__ u, float *__restrict__ S, TAct *__restrict__ m,
+state_update_kernel(const TAct *__restrict__ u, TState *__restrict__ S, TAct *__restrict__ m,
                     const float *__restrict__ alpha, const float *__restrict__ beta,
                     const float *__restrict__ lam, int pos, const int *__restrict__ pos_dev, int n_ctx, int H,
                     int d, int64_t nvec)
@@ -54,8 +54,7 @@ state_update_kernel(const TAct *__restrict__ u, float *__restrict__ S, TAct *__r
         for (int k = 0; k < UNROLL; ++k) {
             const int64_t j = i + k * nthreads;
             if (j < nvec) {
-                const f32x4_t sv = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(S) + j);
-                s[k] = make_float4(sv[0], sv[1], sv[2], sv[3]);
+                s[k] = load_state4(S, j);
                 x[k] = load4(u + j * 4);
             }
         }
@@ -64,13 +63,11 @@ state_update_kernel(const TAct *__restrict__ u, float *__restrict__ S, TAct *__r
             const int64_t j = i + k * nthreads;
             if (j < nvec) {
                 float4 n, o;
-                n.x = fmaf(l, s[k].x, p * x[k].x); o.x = fmaf(q, n.x, be);
-                n.y = fmaf(l, s[k].y, p * x[k].y); o.y = fmaf(q, n.y, be);
-                n.z = fmaf(l, s[k].z, p * x[k].z); o.z = fmaf(q, n.z, be);
-                n.w = fmaf(l, s[k].w, p * x[k].w); o.w = fmaf(q, n.w, be);
-                f32x4_t nv;
-                nv[0] = n.x; nv[1] = n.y; nv[2] = n.z; nv[3] = n.w;
-                __builtin_nontemporal_store(nv, reinterpret_cast<f32x4_t *>(S) + j);
+                n.x = to_state(fmaf(l, s[k].x, p * x[k].x), S); o.x = fmaf(q, n.x, be);
+                n.y = to_state(fmaf(l, s[k].y, p * x[k].y), S); o.y = fmaf(q, n.y, be);
+                n.z = to_state(fmaf(l, s[k].z, p * x[k].z), S); o.z = fmaf(q, n.z, be);
+                n.w = to_state(fmaf(l, s[k].w, p * x[k].w), S); o.w = fmaf(q, n.w, be);
+                store_state4(S, j, n);
                 store4(m + j * 4, o);
             }
         }
@@ -81,9 +78,9 @@ state_update_kernel(const TAct *__restrict__ u, float *__restrict__ S, TAct *__r
 // t from a zero state (positions 0..P-1).  The final state is written to `rep`
 // consecutive samples: S[((seq0 + seq) * rep + r)][d] of this layer's slab.
 // Dynamic LDS: 2 * H * P floats (alpha then beta of the P positions).
-template <typename TAct>
+template <typename TAct, typename TState = float>
 __global__ void __launch_bounds__(256)
-mixer_scan_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__restrict__ S,
+mixer_scan_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, TState *__restrict__ S,
                   const float *__restrict__ alpha, const float *__restrict__ beta,
                   const float *__restrict__ lam, int n_ctx, int H, int d, int nseq, int P,
                   int64_t seq0, int rep)
@@ -112,14 +109,14 @@ mixer_scan_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__res
         const float a = sa[h * P + t], be = sb[h * P + t];
         const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
         float4 o;
-        s.x = fmaf(l, s.x, p * x.x); o.x = fmaf(q, s.x, be);
-        s.y = fmaf(l, s.y, p * x.y); o.y = fmaf(q, s.y, be);
-        s.z = fmaf(l, s.z, p * x.z); o.z = fmaf(q, s.z, be);
-        s.w = fmaf(l, s.w, p * x.w); o.w = fmaf(q, s.w, be);
+        s.x = to_state(fmaf(l, s.x, p * x.x), S); o.x = fmaf(q, s.x, be);
+        s.y = to_state(fmaf(l, s.y, p * x.y), S); o.y = fmaf(q, s.y, be);
+        s.z = to_state(fmaf(l, s.z, p * x.z), S); o.z = fmaf(q, s.z, be);
+        s.w = to_state(fmaf(l, s.w, p * x.w), S); o.w = fmaf(q, s.w, be);
         store4(mp + (int64_t)t * d, o);
     }
-    float *dst = S + ((seq0 + seq) * rep) * (int64_t)d + cv * 4;
-    for (int r = 0; r < rep; ++r) store4(dst + (int64_t)r * d, s);
+    const int64_t dst = (((seq0 + seq) * rep) * (int64_t)d + cv * 4) >> 2;       // vector index
+    for (int r = 0; r < rep; ++r) store_state4(S, dst + (int64_t)r * (d >> 2), s);
 }
 
 // Token mixing of a non-projected layer in one pass over the row (decode): LayerNorm1,
@@ -132,9 +129,9 @@ mixer_scan_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__res
 // out: 16d + 2d bytes per sample for bf16 activations.  VPL = float4 vectors per
 // lane (d <= 256 * VPL).  Position: pos_rows[row], else *pos_dev, else pos; a
 // position outside [0, n_ctx) leaves S alone and adds nothing.
-template <typename TAct, int VPL>
+template <typename TAct, int VPL, typename TState = float>
 __global__ void __launch_bounds__(256)
-np_token_mix_kernel(float *x, float *__restrict__ S, TAct *__restrict__ out, const float *__restrict__ g1,
+np_token_mix_kernel(float *x, TState *__restrict__ S, TAct *__restrict__ out, const float *__restrict__ g1,
                     const float *__restrict__ b1, const float *__restrict__ g2, const float *__restrict__ b2,
                     const float *__restrict__ alpha, const float *__restrict__ beta,
                     const float *__restrict__ lam, int pos, const int *__restrict__ pos_dev,
@@ -186,17 +183,18 @@ np_token_mix_kernel(float *x, float *__restrict__ S, TAct *__restrict__ out, con
                 const float a = alpha[(size_t)h * n_ctx + p], be = beta[(size_t)h * n_ctx + p], l = lam[h];
                 const bool row_repeat = h < H / 2;
                 const float pp = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
-                const f32x4_t sv = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(S + row * d + c));
-                f32x4_t nv;
-                nv[0] = fmaf(l, sv[0], pp * u0);
-                nv[1] = fmaf(l, sv[1], pp * u1);
-                nv[2] = fmaf(l, sv[2], pp * u2);
-                nv[3] = fmaf(l, sv[3], pp * u3);
-                __builtin_nontemporal_store(nv, reinterpret_cast<f32x4_t *>(S + row * d + c));
-                v[i].x += (float)(TAct)fmaf(q, nv[0], be);
-                v[i].y += (float)(TAct)fmaf(q, nv[1], be);
-                v[i].z += (float)(TAct)fmaf(q, nv[2], be);
-                v[i].w += (float)(TAct)fmaf(q, nv[3], be);
+                const int64_t sj = (row * d + c) >> 2;
+                const float4 sv = load_state4(S, sj);
+                float4 nv;
+                nv.x = to_state(fmaf(l, sv.x, pp * u0), S);
+                nv.y = to_state(fmaf(l, sv.y, pp * u1), S);
+                nv.z = to_state(fmaf(l, sv.z, pp * u2), S);
+                nv.w = to_state(fmaf(l, sv.w, pp * u3), S);
+                store_state4(S, sj, nv);
+                v[i].x += (float)(TAct)fmaf(q, nv.x, be);
+                v[i].y += (float)(TAct)fmaf(q, nv.y, be);
+                v[i].z += (float)(TAct)fmaf(q, nv.z, be);
+                v[i].w += (float)(TAct)fmaf(q, nv.w, be);
                 store4(x + row * d + c, v[i]);
             }
             sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
@@ -233,9 +231,9 @@ np_token_mix_kernel(float *x, float *__restrict__ S, TAct *__restrict__ out, con
 // [0, n_ctx) is inactive: its state is left as it is and its m row is zero.
 // Thread = (sample, 4 channels); alpha and beta come straight from the tables
 // (a few KB, cache resident).
-template <typename TAct>
+template <typename TAct, typename TState = float>
 __global__ void __launch_bounds__(256)
-state_update_ragged_kernel(const TAct *__restrict__ u, float *__restrict__ S, TAct *__restrict__ m,
+state_update_ragged_kernel(const TAct *__restrict__ u, TState *__restrict__ S, TAct *__restrict__ m,
                            const float *__restrict__ alpha, const float *__restrict__ beta,
                            const float *__restrict__ lam, const int *__restrict__ pos_rows, int n_ctx, int H,
                            int d, int64_t nvec)
@@ -253,15 +251,14 @@ state_update_ragged_kernel(const TAct *__restrict__ u, float *__restrict__ S, TA
     const float a = alpha[(size_t)h * n_ctx + pos], be = beta[(size_t)h * n_ctx + pos], l = lam[h];
     const bool row_repeat = h < H / 2;
     const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
-    const f32x4_t sv = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(S) + j);
+    const float4 sv = load_state4(S, j);
     const float4 x = load4(u + j * 4);
-    float4 o;
-    f32x4_t nv;
-    nv[0] = fmaf(l, sv[0], p * x.x); o.x = fmaf(q, nv[0], be);
-    nv[1] = fmaf(l, sv[1], p * x.y); o.y = fmaf(q, nv[1], be);
-    nv[2] = fmaf(l, sv[2], p * x.z); o.z = fmaf(q, nv[2], be);
-    nv[3] = fmaf(l, sv[3], p * x.w); o.w = fmaf(q, nv[3], be);
-    __builtin_nontemporal_store(nv, reinterpret_cast<f32x4_t *>(S) + j);
+    float4 o, nv;
+    nv.x = to_state(fmaf(l, sv.x, p * x.x), S); o.x = fmaf(q, nv.x, be);
+    nv.y = to_state(fmaf(l, sv.y, p * x.y), S); o.y = fmaf(q, nv.y, be);
+    nv.z = to_state(fmaf(l, sv.z, p * x.z), S); o.z = fmaf(q, nv.z, be);
+    nv.w = to_state(fmaf(l, sv.w, p * x.w), S); o.w = fmaf(q, nv.w, be);
+    store_state4(S, j, nv);
     store4(m + j * 4, o);
 }
 
@@ -273,9 +270,9 @@ state_update_ragged_kernel(const TAct *__restrict__ u, float *__restrict__ S, TA
 // the launch).  Its final state goes to sample slot[seq0 + s] if slot is given
 // (skipped when outside [0, nslots)), else to the `rep` samples
 // (seq0 + s) * rep + r.  Dynamic LDS: 2 * H * Pmax floats.
-template <typename TAct>
+template <typename TAct, typename TState = float>
 __global__ void __launch_bounds__(256)
-mixer_scan_ragged_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__restrict__ S,
+mixer_scan_ragged_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, TState *__restrict__ S,
                          const float *__restrict__ alpha, const float *__restrict__ beta,
                          const float *__restrict__ lam, int n_ctx, int H, int d, int nseq, int Pmax,
                          const int32_t *__restrict__ offsets, int64_t base, int64_t rows, int64_t seq0, int rep,
@@ -308,18 +305,19 @@ mixer_scan_ragged_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float
         const float a = sa[h * Pmax + t], be = sb[h * Pmax + t];
         const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
         float4 o;
-        s.x = fmaf(l, s.x, p * x.x); o.x = fmaf(q, s.x, be);
-        s.y = fmaf(l, s.y, p * x.y); o.y = fmaf(q, s.y, be);
-        s.z = fmaf(l, s.z, p * x.z); o.z = fmaf(q, s.z, be);
-        s.w = fmaf(l, s.w, p * x.w); o.w = fmaf(q, s.w, be);
+        s.x = to_state(fmaf(l, s.x, p * x.x), S); o.x = fmaf(q, s.x, be);
+        s.y = to_state(fmaf(l, s.y, p * x.y), S); o.y = fmaf(q, s.y, be);
+        s.z = to_state(fmaf(l, s.z, p * x.z), S); o.z = fmaf(q, s.z, be);
+        s.w = to_state(fmaf(l, s.w, p * x.w), S); o.w = fmaf(q, s.w, be);
         store4(mp + (int64_t)t * d, o);
     }
+    const int dq = d >> 2;
     if (slot) {
         const int64_t dst = slot[seq0 + seq];
-        if (dst >= 0 && dst < nslots) store4(S + dst * (int64_t)d + cv * 4, s);
+        if (dst >= 0 && dst < nslots) store_state4(S, dst * dq + cv, s);
     } else {
-        float *dst = S + ((seq0 + seq) * rep) * (int64_t)d + cv * 4;
-        for (int r = 0; r < rep; ++r) store4(dst + (int64_t)r * d, s);
+        const int64_t dst = ((seq0 + seq) * rep) * (int64_t)dq + cv;
+        for (int r = 0; r < rep; ++r) store_state4(S, dst + (int64_t)r * dq, s);
     }
 }
 

@@ -59,6 +59,8 @@ struct srm_model {
     int device;
     int d, ff, V, L, H;
     bool noproj;           // non-projected mixer layers
+    bool shalf;            // recurrent state (and lambda) in binary16
+    size_t ssize;          // bytes per state element
     size_t wsize;          // bytes per matrix element
     void *slab;
     const void *embed, *head;
@@ -116,6 +118,8 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     if (cfg->weight_dtype == SRM_BF16 && cfg->d_model % 64)
         return fail(SRM_EINVAL, "srm_init_weights: bf16 needs d_model %% 64 == 0");
     if (!(cfg->ln_eps > 0.0f)) return fail(SRM_EINVAL, "srm_init_weights: ln_eps must be > 0");
+    if (cfg->state_dtype != SRM_FP32 && cfg->state_dtype != SRM_FP16)
+        return fail(SRM_EINVAL, "srm_init_weights: unknown state_dtype %d", cfg->state_dtype);
     if (!w->embed || !w->head || !w->lnf_g || !w->lnf_b || !w->layers)
         return fail(SRM_EINVAL, "srm_init_weights: null weight pointer");
     const int d = cfg->d_model, L = cfg->n_layers, H = cfg->n_heads, V = cfg->vocab;
@@ -139,6 +143,8 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     m->cfg = *cfg;
     m->d = d; m->ff = (int)ff; m->V = V; m->L = L; m->H = H;
     m->noproj = cfg->no_projections != 0;
+    m->shalf = cfg->state_dtype == SRM_FP16;
+    m->ssize = m->shalf ? 2 : 4;
     const bool bf = cfg->weight_dtype == SRM_BF16;
     m->wsize = bf ? 2 : 4;
     m->slab = nullptr;
@@ -161,7 +167,13 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
             const bool pj = !m->noproj;
             o[2] = pj ? sb.add(y.w_in, (size_t)d * d, bf) : 0;   o[3] = pj ? sb.add(y.b_in, d, false) : 0;
             o[4] = sb.add(y.alpha, H * nc, false);      o[5] = sb.add(y.beta, H * nc, false);
-            o[6] = sb.add(y.lambda, H, false);
+            if (m->shalf) {                              // decay constants as binary16 values
+                float lh[kMaxHeads];
+                for (int h = 0; h < H; ++h) lh[h] = (float)(_Float16)y.lambda[h];
+                o[6] = sb.add(lh, H, false);
+            } else {
+                o[6] = sb.add(y.lambda, H, false);
+            }
             o[7] = pj ? sb.add(y.w_out, (size_t)d * d, bf) : 0;  o[8] = pj ? sb.add(y.b_out, d, false) : 0;
             o[9] = sb.add(y.ln2_g, d, false);           o[10] = sb.add(y.ln2_b, d, false);
             o[11] = sb.add(y.w_up, ff * d, bf);         o[12] = sb.add(y.b_up, ff, false);
@@ -212,7 +224,13 @@ extern "C" void srm_free(srm_model *m)
 extern "C" size_t srm_state_bytes(const srm_model *m, int64_t batch)
 {
     if (!m || batch <= 0) return 0;
-    return (size_t)m->L * (size_t)batch * (size_t)m->d * sizeof(float);
+    return (size_t)m->L * (size_t)batch * (size_t)m->d * m->ssize;
+}
+
+// Layer l's [B][d] slab of a state array.
+static void *layer_state(const srm_model *m, void *state, int l, int64_t B)
+{
+    return static_cast<unsigned char *>(state) + (size_t)l * (size_t)B * (size_t)m->d * m->ssize;
 }
 
 // ------------------------------------------------------------------ workspace
@@ -392,9 +410,9 @@ static int nucleus(const float *logits, int64_t rows, int V, const Sampling &sm,
 }
 
 struct MixArgs {           // EPI_MIX: state slab of the layer and its coefficient tables
-    float *state = nullptr;
+    void *state = nullptr;
     const float *alpha = nullptr, *beta = nullptr, *lam = nullptr;
-    int n_ctx = 0, H = 0, dh = 0;
+    int n_ctx = 0, H = 0, dh = 0, state_half = 0;
 };
 
 // out = epilogue(A W^T + bias) with operands of type T (float or bf16)
@@ -404,7 +422,7 @@ static int linear(const void *A, const void *W, const float *bias, int64_t M, in
                   int *nparts_out = nullptr, Sampling sm = Sampling(), int ksplit = 1, MixArgs mx = MixArgs())
 {
     GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows,
-               mx.state, mx.alpha, mx.beta, mx.lam, mx.n_ctx, mx.H, mx.dh};
+               mx.state, mx.alpha, mx.beta, mx.lam, mx.n_ctx, mx.H, mx.dh, mx.state_half};
     if constexpr (sizeof(T) == 2)
         return launch_bf16<EPI, bf16>(static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), M, N, K, ep,
                                       st, min_bn, nparts_out, ksplit);
@@ -454,7 +472,7 @@ static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, c
 }
 
 template <typename T>
-static int state_update(const srm_model *m, int layer, int pos, int64_t B, const void *u, float *S, void *mx,
+static int state_update(const srm_model *m, int layer, int pos, int64_t B, const void *u, void *S, void *mx,
                         hipStream_t st, const int *pos_dev = nullptr)
 {
     // Two 16-byte state vectors per thread and one pass over the slab (measured
@@ -470,9 +488,14 @@ static int state_update(const srm_model *m, int layer, int pos, int64_t B, const
     while (b) { int t = a % b; a = b; b = t; }
     const int step = dv / a;
     const int64_t nb = cdiv(cdiv(nvec, 256 * UNROLL), step) * step;
-    hipLaunchKernelGGL((state_update_kernel<T, UNROLL>), dim3((unsigned)nb), dim3(256), 0, st,
-                       static_cast<const T *>(u), S, static_cast<T *>(mx), y.alpha, y.beta, y.lam, pos, pos_dev,
-                       m->cfg.n_ctx, m->H, m->d, nvec);
+    if (m->shalf)
+        hipLaunchKernelGGL((state_update_kernel<T, UNROLL, f16>), dim3((unsigned)nb), dim3(256), 0, st,
+                           static_cast<const T *>(u), static_cast<f16 *>(S), static_cast<T *>(mx), y.alpha, y.beta,
+                           y.lam, pos, pos_dev, m->cfg.n_ctx, m->H, m->d, nvec);
+    else
+        hipLaunchKernelGGL((state_update_kernel<T, UNROLL>), dim3((unsigned)nb), dim3(256), 0, st,
+                           static_cast<const T *>(u), static_cast<float *>(S), static_cast<T *>(mx), y.alpha, y.beta,
+                           y.lam, pos, pos_dev, m->cfg.n_ctx, m->H, m->d, nvec);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
@@ -500,27 +523,35 @@ static bool fuse_mixer(const srm_model *m, int64_t rows) { return !m->noproj && 
 // LayerNorm after the last layer.
 template <typename T, typename MIX>
 static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hipStream_t st, MIX &&mix,
-                 bool norm_next, bool allow_split = false, float *fuse_state = nullptr, Sampling fuse_pos = Sampling(),
-                 float *np_state = nullptr)
+                 bool norm_next, bool allow_split = false, void *fuse_state = nullptr, Sampling fuse_pos = Sampling(),
+                 void *np_state = nullptr)
 {
     const LayerDev &y = m->layers[l];
     const int d = m->d, ff = m->ff;
     // split-K down projection (decode with few rows, bf16): see kSplitK
+    // (not with the fused non-projected layer: no LayerNorm kernel follows there to add the slabs)
     const bool split = allow_split && norm_next && sizeof(T) == 2 && w.part && ff >= 1024 &&
-                       ff % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 256;
+                       ff % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 256 && !(m->noproj && np_state);
     if (m->noproj && np_state) {
         // non-projected layer, decode: LayerNorm1, state update, residual add and LayerNorm2 in one kernel
         const unsigned nb = (unsigned)cdiv(rows, 4);
+#define NP_LAUNCH(VPL, TS)                                                                                    \
+    hipLaunchKernelGGL((np_token_mix_kernel<T, VPL, TS>), dim3(nb), dim3(256), 0, st, w.x,                     \
+                       static_cast<TS *>(np_state), static_cast<T *>(w.a), y.ln1_g, y.ln1_b, y.ln2_g, y.ln2_b, \
+                       y.alpha, y.beta, y.lam, fuse_pos.pos, fuse_pos.pos_dev, fuse_pos.pos_rows, m->cfg.n_ctx, \
+                       m->H, d, rows, m->cfg.ln_eps)
 #define NP_CASE(VPL)                                                                                          \
-    hipLaunchKernelGGL((np_token_mix_kernel<T, VPL>), dim3(nb), dim3(256), 0, st, w.x, np_state,               \
-                       static_cast<T *>(w.a), y.ln1_g, y.ln1_b, y.ln2_g, y.ln2_b, y.alpha, y.beta, y.lam,      \
-                       fuse_pos.pos, fuse_pos.pos_dev, fuse_pos.pos_rows, m->cfg.n_ctx, m->H, d, rows, m->cfg.ln_eps)
+    do {                                                                                                      \
+        if (m->shalf) NP_LAUNCH(VPL, f16);                                                                    \
+        else NP_LAUNCH(VPL, float);                                                                           \
+    } while (0)
         if (d <= 256) NP_CASE(1);
         else if (d <= 512) NP_CASE(2);
         else if (d <= 1024) NP_CASE(4);
         else if (d <= 2048) NP_CASE(8);
         else NP_CASE(16);
 #undef NP_CASE
+#undef NP_LAUNCH
         HIP_TRY(hipGetLastError());
     } else if (m->noproj) {
         // non-projected layer: mixer on the LayerNorm output, its result added to x by the LayerNorm kernel
@@ -529,7 +560,7 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
                                      0, w.mx)));
     } else if (fuse_state) {
         // few rows: the state update rides in the in-projection's epilogue (one kernel less per layer)
-        const MixArgs mx{fuse_state, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d / m->H};
+        const MixArgs mx{fuse_state, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d / m->H, m->shalf ? 1 : 0};
         SRM_TRY((linear<EPI_MIX, T>(w.a, y.w_in, y.b_in, rows, d, d, w.mx, st, nullptr, nullptr, 64, nullptr, fuse_pos,
                                     1, mx)));
     } else {
@@ -572,7 +603,7 @@ static int head_argmax(const srm_model *m, const Workspace &w, const void *a, in
 
 // ------------------------------------------------------------------ decode
 template <typename T>
-static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, float *state, int32_t *tok_out,
+static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, void *state, int32_t *tok_out,
                        float *logits, float *hidden, void *ws, hipStream_t st, const int *pos_dev = nullptr,
                        TokenStore ts = TokenStore(), float temperature = 0.0f, uint32_t seed = 0, float top_p = 1.0f)
 {
@@ -580,13 +611,13 @@ static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, 
     const int d = m->d;
     SRM_TRY((layernorm<T, true>(m, nullptr, 0, tok_in, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a, B, st)));
     auto mix = [&](int l) {
-        return state_update<T>(m, l, pos, B, w.u, state + (size_t)l * B * d, w.mx, st, pos_dev);
+        return state_update<T>(m, l, pos, B, w.u, layer_state(m, state, l, B), w.mx, st, pos_dev);
     };
     const bool fuse = fuse_mixer(m, B);
     const Sampling where{0.0f, 0, pos, pos_dev, nullptr, 1.0f};
     for (int l = 0; l < m->L; ++l)
-        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? state + (size_t)l * B * d : nullptr, where,
-                          state + (size_t)l * B * d)));
+        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? layer_state(m, state, l, B) : nullptr, where,
+                          layer_state(m, state, l, B))));
     if (hidden) HIP_TRY(hipMemcpyAsync(hidden, w.x, (size_t)B * d * 4, hipMemcpyDeviceToDevice, st));
     const Sampling sm{temperature, seed, pos, pos_dev, nullptr, top_p};
     const bool topp = temperature > 0.0f && top_p < 1.0f;
@@ -598,7 +629,7 @@ static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, 
 }
 
 static int decode_step_common(const char *who, srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in,
-                              float *d_state, int32_t *d_tok_out, float *d_logits, float *d_hidden,
+                              void *d_state, int32_t *d_tok_out, float *d_logits, float *d_hidden,
                               void *d_workspace, size_t workspace_bytes, void *hip_stream, float temperature,
                               uint32_t seed, float top_p = 1.0f)
 {
@@ -619,7 +650,7 @@ static int decode_step_common(const char *who, srm_model *m, int64_t B, int32_t 
                                               d_workspace, st, nullptr, TokenStore(), temperature, seed, top_p);
 }
 
-extern "C" int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
+extern "C" int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, void *d_state,
                                int32_t *d_tok_out, float *d_logits, float *d_hidden, void *d_workspace,
                                size_t workspace_bytes, void *hip_stream)
 {
@@ -627,7 +658,7 @@ extern "C" int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32
                               d_workspace, workspace_bytes, hip_stream, 0.0f, 0);
 }
 
-extern "C" int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
+extern "C" int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, void *d_state,
                                        int32_t *d_tok_out, float temperature, uint32_t seed, float *d_logits,
                                        float *d_hidden, void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
@@ -635,7 +666,7 @@ extern "C" int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, con
                               d_workspace, workspace_bytes, hip_stream, temperature, seed);
 }
 
-extern "C" int srm_decode_step_topp(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, float *d_state,
+extern "C" int srm_decode_step_topp(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, void *d_state,
                                     int32_t *d_tok_out, float temperature, float top_p, uint32_t seed,
                                     float *d_logits, float *d_hidden, void *d_workspace, size_t workspace_bytes,
                                     void *hip_stream)
@@ -647,7 +678,7 @@ extern "C" int srm_decode_step_topp(srm_model *m, int64_t B, int32_t pos, const 
 // ------------------------------------------------------------------ decode, one position per sample
 template <typename T>
 static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int advance, const int32_t *tok_in,
-                              float *state, int32_t *tok_out, float *logits, void *ws, hipStream_t st,
+                              void *state, int32_t *tok_out, float *logits, void *ws, hipStream_t st,
                               float temperature, uint32_t seed, float top_p)
 {
     const Workspace w = carve(m, ws, B);
@@ -656,17 +687,22 @@ static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int ad
     auto mix = [&](int l) {
         const LayerDev &y = m->layers[l];
         const int64_t nvec = B * (d / 4);
-        hipLaunchKernelGGL((state_update_ragged_kernel<T>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
-                           static_cast<const T *>(w.u), state + (size_t)l * B * d, static_cast<T *>(w.mx), y.alpha,
-                           y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
+        if (m->shalf)
+            hipLaunchKernelGGL((state_update_ragged_kernel<T, f16>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
+                               static_cast<const T *>(w.u), static_cast<f16 *>(layer_state(m, state, l, B)),
+                               static_cast<T *>(w.mx), y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
+        else
+            hipLaunchKernelGGL((state_update_ragged_kernel<T>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
+                               static_cast<const T *>(w.u), static_cast<float *>(layer_state(m, state, l, B)),
+                               static_cast<T *>(w.mx), y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
         HIP_TRY(hipGetLastError());
         return (int)SRM_OK;
     };
     const bool fuse = fuse_mixer(m, B);
     const Sampling where{0.0f, 0, 0, nullptr, pos_rows, 1.0f};
     for (int l = 0; l < m->L; ++l)
-        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? state + (size_t)l * B * d : nullptr, where,
-                          state + (size_t)l * B * d)));
+        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? layer_state(m, state, l, B) : nullptr, where,
+                          layer_state(m, state, l, B))));
     const bool topp = temperature > 0.0f && top_p < 1.0f;
     FinalizeRagged rg{};
     rg.pos_rows = pos_rows;
@@ -681,7 +717,7 @@ static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int ad
 }
 
 extern "C" int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, int32_t advance,
-                                      const int32_t *d_tok_in, float *d_state, int32_t *d_tok_out,
+                                      const int32_t *d_tok_in, void *d_state, int32_t *d_tok_out,
                                       float temperature, float top_p, uint32_t seed, float *d_logits,
                                       void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
@@ -704,7 +740,7 @@ extern "C" int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, i
 }
 
 // ------------------------------------------------------------------ generate (G steps in one call)
-static int generate_step(srm_model *m, int64_t B, int32_t *tok, float *state, void *ws, const int *ctr,
+static int generate_step(srm_model *m, int64_t B, int32_t *tok, void *state, void *ws, const int *ctr,
                          TokenStore ts, hipStream_t st, float temperature, uint32_t seed, float top_p, float *logits)
 {
     SRM_TRY(m->wsize == 2 ? decode_impl<bf16>(m, B, 0, tok, state, tok, logits, nullptr, ws, st, ctr, ts, temperature,
@@ -716,7 +752,7 @@ static int generate_step(srm_model *m, int64_t B, int32_t *tok, float *state, vo
     return SRM_OK;
 }
 
-static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, void *d_state,
                            int32_t *d_tokens_out, float temperature, uint32_t seed, float top_p, float *d_logits,
                            void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
@@ -770,7 +806,7 @@ static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int
     return SRM_OK;
 }
 
-extern "C" int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+extern "C" int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, void *d_state,
                             int32_t *d_tokens_out, float temperature, uint32_t seed, void *d_workspace,
                             size_t workspace_bytes, void *hip_stream)
 {
@@ -778,7 +814,7 @@ extern "C" int srm_generate(srm_model *m, int64_t B, int32_t pos0, int32_t G, in
                            workspace_bytes, hip_stream);
 }
 
-extern "C" int srm_generate_topp(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, float *d_state,
+extern "C" int srm_generate_topp(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, void *d_state,
                                  int32_t *d_tokens_out, float temperature, float top_p, uint32_t seed,
                                  float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
@@ -807,7 +843,7 @@ static int64_t seqs_per_pass(const srm_model *m, size_t workspace_bytes, int T, 
 static int scan_chunk_len(const srm_model *m, int64_t nseq, int P)
 {
     const int64_t dv = m->d / 4;
-    if (P < 64 || nseq * dv >= 65536) return 0;
+    if (P < 64 || nseq * dv >= 65536 || m->shalf) return 0;   // a half-precision cache is rounded at every step
     for (int c : {16, 32, 64, 128}) {
         const int64_t nch = cdiv(P, c);
         if (nch < 2) break;
@@ -818,7 +854,7 @@ static int scan_chunk_len(const srm_model *m, int64_t nseq, int P)
 
 // The mixer of one prefill pass: nc sequences in rows of w.u -> w.mx, final states to S_layer.
 template <typename T>
-static int prefill_mixer(const srm_model *m, int l, const Workspace &w, float *S_layer, int nc, int P, int chunk,
+static int prefill_mixer(const srm_model *m, int l, const Workspace &w, void *S_layer, int nc, int P, int chunk,
                          int nchunks, const int32_t *offsets, int64_t base, int64_t rows, int64_t seq0, int rep,
                          const int32_t *slot, int64_t nslots, hipStream_t st)
 {
@@ -831,27 +867,34 @@ static int prefill_mixer(const srm_model *m, int l, const Workspace &w, float *S
                            y.alpha, y.lam, m->cfg.n_ctx, m->H, d, nc, P, chunk, nchunks, offsets, base, rows, seq0);
         HIP_TRY(hipGetLastError());
         hipLaunchKernelGGL((scan_chunk_apply_kernel<T>), dim3(nb), dim3(256), 0, st, static_cast<const T *>(w.u),
-                           static_cast<T *>(w.mx), S_layer, F, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc, P,
-                           chunk, nchunks, offsets, base, rows, seq0, rep, slot, nslots);
+                           static_cast<T *>(w.mx), static_cast<float *>(S_layer), F, y.alpha, y.beta, y.lam,
+                           m->cfg.n_ctx, m->H, d, nc, P, chunk, nchunks, offsets, base, rows, seq0, rep, slot, nslots);
         HIP_TRY(hipGetLastError());
         return SRM_OK;
     }
     const unsigned nb = (unsigned)cdiv((int64_t)nc * (d / 4), 256);
     const size_t scan_lds = (size_t)2 * m->H * P * sizeof(float);
-    if (offsets)
-        hipLaunchKernelGGL((mixer_scan_ragged_kernel<T>), dim3(nb), dim3(256), scan_lds, st,
-                           static_cast<const T *>(w.u), static_cast<T *>(w.mx), S_layer, y.alpha, y.beta, y.lam,
-                           m->cfg.n_ctx, m->H, d, nc, P, offsets, base, rows, seq0, rep, slot, nslots);
-    else
-        hipLaunchKernelGGL((mixer_scan_kernel<T>), dim3(nb), dim3(256), scan_lds, st, static_cast<const T *>(w.u),
-                           static_cast<T *>(w.mx), S_layer, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc, P, seq0,
-                           rep);
+#define SCAN_LAUNCH(TS)                                                                                        \
+    do {                                                                                                       \
+        if (offsets)                                                                                           \
+            hipLaunchKernelGGL((mixer_scan_ragged_kernel<T, TS>), dim3(nb), dim3(256), scan_lds, st,           \
+                               static_cast<const T *>(w.u), static_cast<T *>(w.mx), static_cast<TS *>(S_layer), \
+                               y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc, P, offsets, base, rows, seq0, \
+                               rep, slot, nslots);                                                             \
+        else                                                                                                   \
+            hipLaunchKernelGGL((mixer_scan_kernel<T, TS>), dim3(nb), dim3(256), scan_lds, st,                  \
+                               static_cast<const T *>(w.u), static_cast<T *>(w.mx), static_cast<TS *>(S_layer), \
+                               y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc, P, seq0, rep);               \
+    } while (0)
+    if (m->shalf) SCAN_LAUNCH(f16);
+    else SCAN_LAUNCH(float);
+#undef SCAN_LAUNCH
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
 
 template <typename T>
-static int prefill_impl(srm_model *m, const int32_t *prompts, int N, int P, int k, float *state,
+static int prefill_impl(srm_model *m, const int32_t *prompts, int N, int P, int k, void *state,
                         int32_t *next_tok, float *logits, void *ws, int64_t per_pass, hipStream_t st)
 {
     const int d = m->d;
@@ -865,7 +908,7 @@ static int prefill_impl(srm_model *m, const int32_t *prompts, int N, int P, int 
         SRM_TRY((layernorm<T, true>(m, nullptr, 0, prompts + n0 * P, w.x, m->layers[0].ln1_g,
                                     m->layers[0].ln1_b, w.a, rows, st)));
         auto mix = [&](int l) {
-            return prefill_mixer<T>(m, l, w, state + (size_t)l * Btot * d, (int)nc, P, chunk, nchunks, nullptr, 0, rows,
+            return prefill_mixer<T>(m, l, w, layer_state(m, state, l, Btot), (int)nc, P, chunk, nchunks, nullptr, 0, rows,
                                     n0, k, nullptr, 0, st);
         };
         for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, rows, st, mix, l + 1 < m->L)));
@@ -878,7 +921,7 @@ static int prefill_impl(srm_model *m, const int32_t *prompts, int N, int P, int 
 }
 
 extern "C" int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, int32_t P, int32_t fanout_k,
-                           float *d_state, int32_t *d_next_tok, float *d_logits, void *d_workspace,
+                           void *d_state, int32_t *d_next_tok, float *d_logits, void *d_workspace,
                            size_t workspace_bytes, void *hip_stream)
 {
     if (!m || !d_prompts || !d_state || !d_next_tok || !d_workspace)
@@ -904,7 +947,7 @@ extern "C" int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, in
 // ------------------------------------------------------------------ prefill of packed ragged prompts
 template <typename T>
 static int prefill_ragged_impl(srm_model *m, const int32_t *tokens, const int32_t *h_off, const int32_t *d_off, int N,
-                               int k, const int32_t *slot, int64_t state_batch, float *state, int32_t *next_tok,
+                               int k, const int32_t *slot, int64_t state_batch, void *state, int32_t *next_tok,
                                int32_t *pos_out, float *logits, void *ws, int64_t max_rows, int pmax_call,
                                hipStream_t st)
 {
@@ -926,7 +969,7 @@ static int prefill_ragged_impl(srm_model *m, const int32_t *tokens, const int32_
         SRM_TRY((layernorm<T, true>(m, nullptr, 0, tokens + base, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a,
                                     rows, st)));
         auto mix = [&](int l) {
-            return prefill_mixer<T>(m, l, w, state + (size_t)l * state_batch * d, nc, chunk ? pmax_call : pmax, chunk,
+            return prefill_mixer<T>(m, l, w, layer_state(m, state, l, state_batch), nc, chunk ? pmax_call : pmax, chunk,
                                     nchunks, d_off, base, rows, (int64_t)n0, k, slot, state_batch, st);
         };
         for (int l = 0; l < m->L; ++l) SRM_TRY((block<T>(m, l, w, rows, st, mix, l + 1 < m->L)));
@@ -947,7 +990,7 @@ static int prefill_ragged_impl(srm_model *m, const int32_t *tokens, const int32_
 
 extern "C" int srm_prefill_ragged(srm_model *m, const int32_t *d_tokens, const int32_t *h_offsets,
                                   const int32_t *d_offsets, int32_t N, int32_t fanout_k, const int32_t *d_slot,
-                                  int64_t state_batch, float *d_state, int32_t *d_next_tok, int32_t *d_pos,
+                                  int64_t state_batch, void *d_state, int32_t *d_next_tok, int32_t *d_pos,
                                   float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
     const char *who = "srm_prefill_ragged";
@@ -1041,7 +1084,7 @@ extern "C" int srm_parallel_forward(srm_model *m, const int32_t *d_tok, int32_t 
 
 // ------------------------------------------------------------------ kernel-level entry points
 extern "C" int srm_mixer_update(srm_model *m, int32_t layer, int32_t pos, int64_t B, const void *d_u,
-                                float *d_state_layer, void *d_m, void *hip_stream)
+                                void *d_state_layer, void *d_m, void *hip_stream)
 {
     if (!m || !d_u || !d_state_layer || !d_m) return fail(SRM_EINVAL, "srm_mixer_update: null argument");
     if (layer < 0 || layer >= m->L) return fail(SRM_EINVAL, "srm_mixer_update: layer %d outside [0, %d)", layer, m->L);

@@ -81,9 +81,9 @@ def test_non_projected_fp32_all_paths_match_oracle(srm, orc_mod):
         assert rel_err_rows(l3[b:b + 1].cpu().numpy(), rf["logits"][b:b + 1, n - 1]) <= 1e-4
 
 
-@pytest.mark.parametrize("B", [5, 300])
-def test_non_projected_bf16_decode_matches_oracle(srm, orc_mod, B):
-    cfg = srm_synth.tiny_config(vocab=400, d_model=128, n_layers=3, n_heads=4, n_ctx=12, weight_dtype="bf16", seed=61,
+@pytest.mark.parametrize("B,d", [(5, 128), (300, 128), (300, 512)])
+def test_non_projected_bf16_decode_matches_oracle(srm, orc_mod, B, d):
+    cfg = srm_synth.tiny_config(vocab=400, d_model=d, n_layers=3, n_heads=4, n_ctx=12, weight_dtype="bf16", seed=61,
                                 use_projections=False)
     w = srm_synth.make_weights(cfg, stress=True)
     T = 8
@@ -108,3 +108,87 @@ def test_non_projected_bf16_decode_matches_oracle(srm, orc_mod, B):
     s_ref = ref["state"]                                       # [rows][L][d]
     s_got = st.view(cfg.n_layers, B, cfg.d_model)[:, rows].permute(1, 0, 2).cpu().numpy()
     assert np.abs(s_got - s_ref).max() <= 2e-2 * np.abs(s_ref).max()
+
+
+# ---- half-precision cache ("SRM architecture optimization", last sentence) ----------------------
+def test_half_state_fp32_weights_all_paths_match_oracle(srm, orc_mod):
+    cfg = dataclasses.replace(srm_synth.CONFIGS["C1"], state_dtype="fp16")
+    w = srm_synth.make_weights(cfg)
+    orc = orc_mod.Oracle(cfg, w, "f64")
+    model = srm.Model(cfg, w)
+    assert model.state_bytes(10) == cfg.n_layers * 10 * cfg.d_model * 2
+    prompts = srm_synth.make_prompts(cfg)
+    B, P = prompts.shape
+    G = 24
+    ref = orc.greedy(prompts, G, want_logits=True)
+    print("half state: prefill + generate", flush=True)
+    ws = model.new_workspace(B * P)
+    st, tk = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    assert st.dtype == torch.float16
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    model.prefill(to_dev(prompts), 1, st, tk, logits=lg, workspace=ws)
+    assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, 0]) <= 1e-3
+    # the same prompts one decode step at a time: every update is rounded alike; the two paths use different
+    # GEMM kernels (fp32 sums in another order), so a cache value may differ in its last binary16 place
+    st_b, tk_b = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    pc = to_dev(prompts).t().contiguous()
+    for t in range(P):
+        model.decode_step(B, t, pc[t], st_b, tk_b, workspace=ws)
+    torch.cuda.synchronize()
+    assert (st != st_b).float().mean() < 0.2                   # last-place differences persist and spread downstream
+    assert (st.float() - st_b.float()).abs().max() <= 2e-3 * st_b.float().abs().max()
+    assert torch.equal(tk, tk_b)
+    out = torch.empty((G - 1, B), dtype=torch.int32, device="cuda")
+    first = tk.cpu().numpy().copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        model.generate(B, P, G - 1, tk, st, out, workspace=ws)
+    side.synchronize()
+    got = np.concatenate([first[:, None], out.cpu().numpy().T], axis=1)
+    absmax = np.abs(ref["logits"]).max(axis=2)
+    # the GPU rounds an fp32 sum to binary16, the oracle an fp64 sum: a rare last-bit difference in a cache
+    # value may move a logit by ~1e-4 relative, so near ties are judged with that margin
+    assert check_tokens(got, ref["tokens"], ref["margin"], absmax, rtol=1e-3) <= 2
+    # cache against the oracle's after the whole run: binary16 values, equal except rare last-place differences
+    seq = np.concatenate([prompts, ref["tokens"][:, :G - 1]], axis=1)
+    s_ref = orc.greedy(seq, 1)["state"]                         # [B][L][d]
+    if (got == ref["tokens"]).all():
+        s_got = st.float().view(cfg.n_layers, B, cfg.d_model).permute(1, 0, 2).cpu().numpy()
+        diff = s_got != s_ref
+        assert diff.mean() < 0.3
+        assert np.abs(s_got - s_ref).max() <= 2e-3 * np.abs(s_ref).max()
+    # ragged decode equals the uniform step bit for bit
+    st_c, tk_c = st_b.clone(), tk_b.clone()
+    pos = torch.full((B,), P, dtype=torch.int32, device="cuda")
+    model.decode_step(B, P, tk_b, st_b, tk_b, workspace=ws)
+    model.decode_step_ragged(B, pos, tk_c, st_c, tk_c, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(st_b, st_c) and torch.equal(tk_b, tk_c)
+
+
+@pytest.mark.parametrize("use_projections,B", [(True, 300), (False, 300), (True, 3000)])
+def test_half_state_bf16_weights_match_oracle(srm, orc_mod, use_projections, B):
+    """bf16 weights with a binary16 cache; B = 3000 takes the separate state-update kernel, 300 the fused ones."""
+    cfg = srm_synth.tiny_config(vocab=400, d_model=512, n_layers=2, n_heads=4, n_ctx=12, weight_dtype="bf16", seed=62,
+                                use_projections=use_projections, state_dtype="fp16")
+    w = srm_synth.make_weights(cfg, stress=True)
+    T = 8
+    toks = srm_synth.make_prompts(cfg, batch=B, length=T)
+    rows = sorted({0, 1, B // 2, B - 1})
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks[rows])
+    model = srm.Model(cfg, w)
+    ws, st = model.new_workspace(B * T), model.new_state(B)
+    out = torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    print(f"half state bf16 B={B} projections={use_projections}", flush=True)
+    for t in range(T):
+        model.decode_step(B, t, tc[t], st, out, logits=lg, workspace=ws)
+        assert rel_err_rows(lg[rows].cpu().numpy(), ref["logits"][:, t]) <= 2e-2
+    st2, tk2 = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    model.prefill(to_dev(toks), 1, st2, tk2, workspace=ws)
+    torch.cuda.synchronize()
+    assert (st.float() - st2.float()).abs().max() <= 2e-2 * st.float().abs().max()
+    s_got = st.float().view(cfg.n_layers, B, cfg.d_model)[:, rows].permute(1, 0, 2).cpu().numpy()
+    assert np.abs(s_got - ref["state"]).max() <= 2e-2 * np.abs(ref["state"]).max()
