@@ -132,16 +132,19 @@ def cpu_baseline(cfg, w, rows, T):
             "sample": f"{rows} samples x {T} decode positions of {cfg.name} (fp32 build, OpenMP over samples), {dt:.1f} s"}
 
 
-def concurrency_sweep(torch, srm, srm_synth, steps):
+def concurrency_sweep(torch, srm, srm_synth, steps, state_dtype="fp32"):
     """C5: 256 distinct prompts prefilled once, state fanned out to k replicas each, greedy decode;
     then the largest batch (state + workspace resident) that completes one decode step."""
     cfg = srm_synth.CONFIGS["C5"]
+    if state_dtype != "fp32":
+        import dataclasses
+        cfg = dataclasses.replace(cfg, state_dtype=state_dtype)
     w = srm_synth.make_weights(cfg)
     model = srm.Model(cfg, w)
     prompts = torch.from_numpy(srm_synth.make_prompts(cfg)).cuda()
     N, P = prompts.shape
     out = {"metric": "generated tokens/sec on 1 MI355X at max batch", "unit": "tokens/s", "n_gpus": 1,
-           "data": "synthetic", "dtype": "bf16", "sweep": [], "config": {"workload": "C5: C4's model, 256 prompts x k"}}
+           "data": "synthetic", "dtype": "bf16", "sweep": [], "config": {"workload": f"C5: C4's model, 256 prompts x k, {state_dtype} state"}}
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for k in cfg.fanout:
         B = N * k
@@ -163,16 +166,18 @@ def concurrency_sweep(torch, srm, srm_synth, steps):
                              "prefill_s": t_pre, "state_gib": model.state_bytes(B) / 2**30})
         del state, ws, tok
         torch.cuda.empty_cache()
-    # largest resident batch: state (64 KiB/sequence) + workspace, one successful step
+    # largest resident batch: the state of every sequence + a workspace for slices of 131072 samples
+    # (a decode call takes the step in slices when the workspace is smaller than the batch); one successful step
     free, total = torch.cuda.mem_get_info()
-    per_seq = model.state_bytes(1) + model.workspace_bytes(1 << 20) / (1 << 20)
-    hi = int((free - (2 << 30)) / per_seq) // 4096 * 4096
+    slice_rows = 131072
+    ws = model.new_workspace(slice_rows)
+    per_seq = model.state_bytes(1) + 8
+    hi = int((free - ws.numel() - (2 << 30)) / per_seq) // 4096 * 4096
     best = None
     B = hi
     while B > 0 and best is None:
         try:
-            state = torch.zeros((cfg.n_layers, B, cfg.d_model), dtype=torch.float32, device="cuda")
-            ws = model.new_workspace(B)
+            state = model.new_state(B)
             tok = torch.zeros(B, dtype=torch.int32, device="cuda")
             e0.record()
             model.decode_step(B, 0, tok, state, tok, workspace=ws)
@@ -181,8 +186,8 @@ def concurrency_sweep(torch, srm, srm_synth, steps):
             if ok:
                 best = {"batch": B, "ms_per_step": e0.elapsed_time(e1), "tokens_per_s": B / (e0.elapsed_time(e1) * 1e-3),
                         "state_gib": model.state_bytes(B) / 2**30, "workspace_gib": ws.numel() / 2**30,
-                        "hbm_total_gib": total / 2**30}
-            del state, ws, tok
+                        "rows_per_slice": slice_rows, "hbm_total_gib": total / 2**30}
+            del state, tok
         except (RuntimeError, torch.cuda.OutOfMemoryError):
             pass
         torch.cuda.empty_cache()
@@ -218,7 +223,7 @@ def main():
     srm.lib()                                     # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
     if args.concurrency:
-        concurrency_sweep(torch, srm, srm_synth, min(args.steps, 8))
+        concurrency_sweep(torch, srm, srm_synth, min(args.steps, 8), args.state_dtype)
         return
     cfg = srm_synth.CONFIGS[args.workload]
     if args.no_projections or args.state_dtype != "fp32":

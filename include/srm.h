@@ -118,8 +118,14 @@ size_t srm_state_bytes(const srm_model *m, int64_t batch);
 
 /*
  * Bytes of scratch a call needs for `rows` token rows processed at once
- * (srm_decode_step: rows = B; srm_prefill / srm_parallel_forward: any multiple
- * of the sequence length, at least one sequence; more rows = fewer passes).
+ * (decode calls: rows = B takes the step in one pass; srm_prefill /
+ * srm_parallel_forward: any multiple of the sequence length, at least one
+ * sequence; more rows = fewer passes).  The decode calls (srm_decode_step*,
+ * srm_generate*) accept a smaller workspace and then take the step in slices of
+ * as many samples as it holds, at least min(B, 256) - the samples are
+ * independent - so the number of resident sequences is bounded by the state,
+ * not by the workspace.  Results do not depend on the slicing in fp32 models;
+ * in bf16 models a different slice size may select another GEMM tile shape.
  */
 size_t srm_workspace_bytes(const srm_model *m, int64_t rows);
 
@@ -131,7 +137,8 @@ size_t srm_workspace_bytes(const srm_model *m, int64_t rows);
  * Optional outputs (NULL to skip): d_logits[B][vocab] fp32, d_hidden[B][d]
  * fp32 (residual stream after the last block, before the final LayerNorm).
  * d_tok_out may alias d_tok_in.  Errors: SRM_EINVAL (null pointer, B <= 0,
- * pos outside [0, n_ctx)), SRM_ENOMEM (workspace_bytes < srm_workspace_bytes(m, B)).
+ * pos outside [0, n_ctx)), SRM_ENOMEM (workspace smaller than
+ * srm_workspace_bytes(m, min(B, 256))).
  */
 int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in,
                     void *d_state, int32_t *d_tok_out, float *d_logits, float *d_hidden,

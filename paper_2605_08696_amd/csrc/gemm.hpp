@@ -31,6 +31,7 @@ struct GemmEpi {
     int32_t pos;         // position of the counter, unless pos_dev or pos_rows is set
     const int *pos_dev;  // one position for all rows, in device memory
     const int *pos_rows; // [M] one position per row, in device memory
+    uint32_t row_base;   // sample index of row 0 (the random counter is keyed on the sample, not on the GEMM row)
     // EPI_MIX: the recurrent state update (Eq. 2 / Eq. 3) applied to the product, which is the
     // stacked head projection u: S <- lam*S + p*u, out = q*S + beta at the row's position
     // (pos / pos_dev / pos_rows as above; a position outside [0, n_ctx) leaves S alone and
@@ -251,7 +252,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
             int brel = 0;
             if (ep.temp > 0.0f) {
                 const int srow = m0 + wm * WTM + i * 32 + lr;
-                const uint32_t rk = srm_rowkey(ep.seed, epi_pos(ep, srow, M), (uint32_t)srow);
+                const uint32_t rk = srm_rowkey(ep.seed, epi_pos(ep, srow, M), (uint32_t)srow + ep.row_base);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -548,7 +549,7 @@ gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
             if (row < M) epi_store<EPI, float>(ep, row, col, v);
             if constexpr (EPI == EPI_ARGMAX) {
                 const float vs = ep.temp > 0.0f
-                                     ? v + ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep, row, M), (uint32_t)row), (uint32_t)col)
+                                     ? v + ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep, row, M), (uint32_t)row + ep.row_base), (uint32_t)col)
                                      : v;
                 if (arg_better(vs, col, bv, bi)) { bv = vs; bi = col; }
             }
@@ -626,7 +627,7 @@ gemv_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
             }
             if constexpr (EPI == EPI_ARGMAX) {
                 if (live && ep.temp > 0.0f)
-                    v += ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep, row, M), (uint32_t)row), (uint32_t)n);
+                    v += ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep, row, M), (uint32_t)row + ep.row_base), (uint32_t)n);
                 float bv = live ? v : -INFINITY;
                 int bi = live ? n : 0x7fffffff;
 #pragma unroll

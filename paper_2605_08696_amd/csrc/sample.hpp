@@ -134,7 +134,8 @@ __global__ void __launch_bounds__(NT)
 nucleus_kernel(const float *__restrict__ logits, int64_t ld, int V, float temp, float top_p, uint32_t seed, int pos,
                const int *__restrict__ pos_dev, const int *pos_rows, int32_t *__restrict__ tok,
                int32_t *__restrict__ store, const int *__restrict__ step_dev, int64_t store_stride,
-               int32_t *pos_advance, int *__restrict__ slow_count = nullptr, int *__restrict__ slow_list = nullptr)
+               int32_t *pos_advance, int *__restrict__ slow_count = nullptr, int *__restrict__ slow_list = nullptr,
+               uint32_t row_base = 0)
 {
     constexpr int NW = NT / 64;
     __shared__ float red[NW];
@@ -145,7 +146,7 @@ nucleus_kernel(const float *__restrict__ logits, int64_t ld, int V, float temp, 
     int w0 = FIND_W0 ? 0 : tok[row];
     if (!FIND_W0 && w0 < 0) return;                       // idle row (the whole block leaves)
     const uint32_t p = (uint32_t)(pos_rows ? pos_rows[row] : (pos_dev ? *pos_dev : pos));
-    const uint32_t rk = srm_rowkey(seed, p, (uint32_t)row);
+    const uint32_t rk = srm_rowkey(seed, p, (uint32_t)row + row_base);     // the counter is keyed on the sample index
     const float inv = 1.4426950408889634f / temp;
 
     if constexpr (FIND_W0) {
@@ -226,7 +227,8 @@ __global__ void __launch_bounds__(NT)
 nucleus_slow_kernel(const float *__restrict__ logits, int64_t ld, int V, float temp, float top_p, uint32_t seed, int pos,
                     const int *__restrict__ pos_dev, const int *pos_rows, int32_t *__restrict__ tok,
                     int32_t *__restrict__ store, const int *__restrict__ step_dev, int64_t store_stride,
-                    int32_t *pos_advance, const int *__restrict__ slow_count, const int *__restrict__ slow_list)
+                    int32_t *pos_advance, const int *__restrict__ slow_count, const int *__restrict__ slow_list,
+                    uint32_t row_base)
 {
     static_assert(EPT % 4 == 0, "EPT must be a multiple of 4");
     constexpr int NW = NT / 64;
@@ -266,7 +268,7 @@ nucleus_slow_kernel(const float *__restrict__ logits, int64_t ld, int V, float t
         const int w0 = min(max(tok[row], 0), V - 1);
         const uint32_t kw = order_key(L[w0]);
         const uint32_t p = (uint32_t)(pos_rows ? pos_rows[row] : (pos_dev ? *pos_dev : pos));
-        const uint32_t rk = srm_rowkey(seed, p, (uint32_t)row);
+        const uint32_t rk = srm_rowkey(seed, p, (uint32_t)row + row_base);
         const float M = block_max<NW>(mt, red);
         float z = 0.0f, fa = 0.0f;
 #pragma unroll

@@ -68,7 +68,7 @@ struct srm_model {
     std::vector<LayerDev> layers;
     // cached graph of one decode step for srm_generate (see there)
     hipGraphExec_t gexec;
-    struct { int64_t B; const void *tok, *state, *store, *ws; float temp; uint32_t seed; float top_p; const void *logits; } gkey;
+    struct { int64_t B; const void *tok, *state, *store, *ws; float temp; uint32_t seed; float top_p; const void *logits; size_t ws_bytes; } gkey;
 };
 
 static uint16_t host_f32_to_bf16(float f)
@@ -149,7 +149,7 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     m->wsize = bf ? 2 : 4;
     m->slab = nullptr;
     m->gexec = nullptr;
-    m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, 1.0f, nullptr};
+    m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, 1.0f, nullptr, 0};
 
     struct Offs { size_t v[15]; };
     std::vector<Offs> lo(L);
@@ -381,6 +381,7 @@ struct Sampling {          // temp == 0: greedy
     const int *pos_dev = nullptr;
     const int *pos_rows = nullptr;
     float top_p = 1.0f;    // < 1 (with temp > 0): nucleus truncation, needs the logits in memory
+    uint32_t row_base = 0; // sample index of the first row
 };
 
 // Nucleus pass over the logits the LM head has just written; tok holds the
@@ -393,18 +394,18 @@ static int nucleus(const float *logits, int64_t rows, int V, const Sampling &sm,
         // vocabulary too large for the register-resident search: one kernel, searching from memory
         hipLaunchKernelGGL((nucleus_kernel<256, false, false>), dim3((unsigned)rows), dim3(256), 0, st, logits,
                            (int64_t)V, V, sm.temp, sm.top_p, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, tok, store,
-                           step_dev, store_stride, pos_advance, nullptr, nullptr);
+                           step_dev, store_stride, pos_advance, nullptr, nullptr, sm.row_base);
         HIP_TRY(hipGetLastError());
         return SRM_OK;
     }
     hipLaunchKernelGGL((nucleus_kernel<256, false, true>), dim3((unsigned)rows), dim3(256), 0, st, logits, (int64_t)V,
                        V, sm.temp, sm.top_p, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, tok, store, step_dev,
-                       store_stride, pos_advance, slow, slow + 64);
+                       store_stride, pos_advance, slow, slow + 64, sm.row_base);
     HIP_TRY(hipGetLastError());
     const unsigned nb = (unsigned)std::min<int64_t>(rows, 256);
     hipLaunchKernelGGL((nucleus_slow_kernel<NT, EPT>), dim3(nb), dim3(NT), 0, st, logits, (int64_t)V, V, sm.temp,
                        sm.top_p, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, tok, store, step_dev, store_stride,
-                       pos_advance, slow, slow + 64);
+                       pos_advance, slow, slow + 64, sm.row_base);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
@@ -421,7 +422,7 @@ static int linear(const void *A, const void *W, const float *bias, int64_t M, in
                   hipStream_t st, float *pv = nullptr, int32_t *pi = nullptr, int min_bn = 64,
                   int *nparts_out = nullptr, Sampling sm = Sampling(), int ksplit = 1, MixArgs mx = MixArgs())
 {
-    GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows,
+    GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, sm.row_base,
                mx.state, mx.alpha, mx.beta, mx.lam, mx.n_ctx, mx.H, mx.dh, mx.state_half};
     if constexpr (sizeof(T) == 2)
         return launch_bf16<EPI, bf16>(static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), M, N, K, ep,
@@ -602,29 +603,100 @@ static int head_argmax(const srm_model *m, const Workspace &w, const void *a, in
 }
 
 // ------------------------------------------------------------------ decode
+// One decode step for the rows b0 .. b0+nb-1 of a batch of B samples; uniform position
+// (pos / pos_dev) or one position per sample (pos_rows, base pointer of the batch).
+struct DecodeArgs {
+    int64_t B;
+    int pos;
+    const int *pos_dev;
+    int32_t *pos_rows;
+    int advance;
+    const int32_t *tok_in;
+    void *state;
+    int32_t *tok_out;
+    float *logits, *hidden;
+    TokenStore ts;
+    float temperature;
+    uint32_t seed;
+    float top_p;
+};
+
 template <typename T>
-static int decode_impl(srm_model *m, int64_t B, int pos, const int32_t *tok_in, void *state, int32_t *tok_out,
-                       float *logits, float *hidden, void *ws, hipStream_t st, const int *pos_dev = nullptr,
-                       TokenStore ts = TokenStore(), float temperature = 0.0f, uint32_t seed = 0, float top_p = 1.0f)
+static int decode_rows(srm_model *m, const DecodeArgs &a, int64_t b0, int64_t nb, void *ws, hipStream_t st)
 {
-    const Workspace w = carve(m, ws, B);
+    const Workspace w = carve(m, ws, nb);
     const int d = m->d;
-    SRM_TRY((layernorm<T, true>(m, nullptr, 0, tok_in, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a, B, st)));
-    auto mix = [&](int l) {
-        return state_update<T>(m, l, pos, B, w.u, layer_state(m, state, l, B), w.mx, st, pos_dev);
+    int32_t *pos_rows = a.pos_rows ? a.pos_rows + b0 : nullptr;
+    auto slab = [&](int l) {       // rows b0.. of layer l's state
+        return static_cast<void *>(static_cast<unsigned char *>(layer_state(m, a.state, l, a.B)) +
+                                   (size_t)b0 * d * m->ssize);
     };
-    const bool fuse = fuse_mixer(m, B);
-    const Sampling where{0.0f, 0, pos, pos_dev, nullptr, 1.0f};
+    SRM_TRY((layernorm<T, true>(m, nullptr, 0, a.tok_in + b0, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a, nb,
+                                st)));
+    auto mix = [&](int l) {
+        if (!pos_rows) return state_update<T>(m, l, a.pos, nb, w.u, slab(l), w.mx, st, a.pos_dev);
+        const LayerDev &y = m->layers[l];
+        const int64_t nvec = nb * (d / 4);
+        if (m->shalf)
+            hipLaunchKernelGGL((state_update_ragged_kernel<T, f16>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
+                               static_cast<const T *>(w.u), static_cast<f16 *>(slab(l)), static_cast<T *>(w.mx),
+                               y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
+        else
+            hipLaunchKernelGGL((state_update_ragged_kernel<T>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
+                               static_cast<const T *>(w.u), static_cast<float *>(slab(l)), static_cast<T *>(w.mx),
+                               y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
+        HIP_TRY(hipGetLastError());
+        return (int)SRM_OK;
+    };
+    const bool fuse = fuse_mixer(m, nb);
+    const Sampling where{0.0f, 0, a.pos, a.pos_dev, pos_rows, 1.0f, 0};
     for (int l = 0; l < m->L; ++l)
-        SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? layer_state(m, state, l, B) : nullptr, where,
-                          layer_state(m, state, l, B))));
-    if (hidden) HIP_TRY(hipMemcpyAsync(hidden, w.x, (size_t)B * d * 4, hipMemcpyDeviceToDevice, st));
-    const Sampling sm{temperature, seed, pos, pos_dev, nullptr, top_p};
-    const bool topp = temperature > 0.0f && top_p < 1.0f;
+        SRM_TRY((block<T>(m, l, w, nb, st, mix, true, true, fuse ? slab(l) : nullptr, where, slab(l))));
+    if (a.hidden)
+        HIP_TRY(hipMemcpyAsync(a.hidden + (size_t)b0 * d, w.x, (size_t)nb * d * 4, hipMemcpyDeviceToDevice, st));
+    const Sampling sm{a.temperature, a.seed, a.pos, a.pos_dev, pos_rows, a.top_p, (uint32_t)b0};
+    const bool topp = a.temperature > 0.0f && a.top_p < 1.0f;
     FinalizeRagged rg{};
+    if (a.pos_rows) {
+        rg.pos_rows = a.pos_rows;             // indexed with row0 + row
+        rg.advance = a.advance && !topp;      // with a nucleus pass the positions move after it
+        rg.n_ctx = m->cfg.n_ctx;
+    }
     if (topp) rg.zero_counter = w.slow;
-    SRM_TRY((head_argmax<T>(m, w, w.a, B, logits, tok_out, 0, 1, st, ts, sm, rg)));
-    if (topp) SRM_TRY(nucleus(logits, B, m->V, sm, tok_out, ts.store, ts.step_dev, ts.stride, nullptr, w.slow, st));
+    float *lg = a.logits ? a.logits + (size_t)b0 * m->V : nullptr;
+    SRM_TRY((head_argmax<T>(m, w, w.a, nb, lg, a.tok_out, b0, 1, st, a.ts, sm, rg)));
+    if (topp)
+        SRM_TRY(nucleus(lg, nb, m->V, sm, a.tok_out + b0, a.ts.store ? a.ts.store + b0 : nullptr, a.ts.step_dev,
+                        a.ts.stride, (pos_rows && a.advance) ? pos_rows : nullptr, w.slow, st));
+    return SRM_OK;
+}
+
+// Rows per pass of a decode call: the whole batch if the workspace holds it, else as many
+// rows as it holds (the samples are independent, so a step can be taken in slices; this lets
+// a caller keep far more sequences resident than one workspace covers).  0: too small.
+// srm_workspace_bytes(rows) = the row arrays + 256 bytes that srm_generate uses for its step
+// counters at the very end of the caller's buffer, so the row arrays get workspace_bytes - 256.
+static int64_t decode_rows_per_pass(const srm_model *m, int64_t B, size_t workspace_bytes)
+{
+    if (srm_workspace_bytes(m, B) <= workspace_bytes) return B;
+    int64_t lo = 0, hi = B;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) / 2;
+        if (srm_workspace_bytes(m, mid) <= workspace_bytes) lo = mid; else hi = mid - 1;
+    }
+    if (lo >= 256) lo = lo / 256 * 256;       // whole GEMM tiles per pass
+    return lo < std::min<int64_t>(B, 256) ? 0 : lo;
+}
+
+static int decode_batch(srm_model *m, const DecodeArgs &a, void *ws, size_t workspace_bytes, hipStream_t st)
+{
+    const int64_t rpp = decode_rows_per_pass(m, a.B, workspace_bytes);
+    if (rpp <= 0) return fail(SRM_ENOMEM, "workspace %zu bytes holds fewer than %lld rows", workspace_bytes,
+                              (long long)std::min<int64_t>(a.B, 256));
+    for (int64_t b0 = 0; b0 < a.B; b0 += rpp) {
+        const int64_t nb = std::min<int64_t>(rpp, a.B - b0);
+        SRM_TRY(m->wsize == 2 ? decode_rows<bf16>(m, a, b0, nb, ws, st) : decode_rows<float>(m, a, b0, nb, ws, st));
+    }
     return SRM_OK;
 }
 
@@ -640,14 +712,10 @@ static int decode_step_common(const char *who, srm_model *m, int64_t B, int32_t 
     if (!(top_p > 0.0f)) return fail(SRM_EINVAL, "%s: top_p must be > 0", who);
     if (temperature > 0.0f && top_p < 1.0f && !d_logits)
         return fail(SRM_EINVAL, "%s: top_p < 1 needs a logits buffer", who);
-    if (workspace_bytes < srm_workspace_bytes(m, B))
-        return fail(SRM_ENOMEM, "%s: workspace %zu < %zu bytes", who, workspace_bytes, srm_workspace_bytes(m, B));
     SRM_TRY(check_device(m));
-    hipStream_t st = as_stream(hip_stream);
-    return m->wsize == 2 ? decode_impl<bf16>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden, d_workspace,
-                                             st, nullptr, TokenStore(), temperature, seed, top_p)
-                         : decode_impl<float>(m, B, pos, d_tok_in, d_state, d_tok_out, d_logits, d_hidden,
-                                              d_workspace, st, nullptr, TokenStore(), temperature, seed, top_p);
+    const DecodeArgs a{B, pos, nullptr, nullptr, 0, d_tok_in, d_state, d_tok_out, d_logits, d_hidden, TokenStore(),
+                       temperature, seed, top_p};
+    return decode_batch(m, a, d_workspace, workspace_bytes, as_stream(hip_stream));
 }
 
 extern "C" int srm_decode_step(srm_model *m, int64_t B, int32_t pos, const int32_t *d_tok_in, void *d_state,
@@ -729,25 +797,19 @@ extern "C" int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, i
     if (!(top_p > 0.0f)) return fail(SRM_EINVAL, "%s: top_p must be > 0", who);
     if (temperature > 0.0f && top_p < 1.0f && !d_logits)
         return fail(SRM_EINVAL, "%s: top_p < 1 needs a logits buffer", who);
-    if (workspace_bytes < srm_workspace_bytes(m, B))
-        return fail(SRM_ENOMEM, "%s: workspace %zu < %zu bytes", who, workspace_bytes, srm_workspace_bytes(m, B));
     SRM_TRY(check_device(m));
-    hipStream_t st = as_stream(hip_stream);
-    return m->wsize == 2 ? decode_ragged_impl<bf16>(m, B, d_pos, advance != 0, d_tok_in, d_state, d_tok_out, d_logits,
-                                                    d_workspace, st, temperature, seed, top_p)
-                         : decode_ragged_impl<float>(m, B, d_pos, advance != 0, d_tok_in, d_state, d_tok_out,
-                                                     d_logits, d_workspace, st, temperature, seed, top_p);
+    const DecodeArgs a{B, 0, nullptr, d_pos, advance != 0, d_tok_in, d_state, d_tok_out, d_logits, nullptr, TokenStore(),
+                       temperature, seed, top_p};
+    return decode_batch(m, a, d_workspace, workspace_bytes, as_stream(hip_stream));
 }
 
 // ------------------------------------------------------------------ generate (G steps in one call)
-static int generate_step(srm_model *m, int64_t B, int32_t *tok, void *state, void *ws, const int *ctr,
+static int generate_step(srm_model *m, int64_t B, int32_t *tok, void *state, void *ws, size_t ws_bytes, int *ctr,
                          TokenStore ts, hipStream_t st, float temperature, uint32_t seed, float top_p, float *logits)
 {
-    SRM_TRY(m->wsize == 2 ? decode_impl<bf16>(m, B, 0, tok, state, tok, logits, nullptr, ws, st, ctr, ts, temperature,
-                                              seed, top_p)
-                          : decode_impl<float>(m, B, 0, tok, state, tok, logits, nullptr, ws, st, ctr, ts,
-                                               temperature, seed, top_p));
-    hipLaunchKernelGGL(counters_advance_kernel, dim3(1), dim3(1), 0, st, const_cast<int *>(ctr));
+    const DecodeArgs a{B, 0, ctr, nullptr, 0, tok, state, tok, logits, nullptr, ts, temperature, seed, top_p};
+    SRM_TRY(decode_batch(m, a, ws, ws_bytes, st));
+    hipLaunchKernelGGL(counters_advance_kernel, dim3(1), dim3(1), 0, st, ctr);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
@@ -767,31 +829,37 @@ static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int
     if (pos0 < 0 || (int64_t)pos0 + G > m->cfg.n_ctx)
         return fail(SRM_EINVAL, "srm_generate: positions %d..%lld outside [0, %d)", pos0, (long long)pos0 + G - 1,
                     m->cfg.n_ctx);
-    if (workspace_bytes < srm_workspace_bytes(m, B))
-        return fail(SRM_ENOMEM, "srm_generate: workspace %zu < %zu bytes", workspace_bytes, srm_workspace_bytes(m, B));
+    // the step counters live in the last 256 bytes of the workspace, whatever rows the rest is cut into
+    if (workspace_bytes < 512) return fail(SRM_ENOMEM, "srm_generate: workspace too small");
+    const size_t ws_bytes = workspace_bytes / 256 * 256;          // counters in its last 256 bytes
+    if (decode_rows_per_pass(m, B, ws_bytes) <= 0)
+        return fail(SRM_ENOMEM, "srm_generate: workspace %zu bytes holds fewer than %lld rows", workspace_bytes,
+                    (long long)std::min<int64_t>(B, 256));
     SRM_TRY(check_device(m));
     hipStream_t st = as_stream(hip_stream);
-    const Workspace w = carve(m, d_workspace, B);
-    const TokenStore ts{d_tokens_out, w.ctr + 1, B};
-    hipLaunchKernelGGL(counters_set_kernel, dim3(1), dim3(1), 0, st, w.ctr, pos0, 0);
+    int *ctr = reinterpret_cast<int *>(static_cast<unsigned char *>(d_workspace) + ws_bytes - 256);
+    const TokenStore ts{d_tokens_out, ctr + 1, B};
+    hipLaunchKernelGGL(counters_set_kernel, dim3(1), dim3(1), 0, st, ctr, pos0, 0);
     HIP_TRY(hipGetLastError());
     // first step eagerly (it also performs every one-time kernel attribute set-up)
-    SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed, top_p, d_logits));
+    SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p, d_logits));
     if (G == 1) return SRM_OK;
     // The legacy default stream cannot be captured: loop eagerly there.
     if (st == nullptr) {
         for (int g = 1; g < G; ++g)
-            SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed, top_p, d_logits));
+            SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p,
+                                  d_logits));
         return SRM_OK;
     }
     const bool hit = m->gexec && m->gkey.B == B && m->gkey.tok == d_tok && m->gkey.state == d_state &&
                      m->gkey.store == d_tokens_out && m->gkey.ws == d_workspace && m->gkey.temp == temperature &&
-                     m->gkey.seed == seed && m->gkey.top_p == top_p && m->gkey.logits == d_logits;
+                     m->gkey.seed == seed && m->gkey.top_p == top_p && m->gkey.logits == d_logits &&
+                     m->gkey.ws_bytes == workspace_bytes;
     if (!hit) {
         if (m->gexec) { (void)hipGraphExecDestroy(m->gexec); m->gexec = nullptr; }
         hipGraph_t graph = nullptr;
         HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-        const int rc = generate_step(m, B, d_tok, d_state, d_workspace, w.ctr, ts, st, temperature, seed, top_p,
+        const int rc = generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p,
                                      d_logits);
         const hipError_t e = hipStreamEndCapture(st, &graph);
         if (rc != SRM_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
@@ -799,7 +867,7 @@ static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int
         const hipError_t e2 = hipGraphInstantiate(&m->gexec, graph, nullptr, nullptr, 0);
         (void)hipGraphDestroy(graph);
         if (e2 != hipSuccess) { m->gexec = nullptr; return fail(SRM_EHIP, "srm_generate: hipGraphInstantiate: %s", hipGetErrorString(e2)); }
-        m->gkey = {B, d_tok, d_state, d_tokens_out, d_workspace, temperature, seed, top_p, d_logits};
+        m->gkey = {B, d_tok, d_state, d_tokens_out, d_workspace, temperature, seed, top_p, d_logits, workspace_bytes};
         // the captured step was recorded, not run: replay it G - 1 times below
     }
     for (int g = 1; g < G; ++g) HIP_TRY(hipGraphLaunch(m->gexec, st));
@@ -1105,7 +1173,7 @@ extern "C" int srm_sample_logits(const float *d_logits, int64_t rows, int32_t vo
     if (!(top_p > 0.0f)) return fail(SRM_EINVAL, "srm_sample_logits: top_p must be > 0");
     hipLaunchKernelGGL((nucleus_kernel<256, true, false>), dim3((unsigned)rows), dim3(256), 0, as_stream(hip_stream),
                        d_logits, (int64_t)vocab, vocab, temperature, top_p, seed, pos, nullptr, nullptr, d_tok_out,
-                       nullptr, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
+                       nullptr, nullptr, (int64_t)0, nullptr, nullptr, nullptr, 0u);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }

@@ -395,3 +395,64 @@ def test_small_batch_bf16_decode_with_split_k_down_projection(srm, orc_mod, B):
         assert rel_err_rows(lg[rows].cpu().numpy(), ref["logits"][:, t]) <= 2e-2
         assert rel_err_rows(hd[rows].cpu().numpy(), ref["hidden"][:, t]) <= 2e-2
     assert bool(torch.isfinite(st).all())
+
+
+def test_decode_in_slices_when_the_workspace_is_smaller_than_the_batch(srm):
+    """A workspace for 256 rows under a batch of 700: the step is taken in three slices.  Tokens,
+    logits and states equal the one-pass step bit for bit (fp32), for greedy, sampled, nucleus,
+    ragged and multi-step calls - in particular the random draws stay keyed on the sample index."""
+    cfg = srm_synth.tiny_config(vocab=300, d_model=32, n_layers=2, n_heads=4, n_ctx=16, seed=81)
+    w = srm_synth.make_weights(cfg, stress=True)
+    w["head"] = w["head"] * 20.0
+    model = srm.Model(cfg, w)
+    B = 700
+    rng = np.random.default_rng(4)
+    tok0 = to_dev(rng.integers(0, cfg.vocab, B).astype(np.int32))
+    st0 = torch.randn(cfg.n_layers * B * cfg.d_model, device="cuda") * 0.3
+    big = model.new_workspace(B)
+    small = torch.empty(model.workspace_bytes(256) + 100, dtype=torch.uint8, device="cuda")
+    print("sliced decode B=700 rows-per-pass=256", flush=True)
+
+    def run(ws, **kw):
+        st, tk = st0.clone(), tok0.clone()
+        lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+        hd = torch.empty((B, cfg.d_model), dtype=torch.float32, device="cuda")
+        for g in range(3):
+            model.decode_step(B, 2 + g, tk, st, tk, logits=lg, hidden=hd, workspace=ws, **kw)
+        torch.cuda.synchronize()
+        return st, tk, lg, hd
+
+    for kw in ({}, {"temperature": 0.8, "seed": 5}, {"temperature": 0.8, "seed": 5, "top_p": 0.8}):
+        a, b = run(big, **kw), run(small, **kw)
+        for x, y in zip(a, b):
+            assert torch.equal(x, y), f"sliced step differs ({kw})"
+    # ragged positions, with idle slots in every slice
+    pos0 = torch.from_numpy(rng.integers(0, 10, B).astype(np.int32)).cuda()
+    pos0[::37] = -1
+    outs = []
+    for ws in (big, small):
+        st, tk, pos = st0.clone(), tok0.clone(), pos0.clone()
+        lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+        for g in range(3):
+            model.decode_step_ragged(B, pos, tk, st, tk, advance=True, temperature=0.8, seed=6, top_p=0.8, logits=lg,
+                                     workspace=ws)
+            tk[::37] = 0
+        torch.cuda.synchronize()
+        outs.append((st, tk, pos))
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)
+    assert (outs[0][2][::37] == -1).all()
+    # multi-step call with graph replay
+    res = []
+    side = torch.cuda.Stream()
+    for ws in (big, small):
+        st, tk = st0.clone(), tok0.clone()
+        out = torch.empty((5, B), dtype=torch.int32, device="cuda")
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            model.generate(B, 3, 5, tk, st, out, workspace=ws, temperature=0.8, seed=9)
+        side.synchronize()
+        res.append((st, out))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+    with pytest.raises(srm.SrmError):                           # fewer than 256 rows
+        model.decode_step(B, 0, tok0, st0.clone(), tok0.clone(), workspace=small[:model.workspace_bytes(100)])
