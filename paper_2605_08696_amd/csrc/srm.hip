@@ -455,9 +455,20 @@ static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, c
                      const float *part = nullptr, int nsplit = 0, const void *add_act = nullptr)
 {
     const int d = m->d;
+    T *o = static_cast<T *>(out);
+    if (!GATHER && !seq_end && !part && !add_act && in_stride == d && rows >= 4096 && d <= 1024 && d % 256 == 0) {
+        // plain, many rows: several rows per wavefront
+        constexpr int RPW = 2;
+        const unsigned nb2 = (unsigned)cdiv(rows, 4 * RPW);
+        if (d == 256) hipLaunchKernelGGL((ln_rows_kernel<T, 1, RPW>), dim3(nb2), dim3(256), 0, st, x_in, g, b, o, rows, d, m->cfg.ln_eps);
+        else if (d == 512) hipLaunchKernelGGL((ln_rows_kernel<T, 2, RPW>), dim3(nb2), dim3(256), 0, st, x_in, g, b, o, rows, d, m->cfg.ln_eps);
+        else if (d == 768) hipLaunchKernelGGL((ln_rows_kernel<T, 3, RPW>), dim3(nb2), dim3(256), 0, st, x_in, g, b, o, rows, d, m->cfg.ln_eps);
+        else hipLaunchKernelGGL((ln_rows_kernel<T, 4, RPW>), dim3(nb2), dim3(256), 0, st, x_in, g, b, o, rows, d, m->cfg.ln_eps);
+        HIP_TRY(hipGetLastError());
+        return SRM_OK;
+    }
     const unsigned nb = (unsigned)cdiv(rows, 4);
     const T *emb = static_cast<const T *>(m->embed);
-    T *o = static_cast<T *>(out);
 #define LN_CASE(VPL)                                                                                     \
     hipLaunchKernelGGL((ln_kernel<T, T, VPL, GATHER>), dim3(nb), dim3(256), 0, st, x_in, in_stride, tok, \
                        emb, m->V, x_out, g, b, o, rows, d, m->cfg.ln_eps, seq_end, base, src_rows, part, nsplit,       \
