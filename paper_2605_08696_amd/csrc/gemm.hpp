@@ -577,25 +577,32 @@ gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
 // quarter of K.  The MR activation rows sit in LDS (every lane reads the same
 // address: a broadcast), each lane streams its own W row with 16-byte loads, and
 // the four K-quarters are added through LDS in a fixed order.  One argmax partial
-// per block, the layout gemm_f32_kernel uses.  Needs K % 16 == 0.
-// Dynamic LDS: (MR * K + 4 * MR * 64) floats.
+// per block, the layout gemm_f32_kernel uses.  Needs (K / gridDim.y) % 16 == 0.
+// Dynamic LDS: (MR * K / gridDim.y + 4 * MR * 64) floats.
 template <int EPI, int MR>
 __global__ void __launch_bounds__(256)
 gemv_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M, int N, int K, GemmEpi ep)
 {
     extern __shared__ __align__(16) float gemv_sm[];
-    float *xs = gemv_sm;                   // [MR][K]
-    float *part = gemv_sm + MR * K;        // [4][MR][64]
+    // Split K (gridDim.y > 1, EPI_F32 only), as in gemm_bf16_kernel: block row y contracts
+    // k in [y * Kp, (y + 1) * Kp) into its own output slab; slab 0 carries the bias.
+    const int Kp = K / (int)gridDim.y, kb = blockIdx.y * Kp;
+    if (gridDim.y > 1) {
+        ep.out = reinterpret_cast<float *>(ep.out) + (int64_t)blockIdx.y * M * ep.ldo;
+        if (blockIdx.y) ep.bias = nullptr;
+    }
+    float *xs = gemv_sm;                   // [MR][Kp]
+    float *part = gemv_sm + MR * Kp;       // [4][MR][64]
     const int tid = threadIdx.x, c = tid & 63, q = tid >> 6;
     const int n = blockIdx.x * 64 + c;
-    const int Ks = K >> 2;
-    const float *wrow = W + (size_t)min(n, N - 1) * K + q * Ks;
+    const int Ks = Kp >> 2;
+    const float *wrow = W + (size_t)min(n, N - 1) * K + kb + q * Ks;
     for (int mg = 0; mg < M; mg += MR) {
         __syncthreads();
-        for (int i = tid; i < MR * K / 4; i += 256) {
-            const int m = (i * 4) / K, k = (i * 4) - m * K;
-            const float4 v = mg + m < M ? load4(A + (size_t)(mg + m) * K + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-            store4(xs + m * K + k, v);
+        for (int i = tid; i < MR * Kp / 4; i += 256) {
+            const int m = (i * 4) / Kp, k = (i * 4) - m * Kp;
+            const float4 v = mg + m < M ? load4(A + (size_t)(mg + m) * K + kb + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            store4(xs + m * Kp + k, v);
         }
         __syncthreads();
         float acc[MR];
@@ -605,7 +612,7 @@ gemv_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
             const float4 w4 = load4(wrow + k);
 #pragma unroll
             for (int m = 0; m < MR; ++m) {
-                const float4 x4 = load4(xs + m * K + q * Ks + k);
+                const float4 x4 = load4(xs + m * Kp + q * Ks + k);
                 acc[m] = fmaf(w4.x, x4.x, acc[m]);
                 acc[m] = fmaf(w4.y, x4.y, acc[m]);
                 acc[m] = fmaf(w4.z, x4.z, acc[m]);

@@ -255,6 +255,10 @@ struct Workspace {
 // residual stream (in slab order: deterministic).
 constexpr int kSplitK = 4;
 constexpr int64_t kSplitMaxRows = 2048;
+// fp32 models with at most kGemvRows rows run their projections as GEMVs, whose grid is only
+// N / 64 blocks: the two residual projections are cut into up to kGemvSplitMax K slices the same way.
+constexpr int kGemvSplitMax = 8;
+constexpr int64_t kGemvRows = 32;
 
 static Workspace carve(const srm_model *m, void *base, int64_t rows)
 {
@@ -276,7 +280,11 @@ static Workspace carve(const srm_model *m, void *base, int64_t rows)
     w.pv = reinterpret_cast<float *>(take(r * nparts * 4));
     w.pi = reinterpret_cast<int32_t *>(take(r * nparts * 4));
     w.slow = reinterpret_cast<int *>(take(256 + r * 4));
-    w.part = rows <= kSplitMaxRows ? reinterpret_cast<float *>(take((size_t)kSplitK * r * d * 4)) : nullptr;
+    // sized so that the workspace grows monotonically with the row count
+    const size_t part_rows = std::max<size_t>((size_t)kSplitK * std::min<int64_t>(rows, kSplitMaxRows),
+                                              (size_t)kGemvSplitMax * std::min<int64_t>(rows, kGemvRows));
+    float *part = reinterpret_cast<float *>(take(part_rows * d * 4));
+    w.part = rows <= kSplitMaxRows ? part : nullptr;
     w.ctr = reinterpret_cast<int *>(take(256));
     w.bytes = off;
     return w;
@@ -355,17 +363,19 @@ static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, Ge
 
 template <int EPI>
 static int launch_f32(const float *A, const float *W, int64_t M, int N, int K, GemmEpi ep, hipStream_t st,
-                      int *nparts_out)
+                      int *nparts_out, int ksplit = 1)
 {
     if (M <= 0 || M >= (1 << 30) || N <= 0 || K <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
     ep.nparts = (int)cdiv(N, 64);
     if (nparts_out) *nparts_out = ep.nparts;
     constexpr int MR = 8;
-    const size_t gemv_lds = ((size_t)MR * K + 4 * MR * 64) * sizeof(float);
+    const size_t gemv_lds = ((size_t)MR * (K / ksplit) + 4 * MR * 64) * sizeof(float);
+    if (ksplit > 1 && !(EPI == EPI_F32 && M <= 32 && K % (16 * ksplit) == 0 && gemv_lds <= 64 * 1024))
+        return fail(SRM_EINVAL, "fp32 GEMM: bad split of K = %d", K);
     if (M <= 32 && K % 16 == 0 && gemv_lds <= 64 * 1024) {
         // few rows: stream W once per group of MR rows
-        hipLaunchKernelGGL((gemv_f32_kernel<EPI, MR>), dim3((unsigned)cdiv(N, 64)), dim3(256), gemv_lds, st, A, W,
-                           (int)M, N, K, ep);
+        hipLaunchKernelGGL((gemv_f32_kernel<EPI, MR>), dim3((unsigned)cdiv(N, 64), (unsigned)ksplit), dim3(256),
+                           gemv_lds, st, A, W, (int)M, N, K, ep);
     } else {
         const int64_t nb = cdiv(M, 64) * cdiv(N, 64);
         hipLaunchKernelGGL(gemm_f32_kernel<EPI>, dim3((unsigned)nb), dim3(256), 0, st, A, W, (int)M, N, K, ep);
@@ -429,7 +439,7 @@ static int linear(const void *A, const void *W, const float *bias, int64_t M, in
                                       st, min_bn, nparts_out, ksplit);
     else
         return launch_f32<EPI>(static_cast<const float *>(A), static_cast<const float *>(W), M, N, K, ep, st,
-                               nparts_out);
+                               nparts_out, ksplit);
 }
 
 struct TokenStore {        // optional second destination of the greedy tokens (srm_generate)
@@ -579,21 +589,41 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
         SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, d, d, w.u, st)));
         SRM_TRY(mix(l));
     }
+    // fp32, few rows: K slices of the residual GEMVs, chosen so that a slice keeps at least 64 k
+    auto gemv_split = [&](int K) {
+        if (!(allow_split && sizeof(T) == 4 && rows <= kGemvRows && w.part)) return 1;
+        int sp = kGemvSplitMax;
+        while (sp > 1 && (K % (16 * sp) || K / sp < 64)) sp >>= 1;
+        return sp;
+    };
     if (!m->noproj) {
-        SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.x, st)));
-        SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
+        const int sp = gemv_split(d);
+        if (sp > 1) {
+            SRM_TRY((linear<EPI_F32, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.part, st, nullptr, nullptr, 64, nullptr,
+                                        Sampling(), sp)));
+            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, y.ln2_g, y.ln2_b, w.a, rows, st, nullptr, 0, 0, w.part,
+                                         sp)));
+        } else {
+            SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.x, st)));
+            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
+        }
     }
     SRM_TRY((linear<EPI_GELU, T>(w.a, y.w_up, y.b_up, rows, ff, d, w.g, st)));
+    const int spd = (norm_next && !(m->noproj && np_state)) ? gemv_split(ff) : 1;
     if (split)
         SRM_TRY((linear<EPI_F32, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.part, st, nullptr, nullptr, 64, nullptr,
                                     Sampling(), kSplitK)));
+    else if (spd > 1)
+        SRM_TRY((linear<EPI_F32, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.part, st, nullptr, nullptr, 64, nullptr,
+                                    Sampling(), spd)));
     else
         SRM_TRY((linear<EPI_RESID, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.x, st)));
     if (norm_next && !(m->noproj && np_state && l + 1 < m->L)) {   // the fused kernel does its own LayerNorm1
         const float *g = l + 1 < m->L ? m->layers[l + 1].ln1_g : m->lnf_g;
         const float *b = l + 1 < m->L ? m->layers[l + 1].ln1_b : m->lnf_b;
-        if (split)      // x += slabs, then normalise
-            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, g, b, w.a, rows, st, nullptr, 0, 0, w.part, kSplitK)));
+        if (split || spd > 1)      // x += slabs, then normalise
+            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, g, b, w.a, rows, st, nullptr, 0, 0, w.part,
+                                         split ? kSplitK : spd)));
         else
             SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, g, b, w.a, rows, st)));
     }

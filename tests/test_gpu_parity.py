@@ -456,3 +456,13 @@ def test_decode_in_slices_when_the_workspace_is_smaller_than_the_batch(srm):
     assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
     with pytest.raises(srm.SrmError):                           # fewer than 256 rows
         model.decode_step(B, 0, tok0, st0.clone(), tok0.clone(), workspace=small[:model.workspace_bytes(100)])
+
+
+@pytest.mark.parametrize("dtype_name", ["fp32", "bf16"])
+def test_workspace_bytes_grows_monotonically(srm, dtype_name):
+    """The calls find the rows a workspace holds by bisection over srm_workspace_bytes."""
+    cfg = srm_synth.tiny_config(vocab=96, d_model=64, n_layers=1, n_heads=4, n_ctx=8, weight_dtype=dtype_name, seed=3)
+    model = srm.Model(cfg, srm_synth.make_weights(cfg))
+    sizes = [model.workspace_bytes(r) for r in range(1, 4200)]
+    assert all(b >= a for a, b in zip(sizes, sizes[1:]))
+    assert model.workspace_bytes(1 << 20) > sizes[-1]
