@@ -241,6 +241,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
     }
     const bool want_store = EPI != EPI_ARGMAX || ep.out != nullptr;
     const bool n_edge = wcol0 + WTN > N;              // wave-uniform
+    const bool interior = vec_ok && m0 + BM <= M && n0 + BN <= N;      // block-uniform
 
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -299,6 +300,35 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                 for (int g = 0; g < 4; ++g)
                     *reinterpret_cast<float4 *>(stage + lr * STG + j * 32 + 8 * g + 4 * lk) =
                         make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+            if (interior && (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_RESID || EPI == EPI_F32)) {
+                // tile inside the matrix: no edge tests, all staged reads (and, for the residual
+                // add, all loads of the old values) issued before the first use, so their
+                // latencies overlap instead of adding up once per 128-byte row segment
+                constexpr int NIT = 32 / RPI;
+                const int64_t row0 = m0 + wm * WTM + i * 32 + s_row;
+                float4 v[NIT];
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+                    v[it] = *reinterpret_cast<const float4 *>(stage + (it * RPI + s_row) * STG + s_col);
+                if constexpr (EPI == EPI_RESID) {
+                    float *p = reinterpret_cast<float *>(ep.out) + row0 * ep.ldo + gcol;
+                    float4 o[NIT];
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) o[it] = load4(p + (int64_t)it * RPI * ep.ldo);
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it)
+                        store4(p + (int64_t)it * RPI * ep.ldo,
+                               make_float4(o[it].x + (v[it].x + bias4.x), o[it].y + (v[it].y + bias4.y),
+                                           o[it].z + (v[it].z + bias4.z), o[it].w + (v[it].w + bias4.w)));
+                } else {
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        v[it].x += bias4.x; v[it].y += bias4.y; v[it].z += bias4.z; v[it].w += bias4.w;
+                        epi_store4<EPI, TAct>(ep, row0 + it * RPI, gcol, v[it]);
+                    }
+                }
+                continue;
+            }
 #pragma unroll
             for (int it = 0; it < 32 / RPI; ++it) {
                 const int lrow = it * RPI + s_row;
