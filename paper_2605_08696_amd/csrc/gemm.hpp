@@ -300,7 +300,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                 for (int g = 0; g < 4; ++g)
                     *reinterpret_cast<float4 *>(stage + lr * STG + j * 32 + 8 * g + 4 * lk) =
                         make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-            if (interior && (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_RESID || EPI == EPI_F32)) {
+            if (interior && EPI != EPI_MIX) {
                 // tile inside the matrix: no edge tests, all staged reads (and, for the residual
                 // add, all loads of the old values) issued before the first use, so their
                 // latencies overlap instead of adding up once per 128-byte row segment
