@@ -162,3 +162,15 @@ def test_error_codes_on_the_gpu(srm):
         model.prefill(torch.zeros((2, 17), dtype=torch.int32, device="cuda"), 1, model.new_state(2),
                       torch.zeros(2, dtype=torch.int32, device="cuda"), workspace=model.new_workspace(64))
     assert model.state_bytes(7) == cfg.n_layers * 7 * cfg.d_model * 4
+
+
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
+def test_linear_bf16_interior_tiles(srm, tile, epi):
+    """Shapes that are whole multiples of every tile: the epilogues take their no-edge paths."""
+    _linear_case(srm, srm.SRM_BF16, 512, 768, 128, epi, tile, seed=300 + 10 * tile + epi)
+
+
+def test_linear_bf16_interior_tiles_n_multiple_of_4_only(srm):
+    _linear_case(srm, srm.SRM_BF16, 256, 260, 64, 0, 2, seed=41)
+    _linear_case(srm, srm.SRM_BF16, 256, 260, 64, 1, 2, seed=42)
