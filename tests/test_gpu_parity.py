@@ -466,3 +466,46 @@ def test_workspace_bytes_grows_monotonically(srm, dtype_name):
     sizes = [model.workspace_bytes(r) for r in range(1, 4200)]
     assert all(b >= a for a, b in zip(sizes, sizes[1:]))
     assert model.workspace_bytes(1 << 20) > sizes[-1]
+
+
+@pytest.mark.parametrize("dtype_name,d,H,V,e", [("fp32", 4096, 64, 1001, 1), ("bf16", 4096, 64, 1001, 1),
+                                                ("fp32", 1536, 2, 777, 2), ("bf16", 2048, 8, 130, 3),
+                                                ("fp32", 8, 2, 5, 4)])
+def test_extreme_shapes_match_oracle(srm, orc_mod, dtype_name, d, H, V, e):
+    """The largest supported width (4096) and head count (64), odd vocabularies, small and odd
+    MLP expansions, the smallest model: prefill, decode, the parallel form against the oracle."""
+    if dtype_name == "bf16" and d % 64:
+        pytest.skip("bf16 needs d_model % 64 == 0")
+    cfg = srm_synth.tiny_config(vocab=V, d_model=d, n_layers=2, n_heads=H, n_ctx=10, weight_dtype=dtype_name,
+                                seed=d + H, mlp_expansion=e)
+    w = srm_synth.make_weights(cfg, stress=True)
+    B, T = 3, 7
+    toks = srm_synth.make_prompts(cfg, batch=B, length=T)
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks)
+    tol = 2e-2 if dtype_name == "bf16" else 1e-4
+    model = srm.Model(cfg, w)
+    ws = model.new_workspace(B * T)
+    print(f"extreme shape {dtype_name} d={d} H={H} V={V} e={e}", flush=True)
+    st, out = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    hd = torch.empty((B, d), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    for t in range(T):
+        model.decode_step(B, t, tc[t], st, out, logits=lg, hidden=hd, workspace=ws)
+        assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, t]) <= tol
+        assert rel_err_rows(hd.cpu().numpy(), ref["hidden"][:, t]) <= tol
+    st2, tk2 = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    model.prefill(to_dev(toks), 1, st2, tk2, logits=lg, workspace=ws)
+    assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, T - 1]) <= tol
+    assert (st - st2).abs().max() <= (2e-2 if dtype_name == "bf16" else 1e-5) * st.abs().max()
+    hid = torch.empty((B, T, d), dtype=torch.float32, device="cuda")
+    model.parallel_forward(to_dev(toks), hid, workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err_rows(hid.cpu().numpy().reshape(B * T, d), ref["hidden"].reshape(B * T, d)) <= tol
+    # sampled token from the sampler equals the oracle's rule on the same logits (odd vocabulary)
+    tkn = torch.empty(B, dtype=torch.int32, device="cuda")
+    srm.sample_logits(lg, 0.9, 0.8, 4, 2, tkn)
+    torch.cuda.synchronize()
+    for b in range(B):
+        tok, mg, mm = orc_mod.pick_topp(lg[b].cpu().numpy(), 0.9, 0.8, 4, 2, b, want_margins=True)
+        assert int(tkn[b]) == tok or mm < 1e-5 or mg < 1e-5
