@@ -264,6 +264,23 @@ int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, int32_t adva
                            void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * G ragged decode steps in one call: a serving loop that runs on the device.
+ * Step g feeds d_tok[B] back at each sample's own position d_pos[b], advances
+ * the positions of the active samples and stores the tokens at
+ * d_tokens_out[g][B] (-1 for idle samples).  A sample that emits eos_id
+ * (eos_id < 0: no such token) or runs out of positions goes idle - position -1
+ * respectively >= n_ctx - and stays idle, its state untouched, until the caller
+ * admits a new prompt into the slot (srm_prefill_ragged with d_slot).  As in
+ * srm_generate, one step is captured into a HIP graph and replayed; the
+ * positions are device data, so the graph needs no update between steps or
+ * calls.  Sampling as in srm_decode_step_ragged.
+ * Errors: as srm_generate and srm_decode_step_ragged; SRM_EINVAL for eos_id >= vocab.
+ */
+int srm_generate_ragged(srm_model *m, int64_t B, int32_t G, int32_t *d_pos, int32_t *d_tok, void *d_state,
+                        int32_t *d_tokens_out, int32_t eos_id, float temperature, float top_p, uint32_t seed,
+                        float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * srm_prefill for N prompts of different lengths, packed back to back in
  * d_tokens: prompt n is d_tokens[offsets[n] .. offsets[n+1]-1], positions
  * 0 .. length-1, from a zero state.  The offsets (N + 1 values, int32) are

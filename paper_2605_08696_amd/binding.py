@@ -72,6 +72,9 @@ def lib():
         L.srm_decode_step_ragged.restype = C.c_int
         L.srm_decode_step_ragged.argtypes = [vp, i64, vp, i32, vp, vp, vp, C.c_float, C.c_float, C.c_uint32, vp, vp,
                                              sz, vp]
+        L.srm_generate_ragged.restype = C.c_int
+        L.srm_generate_ragged.argtypes = [vp, i64, i32, vp, vp, vp, vp, i32, C.c_float, C.c_float, C.c_uint32, vp, vp,
+                                          sz, vp]
         L.srm_decode_step_topp.restype = C.c_int
         L.srm_decode_step_topp.argtypes = [vp, i64, i32, vp, vp, vp, C.c_float, C.c_float, C.c_uint32, vp, vp, vp, sz,
                                            vp]
@@ -268,6 +271,21 @@ class Model:
         _check(lib().srm_decode_step_ragged(self._h, B, p_pos, 1 if advance else 0, p_in, p_st, p_out,
                                             float(temperature), float(top_p), int(seed), p_lg, p_ws,
                                             workspace.numel(), _stream(stream)))
+
+    def generate_ragged(self, B, G, pos, tok, state, tokens_out, eos_id=-1, temperature=0.0, top_p=1.0, seed=0,
+                        logits=None, workspace=None, stream=None):
+        """G ragged steps on the device; a sample that emits eos_id goes idle (position -1)."""
+        torch = _torch()
+        p_pos = _dev(pos, torch.int32, B, "pos")
+        p_tk = _dev(tok, torch.int32, B, "tok")
+        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.d, "state")
+        if state.numel() != self.L * B * self.d:
+            raise ValueError("state: must be exactly [L][B][d]")
+        p_out = _dev(tokens_out, torch.int32, G * B, "tokens_out")
+        p_lg = None if logits is None else _dev(logits, torch.float32, B * self.vocab, "logits")
+        p_ws = _dev(workspace, torch.uint8, 1, "workspace")
+        _check(lib().srm_generate_ragged(self._h, B, G, p_pos, p_tk, p_st, p_out, int(eos_id), float(temperature),
+                                         float(top_p), int(seed), p_lg, p_ws, workspace.numel(), _stream(stream)))
 
     def prefill_ragged(self, tokens, offsets, state, next_tok, fanout_k=1, slot=None, pos=None, logits=None,
                        workspace=None, stream=None):

@@ -692,6 +692,7 @@ struct FinalizeRagged {
     const int32_t *offsets;   // prefill: sequence boundaries, offsets[row0 + row + 1] - offsets[row0 + row] = length
     int32_t *pos_set;         // prefill: pos_set[destination] = length of the sequence
     int32_t *zero_counter;    // set to 0 (the row list of the nucleus pass that follows)
+    int32_t eos_plus1;        // decode with advance: eos token + 1 (0: none); a row that emits it goes idle (position -1)
 };
 
 // Reduce the per-tile partials of each row to one token; writes `rep`
@@ -727,7 +728,7 @@ argmax_finalize_kernel(const float *__restrict__ part_val, const int32_t *__rest
         const int p = rg.pos_rows[row0 + row];
         const bool active = p >= 0 && p < rg.n_ctx;
         if (!active) bi = -1;
-        else if (rg.advance && lane == 0) rg.pos_rows[row0 + row] = p + 1;
+        else if (rg.advance && lane == 0) rg.pos_rows[row0 + row] = (rg.eos_plus1 && bi == rg.eos_plus1 - 1) ? -1 : p + 1;
     }
     if (rg.slot) {
         const int64_t dst = rg.slot[row0 + row];

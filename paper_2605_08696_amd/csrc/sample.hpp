@@ -125,7 +125,8 @@ __device__ __forceinline__ void row_foreach(const float *__restrict__ L, int V, 
 // else pos.  If store is not null the token also goes to
 // store[*step_dev * store_stride + row].  If pos_advance is not null the
 // position of every non-idle row is incremented at the end (pos_advance may be
-// the same array as pos_rows).
+// the same array as pos_rows), or set to -1 (idle) if the row's token is
+// eos_plus1 - 1 (eos_plus1 = 0: no such token).
 // With DEFER, a row that needs the search is appended to slow_list (its count in
 // *slow_count, which must be zero at launch) and left to nucleus_slow_kernel,
 // which also does that row's store / pos_advance.
@@ -135,7 +136,7 @@ nucleus_kernel(const float *__restrict__ logits, int64_t ld, int V, float temp, 
                const int *__restrict__ pos_dev, const int *pos_rows, int32_t *__restrict__ tok,
                int32_t *__restrict__ store, const int *__restrict__ step_dev, int64_t store_stride,
                int32_t *pos_advance, int *__restrict__ slow_count = nullptr, int *__restrict__ slow_list = nullptr,
-               uint32_t row_base = 0)
+               uint32_t row_base = 0, int eos_plus1 = 0)
 {
     constexpr int NW = NT / 64;
     __shared__ float red[NW];
@@ -213,7 +214,7 @@ nucleus_kernel(const float *__restrict__ logits, int64_t ld, int V, float temp, 
     if (tid == 0) {
         tok[row] = result;
         if (store) store[(int64_t)(*step_dev) * store_stride + row] = result;
-        if (pos_advance) pos_advance[row] = (int32_t)p + 1;
+        if (pos_advance) pos_advance[row] = (eos_plus1 && result == eos_plus1 - 1) ? -1 : (int32_t)p + 1;
     }
 }
 
@@ -228,7 +229,7 @@ nucleus_slow_kernel(const float *__restrict__ logits, int64_t ld, int V, float t
                     const int *__restrict__ pos_dev, const int *pos_rows, int32_t *__restrict__ tok,
                     int32_t *__restrict__ store, const int *__restrict__ step_dev, int64_t store_stride,
                     int32_t *pos_advance, const int *__restrict__ slow_count, const int *__restrict__ slow_list,
-                    uint32_t row_base)
+                    uint32_t row_base, int eos_plus1)
 {
     static_assert(EPT % 4 == 0, "EPT must be a multiple of 4");
     constexpr int NW = NT / 64;
@@ -307,7 +308,7 @@ nucleus_slow_kernel(const float *__restrict__ logits, int64_t ld, int V, float t
         if (tid == 0) {
             tok[row] = result;
             if (store) store[(int64_t)(*step_dev) * store_stride + row] = result;
-            if (pos_advance) pos_advance[row] = (int32_t)p + 1;
+            if (pos_advance) pos_advance[row] = (eos_plus1 && result == eos_plus1 - 1) ? -1 : (int32_t)p + 1;
         }
     }
 }

@@ -68,7 +68,7 @@ struct srm_model {
     std::vector<LayerDev> layers;
     // cached graph of one decode step for srm_generate (see there)
     hipGraphExec_t gexec;
-    struct { int64_t B; const void *tok, *state, *store, *ws; float temp; uint32_t seed; float top_p; const void *logits; size_t ws_bytes; } gkey;
+    struct { int64_t B; const void *tok, *state, *store, *ws; float temp; uint32_t seed; float top_p; const void *logits; size_t ws_bytes; const void *pos; int eos_plus1; } gkey;
 };
 
 static uint16_t host_f32_to_bf16(float f)
@@ -149,7 +149,7 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     m->wsize = bf ? 2 : 4;
     m->slab = nullptr;
     m->gexec = nullptr;
-    m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, 1.0f, nullptr, 0};
+    m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, 1.0f, nullptr, 0, nullptr, 0};
 
     struct Offs { size_t v[15]; };
     std::vector<Offs> lo(L);
@@ -392,6 +392,7 @@ struct Sampling {          // temp == 0: greedy
     const int *pos_rows = nullptr;
     float top_p = 1.0f;    // < 1 (with temp > 0): nucleus truncation, needs the logits in memory
     uint32_t row_base = 0; // sample index of the first row
+    int eos_plus1 = 0;     // ragged decode with advance: end-of-sequence token + 1 (0: none)
 };
 
 // Nucleus pass over the logits the LM head has just written; tok holds the
@@ -404,18 +405,18 @@ static int nucleus(const float *logits, int64_t rows, int V, const Sampling &sm,
         // vocabulary too large for the register-resident search: one kernel, searching from memory
         hipLaunchKernelGGL((nucleus_kernel<256, false, false>), dim3((unsigned)rows), dim3(256), 0, st, logits,
                            (int64_t)V, V, sm.temp, sm.top_p, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, tok, store,
-                           step_dev, store_stride, pos_advance, nullptr, nullptr, sm.row_base);
+                           step_dev, store_stride, pos_advance, nullptr, nullptr, sm.row_base, sm.eos_plus1);
         HIP_TRY(hipGetLastError());
         return SRM_OK;
     }
     hipLaunchKernelGGL((nucleus_kernel<256, false, true>), dim3((unsigned)rows), dim3(256), 0, st, logits, (int64_t)V,
                        V, sm.temp, sm.top_p, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, tok, store, step_dev,
-                       store_stride, pos_advance, slow, slow + 64, sm.row_base);
+                       store_stride, pos_advance, slow, slow + 64, sm.row_base, sm.eos_plus1);
     HIP_TRY(hipGetLastError());
     const unsigned nb = (unsigned)std::min<int64_t>(rows, 256);
     hipLaunchKernelGGL((nucleus_slow_kernel<NT, EPT>), dim3(nb), dim3(NT), 0, st, logits, (int64_t)V, V, sm.temp,
                        sm.top_p, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, tok, store, step_dev, store_stride,
-                       pos_advance, slow, slow + 64, sm.row_base);
+                       pos_advance, slow, slow + 64, sm.row_base, sm.eos_plus1);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
@@ -660,6 +661,7 @@ struct DecodeArgs {
     float temperature;
     uint32_t seed;
     float top_p;
+    int eos_plus1 = 0;
 };
 
 template <typename T>
@@ -695,13 +697,14 @@ static int decode_rows(srm_model *m, const DecodeArgs &a, int64_t b0, int64_t nb
         SRM_TRY((block<T>(m, l, w, nb, st, mix, true, true, fuse ? slab(l) : nullptr, where, slab(l))));
     if (a.hidden)
         HIP_TRY(hipMemcpyAsync(a.hidden + (size_t)b0 * d, w.x, (size_t)nb * d * 4, hipMemcpyDeviceToDevice, st));
-    const Sampling sm{a.temperature, a.seed, a.pos, a.pos_dev, pos_rows, a.top_p, (uint32_t)b0};
+    const Sampling sm{a.temperature, a.seed, a.pos, a.pos_dev, pos_rows, a.top_p, (uint32_t)b0, a.eos_plus1};
     const bool topp = a.temperature > 0.0f && a.top_p < 1.0f;
     FinalizeRagged rg{};
     if (a.pos_rows) {
         rg.pos_rows = a.pos_rows;             // indexed with row0 + row
         rg.advance = a.advance && !topp;      // with a nucleus pass the positions move after it
         rg.n_ctx = m->cfg.n_ctx;
+        rg.eos_plus1 = a.eos_plus1;
     }
     if (topp) rg.zero_counter = w.slow;
     float *lg = a.logits ? a.logits + (size_t)b0 * m->V : nullptr;
@@ -846,9 +849,12 @@ extern "C" int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, i
 
 // ------------------------------------------------------------------ generate (G steps in one call)
 static int generate_step(srm_model *m, int64_t B, int32_t *tok, void *state, void *ws, size_t ws_bytes, int *ctr,
-                         TokenStore ts, hipStream_t st, float temperature, uint32_t seed, float top_p, float *logits)
+                         TokenStore ts, hipStream_t st, float temperature, uint32_t seed, float top_p, float *logits,
+                         int32_t *pos_rows = nullptr, int eos_plus1 = 0)
 {
-    const DecodeArgs a{B, 0, ctr, nullptr, 0, tok, state, tok, logits, nullptr, ts, temperature, seed, top_p};
+    // uniform position: read from the device counter; ragged: one position per sample, advanced on the device
+    const DecodeArgs a{B, 0, pos_rows ? nullptr : ctr, pos_rows, pos_rows ? 1 : 0, tok, state, tok, logits, nullptr, ts,
+                       temperature, seed, top_p, eos_plus1};
     SRM_TRY(decode_batch(m, a, ws, ws_bytes, st));
     hipLaunchKernelGGL(counters_advance_kernel, dim3(1), dim3(1), 0, st, ctr);
     HIP_TRY(hipGetLastError());
@@ -857,7 +863,8 @@ static int generate_step(srm_model *m, int64_t B, int32_t *tok, void *state, voi
 
 static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, void *d_state,
                            int32_t *d_tokens_out, float temperature, uint32_t seed, float top_p, float *d_logits,
-                           void *d_workspace, size_t workspace_bytes, void *hip_stream)
+                           void *d_workspace, size_t workspace_bytes, void *hip_stream, int32_t *d_pos = nullptr,
+                           int eos_plus1 = 0)
 {
     if (!m || !d_tok || !d_state || !d_tokens_out || !d_workspace) return fail(SRM_EINVAL, "srm_generate: null argument");
     if (!(top_p > 0.0f)) return fail(SRM_EINVAL, "srm_generate: top_p must be > 0");
@@ -867,7 +874,7 @@ static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int
     if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "srm_generate: batch %lld out of range", (long long)B);
     if (G <= 0) return fail(SRM_EINVAL, "srm_generate: G must be positive");
     if (!(temperature >= 0.0f)) return fail(SRM_EINVAL, "srm_generate: temperature must be >= 0");
-    if (pos0 < 0 || (int64_t)pos0 + G > m->cfg.n_ctx)
+    if (!d_pos && (pos0 < 0 || (int64_t)pos0 + G > m->cfg.n_ctx))
         return fail(SRM_EINVAL, "srm_generate: positions %d..%lld outside [0, %d)", pos0, (long long)pos0 + G - 1,
                     m->cfg.n_ctx);
     // the step counters live in the last 256 bytes of the workspace, whatever rows the rest is cut into
@@ -883,32 +890,34 @@ static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int
     hipLaunchKernelGGL(counters_set_kernel, dim3(1), dim3(1), 0, st, ctr, pos0, 0);
     HIP_TRY(hipGetLastError());
     // first step eagerly (it also performs every one-time kernel attribute set-up)
-    SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p, d_logits));
+    SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p, d_logits,
+                          d_pos, eos_plus1));
     if (G == 1) return SRM_OK;
     // The legacy default stream cannot be captured: loop eagerly there.
     if (st == nullptr) {
         for (int g = 1; g < G; ++g)
             SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p,
-                                  d_logits));
+                                  d_logits, d_pos, eos_plus1));
         return SRM_OK;
     }
     const bool hit = m->gexec && m->gkey.B == B && m->gkey.tok == d_tok && m->gkey.state == d_state &&
                      m->gkey.store == d_tokens_out && m->gkey.ws == d_workspace && m->gkey.temp == temperature &&
                      m->gkey.seed == seed && m->gkey.top_p == top_p && m->gkey.logits == d_logits &&
-                     m->gkey.ws_bytes == workspace_bytes;
+                     m->gkey.ws_bytes == workspace_bytes && m->gkey.pos == d_pos && m->gkey.eos_plus1 == eos_plus1;
     if (!hit) {
         if (m->gexec) { (void)hipGraphExecDestroy(m->gexec); m->gexec = nullptr; }
         hipGraph_t graph = nullptr;
         HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
         const int rc = generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p,
-                                     d_logits);
+                                     d_logits, d_pos, eos_plus1);
         const hipError_t e = hipStreamEndCapture(st, &graph);
         if (rc != SRM_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
         if (e != hipSuccess) return fail(SRM_EHIP, "srm_generate: stream capture failed: %s", hipGetErrorString(e));
         const hipError_t e2 = hipGraphInstantiate(&m->gexec, graph, nullptr, nullptr, 0);
         (void)hipGraphDestroy(graph);
         if (e2 != hipSuccess) { m->gexec = nullptr; return fail(SRM_EHIP, "srm_generate: hipGraphInstantiate: %s", hipGetErrorString(e2)); }
-        m->gkey = {B, d_tok, d_state, d_tokens_out, d_workspace, temperature, seed, top_p, d_logits, workspace_bytes};
+        m->gkey = {B, d_tok, d_state, d_tokens_out, d_workspace, temperature, seed, top_p, d_logits, workspace_bytes,
+                   d_pos, eos_plus1};
         // the captured step was recorded, not run: replay it G - 1 times below
     }
     for (int g = 1; g < G; ++g) HIP_TRY(hipGraphLaunch(m->gexec, st));
@@ -929,6 +938,17 @@ extern "C" int srm_generate_topp(srm_model *m, int64_t B, int32_t pos0, int32_t 
 {
     return generate_common(m, B, pos0, G, d_tok, d_state, d_tokens_out, temperature, seed, top_p, d_logits,
                            d_workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int srm_generate_ragged(srm_model *m, int64_t B, int32_t G, int32_t *d_pos, int32_t *d_tok, void *d_state,
+                                   int32_t *d_tokens_out, int32_t eos_id, float temperature, float top_p,
+                                   uint32_t seed, float *d_logits, void *d_workspace, size_t workspace_bytes,
+                                   void *hip_stream)
+{
+    if (!d_pos) return fail(SRM_EINVAL, "srm_generate_ragged: null argument");
+    if (m && eos_id >= m->V) return fail(SRM_EINVAL, "srm_generate_ragged: eos_id %d outside the vocabulary", eos_id);
+    return generate_common(m, B, 0, G, d_tok, d_state, d_tokens_out, temperature, seed, top_p, d_logits, d_workspace,
+                           workspace_bytes, hip_stream, d_pos, eos_id >= 0 ? eos_id + 1 : 0);
 }
 
 // ------------------------------------------------------------------ prefill

@@ -344,3 +344,48 @@ def test_chunked_scan_bf16(srm, orc_mod):
     assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, 0]) <= 2e-2
     s_got = st.view(cfg.n_layers, N, cfg.d_model).permute(1, 0, 2).cpu().numpy()
     assert np.abs(s_got - ref["state"]).max() <= 2e-2 * np.abs(ref["state"]).max()
+
+
+def test_generate_ragged_stops_samples_at_eos(c1):
+    """The device-side serving loop: ragged prompts, G steps per call with graph replay, a sample
+    that emits the end token goes idle.  Two calls in a row continue each other."""
+    cfg, w, model, orc = c1
+    prompts = srm_synth.make_prompts(cfg)
+    B, G = len(LENGTHS), 20
+    ref = _oracle_streams(orc, prompts, LENGTHS, G)
+    streams = np.stack([r["tokens"][0] for r in ref])            # [B][G], index 0 = token after the prompt
+    # an end token that some stream emits after its first token, and none emits first
+    cand = [int(t) for t in streams[:, 3:9].ravel() if t not in streams[:, 0]]
+    eos = cand[0]
+    want = np.full((B, G - 1), -1, np.int64)
+    end_pos = np.zeros(B, np.int64)
+    for b in range(B):
+        hit = [j for j in range(1, G) if streams[b, j] == eos]
+        stop = hit[0] if hit else G - 1
+        want[b, :stop] = streams[b, 1:stop + 1]
+        end_pos[b] = -1 if hit else LENGTHS[b] + G - 1
+    assert (want == -1).any() and (want[:, -1] != -1).any()
+    toks, off = _pack(prompts, LENGTHS)
+    ws = model.new_workspace(int(off[-1]))
+    print(f"generate_ragged B={B} eos={eos}", flush=True)
+    for split in (None, 8):                                      # one call of 19 steps; 8 + 11 steps
+        st = model.new_state(B)
+        tk = torch.empty(B, dtype=torch.int32, device="cuda")
+        pos = torch.empty(B, dtype=torch.int32, device="cuda")
+        keep = model.prefill_ragged(to_dev(toks), off, st, tk, pos=pos, workspace=ws)
+        torch.cuda.synchronize()
+        del keep
+        out = torch.full((G - 1, B), -7, dtype=torch.int32, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            if split is None:
+                model.generate_ragged(B, G - 1, pos, tk, st, out, eos_id=eos, workspace=ws)
+            else:
+                model.generate_ragged(B, split, pos, tk, st, out[:split], eos_id=eos, workspace=ws)
+                # idle samples keep emitting -1 as their token: feed something valid
+                tk.clamp_(min=0)
+                model.generate_ragged(B, G - 1 - split, pos, tk, st, out[split:], eos_id=eos, workspace=ws)
+        side.synchronize()
+        np.testing.assert_array_equal(out.cpu().numpy().T, want)
+        np.testing.assert_array_equal(pos.cpu().numpy(), end_pos)
