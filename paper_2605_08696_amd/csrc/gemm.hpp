@@ -300,7 +300,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                 for (int g = 0; g < 4; ++g)
                     *reinterpret_cast<float4 *>(stage + lr * STG + j * 32 + 8 * g + 4 * lk) =
                         make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-            if (interior && EPI != EPI_MIX) {
+            if (interior) {
                 // tile inside the matrix: no edge tests, all staged reads (and, for the residual
                 // add, all loads of the old values) issued before the first use, so their
                 // latencies overlap instead of adding up once per 128-byte row segment
@@ -320,6 +320,53 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                         store4(p + (int64_t)it * RPI * ep.ldo,
                                make_float4(o[it].x + (v[it].x + bias4.x), o[it].y + (v[it].y + bias4.y),
                                            o[it].z + (v[it].z + bias4.z), o[it].w + (v[it].w + bias4.w)));
+                } else if constexpr (EPI == EPI_MIX) {
+                    // the state update of NIT rows: positions, coefficients and old states are all
+                    // requested before the first is used
+                    const int h = gcol / ep.dh;
+                    const bool row_repeat = h < ep.H / 2;
+                    const float l = ep.lam[h];
+                    int ps[NIT];
+                    float al[NIT], be[NIT];
+                    float4 s0[NIT];
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        const int64_t row = row0 + it * RPI;
+                        ps[it] = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row]
+                                                   : (ep.pos_dev ? (uint32_t)*ep.pos_dev : (uint32_t)ep.pos));
+                    }
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        const int64_t sj = ((row0 + it * RPI) * ep.ldo + gcol) >> 2;
+                        const bool act = ps[it] >= 0 && ps[it] < ep.n_ctx;
+                        const int pc = act ? ps[it] : 0;
+                        al[it] = ep.alpha[(size_t)h * ep.n_ctx + pc];
+                        be[it] = ep.beta[(size_t)h * ep.n_ctx + pc];
+                        s0[it] = ep.state_half ? load_state4(static_cast<const f16 *>(ep.state), sj)
+                                               : load_state4(static_cast<const float *>(ep.state), sj);
+                    }
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        const int64_t row = row0 + it * RPI;
+                        const int64_t sj = (row * ep.ldo + gcol) >> 2;
+                        TAct *o = reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + gcol;
+                        if (!(ps[it] >= 0 && ps[it] < ep.n_ctx)) { store4(o, make_float4(0.f, 0.f, 0.f, 0.f)); continue; }
+                        const float p = row_repeat ? al[it] : 1.0f, q = row_repeat ? 1.0f : al[it];
+                        float4 n;
+                        n.x = fmaf(l, s0[it].x, p * (float)(TAct)(v[it].x + bias4.x));
+                        n.y = fmaf(l, s0[it].y, p * (float)(TAct)(v[it].y + bias4.y));
+                        n.z = fmaf(l, s0[it].z, p * (float)(TAct)(v[it].z + bias4.z));
+                        n.w = fmaf(l, s0[it].w, p * (float)(TAct)(v[it].w + bias4.w));
+                        if (ep.state_half) {
+                            f16 *sp = static_cast<f16 *>(ep.state);
+                            n = make_float4(to_state(n.x, sp), to_state(n.y, sp), to_state(n.z, sp), to_state(n.w, sp));
+                            store_state4(sp, sj, n);
+                        } else {
+                            store_state4(static_cast<float *>(ep.state), sj, n);
+                        }
+                        store4(o, make_float4(fmaf(q, n.x, be[it]), fmaf(q, n.y, be[it]), fmaf(q, n.z, be[it]),
+                                              fmaf(q, n.w, be[it])));
+                    }
                 } else {
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
