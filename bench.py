@@ -117,6 +117,32 @@ def kernel_legs(torch, srm, model, cfg, B, iters):
     return legs
 
 
+def achievable_rates(torch, srm):
+    """What the chip delivers to the simplest possible kernels: a plain 1 GiB copy (read + write,
+    streaming and ordinary loads/stores; the better one counts) and a register-resident chain of
+    bf16 matrix-core products on 8 wavefronts per SIMD."""
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    rates = {}
+    for name, streaming in (("copy_streaming_gbs", True), ("copy_plain_gbs", False)):
+        t = time_launches(torch, lambda: srm.probe_copy(dst, src, streaming=streaming), 10)
+        rates[name] = 2.0 * src.numel() * 4 / t * 1e-9
+    del src, dst
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    blocks, iters = cus * 8, 20000
+    out = torch.empty(blocks * 256, device="cuda")
+    flop = [0.0]
+
+    def run():
+        flop[0] = srm.probe_mfma(out, blocks, iters)
+
+    t = time_launches(torch, run, 5, warm=2)
+    assert bool((out == 1024.0 * iters).all())
+    return {"copy_gbs": max(rates.values()), **rates, "copy_bytes": 2 << 30,
+            "mfma_bf16_tflops": flop[0] / t * 1e-12, "mfma_probe": f"{blocks} work-groups x 4 wavefronts x {iters} x 4 "
+            "independent 32x32x16 bf16 products, operands in registers"}
+
+
 def cpu_baseline(cfg, w, rows, T):
     """The fp32 oracle, as it stands, on `rows` samples x T teacher-forced positions."""
     import numpy as np
@@ -330,12 +356,15 @@ def main():
     if not args.no_kernel_legs:
         legs = kernel_legs(torch, srm, model, cfg, B, args.kernel_iters)
         out["kernels"] = legs
+        ach = achievable_rates(torch, srm)
+        out["achievable"] = ach
         if esz == 2:
             up = legs["gemm_up"]
             out["roofline"] = {"kernel": "gemm_bf16_kernel (MLP up, GELU epilogue)", "bound": "mfma",
                                "achieved": up["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                                "frac": up["tflops"] / PEAK_BF16_TFLOPS,
                                "traffic": measured_traffic("gemm_bf16_kernel<256,256,2,4,EPI=GELU>") if cfg.name == "C4" else None,
+                               "frac_of_achievable": up["tflops"] / ach["mfma_bf16_tflops"],
                                "avg_launch_ms": up["ms"], "flop_per_launch": 2.0 * B * ff * d,
                                "algorithmic_bytes_per_launch": (B * d + ff * d + B * ff) * 2.0}
         else:
@@ -347,6 +376,7 @@ def main():
         out["roofline_state_update"] = {"kernel": "state_update_kernel", "bound": "hbm", "achieved": su["gbs"],
                                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": su["gbs"] / PEAK_HBM_GBS,
                                         "traffic": measured_traffic("state_update_kernel<bf16,2>") if cfg.name == "C4" else None,
+                                        "frac_of_achievable": su["gbs"] / ach["copy_gbs"],
                                         "avg_launch_ms": su["ms"], "bytes_per_launch": su["bytes"]}
     if not args.no_cpu_baseline:
         rows = min(16, os.cpu_count() or 1)

@@ -345,6 +345,23 @@ int srm_linear(int32_t dtype, int32_t epilogue, const void *d_A, const void *d_W
                int32_t *d_argmax, void *d_scratch, void *hip_stream);
 size_t srm_linear_scratch_bytes(int64_t M, int32_t N);
 
+/*
+ * Measuring tools (not part of the model's path): the chip's achievable rates,
+ * which the benchmark reports beside the published peaks.
+ *
+ * srm_probe_copy: d_dst[0..bytes) = d_src[0..bytes) with one plain kernel (device
+ * pointers, 16-byte aligned, bytes % 16 == 0, no overlap); streaming != 0 uses
+ * non-temporal loads and stores.  HBM traffic = 2 * bytes.
+ *
+ * srm_probe_mfma: `blocks` work-groups of four wavefronts each issue `iters`
+ * rounds of four independent 32x32x16 bf16 matrix-core products on register
+ * operands (A = B = 1) and write one fp32 sum per lane to d_out[blocks * 256]
+ * (= 1024 * iters each).  *flop (host pointer, may be NULL) receives the
+ * floating-point operations of the launch.
+ */
+int srm_probe_copy(void *d_dst, const void *d_src, size_t bytes, int32_t streaming, void *hip_stream);
+int srm_probe_mfma(float *d_out, int32_t blocks, int32_t iters, double *flop, void *hip_stream);
+
 /* Message for the last failure on the calling thread ("" if none). */
 const char *srm_last_error(void);
 

@@ -93,6 +93,10 @@ def lib():
         L.srm_linear.argtypes = [i32, i32, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.srm_linear_scratch_bytes.restype = sz
         L.srm_linear_scratch_bytes.argtypes = [i64, i32]
+        L.srm_probe_copy.restype = C.c_int
+        L.srm_probe_copy.argtypes = [vp, vp, sz, i32, vp]
+        L.srm_probe_mfma.restype = C.c_int
+        L.srm_probe_mfma.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
         L.srm_last_error.restype = C.c_char_p
         L.srm_last_error.argtypes = []
         _lib = L
@@ -338,6 +342,25 @@ def sample_logits(logits, temperature, top_p, seed, pos, tok_out, stream=None):
     _check(lib().srm_sample_logits(_dev(logits, torch.float32, rows * V, "logits"), rows, V, float(temperature),
                                    float(top_p), int(seed), int(pos), _dev(tok_out, torch.int32, rows, "tok_out"),
                                    _stream(stream)))
+
+
+def probe_copy(dst, src, streaming=True, stream=None):
+    """srm_probe_copy: dst = src (same-sized contiguous torch tensors); returns the HBM bytes moved."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (src.is_cuda and dst.is_cuda):
+        raise ValueError("probe_copy: dst and src must be device tensors of one size")
+    if not (src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("probe_copy: tensors must be contiguous")
+    _check(lib().srm_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, int(bool(streaming)), _stream(stream)))
+    return 2 * nbytes
+
+
+def probe_mfma(out, blocks: int, iters: int, stream=None) -> float:
+    """srm_probe_mfma into out (fp32, blocks * 256 elements); returns the launch's flop count."""
+    flop = C.c_double(0.0)
+    _check(lib().srm_probe_mfma(_dev(out, _torch().float32, blocks * 256, "out"), int(blocks), int(iters),
+                                C.byref(flop), _stream(stream)))
+    return flop.value
 
 
 def linear_scratch_bytes(M: int, N: int) -> int:

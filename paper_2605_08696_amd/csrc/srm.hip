@@ -15,6 +15,7 @@
 #include "gemm.hpp"
 #include "mixer.hpp"
 #include "norm.hpp"
+#include "probe.hpp"
 #include "sample.hpp"
 
 // ------------------------------------------------------------------ errors
@@ -1236,6 +1237,36 @@ extern "C" int srm_sample_logits(const float *d_logits, int64_t rows, int32_t vo
                        d_logits, (int64_t)vocab, vocab, temperature, top_p, seed, pos, nullptr, nullptr, d_tok_out,
                        nullptr, nullptr, (int64_t)0, nullptr, nullptr, nullptr, 0u);
     HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
+extern "C" int srm_probe_copy(void *d_dst, const void *d_src, size_t bytes, int32_t streaming, void *hip_stream)
+{
+    if (!d_dst || !d_src) return fail(SRM_EINVAL, "srm_probe_copy: null argument");
+    if (bytes == 0 || bytes % 16 || ((uintptr_t)d_dst | (uintptr_t)d_src) % 16)
+        return fail(SRM_EINVAL, "srm_probe_copy: size and pointers must be multiples of 16 bytes");
+    constexpr int U = 4;
+    const int64_t n16 = (int64_t)(bytes / 16);
+    const int64_t blocks = cdiv(n16, 256 * U);
+    if (blocks >= (1ll << 31)) return fail(SRM_EINVAL, "srm_probe_copy: at most 32 TiB per call");
+    if (streaming)
+        hipLaunchKernelGGL((probe_copy_kernel<U, true>), dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream),
+                           (const u32x4_t *)d_src, (u32x4_t *)d_dst, n16);
+    else
+        hipLaunchKernelGGL((probe_copy_kernel<U, false>), dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream),
+                           (const u32x4_t *)d_src, (u32x4_t *)d_dst, n16);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
+extern "C" int srm_probe_mfma(float *d_out, int32_t blocks, int32_t iters, double *flop, void *hip_stream)
+{
+    if (!d_out) return fail(SRM_EINVAL, "srm_probe_mfma: null argument");
+    if (blocks <= 0 || blocks > (1 << 20) || iters <= 0 || iters > (1 << 20))
+        return fail(SRM_EINVAL, "srm_probe_mfma: blocks and iters must lie in [1, 2^20]");
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), d_out, iters, 1.0f);
+    HIP_TRY(hipGetLastError());
+    if (flop) *flop = (double)blocks * 4 /*wavefronts*/ * iters * 4 /*tiles*/ * (2.0 * 32 * 32 * 16);
     return SRM_OK;
 }
 

@@ -174,3 +174,29 @@ def test_linear_bf16_interior_tiles(srm, tile, epi):
 def test_linear_bf16_interior_tiles_n_multiple_of_4_only(srm):
     _linear_case(srm, srm.SRM_BF16, 256, 260, 64, 0, 2, seed=41)
     _linear_case(srm, srm.SRM_BF16, 256, 260, 64, 1, 2, seed=42)
+
+
+@pytest.mark.parametrize("streaming", [True, False])
+@pytest.mark.parametrize("nbytes", [16, 4096 * 16 + 48, 64 << 20])
+def test_probe_copy_copies(srm, streaming, nbytes):
+    print(f"probe_copy bytes={nbytes} streaming={streaming}", flush=True)
+    src = torch.randint(0, 255, (nbytes + 32,), dtype=torch.uint8, device="cuda")
+    dst = torch.full((nbytes + 32,), 255, dtype=torch.uint8, device="cuda")
+    moved = srm.probe_copy(dst[:nbytes], src[:nbytes], streaming=streaming)
+    torch.cuda.synchronize()
+    assert moved == 2 * nbytes
+    assert torch.equal(dst[:nbytes], src[:nbytes]) and (dst[nbytes:] == 255).all()
+    with pytest.raises(srm.SrmError):
+        srm.probe_copy(dst[:24], src[:24])
+
+
+def test_probe_mfma_counts_every_product(srm):
+    blocks, iters = 3, 1000
+    out = torch.zeros(blocks * 256, device="cuda")
+    print(f"probe_mfma blocks={blocks} iters={iters}", flush=True)
+    flop = srm.probe_mfma(out, blocks, iters)
+    torch.cuda.synchronize()
+    assert flop == blocks * 4 * iters * 4 * 2.0 * 32 * 32 * 16
+    assert (out == 1024.0 * iters).all()          # 64 accumulator registers per lane, each 16 * iters
+    with pytest.raises(srm.SrmError):
+        srm.probe_mfma(out, 0, iters)
