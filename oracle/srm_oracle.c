@@ -39,7 +39,10 @@
  * Pins (tests/test_oracle_pins.py): Eq. 1 worked example for n = 3; literal
  * Eq. 2 / Eq. 3 closed forms; parallel == recurrent on brute-force inputs;
  * cumsum / first-order IIR special cases checked against library routines;
- * rank-1 generator; causality; constant state size; printed parameter counts.
+ * rank-1 generator; causality; constant state size; printed parameter counts;
+ * the other head layouts (row-only, column-only, combined) against matrices
+ * written out entry by entry, running sums and the sum of a row-only and a
+ * column-only model.
  * The numerical value of a whole-model logit has no printed example in the
  * paper: for whole-model outputs "parity unpinned" beyond those structural
  * pins and the cross-form identity.
@@ -62,10 +65,29 @@ typedef struct {
     int vocab, d, L, H, e, n_ctx;
     int no_proj;        /* 1: non-projected ("head-parallel") mixer layers, see orc_set_projections */
     int half_state;     /* 1: cache and decay constants in half precision, see orc_set_state_half */
+    int layout;         /* ORC_MIXED, ORC_ROW, ORC_COLUMN or ORC_COMBINED, see orc_create_layout */
     double eps;
     real *embed, *head, *lnf_g, *lnf_b;
     orc_layer *layers;
 } orc_model;
+
+/*
+ * Head layouts ("Method", the paragraph after Eq. 2 on combining row- and
+ * column-repeat outputs; the rows of Table S0):
+ *   ORC_MIXED     heads 0..H/2-1 row-repeat, H/2..H-1 column-repeat (H even);
+ *   ORC_ROW       every head row-repeat;  ORC_COLUMN  every head column-repeat
+ *                 (any H dividing d; H = 1 is the non-headed model);
+ *   ORC_COMBINED  every head owns one row-repeat and one column-repeat matrix,
+ *                 each with its own alpha, beta, lambda, applied to the same
+ *                 input, and the two outputs are added.  Any other fixed linear
+ *                 combination is this one with the weights folded into alpha and
+ *                 beta.  The cache is twice as large: per layer S[0..d) belongs
+ *                 to the row-repeat matrices, S[d..2d) to the column-repeat ones.
+ * alpha, beta have one row (lam one entry) per "slot": H slots, or 2H for
+ * ORC_COMBINED with slot h = head h's row-repeat matrix and slot H + h its
+ * column-repeat matrix.
+ */
+enum { ORC_MIXED = 0, ORC_ROW = 1, ORC_COLUMN = 2, ORC_COMBINED = 3 };
 
 #define ORC_LAYER_TENSORS 15
 #define ORC_GLOBAL_TENSORS 4
@@ -81,17 +103,19 @@ static real *orc_copy(const float *src, size_t n)
 
 /*
  * tensors: embed[V][d], head[V][d], lnf_g[d], lnf_b[d], then for each layer
- * ln1_g[d] ln1_b[d] w_in[d][d] b_in[d] alpha[H][n_ctx] beta[H][n_ctx] lam[H]
+ * ln1_g[d] ln1_b[d] w_in[d][d] b_in[d] alpha[slots][n_ctx] beta[slots][n_ctx] lam[slots]
  * w_out[d][d] b_out[d] ln2_g[d] ln2_b[d] w_up[e*d][d] b_up[e*d]
  * w_down[d][e*d] b_down[d].  All float32, row-major [out][in]; copied.
  */
-orc_model *orc_create(int vocab, int d, int L, int H, int e, int n_ctx, double eps,
-                      const float *const *tensors)
+orc_model *orc_create_layout(int vocab, int d, int L, int H, int e, int n_ctx, double eps, int layout,
+                             const float *const *tensors)
 {
-    if (vocab <= 0 || d <= 0 || L <= 0 || H <= 0 || (H % 2) || (d % H) || e <= 0 || n_ctx <= 0)
-        return NULL;
+    if (vocab <= 0 || d <= 0 || L <= 0 || H <= 0 || (d % H) || e <= 0 || n_ctx <= 0) return NULL;
+    if (layout < ORC_MIXED || layout > ORC_COMBINED || (layout == ORC_MIXED && (H % 2))) return NULL;
     orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
     m->vocab = vocab; m->d = d; m->L = L; m->H = H; m->e = e; m->n_ctx = n_ctx; m->eps = eps;
+    m->layout = layout;
+    const int slots = layout == ORC_COMBINED ? 2 * H : H;
     size_t dd = (size_t)d * d, ff = (size_t)e * d;
     m->embed = orc_copy(tensors[0], (size_t)vocab * d);
     m->head  = orc_copy(tensors[1], (size_t)vocab * d);
@@ -103,9 +127,9 @@ orc_model *orc_create(int vocab, int d, int L, int H, int e, int n_ctx, double e
         orc_layer *y = &m->layers[l];
         y->ln1_g = orc_copy(t[0], d);            y->ln1_b = orc_copy(t[1], d);
         y->w_in  = orc_copy(t[2], dd);           y->b_in  = orc_copy(t[3], d);
-        y->alpha = orc_copy(t[4], (size_t)H * n_ctx);
-        y->beta  = orc_copy(t[5], (size_t)H * n_ctx);
-        y->lam   = orc_copy(t[6], H);
+        y->alpha = orc_copy(t[4], (size_t)slots * n_ctx);
+        y->beta  = orc_copy(t[5], (size_t)slots * n_ctx);
+        y->lam   = orc_copy(t[6], slots);
         y->w_out = orc_copy(t[7], dd);           y->b_out = orc_copy(t[8], d);
         y->ln2_g = orc_copy(t[9], d);            y->ln2_b = orc_copy(t[10], d);
         y->w_up  = orc_copy(t[11], ff * d);      y->b_up  = orc_copy(t[12], ff);
@@ -113,6 +137,16 @@ orc_model *orc_create(int vocab, int d, int L, int H, int e, int n_ctx, double e
     }
     return m;
 }
+
+/* The mixed-head model (the paper's default); alpha, beta [H][n_ctx], lam [H]. */
+orc_model *orc_create(int vocab, int d, int L, int H, int e, int n_ctx, double eps,
+                      const float *const *tensors)
+{
+    return orc_create_layout(vocab, d, L, H, e, n_ctx, eps, ORC_MIXED, tensors);
+}
+
+/* Cache values per layer per sample: d, or 2d for ORC_COMBINED ("Method": combined layers need twice the cache). */
+int orc_state_width(const orc_model *m) { return m->layout == ORC_COMBINED ? 2 * m->d : m->d; }
 
 /*
  * Non-projected SRM ("Method": the input projection "may or may not be applied,
@@ -285,6 +319,42 @@ void orc_mixer_step_half(real *S, const real *u, const real *alpha_t, const real
 }
 
 /*
+ * The mixer update for any head layout (see the enum): S[d], or S[2d] for
+ * ORC_COMBINED.  alpha_t, beta_t, lam: one value per slot for this position.
+ * half != 0 keeps the cache and lambda as binary16 values (orc_set_state_half).
+ *   row-repeat (Eq. 2):     S <- lam*S + alpha_t*u ;  y = S + beta_t
+ *   column-repeat (Eq. 3):  S <- lam*S + u         ;  y = alpha_t*S + beta_t
+ *   combined: both, on separate caches, m = y_row + y_column.
+ */
+void orc_mixer_step_layout(real *S, const real *u, const real *alpha_t, const real *beta_t, const real *lam,
+                           int H, int d, int layout, int half, real *m)
+{
+    int dh = d / H;
+    for (int h = 0; h < H; ++h) {
+        int row = layout == ORC_ROW || layout == ORC_COMBINED || (layout == ORC_MIXED && h < H / 2);
+        int col = layout == ORC_COLUMN || layout == ORC_COMBINED || (layout == ORC_MIXED && h >= H / 2);
+        int cs = layout == ORC_COMBINED ? H + h : h;              /* slot of the column-repeat matrix */
+        real *Sc = layout == ORC_COMBINED ? S + d : S;            /* its cache */
+        real lr = half ? orc_round_half(lam[h]) : lam[h];
+        real lc = half ? orc_round_half(lam[cs]) : lam[cs];
+        for (int c = h * dh; c < (h + 1) * dh; ++c) {
+            real y = 0;
+            if (row) {
+                real v = lr * S[c] + alpha_t[h] * u[c];
+                S[c] = half ? orc_round_half(v) : v;
+                y += S[c] + beta_t[h];
+            }
+            if (col) {
+                real v = lc * Sc[c] + u[c];
+                Sc[c] = half ? orc_round_half(v) : v;
+                y += alpha_t[cs] * Sc[c] + beta_t[cs];
+            }
+            m[c] = y;
+        }
+    }
+}
+
+/*
  * Parallel mixer for one sample: the T x T matrix of each head is written out
  * in full (Eq. 1 for row-repeat, Eq. 3 for column-repeat heads), each entry
  * with pow(), and applied as a dense product.  Tokens are rows here
@@ -313,6 +383,44 @@ void orc_mixer_parallel(const real *U, const real *alpha, const real *beta, cons
                 Y[(size_t)j * d + c] = acc + b[j];
             }
     }
+    free(M);
+}
+
+/*
+ * orc_mixer_parallel for any head layout: the T x T matrix of a head is Eq. 1
+ * (row-repeat), Eq. 3 (column-repeat) or, for ORC_COMBINED, the sum of the
+ * head's two matrices, with the two bias rows added.
+ */
+void orc_mixer_parallel_layout(const real *U, const real *alpha, const real *beta, const real *lam,
+                               int H, int d, int T, int n_ctx, int pos0, int layout, real *Y)
+{
+    int dh = d / H;
+    real *M = (real *)malloc((size_t)T * T * sizeof(real));
+    real *bias = (real *)malloc((size_t)T * sizeof(real));
+    for (int h = 0; h < H; ++h) {
+        int row = layout == ORC_ROW || layout == ORC_COMBINED || (layout == ORC_MIXED && h < H / 2);
+        int col = layout == ORC_COLUMN || layout == ORC_COMBINED || (layout == ORC_MIXED && h >= H / 2);
+        int cs = layout == ORC_COMBINED ? H + h : h;
+        const real *ar = alpha + (size_t)h * n_ctx + pos0, *br = beta + (size_t)h * n_ctx + pos0;
+        const real *ac = alpha + (size_t)cs * n_ctx + pos0, *bc = beta + (size_t)cs * n_ctx + pos0;
+        for (int j = 0; j < T; ++j) bias[j] = (row ? br[j] : 0) + (col ? bc[j] : 0);
+        for (int i = 0; i < T; ++i)
+            for (int j = 0; j < T; ++j) {
+                real v = 0;
+                if (i <= j) {
+                    if (row) v += (real)pow((double)lam[h], (double)(j - i)) * ar[i];
+                    if (col) v += (real)pow((double)lam[cs], (double)(j - i)) * ac[j];
+                }
+                M[(size_t)i * T + j] = v;
+            }
+        for (int j = 0; j < T; ++j)
+            for (int c = h * dh; c < (h + 1) * dh; ++c) {
+                real acc = 0;
+                for (int i = 0; i < T; ++i) acc += U[(size_t)i * d + c] * M[(size_t)i * T + j];
+                Y[(size_t)j * d + c] = acc + bias[j];
+            }
+    }
+    free(bias);
     free(M);
 }
 
@@ -481,26 +589,29 @@ int orc_pick_topp(const real *logits, int V, double temperature, double top_p, u
 
 /*
  * One token of one sample through the whole model in recurrent form.
- * S: [L][d] cache, updated in place.  hidden (may be NULL): residual stream
+ * S: [L][orc_state_width] cache, updated in place.  hidden (may be NULL): residual stream
  * after the last block [d].  logits (may be NULL): [V].
  */
 void orc_step(const orc_model *m, int tok, int pos, real *S, real *hidden, real *logits)
 {
     int d = m->d, ff = m->e * m->d, H = m->H;
-    real *x = (real *)malloc(sizeof(real) * (size_t)(4 * d + 2 * ff + 3 * H));
+    const int slots = m->layout == ORC_COMBINED ? 2 * H : H, sd = orc_state_width(m);
+    real *x = (real *)malloc(sizeof(real) * (size_t)(4 * d + 2 * ff + 2 * slots));
     real *a = x + d, *u = a + d, *mix = u + d, *g = mix + d, *t = g + ff;
-    real *al = t + ff, *be = al + H;
+    real *al = t + ff, *be = al + slots;
     for (int i = 0; i < d; ++i) x[i] = m->embed[(size_t)tok * d + i];
     for (int l = 0; l < m->L; ++l) {
         const orc_layer *y = &m->layers[l];
         orc_layernorm(x, y->ln1_g, y->ln1_b, d, m->eps, a);
         if (m->no_proj) memcpy(u, a, sizeof(real) * d);
         else orc_linear(y->w_in, y->b_in, a, d, d, u);
-        for (int h = 0; h < H; ++h) {
+        for (int h = 0; h < slots; ++h) {
             al[h] = y->alpha[(size_t)h * m->n_ctx + pos];
             be[h] = y->beta[(size_t)h * m->n_ctx + pos];
         }
-        if (m->half_state) orc_mixer_step_half(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
+        if (m->layout != ORC_MIXED)
+            orc_mixer_step_layout(S + (size_t)l * sd, u, al, be, y->lam, H, d, m->layout, m->half_state, mix);
+        else if (m->half_state) orc_mixer_step_half(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
         else orc_mixer_step(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
         if (m->no_proj) memcpy(t, mix, sizeof(real) * d);
         else orc_linear(y->w_out, y->b_out, mix, d, d, t);
@@ -521,7 +632,7 @@ void orc_step(const orc_model *m, int tok, int pos, real *S, real *hidden, real 
 
 /*
  * Teacher-forced recurrent pass: tokens[B][T] at absolute positions
- * pos0..pos0+T-1, starting from state[B][L][d] (updated in place; zero it for
+ * pos0..pos0+T-1, starting from state[B][L][orc_state_width] (updated in place; zero it for
  * pos0 = 0).  Optional outputs: hidden[B][T][d], logits[B][T][V],
  * greedy[B][T] (argmax of each position's logits).  Returns 0, or -1 on a
  * bad argument.
@@ -533,7 +644,7 @@ int orc_recurrent_forward(const orc_model *m, int B, int T, const int *tokens, i
     for (long long i = 0; i < (long long)B * T; ++i)
         if (tokens[i] < 0 || tokens[i] >= m->vocab) return -1;
     int d = m->d, V = m->vocab;
-    size_t Ld = (size_t)m->L * d;
+    size_t Ld = (size_t)m->L * orc_state_width(m);
     int need_logits = logits || greedy;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int b = 0; b < B; ++b) {
@@ -556,7 +667,7 @@ int orc_recurrent_forward(const orc_model *m, int B, int T, const int *tokens, i
  * generated token is fed back.  temperature == 0: greedy; otherwise sampled with
  * orc_pick_topp (nucleus truncation when top_p < 1), the counter being (seed,
  * position of the token just consumed, b0 + b).
- * state[B][L][d] is overwritten.  Optional: logits[B][G][V] (the raw logits each
+ * state[B][L][orc_state_width] is overwritten.  Optional: logits[B][G][V] (the raw logits each
  * generated token was chosen from) and margin[B][G] (top-1 minus top-2 of the
  * scores the choice was made on).
  */
@@ -567,8 +678,8 @@ int orc_generate_topp(const orc_model *m, int B, int P, int G, const int *prompt
     if (P < 1 || G < 1 || P + G - 1 > m->n_ctx || temperature < 0 || !(top_p > 0)) return -1;
     for (long long i = 0; i < (long long)B * P; ++i)
         if (prompts[i] < 0 || prompts[i] >= m->vocab) return -1;
-    int d = m->d, V = m->vocab;
-    size_t Ld = (size_t)m->L * d;
+    int V = m->vocab;
+    size_t Ld = (size_t)m->L * orc_state_width(m);
 #pragma omp parallel for schedule(dynamic, 1)
     for (int b = 0; b < B; ++b) {
         real *S = state + b * Ld;
@@ -638,7 +749,9 @@ int orc_parallel_forward(const orc_model *m, int B, int T, const int *tokens,
                 if (m->no_proj) memcpy(U + (size_t)s * d, A + (size_t)s * d, sizeof(real) * d);
                 else orc_linear(y->w_in, y->b_in, A + (size_t)s * d, d, d, U + (size_t)s * d);
             }
-            orc_mixer_parallel(U, y->alpha, y->beta, y->lam, m->H, d, T, m->n_ctx, 0, Y);
+            if (m->layout != ORC_MIXED)
+                orc_mixer_parallel_layout(U, y->alpha, y->beta, y->lam, m->H, d, T, m->n_ctx, 0, m->layout, Y);
+            else orc_mixer_parallel(U, y->alpha, y->beta, y->lam, m->H, d, T, m->n_ctx, 0, Y);
             for (int s = 0; s < T; ++s) {
                 real *x = X + (size_t)s * d;
                 if (m->no_proj) memcpy(tmp, Y + (size_t)s * d, sizeof(real) * d);

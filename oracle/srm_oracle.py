@@ -45,6 +45,10 @@ def _load(kind: str):
         lib = C.CDLL(lib_path(kind))
         lib.orc_create.restype = C.c_void_p
         lib.orc_create.argtypes = [C.c_int] * 6 + [C.c_double, C.POINTER(C.c_void_p)]
+        lib.orc_create_layout.restype = C.c_void_p
+        lib.orc_create_layout.argtypes = [C.c_int] * 6 + [C.c_double, C.c_int, C.POINTER(C.c_void_p)]
+        lib.orc_state_width.restype = C.c_int
+        lib.orc_state_width.argtypes = [C.c_void_p]
         lib.orc_destroy.argtypes = [C.c_void_p]
         lib.orc_count_params.restype = C.c_longlong
         lib.orc_count_params.argtypes = [C.c_int] * 7
@@ -120,6 +124,9 @@ def round_half(v: float) -> float:
     return float(_load("f64").orc_round_half(float(v)))
 
 
+LAYOUTS = {"mixed": 0, "row": 1, "column": 2, "combined": 3}
+
+
 def count_params(vocab, d, L, H=4, e=4, n_ctx=512, with_projections=True) -> int:
     return int(_load("f64").orc_count_params(vocab, d, L, H, e, n_ctx, int(with_projections)))
 
@@ -140,10 +147,12 @@ class Oracle:
             tensors += [lw[n] for n in _LAYER_TENSORS]
         self._keep = [np.ascontiguousarray(t, dtype=np.float32) for t in tensors]
         arr = (C.c_void_p * len(self._keep))(*[t.ctypes.data for t in self._keep])
-        self.h = self.lib.orc_create(self.V, self.d, self.L, self.H, self.e, self.n_ctx,
-                                     float(cfg.ln_eps), arr)
+        self.layout = LAYOUTS[getattr(cfg, "head_layout", "mixed")]
+        self.h = self.lib.orc_create_layout(self.V, self.d, self.L, self.H, self.e, self.n_ctx,
+                                            float(cfg.ln_eps), self.layout, arr)
         if not self.h:
             raise ValueError("orc_create rejected the configuration")
+        self.sd = int(self.lib.orc_state_width(C.c_void_p(self.h)))
         self._keep = None  # the C side copied everything
         if not getattr(cfg, "use_projections", True):
             self.lib.orc_set_projections(C.c_void_p(self.h), 0)
@@ -186,6 +195,23 @@ class Oracle:
                                 C.c_int(lam.size), C.c_int(u.size), _p(m))
         return m
 
+    def mixer_step_layout(self, S, u, alpha_t, beta_t, lam, H, layout, half=False):
+        """orc_mixer_step_layout: in place on S ([d], or [2d] for "combined"); returns m."""
+        assert S.dtype == self.real and S.flags.c_contiguous
+        u, alpha_t, beta_t, lam = map(self._r, (u, alpha_t, beta_t, lam))
+        m = np.empty_like(u)
+        self.lib.orc_mixer_step_layout(_p(S), _p(u), _p(alpha_t), _p(beta_t), _p(lam), C.c_int(H),
+                                       C.c_int(u.size), C.c_int(LAYOUTS[layout]), C.c_int(int(half)), _p(m))
+        return m
+
+    def mixer_parallel_layout(self, U, alpha, beta, lam, H, layout, pos0=0):
+        U, alpha, beta, lam = map(self._r, (U, alpha, beta, lam))
+        T, d = U.shape
+        Y = np.empty_like(U)
+        self.lib.orc_mixer_parallel_layout(_p(U), _p(alpha), _p(beta), _p(lam), C.c_int(H), C.c_int(d), C.c_int(T),
+                                           C.c_int(alpha.shape[1]), C.c_int(pos0), C.c_int(LAYOUTS[layout]), _p(Y))
+        return Y
+
     def mixer_parallel(self, U, alpha, beta, lam, pos0=0):
         U, alpha, beta, lam = map(self._r, (U, alpha, beta, lam))
         T, d = U.shape
@@ -205,7 +231,7 @@ class Oracle:
 
     # -- whole model --------------------------------------------------------
     def new_state(self, B):
-        return np.zeros((B, self.L, self.d), dtype=self.real)
+        return np.zeros((B, self.L, self.sd), dtype=self.real)
 
     def recurrent_forward(self, tokens, pos0=0, state=None, want_hidden=True,
                           want_logits=True, want_greedy=False):
@@ -213,7 +239,7 @@ class Oracle:
         B, T = tokens.shape
         if state is None:
             state = self.new_state(B)
-        assert state.dtype == self.real and state.shape == (B, self.L, self.d)
+        assert state.dtype == self.real and state.shape == (B, self.L, self.sd)
         hidden = np.empty((B, T, self.d), self.real) if want_hidden else None
         logits = np.empty((B, T, self.V), self.real) if want_logits else None
         greedy = np.empty((B, T), np.int32) if want_greedy else None

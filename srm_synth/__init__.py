@@ -49,6 +49,7 @@ class SRMConfig:
     n_ctx_fixed: int = 0    # 0: prompt_len + gen_len rounded up to a multiple of 64
     use_projections: bool = True   # False: non-projected mixer layers (w_in / w_out are drawn but unused)
     state_dtype: str = "fp32"      # "fp16": recurrent cache and decay constants in half precision
+    head_layout: str = "mixed"     # "mixed" | "row" | "column" | "combined" (two matrices per head, twice the cache)
 
     @property
     def n_ctx(self) -> int:
@@ -64,6 +65,16 @@ class SRMConfig:
     @property
     def d_ff(self) -> int:
         return self.d_model * self.mlp_expansion
+
+    @property
+    def head_slots(self) -> int:
+        """Rows of alpha / beta (entries of lam) per layer."""
+        return self.n_heads * (2 if self.head_layout == "combined" else 1)
+
+    @property
+    def state_width(self) -> int:
+        """Cache values per layer per sample."""
+        return self.d_model * (2 if self.head_layout == "combined" else 1)
 
 
 CONFIGS: Dict[str, SRMConfig] = {
@@ -81,11 +92,12 @@ CONFIGS: Dict[str, SRMConfig] = {
 
 def tiny_config(name="T", vocab=32, d_model=8, n_layers=2, n_heads=2, n_ctx=16,
                 weight_dtype="fp32", seed=7, mlp_expansion=4, use_projections=True,
-                state_dtype="fp32") -> SRMConfig:
+                state_dtype="fp32", head_layout="mixed") -> SRMConfig:
     """A brute-force sized config for unit tests."""
     return SRMConfig(name, vocab, d_model, n_layers, weight_dtype, seed, seed + 1,
                      2, n_ctx, 0, n_heads=n_heads, mlp_expansion=mlp_expansion,
-                     n_ctx_fixed=n_ctx, use_projections=use_projections, state_dtype=state_dtype)
+                     n_ctx_fixed=n_ctx, use_projections=use_projections, state_dtype=state_dtype,
+                     head_layout=head_layout)
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
@@ -102,7 +114,7 @@ def round_to_bf16(a: np.ndarray) -> np.ndarray:
 
 
 def tensor_shapes(cfg: SRMConfig, n_ctx: int | None = None):
-    d, ff, H, V = cfg.d_model, cfg.d_ff, cfg.n_heads, cfg.vocab
+    d, ff, H, V = cfg.d_model, cfg.d_ff, cfg.head_slots, cfg.vocab
     n = cfg.n_ctx if n_ctx is None else n_ctx
     layer = {
         "ln1_g": (d,), "ln1_b": (d,), "w_in": (d, d), "b_in": (d,),

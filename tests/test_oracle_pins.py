@@ -625,3 +625,130 @@ def test_half_state_recurrence_against_float16_emulation(oracle_mod):
     r32 = oracle_mod.Oracle(cfg32, w, "f64").recurrent_forward(toks)
     rel = np.abs(r["logits"] - r32["logits"]).max() / np.abs(r32["logits"]).max()
     assert 0 < rel < 2e-2                                          # different, and close
+
+
+# ---- head layouts: row-only, column-only, combined ("Method", after Eq. 2; Table S0) ----
+def _brute_mixer(U, alpha, beta, lam, H, layout):
+    """Eq. 1 / Eq. 3 matrices written out entry by entry in numpy, heads applied one by one.
+    Tokens are rows of U; combined heads add the outputs of their two matrices."""
+    T, d = U.shape
+    dh = d // H
+    Y = np.zeros((T, d))
+    for h in range(H):
+        kinds = {"row": [("row", h)], "column": [("col", h)], "combined": [("row", h), ("col", H + h)],
+                 "mixed": [("row" if h < H // 2 else "col", h)]}[layout]
+        for kind, s in kinds:
+            M = np.zeros((T, T))
+            for i in range(T):
+                for j in range(i, T):
+                    M[i, j] = lam[s] ** (j - i) * (alpha[s, i] if kind == "row" else alpha[s, j])
+            Y[:, h * dh:(h + 1) * dh] += M.T @ U[:, h * dh:(h + 1) * dh] + beta[s, :T, None]
+    return Y
+
+
+@pytest.mark.parametrize("layout,H", [("row", 1), ("row", 4), ("column", 1), ("column", 2), ("combined", 1),
+                                      ("combined", 4), ("mixed", 4)])
+def test_head_layouts_three_statements_agree(tiny, layout, H):
+    """Recurrent steps, the explicit matrices in C and a numpy brute force give one answer."""
+    _, _, orc = tiny
+    T, d = 11, 8
+    slots = 2 * H if layout == "combined" else H
+    alpha, beta, lam = _coeffs(slots, T, seed=50 + H)
+    U = np.random.default_rng(51).standard_normal((T, d))
+    want = _brute_mixer(U, alpha, beta, lam, H, layout)
+    S = np.zeros(2 * d if layout == "combined" else d)
+    Y = np.stack([orc.mixer_step_layout(S, U[t], alpha[:, t], beta[:, t], lam, H, layout) for t in range(T)])
+    np.testing.assert_allclose(Y, want, rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(orc.mixer_parallel_layout(U, alpha, beta, lam, H, layout), want, rtol=1e-11, atol=1e-11)
+    if layout == "mixed":                                   # the general routine restates the default one exactly
+        Y0, S0 = _recurrent(orc, U, alpha, beta, lam)
+        np.testing.assert_array_equal(Y, Y0)
+        np.testing.assert_array_equal(S, S0)
+
+
+def test_row_and_column_layouts_reduce_to_cumulative_sums(tiny):
+    """No decay, alpha = 1, beta = 0, one head: both matrices are the all-ones upper triangle,
+    i.e. a running sum over positions; with a general alpha the column form scales that sum."""
+    _, _, orc = tiny
+    T, d = 9, 8
+    U = np.random.default_rng(3).standard_normal((T, d))
+    one, zero = np.ones((1, T)), np.zeros((1, T))
+    for layout in ("row", "column"):
+        np.testing.assert_allclose(orc.mixer_parallel_layout(U, one, zero, [1.0], 1, layout), np.cumsum(U, axis=0),
+                                   rtol=1e-12, atol=1e-12)
+    a = np.random.default_rng(4).standard_normal((1, T))
+    np.testing.assert_allclose(orc.mixer_parallel_layout(U, a, zero, [1.0], 1, "column"),
+                               a[0, :, None] * np.cumsum(U, axis=0), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(orc.mixer_parallel_layout(U, a, zero, [1.0], 1, "row"),
+                               np.cumsum(a[0, :, None] * U, axis=0), rtol=1e-12, atol=1e-12)
+    # with decay both are first-order IIR filters along the sequence
+    lam = 0.93
+    np.testing.assert_allclose(orc.mixer_parallel_layout(U, one, zero, [lam], 1, "row"),
+                               scipy.signal.lfilter([1.0], [1.0, -lam], U, axis=0), rtol=1e-11, atol=1e-11)
+
+
+def test_combined_heads_are_the_sum_of_a_row_and_a_column_model_and_double_the_cache(oracle_mod):
+    H, d, T = 2, 8, 10
+    cfg = srm_synth.tiny_config(vocab=24, d_model=d, n_layers=2, n_heads=H, n_ctx=16, seed=61, head_layout="combined")
+    w = srm_synth.make_weights(cfg, stress=True)
+    assert w["layers"][0]["alpha"].shape == (2 * H, 16) and w["layers"][0]["lam"].shape == (2 * H,)
+    orc = oracle_mod.Oracle(cfg, w, "f64")
+    alpha, beta, lam = (w["layers"][0][k].astype(np.float64) for k in ("alpha", "beta", "lam"))
+    U = np.random.default_rng(62).standard_normal((T, d))
+    Yr = orc.mixer_parallel_layout(U, alpha[:H], beta[:H], lam[:H], H, "row")
+    Yc = orc.mixer_parallel_layout(U, alpha[H:], beta[H:], lam[H:], H, "column")
+    np.testing.assert_allclose(orc.mixer_parallel_layout(U, alpha, beta, lam, H, "combined"), Yr + Yc, rtol=1e-12,
+                               atol=1e-12)
+    # the cache: twice the width, row part first; each half is the cache of the one-kind model
+    S = np.zeros(2 * d)
+    Sr, Sc = np.zeros(d), np.zeros(d)
+    for t in range(T):
+        orc.mixer_step_layout(S, U[t], alpha[:, t], beta[:, t], lam, H, "combined")
+        orc.mixer_step_layout(Sr, U[t], alpha[:H, t], beta[:H, t], lam[:H], H, "row")
+        orc.mixer_step_layout(Sc, U[t], alpha[H:, t], beta[H:, t], lam[H:], H, "column")
+    np.testing.assert_array_equal(S, np.concatenate([Sr, Sc]))
+    toks = srm_synth.make_prompts(cfg, batch=2, length=12)
+    r = orc.recurrent_forward(toks)
+    assert r["state"].shape == (2, cfg.n_layers, 2 * d)                          # double the cache, constant in T
+    p = orc.parallel_forward(toks)
+    np.testing.assert_allclose(p["logits"], r["logits"], rtol=1e-9, atol=1e-9)   # both forms, whole model
+    # a combined model whose column matrices are zero is the row-only model
+    w0 = {k: v for k, v in w.items() if k != "layers"}
+    w0["layers"] = []
+    for lw in w["layers"]:
+        lw0 = dict(lw)
+        lw0["alpha"] = lw["alpha"].copy(); lw0["alpha"][H:] = 0
+        lw0["beta"] = lw["beta"].copy(); lw0["beta"][H:] = 0
+        w0["layers"].append(lw0)
+    cfg_row = srm_synth.tiny_config(vocab=24, d_model=d, n_layers=2, n_heads=H, n_ctx=16, seed=61, head_layout="row")
+    w_row = dict(w0)
+    w_row["layers"] = [{**lw, "alpha": lw["alpha"][:H], "beta": lw["beta"][:H], "lam": lw["lam"][:H]}
+                       for lw in w0["layers"]]
+    np.testing.assert_allclose(oracle_mod.Oracle(cfg, w0, "f64").recurrent_forward(toks)["logits"],
+                               oracle_mod.Oracle(cfg_row, w_row, "f64").recurrent_forward(toks)["logits"],
+                               rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("layout", ["row", "column", "combined"])
+def test_head_layout_models_parallel_equals_recurrent_and_generate(oracle_mod, layout):
+    cfg = srm_synth.tiny_config(vocab=40, d_model=16, n_layers=2, n_heads=4, n_ctx=32, seed=63, head_layout=layout)
+    w = srm_synth.make_weights(cfg, stress=True)
+    orc = oracle_mod.Oracle(cfg, w, "f64")
+    toks = srm_synth.make_prompts(cfg, batch=3, length=20)
+    r, p = orc.recurrent_forward(toks), orc.parallel_forward(toks)
+    np.testing.assert_allclose(p["hidden"], r["hidden"], rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(p["logits"], r["logits"], rtol=1e-9, atol=1e-9)
+    g = orc.greedy(toks[:, :8], 6)
+    assert g["state"].shape == (3, cfg.n_layers, cfg.state_width)
+    # generation continues the teacher-forced pass: feeding the generated tokens back reproduces them
+    full = np.concatenate([toks[:, :8], g["tokens"][:, :-1]], axis=1)
+    np.testing.assert_array_equal(orc.recurrent_forward(full, want_greedy=True)["greedy"][:, 7:], g["tokens"])
+
+
+def test_head_layout_half_precision_cache_values_are_representable(oracle_mod):
+    cfg = srm_synth.tiny_config(vocab=40, d_model=16, n_layers=1, n_heads=2, n_ctx=32, seed=64, head_layout="combined",
+                                state_dtype="fp16")
+    w = srm_synth.make_weights(cfg, stress=True)
+    S = oracle_mod.Oracle(cfg, w, "f64").recurrent_forward(srm_synth.make_prompts(cfg, batch=1, length=32))["state"]
+    np.testing.assert_array_equal(S, S.astype(np.float16).astype(np.float64))
+    assert np.abs(S).max() > 0
