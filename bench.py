@@ -38,6 +38,9 @@ def parse_args():
                     help="the non-projected model variant (mixer layers without in/out head projections)")
     ap.add_argument("--state-dtype", choices=["fp32", "fp16"], default="fp32",
                     help="fp16: the recurrent cache and decay constants in half precision (a model variant)")
+    ap.add_argument("--head-layout", choices=["mixed", "row", "column", "combined"], default="mixed",
+                    help="row / column: one kind of head only; combined: two matrices per head, twice the cache "
+                         "(model variants)")
     ap.add_argument("--top-p", type=float, default=1.0,
                     help="with --temperature: nucleus truncation (the paper's rollouts use 0.9 at temperature 0.7)")
     ap.add_argument("--per-step-calls", action="store_true",
@@ -102,8 +105,9 @@ def kernel_legs(torch, srm, model, cfg, B, iters):
     del W, scratch
     # state update: cycle over the L layer slabs exactly as a step does
     half = getattr(cfg, "state_dtype", "fp32") == "fp16"
-    state = torch.zeros((L, B, d), dtype=torch.float16 if half else torch.float32, device="cuda")
-    u = rnd(B, d)
+    sd = getattr(cfg, "state_width", d)             # 2d with combined heads
+    state = torch.zeros((L, B, sd), dtype=torch.float16 if half else torch.float32, device="cuda")
+    u = rnd(B, sd)
     m = torch.empty_like(u)
     it = [0]
 
@@ -112,7 +116,7 @@ def kernel_legs(torch, srm, model, cfg, B, iters):
         it[0] += 1
 
     t = time_launches(torch, su, max(iters, 2 * L), warm=L)
-    nbytes = B * d * ((4 if half else 8) + 2 * esz)
+    nbytes = B * sd * ((4 if half else 8) + 2 * esz)
     legs["state_update"] = {"ms": t * 1e3, "gbs": nbytes / t * 1e-9, "bytes": nbytes}
     return legs
 
@@ -252,9 +256,10 @@ def main():
         concurrency_sweep(torch, srm, srm_synth, min(args.steps, 8), args.state_dtype)
         return
     cfg = srm_synth.CONFIGS[args.workload]
-    if args.no_projections or args.state_dtype != "fp32":
+    if args.no_projections or args.state_dtype != "fp32" or args.head_layout != "mixed":
         import dataclasses
-        cfg = dataclasses.replace(cfg, use_projections=not args.no_projections, state_dtype=args.state_dtype)
+        cfg = dataclasses.replace(cfg, use_projections=not args.no_projections, state_dtype=args.state_dtype,
+                                  head_layout=args.head_layout)
     B, P = cfg.batch, cfg.prompt_len
     t0 = time.perf_counter()
     w = srm_synth.make_weights(cfg)
@@ -331,7 +336,7 @@ def main():
     flops_step = B * (gemm_dd * L * d * d + 2.0 * V * d)
     esz = 2 if cfg.weight_dtype == "bf16" else 4
     ssz = 2 if cfg.state_dtype == "fp16" else 4
-    bytes_step = (gemm_dd / 2 * L * d * d + V * d) * esz + 2.0 * ssz * B * L * d + B * d * esz
+    bytes_step = (gemm_dd / 2 * L * d * d + V * d) * esz + 2.0 * ssz * B * L * cfg.state_width + B * d * esz
     out = {
         "metric": "generated tokens/sec on 1 MI355X at max batch",
         "value": B / step_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -339,7 +344,8 @@ def main():
         "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: SRM d_model {d}, {L} layers, 4 mixed heads, MLP x4, vocab {V}, "
                                f"{cfg.weight_dtype} weights / {cfg.state_dtype} state, batch {B}, prompt {P}, greedy decode" +
-                               ("" if cfg.use_projections else ", non-projected mixer layers"),
+                               ("" if cfg.use_projections else ", non-projected mixer layers") +
+                               ("" if cfg.head_layout == "mixed" else f", {cfg.head_layout} heads"),
                    "batch": B, "prompt_len": P, "state_bytes": model.state_bytes(B)},
         "step": {"algorithmic_tflop": flops_step * 1e-12, "algorithmic_gb": bytes_step * 1e-9,
                  "achieved_gbs": bytes_step / step_s * 1e-9, "hbm_frac": bytes_step / step_s * 1e-9 / PEAK_HBM_GBS,

@@ -57,12 +57,15 @@ typedef enum {
 } srm_status;
 
 enum { SRM_FP32 = 0, SRM_BF16 = 1, SRM_FP16 = 2 };
+/* Head layouts ("Method", the paragraph after Eq. 2 on combining row- and column-repeat outputs; Table S0). */
+enum { SRM_HEADS_MIXED = 0, SRM_HEADS_ROW = 1, SRM_HEADS_COLUMN = 2, SRM_HEADS_COMBINED = 3 };
 
 typedef struct {
     int32_t vocab;
     int32_t d_model;
     int32_t n_layers;
-    int32_t n_heads;        /* even; first half row-repeat, second half column-repeat */
+    int32_t n_heads;        /* H; see head_layout (mixed heads: even, first half row-repeat, second half
+                               column-repeat) */
     int32_t mlp_expansion;
     int32_t n_ctx;          /* number of positions alpha/beta are defined for */
     int32_t weight_dtype;   /* SRM_FP32 | SRM_BF16 */
@@ -77,14 +80,26 @@ typedef struct {
                                layers ("Method", last paragraph; Tables S2-S4): head h is channels
                                h*d_h .. of the LayerNorm output, the mixer output joins the residual
                                stream directly; w_in, b_in, w_out, b_out are ignored and may be NULL */
+    int32_t head_layout;    /* SRM_HEADS_MIXED (default, 0): "mixed" heads, the model the paper settles on.
+                               SRM_HEADS_ROW / SRM_HEADS_COLUMN: every head row-repeat (Eq. 2) / column-
+                               repeat (Eq. 3); n_heads may be odd, 1 is the non-headed model.
+                               SRM_HEADS_COMBINED: every head owns one row-repeat and one column-repeat
+                               matrix, each with its own alpha, beta, lambda, applied to the same head
+                               input; the two outputs are added (any fixed linear combination is this one
+                               with the weights folded into alpha and beta).  alpha, beta then have 2H
+                               rows and lambda 2H entries: row h = head h's row-repeat matrix, row H + h
+                               its column-repeat matrix.  The cache doubles ("Method": combined layers
+                               need twice the cache): every state row is [2d], first the d values of the
+                               row-repeat matrices, then the d values of the column-repeat ones, and
+                               srm_state_bytes counts 2d.  Needs the head projections. */
 } srm_config;
 
 /* HOST pointers, fp32, caller-owned, not retained after srm_init_weights. */
 typedef struct {
     const float *ln1_g, *ln1_b;        /* [d], [d]                                  */
     const float *w_in, *b_in;          /* [d][d] (rows h*d_h.. are I_h), [d]         */
-    const float *alpha, *beta;         /* [H][n_ctx], [H][n_ctx]                     */
-    const float *lambda;               /* [H], each in (0.9, 1]                      */
+    const float *alpha, *beta;         /* [H][n_ctx], [H][n_ctx] ([2H] rows: combined) */
+    const float *lambda;               /* [H] ([2H]: combined), each in (0, 1]       */
     const float *w_out, *b_out;        /* [d][d] (P_out), [d]                        */
     const float *ln2_g, *ln2_b;        /* [d], [d]                                   */
     const float *w_up, *b_up;          /* [e*d][d], [e*d]                            */
@@ -102,8 +117,9 @@ typedef struct {
  * Copy the weights to the current HIP device (casting matrices to bf16 when
  * configured) and return an opaque model.  ("Method": one parameter set serves
  * both the recurrent and the parallel form.)
- * Errors: SRM_EINVAL for a null pointer, non-positive size, odd n_heads,
- * d_model not divisible by 4*n_heads, d_model > 4096, bf16 with d_model % 64,
+ * Errors: SRM_EINVAL for a null pointer, non-positive size, odd n_heads with
+ * mixed heads, more than 64 coefficient rows per layer, an unknown head_layout,
+ * combined heads without projections, d_model not divisible by 4*n_heads, d_model > 4096, bf16 with d_model % 64,
  * or a lambda outside (0, 1]; SRM_ENOMEM; SRM_EHIP.
  */
 int srm_init_weights(const srm_config *cfg, const srm_host_weights *w, srm_model **out);
@@ -111,7 +127,7 @@ void srm_free(srm_model *m);
 
 /*
  * Bytes of recurrent state for `batch` samples: n_layers * batch * d_model * 4
- * (* 2 with a binary16 state), whatever the position ("Computational Complexity": O(d) space per sample).
+ * (2 with a binary16 state; twice that with combined heads), whatever the position ("Computational Complexity": O(d) space per sample).
  * Returns 0 for a null model or batch <= 0.
  */
 size_t srm_state_bytes(const srm_model *m, int64_t batch);
@@ -326,7 +342,10 @@ int srm_parallel_forward(srm_model *m, const int32_t *d_tok, int32_t B, int32_t 
  * srm_mixer_update: the recurrent state update of one layer (Eq. 2 / Eq. 3)
  * for B samples at position pos.  d_u and d_m are [B][d] in the model's
  * activation type (bf16 for SRM_BF16 models, fp32 otherwise); d_state_layer is
- * that layer's [B][d] fp32 slab, updated in place.  d_m may alias d_u.
+ * that layer's [B][d] slab (fp32, or binary16 with a half-precision state),
+ * updated in place.  d_m may alias d_u.  With combined heads all three rows are
+ * [2d]: the row-repeat half then the column-repeat half, d_u holding the head
+ * input twice; the model adds the two halves of d_m in its out-projection.
  */
 int srm_mixer_update(srm_model *m, int32_t layer, int32_t pos, int64_t B, const void *d_u,
                      void *d_state_layer, void *d_m, void *hip_stream);

@@ -32,7 +32,7 @@ class srm_config(C.Structure):
     _fields_ = [("vocab", C.c_int32), ("d_model", C.c_int32), ("n_layers", C.c_int32),
                 ("n_heads", C.c_int32), ("mlp_expansion", C.c_int32), ("n_ctx", C.c_int32),
                 ("weight_dtype", C.c_int32), ("ln_eps", C.c_float), ("state_dtype", C.c_int32),
-                ("no_projections", C.c_int32)]
+                ("no_projections", C.c_int32), ("head_layout", C.c_int32)]
 
 
 class srm_host_layer(C.Structure):
@@ -132,6 +132,9 @@ def _stream(stream) -> Optional[int]:
     return C.c_void_p(s.cuda_stream)
 
 
+HEAD_LAYOUTS = {"mixed": 0, "row": 1, "column": 2, "combined": 3}
+
+
 class Model:
     """Owns one srm_model.  cfg needs vocab, d_model, n_layers, n_heads,
     mlp_expansion, n_ctx, weight_dtype ("fp32"|"bf16") and ln_eps; weights is
@@ -147,7 +150,10 @@ class Model:
         c = srm_config(cfg.vocab, cfg.d_model, cfg.n_layers, cfg.n_heads, cfg.mlp_expansion,
                        cfg.n_ctx, self.dtype, cfg.ln_eps,
                        SRM_FP16 if getattr(cfg, "state_dtype", "fp32") == "fp16" else SRM_FP32,
-                       0 if getattr(cfg, "use_projections", True) else 1)
+                       0 if getattr(cfg, "use_projections", True) else 1,
+                       HEAD_LAYOUTS[getattr(cfg, "head_layout", "mixed")])
+        combined = getattr(cfg, "head_layout", "mixed") == "combined"
+        self.sd = self.d * (2 if combined else 1)          # state (and mixer) width per sample and layer
         self.state_half = getattr(cfg, "state_dtype", "fp32") == "fp16"
         keep = []
 
@@ -158,7 +164,7 @@ class Model:
             keep.append(a)
             return a.ctypes.data_as(_FP)
 
-        d, ff, H, n, V = self.d, self.ff, self.H, self.n_ctx, self.vocab
+        d, ff, H, n, V = self.d, self.ff, self.H * (2 if combined else 1), self.n_ctx, self.vocab
         shapes = {"ln1_g": (d,), "ln1_b": (d,), "w_in": (d, d), "b_in": (d,), "alpha": (H, n),
                   "beta": (H, n), "lambda": (H,), "w_out": (d, d), "b_out": (d,), "ln2_g": (d,),
                   "ln2_b": (d,), "w_up": (ff, d), "b_up": (ff,), "w_down": (d, ff), "b_down": (d,)}
@@ -200,7 +206,7 @@ class Model:
 
     def new_state(self, batch: int):
         torch = _torch()
-        return torch.zeros((self.L, batch, self.d), dtype=self.state_torch_dtype, device="cuda")
+        return torch.zeros((self.L, batch, self.sd), dtype=self.state_torch_dtype, device="cuda")
 
     def new_workspace(self, rows: int):
         torch = _torch()
@@ -212,8 +218,8 @@ class Model:
         when top_p is given too."""
         torch = _torch()
         p_in = _dev(tok_in, torch.int32, B, "tok_in")
-        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.d, "state")
-        if state.numel() != self.L * B * self.d:
+        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.sd, "state")
+        if state.numel() != self.L * B * self.sd:
             raise ValueError("state: must be exactly [L][B][d]")
         p_out = _dev(tok_out, torch.int32, B, "tok_out")
         p_lg = None if logits is None else _dev(logits, torch.float32, B * self.vocab, "logits")
@@ -233,8 +239,8 @@ class Model:
                  top_p=None, logits=None):
         torch = _torch()
         p_tk = _dev(tok, torch.int32, B, "tok")
-        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.d, "state")
-        if state.numel() != self.L * B * self.d:
+        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.sd, "state")
+        if state.numel() != self.L * B * self.sd:
             raise ValueError("state: must be exactly [L][B][d]")
         p_out = _dev(tokens_out, torch.int32, G * B, "tokens_out")
         p_ws = _dev(workspace, torch.uint8, 1, "workspace")
@@ -251,8 +257,8 @@ class Model:
         N, P = prompts.shape
         Bt = N * fanout_k
         p_pr = _dev(prompts, torch.int32, N * P, "prompts")
-        p_st = _dev(state, self.state_torch_dtype, self.L * Bt * self.d, "state")
-        if state.numel() != self.L * Bt * self.d:
+        p_st = _dev(state, self.state_torch_dtype, self.L * Bt * self.sd, "state")
+        if state.numel() != self.L * Bt * self.sd:
             raise ValueError("state: must be exactly [L][N*k][d]")
         p_nt = _dev(next_tok, torch.int32, Bt, "next_tok")
         p_lg = None if logits is None else _dev(logits, torch.float32, N * self.vocab, "logits")
@@ -266,8 +272,8 @@ class Model:
         torch = _torch()
         p_pos = _dev(pos, torch.int32, B, "pos")
         p_in = _dev(tok_in, torch.int32, B, "tok_in")
-        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.d, "state")
-        if state.numel() != self.L * B * self.d:
+        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.sd, "state")
+        if state.numel() != self.L * B * self.sd:
             raise ValueError("state: must be exactly [L][B][d]")
         p_out = _dev(tok_out, torch.int32, B, "tok_out")
         p_lg = None if logits is None else _dev(logits, torch.float32, B * self.vocab, "logits")
@@ -282,8 +288,8 @@ class Model:
         torch = _torch()
         p_pos = _dev(pos, torch.int32, B, "pos")
         p_tk = _dev(tok, torch.int32, B, "tok")
-        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.d, "state")
-        if state.numel() != self.L * B * self.d:
+        p_st = _dev(state, self.state_torch_dtype, self.L * B * self.sd, "state")
+        if state.numel() != self.L * B * self.sd:
             raise ValueError("state: must be exactly [L][B][d]")
         p_out = _dev(tokens_out, torch.int32, G * B, "tokens_out")
         p_lg = None if logits is None else _dev(logits, torch.float32, B * self.vocab, "logits")
@@ -301,11 +307,11 @@ class Model:
         if N < 1:
             raise ValueError("offsets: need at least two boundaries")
         d_off = torch.from_numpy(h_off).to(tokens.device)
-        Bt = state.numel() // (self.L * self.d)
-        if state.numel() != self.L * Bt * self.d:
+        Bt = state.numel() // (self.L * self.sd)
+        if state.numel() != self.L * Bt * self.sd:
             raise ValueError("state: must be [L][state_batch][d]")
         p_tk = _dev(tokens, torch.int32, int(h_off[-1]), "tokens")
-        p_st = _dev(state, self.state_torch_dtype, self.L * Bt * self.d, "state")
+        p_st = _dev(state, self.state_torch_dtype, self.L * Bt * self.sd, "state")
         p_nt = _dev(next_tok, torch.int32, Bt, "next_tok")
         p_sl = None if slot is None else _dev(slot, torch.int32, N, "slot")
         p_pos = None if pos is None else _dev(pos, torch.int32, Bt, "pos")
@@ -328,7 +334,7 @@ class Model:
 
     def mixer_update(self, layer, pos, B, u, state_layer, m, stream=None):
         torch = _torch()
-        n = B * self.d
+        n = B * self.sd
         p_u = _dev(u, self.act_dtype, n, "u")
         p_s = _dev(state_layer, self.state_torch_dtype, n, "state_layer")
         p_m = _dev(m, self.act_dtype, n, "m")

@@ -39,7 +39,7 @@ struct GemmEpi {
     // lam: [H]; dh = ldo / H.
     void *state;
     const float *alpha, *beta, *lam;
-    int32_t n_ctx, H, dh, state_half;
+    int32_t n_ctx, hrow, dh, state_half;   // heads 0..hrow-1 row-repeat, the rest column-repeat
 };
 
 // Position that keys the random numbers of output row `row` (rows >= M read nothing).
@@ -86,7 +86,7 @@ __device__ __forceinline__ void epi_store(const GemmEpi &ep, int64_t row, int co
         if (pos < 0 || pos >= ep.n_ctx) { store1(o, 0.0f); return; }
         const int h = col / ep.dh;
         const float a = ep.alpha[(size_t)h * ep.n_ctx + pos], be = ep.beta[(size_t)h * ep.n_ctx + pos], l = ep.lam[h];
-        const bool row_repeat = h < ep.H / 2;
+        const bool row_repeat = h < ep.hrow;
         const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
         const float u = (float)(TAct)v;                 // u in the activation type, as the unfused path stores it
         float n;
@@ -166,7 +166,7 @@ __device__ __forceinline__ void epi_store4(const GemmEpi &ep, int64_t row, int c
         if (pos < 0 || pos >= ep.n_ctx) { store4(o, make_float4(0.f, 0.f, 0.f, 0.f)); return; }
         const int h = col / ep.dh;
         const float a = ep.alpha[(size_t)h * ep.n_ctx + pos], be = ep.beta[(size_t)h * ep.n_ctx + pos], l = ep.lam[h];
-        const bool row_repeat = h < ep.H / 2;
+        const bool row_repeat = h < ep.hrow;
         const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
         const int64_t sj = (row * ep.ldo + col) >> 2;
         float4 n, m;
@@ -324,7 +324,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                     // the state update of NIT rows: positions, coefficients and old states are all
                     // requested before the first is used
                     const int h = gcol / ep.dh;
-                    const bool row_repeat = h < ep.H / 2;
+                    const bool row_repeat = h < ep.hrow;
                     const float l = ep.lam[h];
                     int ps[NIT];
                     float al[NIT], be[NIT];

@@ -13,7 +13,10 @@
 // Both head types share one update, S' = lam*S + p*u ; m = q*S' + beta, with
 // (p, q) = (alpha, 1) for row-repeat heads and (1, alpha) for column-repeat
 // heads; multiplying by the constant 1 is exact, so this is Eq. 2 / Eq. 3 as
-// written.  alpha, beta: [H][n_ctx] of this layer; lam: [H].
+// written.  alpha, beta: [H][n_ctx] of this layer; lam: [H].  Heads 0..hrow-1
+// are row-repeat, heads hrow..H-1 column-repeat (hrow = H/2: the mixed layout;
+// H or 0: one kind only).  H and d are the mixer's: a model with combined heads
+// runs as 2H heads over a row of width 2d (see srm_init_weights).
 #pragma once
 #include "common.hpp"
 
@@ -29,7 +32,7 @@ template <typename TAct, int UNROLL, typename TState = float>
 __global__ void __launch_bounds__(256)
 state_update_kernel(const TAct *__restrict__ u, TState *__restrict__ S, TAct *__restrict__ m,
                     const float *__restrict__ alpha, const float *__restrict__ beta,
-                    const float *__restrict__ lam, int pos, const int *__restrict__ pos_dev, int n_ctx, int H,
+                    const float *__restrict__ lam, int pos, const int *__restrict__ pos_dev, int n_ctx, int H, int hrow,
                     int d, int64_t nvec)
 {
     __shared__ float4 coef[kMaxHeads];      // (lam, p, q, beta) per head
@@ -37,7 +40,7 @@ state_update_kernel(const TAct *__restrict__ u, TState *__restrict__ S, TAct *__
     if (threadIdx.x < H) {
         const int h = threadIdx.x;
         const float a = alpha[(size_t)h * n_ctx + pos];
-        const bool row_repeat = h < H / 2;
+        const bool row_repeat = h < hrow;
         coef[h] = make_float4(lam[h], row_repeat ? a : 1.0f, row_repeat ? 1.0f : a,
                               beta[(size_t)h * n_ctx + pos]);
     }
@@ -82,7 +85,7 @@ template <typename TAct, typename TState = float>
 __global__ void __launch_bounds__(256)
 mixer_scan_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, TState *__restrict__ S,
                   const float *__restrict__ alpha, const float *__restrict__ beta,
-                  const float *__restrict__ lam, int n_ctx, int H, int d, int nseq, int P,
+                  const float *__restrict__ lam, int n_ctx, int H, int hrow, int d, int nseq, int P,
                   int64_t seq0, int rep)
 {
     extern __shared__ float sc[];
@@ -99,7 +102,7 @@ mixer_scan_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, TState *__re
     if (seq >= nseq) return;
     const int cv = (int)(gid - seq * dv);
     const int h = cv / dhv;
-    const bool row_repeat = h < H / 2;
+    const bool row_repeat = h < hrow;
     const float l = lam[h];
     const TAct *up = u + (seq * P) * (int64_t)d + cv * 4;
     TAct *mp = m + (seq * P) * (int64_t)d + cv * 4;
@@ -135,7 +138,7 @@ np_token_mix_kernel(float *x, TState *__restrict__ S, TAct *__restrict__ out, co
                     const float *__restrict__ b1, const float *__restrict__ g2, const float *__restrict__ b2,
                     const float *__restrict__ alpha, const float *__restrict__ beta,
                     const float *__restrict__ lam, int pos, const int *__restrict__ pos_dev,
-                    const int *__restrict__ pos_rows, int n_ctx, int H, int d, int64_t rows, float eps)
+                    const int *__restrict__ pos_rows, int n_ctx, int H, int hrow, int d, int64_t rows, float eps)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -181,7 +184,7 @@ np_token_mix_kernel(float *x, TState *__restrict__ S, TAct *__restrict__ out, co
                 const float u3 = (float)(TAct)((v[i].w - mean) * rstd * gg.w + bb.w);
                 const int h = c / dh;
                 const float a = alpha[(size_t)h * n_ctx + p], be = beta[(size_t)h * n_ctx + p], l = lam[h];
-                const bool row_repeat = h < H / 2;
+                const bool row_repeat = h < hrow;
                 const float pp = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
                 const int64_t sj = (row * d + c) >> 2;
                 const float4 sv = load_state4(S, sj);
@@ -235,7 +238,7 @@ template <typename TAct, typename TState = float>
 __global__ void __launch_bounds__(256)
 state_update_ragged_kernel(const TAct *__restrict__ u, TState *__restrict__ S, TAct *__restrict__ m,
                            const float *__restrict__ alpha, const float *__restrict__ beta,
-                           const float *__restrict__ lam, const int *__restrict__ pos_rows, int n_ctx, int H,
+                           const float *__restrict__ lam, const int *__restrict__ pos_rows, int n_ctx, int H, int hrow,
                            int d, int64_t nvec)
 {
     const int dv = d >> 2, dhv = (d / H) >> 2;
@@ -249,7 +252,7 @@ state_update_ragged_kernel(const TAct *__restrict__ u, TState *__restrict__ S, T
         return;
     }
     const float a = alpha[(size_t)h * n_ctx + pos], be = beta[(size_t)h * n_ctx + pos], l = lam[h];
-    const bool row_repeat = h < H / 2;
+    const bool row_repeat = h < hrow;
     const float p = row_repeat ? a : 1.0f, q = row_repeat ? 1.0f : a;
     const float4 sv = load_state4(S, j);
     const float4 x = load4(u + j * 4);
@@ -274,7 +277,7 @@ template <typename TAct, typename TState = float>
 __global__ void __launch_bounds__(256)
 mixer_scan_ragged_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, TState *__restrict__ S,
                          const float *__restrict__ alpha, const float *__restrict__ beta,
-                         const float *__restrict__ lam, int n_ctx, int H, int d, int nseq, int Pmax,
+                         const float *__restrict__ lam, int n_ctx, int H, int hrow, int d, int nseq, int Pmax,
                          const int32_t *__restrict__ offsets, int64_t base, int64_t rows, int64_t seq0, int rep,
                          const int32_t *__restrict__ slot, int64_t nslots)
 {
@@ -292,7 +295,7 @@ mixer_scan_ragged_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, TStat
     if (seq >= nseq) return;
     const int cv = (int)(gid - seq * dv);
     const int h = cv / dhv;
-    const bool row_repeat = h < H / 2;
+    const bool row_repeat = h < hrow;
     const float l = lam[h];
     const int64_t r0 = min(max((int64_t)offsets[seq0 + seq] - base, (int64_t)0), rows);
     const int64_t r1 = min(max((int64_t)offsets[seq0 + seq + 1] - base, r0), rows);
@@ -352,7 +355,7 @@ __device__ __forceinline__ void scan_chunk_range(int64_t seq, int P, const int32
 template <typename TAct>
 __global__ void __launch_bounds__(256)
 scan_chunk_partials_kernel(const TAct *__restrict__ u, float *__restrict__ F, const float *__restrict__ alpha,
-                           const float *__restrict__ lam, int n_ctx, int H, int d, int nseq, int P, int c,
+                           const float *__restrict__ lam, int n_ctx, int H, int hrow, int d, int nseq, int P, int c,
                            int nchunks, const int32_t *__restrict__ offsets, int64_t base, int64_t rows,
                            int64_t seq0)
 {
@@ -369,7 +372,7 @@ scan_chunk_partials_kernel(const TAct *__restrict__ u, float *__restrict__ F, co
     const int t0 = j * c, t1 = min(t0 + c, len);
     if (t0 >= len) return;
     const int h = cv / dhv;
-    const bool row_repeat = h < H / 2;
+    const bool row_repeat = h < hrow;
     const float l = lam[h];
     const TAct *up = u + r0 * (int64_t)d + cv * 4;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -388,7 +391,7 @@ template <typename TAct>
 __global__ void __launch_bounds__(256)
 scan_chunk_apply_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float *__restrict__ S,
                         const float *__restrict__ F, const float *__restrict__ alpha,
-                        const float *__restrict__ beta, const float *__restrict__ lam, int n_ctx, int H, int d,
+                        const float *__restrict__ beta, const float *__restrict__ lam, int n_ctx, int H, int hrow, int d,
                         int nseq, int P, int c, int nchunks, const int32_t *__restrict__ offsets, int64_t base,
                         int64_t rows, int64_t seq0, int rep, const int32_t *__restrict__ slot, int64_t nslots)
 {
@@ -405,7 +408,7 @@ scan_chunk_apply_kernel(const TAct *__restrict__ u, TAct *__restrict__ m, float 
     const int t0 = j * c, t1 = min(t0 + c, len);
     if (t0 >= len) return;
     const int h = cv / dhv;
-    const bool row_repeat = h < H / 2;
+    const bool row_repeat = h < hrow;
     const float l = lam[h];
     float lc = 1.0f;                               // lam^c
     for (int i = 0; i < c; ++i) lc *= l;
@@ -454,7 +457,7 @@ template <typename TAct>
 __global__ void __launch_bounds__(256)
 mixer_parallel_kernel(const TAct *__restrict__ U, TAct *__restrict__ Y,
                       const float *__restrict__ alpha, const float *__restrict__ beta,
-                      const float *__restrict__ lam, int n_ctx, int H, int d, int T)
+                      const float *__restrict__ lam, int n_ctx, int H, int hrow, int d, int T)
 {
     extern __shared__ float pw[];            // [T]
     __shared__ float Ms[64][64 + 4];         // [i][j]
@@ -464,7 +467,7 @@ mixer_parallel_kernel(const TAct *__restrict__ U, TAct *__restrict__ Y,
     const int h = blockIdx.y / ctiles, ct = blockIdx.y % ctiles;
     const int jt = blockIdx.x, b = blockIdx.z;
     const int tid = threadIdx.x;
-    const bool row_repeat = h < H / 2;
+    const bool row_repeat = h < hrow;
     const float *al = alpha + (size_t)h * n_ctx;
     const double lh = (double)lam[h];
     for (int k = tid; k < T; k += 256) pw[k] = (float)pow(lh, (double)k);

@@ -59,6 +59,13 @@ struct srm_model {
     srm_config cfg;
     int device;
     int d, ff, V, L, H;
+    // The mixer's own geometry: row width dm, Hs heads of which the first hrow are row-repeat.
+    // Mixed, row-only and column-only layouts: dm = d, Hs = H.  Combined heads (one row-repeat
+    // and one column-repeat matrix per head, outputs added) run as a mixer of width 2d with 2H
+    // heads, the H row-repeat ones first: the in-projection's rows and the out-projection's
+    // columns are stored twice, so that both halves see the same input and the out-projection
+    // adds their outputs.
+    int dm, Hs, hrow;
     bool noproj;           // non-projected mixer layers
     bool shalf;            // recurrent state (and lambda) in binary16
     size_t ssize;          // bytes per state element
@@ -109,8 +116,15 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     if (cfg->vocab <= 0 || cfg->d_model <= 0 || cfg->n_layers <= 0 || cfg->n_heads <= 0 ||
         cfg->mlp_expansion <= 0 || cfg->n_ctx <= 0)
         return fail(SRM_EINVAL, "srm_init_weights: sizes must be positive");
-    if (cfg->n_heads % 2 || cfg->n_heads > kMaxHeads)
-        return fail(SRM_EINVAL, "srm_init_weights: n_heads must be even and <= %d", kMaxHeads);
+    const int layout = cfg->head_layout;
+    if (layout < SRM_HEADS_MIXED || layout > SRM_HEADS_COMBINED)
+        return fail(SRM_EINVAL, "srm_init_weights: unknown head_layout %d", layout);
+    const int slots = cfg->n_heads * (layout == SRM_HEADS_COMBINED ? 2 : 1);
+    if ((layout == SRM_HEADS_MIXED && cfg->n_heads % 2) || slots > kMaxHeads)
+        return fail(SRM_EINVAL, "srm_init_weights: n_heads must be even for mixed heads, and at most %d "
+                                "coefficient rows per layer", kMaxHeads);
+    if (layout == SRM_HEADS_COMBINED && cfg->no_projections)
+        return fail(SRM_EINVAL, "srm_init_weights: combined heads need the head projections");
     if (cfg->d_model % (4 * cfg->n_heads))
         return fail(SRM_EINVAL, "srm_init_weights: d_model must be a multiple of 4*n_heads");
     if (cfg->d_model > 4096) return fail(SRM_EINVAL, "srm_init_weights: d_model > 4096 unsupported");
@@ -133,7 +147,7 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
             if (!p) return fail(SRM_EINVAL, "srm_init_weights: null weight pointer in layer %d", l);
         if (!cfg->no_projections && (!y.w_in || !y.b_in || !y.w_out || !y.b_out))
             return fail(SRM_EINVAL, "srm_init_weights: null projection weights in layer %d", l);
-        for (int h = 0; h < H; ++h)
+        for (int h = 0; h < slots; ++h)
             if (!(y.lambda[h] > 0.0f && y.lambda[h] <= 1.0f))
                 return fail(SRM_EINVAL, "srm_init_weights: lambda[%d][%d] = %g outside (0, 1]", l, h,
                             (double)y.lambda[h]);
@@ -143,6 +157,10 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     if (!m) return fail(SRM_ENOMEM, "srm_init_weights: host allocation failed");
     m->cfg = *cfg;
     m->d = d; m->ff = (int)ff; m->V = V; m->L = L; m->H = H;
+    const bool comb = layout == SRM_HEADS_COMBINED;
+    m->dm = comb ? 2 * d : d;
+    m->Hs = slots;
+    m->hrow = layout == SRM_HEADS_MIXED ? H / 2 : layout == SRM_HEADS_COLUMN ? 0 : H;
     m->noproj = cfg->no_projections != 0;
     m->shalf = cfg->state_dtype == SRM_FP16;
     m->ssize = m->shalf ? 2 : 4;
@@ -166,16 +184,37 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
             size_t *o = lo[l].v;
             o[0] = sb.add(y.ln1_g, d, false);          o[1] = sb.add(y.ln1_b, d, false);
             const bool pj = !m->noproj;
-            o[2] = pj ? sb.add(y.w_in, (size_t)d * d, bf) : 0;   o[3] = pj ? sb.add(y.b_in, d, false) : 0;
-            o[4] = sb.add(y.alpha, H * nc, false);      o[5] = sb.add(y.beta, H * nc, false);
+            if (comb) {
+                // W_in [d][d] -> [2d][d] (rows repeated), W_out [d][d] -> [d][2d] (columns repeated)
+                std::vector<float> t((size_t)2 * d * d);
+                memcpy(t.data(), y.w_in, (size_t)d * d * 4);
+                memcpy(t.data() + (size_t)d * d, y.w_in, (size_t)d * d * 4);
+                o[2] = sb.add(t.data(), t.size(), bf);
+                memcpy(t.data(), y.b_in, (size_t)d * 4);
+                memcpy(t.data() + d, y.b_in, (size_t)d * 4);
+                o[3] = sb.add(t.data(), (size_t)2 * d, false);
+            } else {
+                o[2] = pj ? sb.add(y.w_in, (size_t)d * d, bf) : 0;   o[3] = pj ? sb.add(y.b_in, d, false) : 0;
+            }
+            o[4] = sb.add(y.alpha, slots * nc, false);  o[5] = sb.add(y.beta, slots * nc, false);
             if (m->shalf) {                              // decay constants as binary16 values
                 float lh[kMaxHeads];
-                for (int h = 0; h < H; ++h) lh[h] = (float)(_Float16)y.lambda[h];
-                o[6] = sb.add(lh, H, false);
+                for (int h = 0; h < slots; ++h) lh[h] = (float)(_Float16)y.lambda[h];
+                o[6] = sb.add(lh, slots, false);
             } else {
-                o[6] = sb.add(y.lambda, H, false);
+                o[6] = sb.add(y.lambda, slots, false);
             }
-            o[7] = pj ? sb.add(y.w_out, (size_t)d * d, bf) : 0;  o[8] = pj ? sb.add(y.b_out, d, false) : 0;
+            if (comb) {
+                std::vector<float> t((size_t)2 * d * d);
+                for (int i = 0; i < d; ++i) {
+                    memcpy(t.data() + (size_t)i * 2 * d, y.w_out + (size_t)i * d, (size_t)d * 4);
+                    memcpy(t.data() + (size_t)i * 2 * d + d, y.w_out + (size_t)i * d, (size_t)d * 4);
+                }
+                o[7] = sb.add(t.data(), t.size(), bf);
+                o[8] = sb.add(y.b_out, d, false);
+            } else {
+                o[7] = pj ? sb.add(y.w_out, (size_t)d * d, bf) : 0;  o[8] = pj ? sb.add(y.b_out, d, false) : 0;
+            }
             o[9] = sb.add(y.ln2_g, d, false);           o[10] = sb.add(y.ln2_b, d, false);
             o[11] = sb.add(y.w_up, ff * d, bf);         o[12] = sb.add(y.b_up, ff, false);
             o[13] = sb.add(y.w_down, (size_t)d * ff, bf); o[14] = sb.add(y.b_down, d, false);
@@ -225,13 +264,13 @@ extern "C" void srm_free(srm_model *m)
 extern "C" size_t srm_state_bytes(const srm_model *m, int64_t batch)
 {
     if (!m || batch <= 0) return 0;
-    return (size_t)m->L * (size_t)batch * (size_t)m->d * m->ssize;
+    return (size_t)m->L * (size_t)batch * (size_t)m->dm * m->ssize;
 }
 
-// Layer l's [B][d] slab of a state array.
+// Layer l's [B][dm] slab of a state array.
 static void *layer_state(const srm_model *m, void *state, int l, int64_t B)
 {
-    return static_cast<unsigned char *>(state) + (size_t)l * (size_t)B * (size_t)m->d * m->ssize;
+    return static_cast<unsigned char *>(state) + (size_t)l * (size_t)B * (size_t)m->dm * m->ssize;
 }
 
 // ------------------------------------------------------------------ workspace
@@ -240,7 +279,8 @@ static int head_min_bn(const srm_model *m) { return m->cfg.weight_dtype == SRM_B
 
 struct Workspace {
     float *x;          // [rows][d]  residual stream
-    void *a, *u, *mx;  // [rows][d]  activation type
+    void *a;           // [rows][d]  activation type
+    void *u, *mx;      // [rows][dm] activation type: mixer input and output
     void *g;           // [rows][ff] activation type
     float *pv;         // [rows][nparts]
     int32_t *pi;       // [rows][nparts]
@@ -271,12 +311,12 @@ static Workspace carve(const srm_model *m, void *base, int64_t rows)
         off += align_up(bytes, 256);
         return r;
     };
-    const size_t r = (size_t)rows, d = m->d, s = m->wsize;
+    const size_t r = (size_t)rows, d = m->d, dm = m->dm, s = m->wsize;
     const size_t nparts = cdiv(m->V, head_min_bn(m));
     w.x = reinterpret_cast<float *>(take(r * d * 4));
     w.a = take(r * d * s);
-    w.u = m->noproj ? w.a : take(r * d * s);      // without projections the mixer reads the LayerNorm output
-    w.mx = take(r * d * s);
+    w.u = m->noproj ? w.a : take(r * dm * s);     // without projections the mixer reads the LayerNorm output
+    w.mx = take(r * dm * s);
     w.g = take(r * (size_t)m->ff * s);
     w.pv = reinterpret_cast<float *>(take(r * nparts * 4));
     w.pi = reinterpret_cast<int32_t *>(take(r * nparts * 4));
@@ -425,7 +465,7 @@ static int nucleus(const float *logits, int64_t rows, int V, const Sampling &sm,
 struct MixArgs {           // EPI_MIX: state slab of the layer and its coefficient tables
     void *state = nullptr;
     const float *alpha = nullptr, *beta = nullptr, *lam = nullptr;
-    int n_ctx = 0, H = 0, dh = 0, state_half = 0;
+    int n_ctx = 0, hrow = 0, dh = 0, state_half = 0;
 };
 
 // out = epilogue(A W^T + bias) with operands of type T (float or bf16)
@@ -435,7 +475,7 @@ static int linear(const void *A, const void *W, const float *bias, int64_t M, in
                   int *nparts_out = nullptr, Sampling sm = Sampling(), int ksplit = 1, MixArgs mx = MixArgs())
 {
     GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, sm.row_base,
-               mx.state, mx.alpha, mx.beta, mx.lam, mx.n_ctx, mx.H, mx.dh, mx.state_half};
+               mx.state, mx.alpha, mx.beta, mx.lam, mx.n_ctx, mx.hrow, mx.dh, mx.state_half};
     if constexpr (sizeof(T) == 2)
         return launch_bf16<EPI, bf16>(static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), M, N, K, ep,
                                       st, min_bn, nparts_out, ksplit);
@@ -506,7 +546,7 @@ static int state_update(const srm_model *m, int layer, int pos, int64_t B, const
     // one channel group.
     constexpr int UNROLL = 2;
     const LayerDev &y = m->layers[layer];
-    const int dv = m->d / 4;
+    const int dv = m->dm / 4;
     const int64_t nvec = B * dv;
     int a = dv, b = 256;
     while (b) { int t = a % b; a = b; b = t; }
@@ -515,11 +555,11 @@ static int state_update(const srm_model *m, int layer, int pos, int64_t B, const
     if (m->shalf)
         hipLaunchKernelGGL((state_update_kernel<T, UNROLL, f16>), dim3((unsigned)nb), dim3(256), 0, st,
                            static_cast<const T *>(u), static_cast<f16 *>(S), static_cast<T *>(mx), y.alpha, y.beta,
-                           y.lam, pos, pos_dev, m->cfg.n_ctx, m->H, m->d, nvec);
+                           y.lam, pos, pos_dev, m->cfg.n_ctx, m->Hs, m->hrow, m->dm, nvec);
     else
         hipLaunchKernelGGL((state_update_kernel<T, UNROLL>), dim3((unsigned)nb), dim3(256), 0, st,
                            static_cast<const T *>(u), static_cast<float *>(S), static_cast<T *>(mx), y.alpha, y.beta,
-                           y.lam, pos, pos_dev, m->cfg.n_ctx, m->H, m->d, nvec);
+                           y.lam, pos, pos_dev, m->cfg.n_ctx, m->Hs, m->hrow, m->dm, nvec);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
 }
@@ -539,7 +579,7 @@ static int check_device(const srm_model *m)
 // work: below this many state elements per layer the state update is fused into
 // the in-projection.  Above it the separate streaming kernel (HBM-bound, two
 // state vectors per thread) is the faster arrangement.
-static bool fuse_mixer(const srm_model *m, int64_t rows) { return !m->noproj && rows * m->d <= (1 << 20); }
+static bool fuse_mixer(const srm_model *m, int64_t rows) { return !m->noproj && rows * m->dm <= (1 << 20); }
 
 // One block (token mixing + channel mixing) on `rows` token rows.  On entry
 // w.a holds LayerNorm1(x) of this layer; mix(l) turns w.u into w.mx.  With
@@ -551,7 +591,7 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
                  void *np_state = nullptr)
 {
     const LayerDev &y = m->layers[l];
-    const int d = m->d, ff = m->ff;
+    const int d = m->d, dm = m->dm, ff = m->ff;
     // split-K down projection (decode with few rows, bf16): see kSplitK
     // (not with the fused non-projected layer: no LayerNorm kernel follows there to add the slabs)
     const bool split = allow_split && norm_next && sizeof(T) == 2 && w.part && ff >= 1024 &&
@@ -563,7 +603,7 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
     hipLaunchKernelGGL((np_token_mix_kernel<T, VPL, TS>), dim3(nb), dim3(256), 0, st, w.x,                     \
                        static_cast<TS *>(np_state), static_cast<T *>(w.a), y.ln1_g, y.ln1_b, y.ln2_g, y.ln2_b, \
                        y.alpha, y.beta, y.lam, fuse_pos.pos, fuse_pos.pos_dev, fuse_pos.pos_rows, m->cfg.n_ctx, \
-                       m->H, d, rows, m->cfg.ln_eps)
+                       m->Hs, m->hrow, d, rows, m->cfg.ln_eps)
 #define NP_CASE(VPL)                                                                                          \
     do {                                                                                                      \
         if (m->shalf) NP_LAUNCH(VPL, f16);                                                                    \
@@ -584,11 +624,11 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
                                      0, w.mx)));
     } else if (fuse_state) {
         // few rows: the state update rides in the in-projection's epilogue (one kernel less per layer)
-        const MixArgs mx{fuse_state, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d / m->H, m->shalf ? 1 : 0};
-        SRM_TRY((linear<EPI_MIX, T>(w.a, y.w_in, y.b_in, rows, d, d, w.mx, st, nullptr, nullptr, 64, nullptr, fuse_pos,
+        const MixArgs mx{fuse_state, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->hrow, dm / m->Hs, m->shalf ? 1 : 0};
+        SRM_TRY((linear<EPI_MIX, T>(w.a, y.w_in, y.b_in, rows, dm, d, w.mx, st, nullptr, nullptr, 64, nullptr, fuse_pos,
                                     1, mx)));
     } else {
-        SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, d, d, w.u, st)));
+        SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, dm, d, w.u, st)));
         SRM_TRY(mix(l));
     }
     // fp32, few rows: K slices of the residual GEMVs, chosen so that a slice keeps at least 64 k
@@ -599,14 +639,14 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
         return sp;
     };
     if (!m->noproj) {
-        const int sp = gemv_split(d);
+        const int sp = gemv_split(dm);
         if (sp > 1) {
-            SRM_TRY((linear<EPI_F32, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.part, st, nullptr, nullptr, 64, nullptr,
+            SRM_TRY((linear<EPI_F32, T>(w.mx, y.w_out, y.b_out, rows, d, dm, w.part, st, nullptr, nullptr, 64, nullptr,
                                         Sampling(), sp)));
             SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, y.ln2_g, y.ln2_b, w.a, rows, st, nullptr, 0, 0, w.part,
                                          sp)));
         } else {
-            SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, d, w.x, st)));
+            SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, dm, w.x, st)));
             SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
         }
     }
@@ -669,26 +709,26 @@ template <typename T>
 static int decode_rows(srm_model *m, const DecodeArgs &a, int64_t b0, int64_t nb, void *ws, hipStream_t st)
 {
     const Workspace w = carve(m, ws, nb);
-    const int d = m->d;
+    const int d = m->d, dm = m->dm;
     int32_t *pos_rows = a.pos_rows ? a.pos_rows + b0 : nullptr;
     auto slab = [&](int l) {       // rows b0.. of layer l's state
         return static_cast<void *>(static_cast<unsigned char *>(layer_state(m, a.state, l, a.B)) +
-                                   (size_t)b0 * d * m->ssize);
+                                   (size_t)b0 * dm * m->ssize);
     };
     SRM_TRY((layernorm<T, true>(m, nullptr, 0, a.tok_in + b0, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a, nb,
                                 st)));
     auto mix = [&](int l) {
         if (!pos_rows) return state_update<T>(m, l, a.pos, nb, w.u, slab(l), w.mx, st, a.pos_dev);
         const LayerDev &y = m->layers[l];
-        const int64_t nvec = nb * (d / 4);
+        const int64_t nvec = nb * (dm / 4);
         if (m->shalf)
             hipLaunchKernelGGL((state_update_ragged_kernel<T, f16>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
                                static_cast<const T *>(w.u), static_cast<f16 *>(slab(l)), static_cast<T *>(w.mx),
-                               y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
+                               y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->Hs, m->hrow, dm, nvec);
         else
             hipLaunchKernelGGL((state_update_ragged_kernel<T>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
                                static_cast<const T *>(w.u), static_cast<float *>(slab(l)), static_cast<T *>(w.mx),
-                               y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
+                               y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->Hs, m->hrow, dm, nvec);
         HIP_TRY(hipGetLastError());
         return (int)SRM_OK;
     };
@@ -795,19 +835,19 @@ static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int ad
                               float temperature, uint32_t seed, float top_p)
 {
     const Workspace w = carve(m, ws, B);
-    const int d = m->d;
+    const int dm = m->dm;
     SRM_TRY((layernorm<T, true>(m, nullptr, 0, tok_in, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a, B, st)));
     auto mix = [&](int l) {
         const LayerDev &y = m->layers[l];
-        const int64_t nvec = B * (d / 4);
+        const int64_t nvec = B * (dm / 4);
         if (m->shalf)
             hipLaunchKernelGGL((state_update_ragged_kernel<T, f16>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
                                static_cast<const T *>(w.u), static_cast<f16 *>(layer_state(m, state, l, B)),
-                               static_cast<T *>(w.mx), y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
+                               static_cast<T *>(w.mx), y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->Hs, m->hrow, dm, nvec);
         else
             hipLaunchKernelGGL((state_update_ragged_kernel<T>), dim3((unsigned)cdiv(nvec, 256)), dim3(256), 0, st,
                                static_cast<const T *>(w.u), static_cast<float *>(layer_state(m, state, l, B)),
-                               static_cast<T *>(w.mx), y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->H, d, nvec);
+                               static_cast<T *>(w.mx), y.alpha, y.beta, y.lam, pos_rows, m->cfg.n_ctx, m->Hs, m->hrow, dm, nvec);
         HIP_TRY(hipGetLastError());
         return (int)SRM_OK;
     };
@@ -972,7 +1012,7 @@ static int64_t seqs_per_pass(const srm_model *m, size_t workspace_bytes, int T, 
 // workspace cuts it into passes, so results do not depend on the workspace size.
 static int scan_chunk_len(const srm_model *m, int64_t nseq, int P)
 {
-    const int64_t dv = m->d / 4;
+    const int64_t dv = m->dm / 4;
     if (P < 64 || nseq * dv >= 65536 || m->shalf) return 0;   // a half-precision cache is rounded at every step
     for (int c : {16, 32, 64, 128}) {
         const int64_t nch = cdiv(P, c);
@@ -989,32 +1029,32 @@ static int prefill_mixer(const srm_model *m, int l, const Workspace &w, void *S_
                          const int32_t *slot, int64_t nslots, hipStream_t st)
 {
     const LayerDev &y = m->layers[l];
-    const int d = m->d;
+    const int d = m->dm;           // the mixer's row width
     if (chunk > 0) {
         float *F = static_cast<float *>(w.g);       // free until the MLP of this layer
         const unsigned nb = (unsigned)cdiv((int64_t)nc * nchunks * (d / 4), 256);
         hipLaunchKernelGGL((scan_chunk_partials_kernel<T>), dim3(nb), dim3(256), 0, st, static_cast<const T *>(w.u), F,
-                           y.alpha, y.lam, m->cfg.n_ctx, m->H, d, nc, P, chunk, nchunks, offsets, base, rows, seq0);
+                           y.alpha, y.lam, m->cfg.n_ctx, m->Hs, m->hrow, d, nc, P, chunk, nchunks, offsets, base, rows, seq0);
         HIP_TRY(hipGetLastError());
         hipLaunchKernelGGL((scan_chunk_apply_kernel<T>), dim3(nb), dim3(256), 0, st, static_cast<const T *>(w.u),
                            static_cast<T *>(w.mx), static_cast<float *>(S_layer), F, y.alpha, y.beta, y.lam,
-                           m->cfg.n_ctx, m->H, d, nc, P, chunk, nchunks, offsets, base, rows, seq0, rep, slot, nslots);
+                           m->cfg.n_ctx, m->Hs, m->hrow, d, nc, P, chunk, nchunks, offsets, base, rows, seq0, rep, slot, nslots);
         HIP_TRY(hipGetLastError());
         return SRM_OK;
     }
     const unsigned nb = (unsigned)cdiv((int64_t)nc * (d / 4), 256);
-    const size_t scan_lds = (size_t)2 * m->H * P * sizeof(float);
+    const size_t scan_lds = (size_t)2 * m->Hs * P * sizeof(float);
 #define SCAN_LAUNCH(TS)                                                                                        \
     do {                                                                                                       \
         if (offsets)                                                                                           \
             hipLaunchKernelGGL((mixer_scan_ragged_kernel<T, TS>), dim3(nb), dim3(256), scan_lds, st,           \
                                static_cast<const T *>(w.u), static_cast<T *>(w.mx), static_cast<TS *>(S_layer), \
-                               y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc, P, offsets, base, rows, seq0, \
+                               y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->Hs, m->hrow, d, nc, P, offsets, base, rows, seq0, \
                                rep, slot, nslots);                                                             \
         else                                                                                                   \
             hipLaunchKernelGGL((mixer_scan_kernel<T, TS>), dim3(nb), dim3(256), scan_lds, st,                  \
                                static_cast<const T *>(w.u), static_cast<T *>(w.mx), static_cast<TS *>(S_layer), \
-                               y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->H, d, nc, P, seq0, rep);               \
+                               y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->Hs, m->hrow, d, nc, P, seq0, rep);     \
     } while (0)
     if (m->shalf) SCAN_LAUNCH(f16);
     else SCAN_LAUNCH(float);
@@ -1059,7 +1099,7 @@ extern "C" int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, in
     if (N <= 0 || P <= 0 || fanout_k <= 0) return fail(SRM_EINVAL, "srm_prefill: N, P and fanout_k must be positive");
     if (P > m->cfg.n_ctx) return fail(SRM_EINVAL, "srm_prefill: P = %d exceeds n_ctx = %d", P, m->cfg.n_ctx);
     if ((int64_t)N * fanout_k >= (1 << 30)) return fail(SRM_EINVAL, "srm_prefill: N * fanout_k too large");
-    if ((size_t)2 * m->H * P * sizeof(float) > 64 * 1024)
+    if ((size_t)2 * m->Hs * P * sizeof(float) > 64 * 1024)
         return fail(SRM_EINVAL, "srm_prefill: n_heads * P too large for the coefficient stage");
     const int64_t max_seqs = std::max<int64_t>(1, ((1 << 30) - 1) / P);
     int64_t per_pass = seqs_per_pass(m, workspace_bytes, P, std::min<int64_t>(N, max_seqs));
@@ -1151,7 +1191,7 @@ extern "C" int srm_prefill_ragged(srm_model *m, const int32_t *d_tokens, const i
                         srm_workspace_bytes(m, len), n, (long long)len);
         pmax = std::max(pmax, (int)len);
     }
-    if ((size_t)2 * m->H * pmax * sizeof(float) > 64 * 1024)
+    if ((size_t)2 * m->Hs * pmax * sizeof(float) > 64 * 1024)
         return fail(SRM_EINVAL, "%s: n_heads * longest prompt too large for the coefficient stage", who);
     SRM_TRY(check_device(m));
     hipStream_t st = as_stream(hip_stream);
@@ -1168,7 +1208,7 @@ template <typename T>
 static int parallel_impl(srm_model *m, const int32_t *tok, int B, int T_, float *hidden, float *logits, void *ws,
                          int64_t per_pass, hipStream_t st)
 {
-    const int d = m->d, dh = d / m->H;
+    const int d = m->d, dm = m->dm, dh = dm / m->Hs;
     for (int64_t b0 = 0; b0 < B; b0 += per_pass) {
         const int64_t nc = std::min<int64_t>(per_pass, B - b0);
         const int64_t rows = nc * T_;
@@ -1177,10 +1217,10 @@ static int parallel_impl(srm_model *m, const int32_t *tok, int B, int T_, float 
                                     w.a, rows, st)));
         auto mix = [&](int l) {
             const LayerDev &y = m->layers[l];
-            const dim3 grid((unsigned)cdiv(T_, 64), (unsigned)(m->H * cdiv(dh, 64)), (unsigned)nc);
+            const dim3 grid((unsigned)cdiv(T_, 64), (unsigned)(m->Hs * cdiv(dh, 64)), (unsigned)nc);
             hipLaunchKernelGGL((mixer_parallel_kernel<T>), grid, dim3(256), (size_t)T_ * sizeof(float), st,
                                static_cast<const T *>(w.u), static_cast<T *>(w.mx), y.alpha, y.beta, y.lam,
-                               m->cfg.n_ctx, m->H, d, T_);
+                               m->cfg.n_ctx, m->Hs, m->hrow, dm, T_);
             HIP_TRY(hipGetLastError());
             return (int)SRM_OK;
         };

@@ -192,3 +192,141 @@ def test_half_state_bf16_weights_match_oracle(srm, orc_mod, use_projections, B):
     assert (st.float() - st2.float()).abs().max() <= 2e-2 * st.float().abs().max()
     s_got = st.float().view(cfg.n_layers, B, cfg.d_model)[:, rows].permute(1, 0, 2).cpu().numpy()
     assert np.abs(s_got - ref["state"]).max() <= 2e-2 * np.abs(ref["state"]).max()
+
+
+# ---- head layouts: row-only, column-only, combined ("Method", after Eq. 2; Table S0) ------------
+@pytest.mark.parametrize("layout,H", [("row", 4), ("column", 4), ("combined", 4), ("row", 1), ("combined", 1),
+                                      ("column", 3)])
+def test_head_layouts_fp32_all_paths_match_oracle(srm, orc_mod, layout, H):
+    d = 96 if H == 3 else 64
+    cfg = srm_synth.tiny_config(vocab=300, d_model=d, n_layers=3, n_heads=H, n_ctx=96, seed=71, head_layout=layout)
+    cfg = dataclasses.replace(cfg, name=f"{layout}{H}")
+    w = srm_synth.make_weights(cfg, stress=True)
+    orc = orc_mod.Oracle(cfg, w, "f64")
+    model = srm.Model(cfg, w)
+    sd = cfg.state_width
+    assert model.state_bytes(10) == cfg.n_layers * 10 * sd * 4
+    B, P, G = 6, 12, 10
+    prompts = srm_synth.make_prompts(cfg, batch=B, length=P)
+    ref = orc.greedy(prompts, G, want_logits=True)
+    print(f"head layout {layout} H={H}: prefill + generate", flush=True)
+    ws = model.new_workspace(B * 80)
+    st, tk = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    assert st.shape == (cfg.n_layers, B, sd)
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    model.prefill(to_dev(prompts), 1, st, tk, logits=lg, workspace=ws)
+    assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, 0]) <= 1e-4
+    out = torch.empty((G - 1, B), dtype=torch.int32, device="cuda")
+    first = tk.cpu().numpy().copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        model.generate(B, P, G - 1, tk, st, out, workspace=ws)
+    side.synchronize()
+    got = np.concatenate([first[:, None], out.cpu().numpy().T], axis=1)
+    assert check_tokens(got, ref["tokens"], ref["margin"], np.abs(ref["logits"]).max(axis=2)) == 0
+    s_ref = ref["state"]                                       # [B][L][sd] after P + G - 1 tokens
+    s_got = st.permute(1, 0, 2).cpu().numpy()
+    assert np.abs(s_got - s_ref).max() <= 1e-4 * np.abs(s_ref).max()
+    # teacher-forced steps (fused mixer epilogue at this size), parallel form, chunked prefill of one long prompt
+    T = 80
+    toks = srm_synth.make_prompts(cfg, batch=2, length=T)
+    rf = orc.recurrent_forward(toks)
+    st2 = model.new_state(2)
+    o2 = torch.empty(2, dtype=torch.int32, device="cuda")
+    l2 = torch.empty((2, cfg.vocab), dtype=torch.float32, device="cuda")
+    h2 = torch.empty((2, d), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    for t in range(T):
+        model.decode_step(2, t, tc[t], st2, o2, logits=l2, hidden=h2, workspace=ws)
+        if t % 9 == 0 or t == T - 1:
+            assert rel_err_rows(l2.cpu().numpy(), rf["logits"][:, t]) <= 1e-4
+            assert rel_err_rows(h2.cpu().numpy(), rf["hidden"][:, t]) <= 1e-4
+    hid = torch.empty((2, T, d), dtype=torch.float32, device="cuda")
+    lgp = torch.empty((2, T, cfg.vocab), dtype=torch.float32, device="cuda")
+    model.parallel_forward(to_dev(toks), hid, logits=lgp, workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err_rows(hid.cpu().numpy().reshape(2 * T, -1), rf["hidden"].reshape(2 * T, -1)) <= 1e-4
+    assert rel_err_rows(lgp.cpu().numpy().reshape(2 * T, -1), rf["logits"].reshape(2 * T, -1)) <= 1e-4
+    st3, tk3 = model.new_state(2), torch.empty(2, dtype=torch.int32, device="cuda")
+    model.prefill(to_dev(toks), 1, st3, tk3, logits=l2, workspace=ws)          # 2 prompts x 80: the chunked scan
+    torch.cuda.synchronize()
+    assert rel_err_rows(l2.cpu().numpy(), rf["logits"][:, T - 1]) <= 1e-4
+    assert (st3 - st2).abs().max() <= 1e-4 * st2.abs().max()
+    # ragged prompts and ragged decode
+    lens = [5, 80]
+    pk = np.concatenate([toks[i, :n] for i, n in enumerate(lens)]).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    st4, tk4 = model.new_state(2), torch.empty(2, dtype=torch.int32, device="cuda")
+    pos = torch.empty(2, dtype=torch.int32, device="cuda")
+    keep = model.prefill_ragged(to_dev(pk), off, st4, tk4, pos=pos, logits=l2, workspace=ws)
+    torch.cuda.synchronize()
+    del keep
+    for b, n in enumerate(lens):
+        assert rel_err_rows(l2[b:b + 1].cpu().numpy(), rf["logits"][b:b + 1, n - 1]) <= 1e-4
+    pos[1] = -1                                                # row 1 is at the end of the table: idle
+    model.decode_step_ragged(2, pos, to_dev(toks[:, 5].copy()), st4, tk4, advance=True, logits=l2, workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err_rows(l2[0:1].cpu().numpy(), rf["logits"][0:1, 5]) <= 1e-4
+    assert int(pos[0]) == 6 and int(pos[1]) == -1 and int(tk4[1]) == -1
+
+
+@pytest.mark.parametrize("layout", ["row", "column", "combined"])
+@pytest.mark.parametrize("B", [40, 9000])
+def test_head_layouts_bf16_decode_and_prefill_match_oracle(srm, orc_mod, layout, B):
+    """bf16 weights; B = 9000 takes the separate streaming state update (rows x width above the fusion limit)."""
+    cfg = srm_synth.tiny_config(vocab=520, d_model=128, n_layers=2, n_heads=4, n_ctx=12, weight_dtype="bf16", seed=72,
+                                head_layout=layout)
+    w = srm_synth.make_weights(cfg, stress=True)
+    T = 7
+    toks = srm_synth.make_prompts(cfg, batch=B, length=T)
+    rows = sorted({0, 1, B // 2, B - 1})
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks[rows])
+    model = srm.Model(cfg, w)
+    ws, st = model.new_workspace(B * T if B < 1000 else B), model.new_state(B)
+    out = torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    print(f"head layout {layout} bf16 B={B}", flush=True)
+    for t in range(T):
+        model.decode_step(B, t, tc[t], st, out, logits=lg, workspace=ws)
+        assert rel_err_rows(lg[rows].cpu().numpy(), ref["logits"][:, t]) <= 2e-2
+    s_ref = ref["state"]                                       # [rows][L][sd]
+    s_got = st[:, rows].permute(1, 0, 2).cpu().numpy()
+    assert np.abs(s_got - s_ref).max() <= 2e-2 * np.abs(s_ref).max()
+    st2, tk2 = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    model.prefill(to_dev(toks), 1, st2, tk2, workspace=ws)     # in passes when the workspace is one step's
+    torch.cuda.synchronize()
+    assert (st - st2).abs().max() <= 2e-2 * st.abs().max()
+    assert ((tk2 >= 0) & (tk2 < cfg.vocab)).all()
+
+
+def test_combined_heads_with_half_precision_cache(srm, orc_mod):
+    cfg = srm_synth.tiny_config(vocab=300, d_model=64, n_layers=2, n_heads=2, n_ctx=32, seed=73, head_layout="combined",
+                                state_dtype="fp16")
+    w = srm_synth.make_weights(cfg)
+    toks = srm_synth.make_prompts(cfg, batch=4, length=24)
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks)
+    model = srm.Model(cfg, w)
+    assert model.state_bytes(4) == cfg.n_layers * 4 * 128 * 2
+    ws, st = model.new_workspace(4 * 24), model.new_state(4)
+    out = torch.empty(4, dtype=torch.int32, device="cuda")
+    lg = torch.empty((4, cfg.vocab), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    for t in range(24):
+        model.decode_step(4, t, tc[t], st, out, logits=lg, workspace=ws)
+        assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, t]) <= 2e-3
+    s_got = st.float().permute(1, 0, 2).cpu().numpy()
+    assert np.abs(s_got - ref["state"]).max() <= 2e-3 * np.abs(ref["state"]).max()
+
+
+def test_head_layout_errors(srm):
+    cfg = srm_synth.tiny_config(vocab=64, d_model=64, n_layers=1, n_heads=2, n_ctx=8, head_layout="combined",
+                                use_projections=False)
+    with pytest.raises(srm.SrmError):
+        srm.Model(cfg, srm_synth.make_weights(cfg))            # combined heads need the projections
+    cfg = srm_synth.tiny_config(vocab=64, d_model=96, n_layers=1, n_heads=3, n_ctx=8)
+    with pytest.raises(srm.SrmError):
+        srm.Model(cfg, srm_synth.make_weights(cfg))            # mixed heads: even count
+    cfg = srm_synth.tiny_config(vocab=64, d_model=96, n_layers=1, n_heads=3, n_ctx=8, head_layout="row")
+    srm.Model(cfg, srm_synth.make_weights(cfg)).close()
