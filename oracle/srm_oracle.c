@@ -42,7 +42,9 @@
  * rank-1 generator; causality; constant state size; printed parameter counts;
  * the other head layouts (row-only, column-only, combined) against matrices
  * written out entry by entry, running sums and the sum of a row-only and a
- * column-only model.
+ * column-only model; the k-filter mixer (Eq. 11) against the equation written
+ * out in the paper's orientation and against a running sum of a library
+ * correlation along the hidden dimension.
  * The numerical value of a whole-model logit has no printed example in the
  * paper: for whole-model outputs "parity unpinned" beyond those structural
  * pins and the cross-form identity.
@@ -66,6 +68,7 @@ typedef struct {
     int no_proj;        /* 1: non-projected ("head-parallel") mixer layers, see orc_set_projections */
     int half_state;     /* 1: cache and decay constants in half precision, see orc_set_state_half */
     int layout;         /* ORC_MIXED, ORC_ROW, ORC_COLUMN or ORC_COMBINED, see orc_create_layout */
+    int kmix;           /* > 1: mixer with that many filters along the hidden dimension, see orc_create_kernel */
     double eps;
     real *embed, *head, *lnf_g, *lnf_b;
     orc_layer *layers;
@@ -107,15 +110,17 @@ static real *orc_copy(const float *src, size_t n)
  * w_out[d][d] b_out[d] ln2_g[d] ln2_b[d] w_up[e*d][d] b_up[e*d]
  * w_down[d][e*d] b_down[d].  All float32, row-major [out][in]; copied.
  */
-orc_model *orc_create_layout(int vocab, int d, int L, int H, int e, int n_ctx, double eps, int layout,
-                             const float *const *tensors)
+static orc_model *orc_create_any(int vocab, int d, int L, int H, int e, int n_ctx, double eps, int layout,
+                                 int k, const float *const *tensors)
 {
     if (vocab <= 0 || d <= 0 || L <= 0 || H <= 0 || (d % H) || e <= 0 || n_ctx <= 0) return NULL;
     if (layout < ORC_MIXED || layout > ORC_COMBINED || (layout == ORC_MIXED && (H % 2))) return NULL;
     orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
     m->vocab = vocab; m->d = d; m->L = L; m->H = H; m->e = e; m->n_ctx = n_ctx; m->eps = eps;
     m->layout = layout;
-    const int slots = layout == ORC_COMBINED ? 2 * H : H;
+    m->kmix = k;
+    const int slots = k > 1 ? k * H : layout == ORC_COMBINED ? 2 * H : H;    /* rows of alpha, entries of lam */
+    const int bslots = k > 1 ? H : slots;                                    /* rows of beta */
     size_t dd = (size_t)d * d, ff = (size_t)e * d;
     m->embed = orc_copy(tensors[0], (size_t)vocab * d);
     m->head  = orc_copy(tensors[1], (size_t)vocab * d);
@@ -128,7 +133,7 @@ orc_model *orc_create_layout(int vocab, int d, int L, int H, int e, int n_ctx, d
         y->ln1_g = orc_copy(t[0], d);            y->ln1_b = orc_copy(t[1], d);
         y->w_in  = orc_copy(t[2], dd);           y->b_in  = orc_copy(t[3], d);
         y->alpha = orc_copy(t[4], (size_t)slots * n_ctx);
-        y->beta  = orc_copy(t[5], (size_t)slots * n_ctx);
+        y->beta  = orc_copy(t[5], (size_t)bslots * n_ctx);
         y->lam   = orc_copy(t[6], slots);
         y->w_out = orc_copy(t[7], dd);           y->b_out = orc_copy(t[8], d);
         y->ln2_g = orc_copy(t[9], d);            y->ln2_b = orc_copy(t[10], d);
@@ -138,6 +143,33 @@ orc_model *orc_create_layout(int vocab, int d, int L, int H, int e, int n_ctx, d
     return m;
 }
 
+orc_model *orc_create_layout(int vocab, int d, int L, int H, int e, int n_ctx, double eps, int layout,
+                             const float *const *tensors)
+{
+    return orc_create_any(vocab, d, L, H, e, n_ctx, eps, layout, 1, tensors);
+}
+
+/*
+ * Mixer with k filters along the hidden dimension (Eq. 11 and the paragraph
+ * above it): Y = sum_i X_(i:d+i, :) W_i + beta, X zero-padded in the hidden
+ * dimension, every W_i a column-repeat matrix (Eq. 3).  Reading defined here
+ * (the text leaves these open): k filters i = 0..k-1; the padding follows the
+ * last hidden element, so filter i sees channel c + i of the mixer input, or
+ * zero past the end; every filter has its own alpha and lambda; beta is added
+ * once.  With H heads the filters' coefficients are per head of the OUTPUT
+ * channel (alpha, lam row i*H + h for filter i, head h; beta row h), while the
+ * shift runs over the whole hidden vector.  Recurrent form: one cache per
+ * filter, T_i <- lam_i T_i + x shifted by i, y = sum_i alpha_i T_i + beta, so
+ * the cache is k*d values per layer: S[i*d + c].
+ * tensors as for orc_create except alpha [k*H][n_ctx], beta [H][n_ctx], lam [k*H].
+ */
+orc_model *orc_create_kernel(int vocab, int d, int L, int H, int e, int n_ctx, double eps, int k,
+                             const float *const *tensors)
+{
+    if (k < 1 || k > d) return NULL;
+    return orc_create_any(vocab, d, L, H, e, n_ctx, eps, ORC_COLUMN, k, tensors);
+}
+
 /* The mixed-head model (the paper's default); alpha, beta [H][n_ctx], lam [H]. */
 orc_model *orc_create(int vocab, int d, int L, int H, int e, int n_ctx, double eps,
                       const float *const *tensors)
@@ -145,8 +177,12 @@ orc_model *orc_create(int vocab, int d, int L, int H, int e, int n_ctx, double e
     return orc_create_layout(vocab, d, L, H, e, n_ctx, eps, ORC_MIXED, tensors);
 }
 
-/* Cache values per layer per sample: d, or 2d for ORC_COMBINED ("Method": combined layers need twice the cache). */
-int orc_state_width(const orc_model *m) { return m->layout == ORC_COMBINED ? 2 * m->d : m->d; }
+/* Cache values per layer per sample: d; 2d for ORC_COMBINED ("Method": combined layers need twice the
+ * cache); k*d with k filters (orc_create_kernel). */
+int orc_state_width(const orc_model *m)
+{
+    return m->kmix > 1 ? m->kmix * m->d : m->layout == ORC_COMBINED ? 2 * m->d : m->d;
+}
 
 /*
  * Non-projected SRM ("Method": the input projection "may or may not be applied,
@@ -425,6 +461,58 @@ void orc_mixer_parallel_layout(const real *U, const real *alpha, const real *bet
 }
 
 /*
+ * One recurrent update of the k-filter mixer (orc_create_kernel) for one
+ * sample: S[k*d], alpha_t and lam [k*H], beta_t [H], values of this position.
+ */
+void orc_mixer_step_kernel(real *S, const real *u, const real *alpha_t, const real *beta_t, const real *lam,
+                           int H, int d, int k, int half, real *m)
+{
+    int dh = d / H;
+    for (int c = 0; c < d; ++c) {
+        int h = c / dh;
+        real y = beta_t[h];
+        for (int i = 0; i < k; ++i) {
+            real x = c + i < d ? u[c + i] : 0;                  /* zero padding past the last channel */
+            real l = half ? orc_round_half(lam[i * H + h]) : lam[i * H + h];
+            real v = l * S[(size_t)i * d + c] + x;
+            S[(size_t)i * d + c] = half ? orc_round_half(v) : v;
+            y += alpha_t[i * H + h] * S[(size_t)i * d + c];
+        }
+        m[c] = y;
+    }
+}
+
+/*
+ * The same mixer over a whole sequence, Eq. 11 as printed: for every filter the
+ * T x T column-repeat matrix (Eq. 3) is written out and applied to the input
+ * shifted by i channels.  U, Y: [T][d] (tokens are rows); alpha [k*H][n_ctx],
+ * beta [H][n_ctx]; pos0 = absolute position of row 0.
+ */
+void orc_mixer_parallel_kernel(const real *U, const real *alpha, const real *beta, const real *lam,
+                               int H, int d, int k, int T, int n_ctx, int pos0, real *Y)
+{
+    int dh = d / H;
+    real *M = (real *)malloc((size_t)T * T * sizeof(real));
+    for (int j = 0; j < T; ++j)
+        for (int c = 0; c < d; ++c) Y[(size_t)j * d + c] = beta[(size_t)(c / dh) * n_ctx + pos0 + j];
+    for (int i = 0; i < k; ++i)
+        for (int h = 0; h < H; ++h) {
+            const real *a = alpha + (size_t)(i * H + h) * n_ctx + pos0;
+            for (int r = 0; r < T; ++r)
+                for (int j = 0; j < T; ++j)
+                    M[(size_t)r * T + j] = r <= j ? (real)pow((double)lam[i * H + h], (double)(j - r)) * a[j] : 0;
+            for (int j = 0; j < T; ++j)
+                for (int c = h * dh; c < (h + 1) * dh; ++c) {
+                    if (c + i >= d) continue;                   /* padded rows of X are zero */
+                    real acc = 0;
+                    for (int r = 0; r < T; ++r) acc += U[(size_t)r * d + c + i] * M[(size_t)r * T + j];
+                    Y[(size_t)j * d + c] += acc;
+                }
+        }
+    free(M);
+}
+
+/*
  * The closed forms on the right of Eq. 2 and Eq. 3, evaluated literally for
  * every position n (a third, independent statement used only as a pin):
  *   row:    Y_n = alpha_n X_n + beta_n + sum_{m<n} lam^{n-m} alpha_m X_m
@@ -595,7 +683,7 @@ int orc_pick_topp(const real *logits, int V, double temperature, double top_p, u
 void orc_step(const orc_model *m, int tok, int pos, real *S, real *hidden, real *logits)
 {
     int d = m->d, ff = m->e * m->d, H = m->H;
-    const int slots = m->layout == ORC_COMBINED ? 2 * H : H, sd = orc_state_width(m);
+    const int slots = m->kmix > 1 ? m->kmix * H : m->layout == ORC_COMBINED ? 2 * H : H, sd = orc_state_width(m);
     real *x = (real *)malloc(sizeof(real) * (size_t)(4 * d + 2 * ff + 2 * slots));
     real *a = x + d, *u = a + d, *mix = u + d, *g = mix + d, *t = g + ff;
     real *al = t + ff, *be = al + slots;
@@ -607,9 +695,11 @@ void orc_step(const orc_model *m, int tok, int pos, real *S, real *hidden, real 
         else orc_linear(y->w_in, y->b_in, a, d, d, u);
         for (int h = 0; h < slots; ++h) {
             al[h] = y->alpha[(size_t)h * m->n_ctx + pos];
-            be[h] = y->beta[(size_t)h * m->n_ctx + pos];
+            if (m->kmix <= 1 || h < H) be[h] = y->beta[(size_t)h * m->n_ctx + pos];
         }
-        if (m->layout != ORC_MIXED)
+        if (m->kmix > 1)
+            orc_mixer_step_kernel(S + (size_t)l * sd, u, al, be, y->lam, H, d, m->kmix, m->half_state, mix);
+        else if (m->layout != ORC_MIXED)
             orc_mixer_step_layout(S + (size_t)l * sd, u, al, be, y->lam, H, d, m->layout, m->half_state, mix);
         else if (m->half_state) orc_mixer_step_half(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
         else orc_mixer_step(S + (size_t)l * d, u, al, be, y->lam, H, d, mix);
@@ -749,7 +839,9 @@ int orc_parallel_forward(const orc_model *m, int B, int T, const int *tokens,
                 if (m->no_proj) memcpy(U + (size_t)s * d, A + (size_t)s * d, sizeof(real) * d);
                 else orc_linear(y->w_in, y->b_in, A + (size_t)s * d, d, d, U + (size_t)s * d);
             }
-            if (m->layout != ORC_MIXED)
+            if (m->kmix > 1)
+                orc_mixer_parallel_kernel(U, y->alpha, y->beta, y->lam, m->H, d, m->kmix, T, m->n_ctx, 0, Y);
+            else if (m->layout != ORC_MIXED)
                 orc_mixer_parallel_layout(U, y->alpha, y->beta, y->lam, m->H, d, T, m->n_ctx, 0, m->layout, Y);
             else orc_mixer_parallel(U, y->alpha, y->beta, y->lam, m->H, d, T, m->n_ctx, 0, Y);
             for (int s = 0; s < T; ++s) {

@@ -47,6 +47,8 @@ def _load(kind: str):
         lib.orc_create.argtypes = [C.c_int] * 6 + [C.c_double, C.POINTER(C.c_void_p)]
         lib.orc_create_layout.restype = C.c_void_p
         lib.orc_create_layout.argtypes = [C.c_int] * 6 + [C.c_double, C.c_int, C.POINTER(C.c_void_p)]
+        lib.orc_create_kernel.restype = C.c_void_p
+        lib.orc_create_kernel.argtypes = [C.c_int] * 6 + [C.c_double, C.c_int, C.POINTER(C.c_void_p)]
         lib.orc_state_width.restype = C.c_int
         lib.orc_state_width.argtypes = [C.c_void_p]
         lib.orc_destroy.argtypes = [C.c_void_p]
@@ -148,8 +150,15 @@ class Oracle:
         self._keep = [np.ascontiguousarray(t, dtype=np.float32) for t in tensors]
         arr = (C.c_void_p * len(self._keep))(*[t.ctypes.data for t in self._keep])
         self.layout = LAYOUTS[getattr(cfg, "head_layout", "mixed")]
-        self.h = self.lib.orc_create_layout(self.V, self.d, self.L, self.H, self.e, self.n_ctx,
-                                            float(cfg.ln_eps), self.layout, arr)
+        self.kmix = int(getattr(cfg, "mixer_kernel", 1))
+        if self.kmix > 1:
+            if self.layout != LAYOUTS["column"]:
+                raise ValueError("a mixer with k filters is built from column-repeat matrices: head_layout 'column'")
+            self.h = self.lib.orc_create_kernel(self.V, self.d, self.L, self.H, self.e, self.n_ctx,
+                                                float(cfg.ln_eps), self.kmix, arr)
+        else:
+            self.h = self.lib.orc_create_layout(self.V, self.d, self.L, self.H, self.e, self.n_ctx,
+                                                float(cfg.ln_eps), self.layout, arr)
         if not self.h:
             raise ValueError("orc_create rejected the configuration")
         self.sd = int(self.lib.orc_state_width(C.c_void_p(self.h)))
@@ -203,6 +212,23 @@ class Oracle:
         self.lib.orc_mixer_step_layout(_p(S), _p(u), _p(alpha_t), _p(beta_t), _p(lam), C.c_int(H),
                                        C.c_int(u.size), C.c_int(LAYOUTS[layout]), C.c_int(int(half)), _p(m))
         return m
+
+    def mixer_step_kernel(self, S, u, alpha_t, beta_t, lam, H, k, half=False):
+        """orc_mixer_step_kernel: in place on S [k*d]; returns m [d]."""
+        assert S.dtype == self.real and S.flags.c_contiguous
+        u, alpha_t, beta_t, lam = map(self._r, (u, alpha_t, beta_t, lam))
+        m = np.empty_like(u)
+        self.lib.orc_mixer_step_kernel(_p(S), _p(u), _p(alpha_t), _p(beta_t), _p(lam), C.c_int(H), C.c_int(u.size),
+                                       C.c_int(k), C.c_int(int(half)), _p(m))
+        return m
+
+    def mixer_parallel_kernel(self, U, alpha, beta, lam, H, k, pos0=0):
+        U, alpha, beta, lam = map(self._r, (U, alpha, beta, lam))
+        T, d = U.shape
+        Y = np.empty_like(U)
+        self.lib.orc_mixer_parallel_kernel(_p(U), _p(alpha), _p(beta), _p(lam), C.c_int(H), C.c_int(d), C.c_int(k),
+                                           C.c_int(T), C.c_int(alpha.shape[1]), C.c_int(pos0), _p(Y))
+        return Y
 
     def mixer_parallel_layout(self, U, alpha, beta, lam, H, layout, pos0=0):
         U, alpha, beta, lam = map(self._r, (U, alpha, beta, lam))

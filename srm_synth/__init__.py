@@ -50,6 +50,7 @@ class SRMConfig:
     use_projections: bool = True   # False: non-projected mixer layers (w_in / w_out are drawn but unused)
     state_dtype: str = "fp32"      # "fp16": recurrent cache and decay constants in half precision
     head_layout: str = "mixed"     # "mixed" | "row" | "column" | "combined" (two matrices per head, twice the cache)
+    mixer_kernel: int = 1          # k > 1: k column-repeat filters along the hidden dimension (head_layout "column")
 
     @property
     def n_ctx(self) -> int:
@@ -69,12 +70,12 @@ class SRMConfig:
     @property
     def head_slots(self) -> int:
         """Rows of alpha / beta (entries of lam) per layer."""
-        return self.n_heads * (2 if self.head_layout == "combined" else 1)
+        return self.n_heads * (self.mixer_kernel if self.mixer_kernel > 1 else 2 if self.head_layout == "combined" else 1)
 
     @property
     def state_width(self) -> int:
         """Cache values per layer per sample."""
-        return self.d_model * (2 if self.head_layout == "combined" else 1)
+        return self.d_model * (self.mixer_kernel if self.mixer_kernel > 1 else 2 if self.head_layout == "combined" else 1)
 
 
 CONFIGS: Dict[str, SRMConfig] = {
@@ -92,12 +93,12 @@ CONFIGS: Dict[str, SRMConfig] = {
 
 def tiny_config(name="T", vocab=32, d_model=8, n_layers=2, n_heads=2, n_ctx=16,
                 weight_dtype="fp32", seed=7, mlp_expansion=4, use_projections=True,
-                state_dtype="fp32", head_layout="mixed") -> SRMConfig:
+                state_dtype="fp32", head_layout="mixed", mixer_kernel=1) -> SRMConfig:
     """A brute-force sized config for unit tests."""
     return SRMConfig(name, vocab, d_model, n_layers, weight_dtype, seed, seed + 1,
                      2, n_ctx, 0, n_heads=n_heads, mlp_expansion=mlp_expansion,
                      n_ctx_fixed=n_ctx, use_projections=use_projections, state_dtype=state_dtype,
-                     head_layout=head_layout)
+                     head_layout=head_layout, mixer_kernel=mixer_kernel)
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
@@ -118,7 +119,7 @@ def tensor_shapes(cfg: SRMConfig, n_ctx: int | None = None):
     n = cfg.n_ctx if n_ctx is None else n_ctx
     layer = {
         "ln1_g": (d,), "ln1_b": (d,), "w_in": (d, d), "b_in": (d,),
-        "alpha": (H, n), "beta": (H, n), "lam": (H,),
+        "alpha": (H, n), "beta": (cfg.n_heads if cfg.mixer_kernel > 1 else H, n), "lam": (H,),
         "w_out": (d, d), "b_out": (d,), "ln2_g": (d,), "ln2_b": (d,),
         "w_up": (ff, d), "b_up": (ff,), "w_down": (d, ff), "b_down": (d,),
     }

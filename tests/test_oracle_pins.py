@@ -752,3 +752,78 @@ def test_head_layout_half_precision_cache_values_are_representable(oracle_mod):
     S = oracle_mod.Oracle(cfg, w, "f64").recurrent_forward(srm_synth.make_prompts(cfg, batch=1, length=32))["state"]
     np.testing.assert_array_equal(S, S.astype(np.float16).astype(np.float64))
     assert np.abs(S).max() > 0
+
+
+# ---- mixer with k filters along the hidden dimension (Eq. 11) ----------------------------------
+def _brute_kernel_mixer(U, alpha, beta, lam, H, k):
+    """Eq. 11 in the paper's orientation: X is (d + k) x n, zero-padded after the last hidden
+    element; Y = sum_i X[i:d+i, :] @ W_i + beta with W_i the column-repeat matrix of Eq. 3
+    (W_i[m, n] = lam^(n-m) alpha_n for m <= n), here one set of coefficients per head of the
+    output rows."""
+    T, d = U.shape
+    dh = d // H
+    X = np.zeros((d + k, T))
+    X[:d] = U.T
+    Y = np.zeros((d, T))
+    for h in range(H):
+        rows = slice(h * dh, (h + 1) * dh)
+        Y[rows] += beta[h, None, :T]
+        for i in range(k):
+            s = i * H + h
+            W = np.array([[lam[s] ** (n - m) * alpha[s, n] if m <= n else 0.0 for n in range(T)] for m in range(T)])
+            Y[rows] += X[i:d + i][rows] @ W
+    return Y.T
+
+
+@pytest.mark.parametrize("H,k", [(1, 1), (1, 3), (2, 4), (1, 8)])
+def test_kernel_mixer_three_statements_agree(tiny, H, k):
+    _, _, orc = tiny
+    T, d = 10, 8
+    alpha, _, lam = _coeffs(k * H, T, seed=80 + k)
+    beta = np.random.default_rng(81).standard_normal((H, T))
+    U = np.random.default_rng(82).standard_normal((T, d))
+    want = _brute_kernel_mixer(U, alpha, beta, lam, H, k)
+    S = np.zeros(k * d)
+    Y = np.stack([orc.mixer_step_kernel(S, U[t], alpha[:, t], beta[:, t], lam, H, k) for t in range(T)])
+    np.testing.assert_allclose(Y, want, rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(orc.mixer_parallel_kernel(U, alpha, beta, lam, H, k), want, rtol=1e-11, atol=1e-11)
+    if k == 1:                                              # one filter, no shift: the column-repeat layer
+        np.testing.assert_allclose(orc.mixer_parallel_layout(U, alpha, beta, lam, H, "column"), want, rtol=1e-12,
+                                   atol=1e-12)
+    else:
+        assert np.abs(orc.mixer_parallel_layout(U, alpha[:H], beta, lam[:H], H, "column") - want).max() > 1e-3
+
+
+def test_kernel_mixer_reduces_to_a_running_sum_of_a_hidden_dimension_convolution(tiny):
+    """No decay, unit alpha, zero beta: the output is the running sum over positions of the input
+    correlated along the hidden dimension with k ones (zero-padded at the end)."""
+    _, _, orc = tiny
+    T, d, k = 7, 8, 3
+    U = np.random.default_rng(5).standard_normal((T, d))
+    conv = scipy.signal.correlate(np.pad(U, ((0, 0), (0, k - 1))), np.ones((1, k)), mode="valid")
+    assert conv.shape == (T, d)
+    got = orc.mixer_parallel_kernel(U, np.ones((k, T)), np.zeros((1, T)), np.ones(k), 1, k)
+    np.testing.assert_allclose(got, np.cumsum(conv, axis=0), rtol=1e-12, atol=1e-12)
+
+
+def test_kernel_mixer_model_forms_agree_and_cache_is_k_times_d(oracle_mod):
+    cfg = srm_synth.tiny_config(vocab=40, d_model=16, n_layers=2, n_heads=2, n_ctx=32, seed=83, head_layout="column",
+                                mixer_kernel=4)
+    w = srm_synth.make_weights(cfg, stress=True)
+    assert w["layers"][0]["alpha"].shape == (8, 32) and w["layers"][0]["beta"].shape == (2, 32)
+    orc = oracle_mod.Oracle(cfg, w, "f64")
+    toks = srm_synth.make_prompts(cfg, batch=3, length=20)
+    r, p = orc.recurrent_forward(toks), orc.parallel_forward(toks)
+    assert r["state"].shape == (3, 2, 4 * 16)
+    np.testing.assert_allclose(p["hidden"], r["hidden"], rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(p["logits"], r["logits"], rtol=1e-9, atol=1e-9)
+    # causal: a later token does not change earlier outputs
+    t2 = toks.copy(); t2[:, 12] = (t2[:, 12] + 1) % cfg.vocab
+    p2 = orc.parallel_forward(t2)
+    np.testing.assert_array_equal(p2["logits"][:, :12], p["logits"][:, :12])
+    assert np.abs(p2["logits"][:, 12:] - p["logits"][:, 12:]).max() > 0
+    g = orc.greedy(toks[:, :8], 6)
+    full = np.concatenate([toks[:, :8], g["tokens"][:, :-1]], axis=1)
+    np.testing.assert_array_equal(orc.recurrent_forward(full, want_greedy=True)["greedy"][:, 7:], g["tokens"])
+    with pytest.raises(ValueError):
+        oracle_mod.Oracle(srm_synth.tiny_config(n_heads=2, mixer_kernel=2), w, "f64")     # needs head_layout "column"
