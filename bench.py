@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--head-layout", choices=["mixed", "row", "column", "combined"], default="mixed",
                     help="row / column: one kind of head only; combined: two matrices per head, twice the cache "
                          "(model variants)")
+    ap.add_argument("--mixer-kernel", type=int, default=1,
+                    help="k > 1: k column-repeat filters along the hidden dimension per mixer layer (a model variant; "
+                         "implies --head-layout column)")
     ap.add_argument("--top-p", type=float, default=1.0,
                     help="with --temperature: nucleus truncation (the paper's rollouts use 0.9 at temperature 0.7)")
     ap.add_argument("--per-step-calls", action="store_true",
@@ -256,10 +259,12 @@ def main():
         concurrency_sweep(torch, srm, srm_synth, min(args.steps, 8), args.state_dtype)
         return
     cfg = srm_synth.CONFIGS[args.workload]
+    if args.mixer_kernel > 1:
+        args.head_layout = "column"
     if args.no_projections or args.state_dtype != "fp32" or args.head_layout != "mixed":
         import dataclasses
         cfg = dataclasses.replace(cfg, use_projections=not args.no_projections, state_dtype=args.state_dtype,
-                                  head_layout=args.head_layout)
+                                  head_layout=args.head_layout, mixer_kernel=args.mixer_kernel)
     B, P = cfg.batch, cfg.prompt_len
     t0 = time.perf_counter()
     w = srm_synth.make_weights(cfg)
@@ -345,7 +350,8 @@ def main():
         "config": {"workload": f"{cfg.name}: SRM d_model {d}, {L} layers, 4 mixed heads, MLP x4, vocab {V}, "
                                f"{cfg.weight_dtype} weights / {cfg.state_dtype} state, batch {B}, prompt {P}, greedy decode" +
                                ("" if cfg.use_projections else ", non-projected mixer layers") +
-                               ("" if cfg.head_layout == "mixed" else f", {cfg.head_layout} heads"),
+                               ("" if cfg.head_layout == "mixed" else f", {cfg.head_layout} heads") +
+                               ("" if cfg.mixer_kernel <= 1 else f", {cfg.mixer_kernel} filters along the hidden dimension"),
                    "batch": B, "prompt_len": P, "state_bytes": model.state_bytes(B)},
         "step": {"algorithmic_tflop": flops_step * 1e-12, "algorithmic_gb": bytes_step * 1e-9,
                  "achieved_gbs": bytes_step / step_s * 1e-9, "hbm_frac": bytes_step / step_s * 1e-9 / PEAK_HBM_GBS,

@@ -92,14 +92,23 @@ typedef struct {
                                need twice the cache): every state row is [2d], first the d values of the
                                row-repeat matrices, then the d values of the column-repeat ones, and
                                srm_state_bytes counts 2d.  Needs the head projections. */
+    int32_t mixer_kernel;   /* 0 or 1: none.  k > 1: every mixer layer has k filters along the hidden
+                               dimension (Eq. 11): Y = sum_i X_(i:d+i, :) W_i + beta with X zero-padded and
+                               each W_i a column-repeat matrix.  Reading: filters i = 0..k-1; the padding
+                               follows the last hidden element, so filter i sees channel c + i of the head
+                               input (zero past the end); own alpha and lambda per filter and head of the
+                               output channel, one beta.  alpha is [k*H][n_ctx] and lambda [k*H] (row
+                               i*H + h: filter i, head h), beta [H][n_ctx].  One cache per filter: every
+                               state row is [k*d], filter-major, and srm_state_bytes counts k*d.  Needs
+                               head_layout = SRM_HEADS_COLUMN and the head projections; k*H <= 64. */
 } srm_config;
 
 /* HOST pointers, fp32, caller-owned, not retained after srm_init_weights. */
 typedef struct {
     const float *ln1_g, *ln1_b;        /* [d], [d]                                  */
     const float *w_in, *b_in;          /* [d][d] (rows h*d_h.. are I_h), [d]         */
-    const float *alpha, *beta;         /* [H][n_ctx], [H][n_ctx] ([2H] rows: combined) */
-    const float *lambda;               /* [H] ([2H]: combined), each in (0, 1]       */
+    const float *alpha, *beta;         /* [H][n_ctx], [H][n_ctx] ([2H] rows: combined; alpha [k*H] rows: mixer_kernel k) */
+    const float *lambda;               /* [H] ([2H]: combined; [k*H]: mixer_kernel k), each in (0, 1] */
     const float *w_out, *b_out;        /* [d][d] (P_out), [d]                        */
     const float *ln2_g, *ln2_b;        /* [d], [d]                                   */
     const float *w_up, *b_up;          /* [e*d][d], [e*d]                            */
@@ -119,7 +128,8 @@ typedef struct {
  * both the recurrent and the parallel form.)
  * Errors: SRM_EINVAL for a null pointer, non-positive size, odd n_heads with
  * mixed heads, more than 64 coefficient rows per layer, an unknown head_layout,
- * combined heads without projections, d_model not divisible by 4*n_heads, d_model > 4096, bf16 with d_model % 64,
+ * combined heads or mixer_kernel > 1 without projections, mixer_kernel > 1 with
+ * another head layout than column, d_model not divisible by 4*n_heads, d_model > 4096, bf16 with d_model % 64,
  * or a lambda outside (0, 1]; SRM_ENOMEM; SRM_EHIP.
  */
 int srm_init_weights(const srm_config *cfg, const srm_host_weights *w, srm_model **out);
@@ -127,7 +137,7 @@ void srm_free(srm_model *m);
 
 /*
  * Bytes of recurrent state for `batch` samples: n_layers * batch * d_model * 4
- * (2 with a binary16 state; twice that with combined heads), whatever the position ("Computational Complexity": O(d) space per sample).
+ * (2 with a binary16 state; times 2 with combined heads, times k with mixer_kernel = k), whatever the position ("Computational Complexity": O(d) space per sample).
  * Returns 0 for a null model or batch <= 0.
  */
 size_t srm_state_bytes(const srm_model *m, int64_t batch);
@@ -345,7 +355,8 @@ int srm_parallel_forward(srm_model *m, const int32_t *d_tok, int32_t B, int32_t 
  * that layer's [B][d] slab (fp32, or binary16 with a half-precision state),
  * updated in place.  d_m may alias d_u.  With combined heads all three rows are
  * [2d]: the row-repeat half then the column-repeat half, d_u holding the head
- * input twice; the model adds the two halves of d_m in its out-projection.
+ * input twice; the model adds the two halves of d_m in its out-projection
+ * (mixer_kernel = k: rows [k*d], copy i holding the head input shifted by i).
  */
 int srm_mixer_update(srm_model *m, int32_t layer, int32_t pos, int64_t B, const void *d_u,
                      void *d_state_layer, void *d_m, void *hip_stream);

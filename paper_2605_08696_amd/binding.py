@@ -32,7 +32,8 @@ class srm_config(C.Structure):
     _fields_ = [("vocab", C.c_int32), ("d_model", C.c_int32), ("n_layers", C.c_int32),
                 ("n_heads", C.c_int32), ("mlp_expansion", C.c_int32), ("n_ctx", C.c_int32),
                 ("weight_dtype", C.c_int32), ("ln_eps", C.c_float), ("state_dtype", C.c_int32),
-                ("no_projections", C.c_int32), ("head_layout", C.c_int32)]
+                ("no_projections", C.c_int32), ("head_layout", C.c_int32),
+                ("mixer_kernel", C.c_int32)]
 
 
 class srm_host_layer(C.Structure):
@@ -151,9 +152,10 @@ class Model:
                        cfg.n_ctx, self.dtype, cfg.ln_eps,
                        SRM_FP16 if getattr(cfg, "state_dtype", "fp32") == "fp16" else SRM_FP32,
                        0 if getattr(cfg, "use_projections", True) else 1,
-                       HEAD_LAYOUTS[getattr(cfg, "head_layout", "mixed")])
-        combined = getattr(cfg, "head_layout", "mixed") == "combined"
-        self.sd = self.d * (2 if combined else 1)          # state (and mixer) width per sample and layer
+                       HEAD_LAYOUTS[getattr(cfg, "head_layout", "mixed")], int(getattr(cfg, "mixer_kernel", 1)))
+        kmix = int(getattr(cfg, "mixer_kernel", 1))
+        copies = kmix if kmix > 1 else 2 if getattr(cfg, "head_layout", "mixed") == "combined" else 1
+        self.sd = self.d * copies                          # state (and mixer) width per sample and layer
         self.state_half = getattr(cfg, "state_dtype", "fp32") == "fp16"
         keep = []
 
@@ -164,9 +166,9 @@ class Model:
             keep.append(a)
             return a.ctypes.data_as(_FP)
 
-        d, ff, H, n, V = self.d, self.ff, self.H * (2 if combined else 1), self.n_ctx, self.vocab
+        d, ff, H, n, V = self.d, self.ff, self.H * copies, self.n_ctx, self.vocab
         shapes = {"ln1_g": (d,), "ln1_b": (d,), "w_in": (d, d), "b_in": (d,), "alpha": (H, n),
-                  "beta": (H, n), "lambda": (H,), "w_out": (d, d), "b_out": (d,), "ln2_g": (d,),
+                  "beta": (self.H if kmix > 1 else H, n), "lambda": (H,), "w_out": (d, d), "b_out": (d,), "ln2_g": (d,),
                   "ln2_b": (d,), "w_up": (ff, d), "b_up": (ff,), "w_down": (d, ff), "b_down": (d,)}
         if len(weights["layers"]) != self.L:
             raise ValueError("wrong number of layers")

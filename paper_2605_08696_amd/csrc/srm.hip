@@ -64,7 +64,8 @@ struct srm_model {
     // and one column-repeat matrix per head, outputs added) run as a mixer of width 2d with 2H
     // heads, the H row-repeat ones first: the in-projection's rows and the out-projection's
     // columns are stored twice, so that both halves see the same input and the out-projection
-    // adds their outputs.
+    // adds their outputs.  A mixer with k filters along the hidden dimension (Eq. 11) runs the
+    // same way with k copies, all column-repeat, copy i of the in-projection shifted by i rows.
     int dm, Hs, hrow;
     bool noproj;           // non-projected mixer layers
     bool shalf;            // recurrent state (and lambda) in binary16
@@ -119,7 +120,12 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     const int layout = cfg->head_layout;
     if (layout < SRM_HEADS_MIXED || layout > SRM_HEADS_COMBINED)
         return fail(SRM_EINVAL, "srm_init_weights: unknown head_layout %d", layout);
-    const int slots = cfg->n_heads * (layout == SRM_HEADS_COMBINED ? 2 : 1);
+    const int kmix = cfg->mixer_kernel > 1 ? cfg->mixer_kernel : 1;
+    if (cfg->mixer_kernel < 0 || kmix > cfg->d_model)
+        return fail(SRM_EINVAL, "srm_init_weights: mixer_kernel %d outside [0, d_model]", cfg->mixer_kernel);
+    if (kmix > 1 && (layout != SRM_HEADS_COLUMN || cfg->no_projections))
+        return fail(SRM_EINVAL, "srm_init_weights: mixer_kernel > 1 needs column-repeat heads and the head projections");
+    const int slots = cfg->n_heads * (kmix > 1 ? kmix : layout == SRM_HEADS_COMBINED ? 2 : 1);
     if ((layout == SRM_HEADS_MIXED && cfg->n_heads % 2) || slots > kMaxHeads)
         return fail(SRM_EINVAL, "srm_init_weights: n_heads must be even for mixed heads, and at most %d "
                                 "coefficient rows per layer", kMaxHeads);
@@ -158,7 +164,8 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     m->cfg = *cfg;
     m->d = d; m->ff = (int)ff; m->V = V; m->L = L; m->H = H;
     const bool comb = layout == SRM_HEADS_COMBINED;
-    m->dm = comb ? 2 * d : d;
+    const int copies = kmix > 1 ? kmix : comb ? 2 : 1;        // times the mixer row repeats the head input
+    m->dm = copies * d;
     m->Hs = slots;
     m->hrow = layout == SRM_HEADS_MIXED ? H / 2 : layout == SRM_HEADS_COLUMN ? 0 : H;
     m->noproj = cfg->no_projections != 0;
@@ -184,19 +191,29 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
             size_t *o = lo[l].v;
             o[0] = sb.add(y.ln1_g, d, false);          o[1] = sb.add(y.ln1_b, d, false);
             const bool pj = !m->noproj;
-            if (comb) {
-                // W_in [d][d] -> [2d][d] (rows repeated), W_out [d][d] -> [d][2d] (columns repeated)
-                std::vector<float> t((size_t)2 * d * d);
-                memcpy(t.data(), y.w_in, (size_t)d * d * 4);
-                memcpy(t.data() + (size_t)d * d, y.w_in, (size_t)d * d * 4);
+            if (copies > 1) {
+                // W_in [d][d] -> [copies*d][d], W_out [d][d] -> [d][copies*d] (columns repeated).  Copy i of
+                // W_in / b_in holds rows i .. d-1 followed by i zero rows (combined heads: no shift), so that
+                // mixer channel i*d + c receives head input c + i, or zero past the last channel (Eq. 11).
+                std::vector<float> t((size_t)copies * d * d, 0.0f), tb((size_t)copies * d, 0.0f);
+                for (int i = 0; i < copies; ++i) {
+                    const int sh = kmix > 1 ? i : 0;
+                    memcpy(t.data() + (size_t)i * d * d, y.w_in + (size_t)sh * d, (size_t)(d - sh) * d * 4);
+                    memcpy(tb.data() + (size_t)i * d, y.b_in + sh, (size_t)(d - sh) * 4);
+                }
                 o[2] = sb.add(t.data(), t.size(), bf);
-                memcpy(t.data(), y.b_in, (size_t)d * 4);
-                memcpy(t.data() + d, y.b_in, (size_t)d * 4);
-                o[3] = sb.add(t.data(), (size_t)2 * d, false);
+                o[3] = sb.add(tb.data(), tb.size(), false);
             } else {
                 o[2] = pj ? sb.add(y.w_in, (size_t)d * d, bf) : 0;   o[3] = pj ? sb.add(y.b_in, d, false) : 0;
             }
-            o[4] = sb.add(y.alpha, slots * nc, false);  o[5] = sb.add(y.beta, slots * nc, false);
+            o[4] = sb.add(y.alpha, slots * nc, false);
+            if (kmix > 1) {                              // beta [H][n_ctx] is added once: rows of filter 0, zeros after
+                std::vector<float> t((size_t)slots * nc, 0.0f);
+                memcpy(t.data(), y.beta, (size_t)H * nc * 4);
+                o[5] = sb.add(t.data(), t.size(), false);
+            } else {
+                o[5] = sb.add(y.beta, slots * nc, false);
+            }
             if (m->shalf) {                              // decay constants as binary16 values
                 float lh[kMaxHeads];
                 for (int h = 0; h < slots; ++h) lh[h] = (float)(_Float16)y.lambda[h];
@@ -204,12 +221,11 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
             } else {
                 o[6] = sb.add(y.lambda, slots, false);
             }
-            if (comb) {
-                std::vector<float> t((size_t)2 * d * d);
-                for (int i = 0; i < d; ++i) {
-                    memcpy(t.data() + (size_t)i * 2 * d, y.w_out + (size_t)i * d, (size_t)d * 4);
-                    memcpy(t.data() + (size_t)i * 2 * d + d, y.w_out + (size_t)i * d, (size_t)d * 4);
-                }
+            if (copies > 1) {
+                std::vector<float> t((size_t)copies * d * d);
+                for (int i = 0; i < d; ++i)
+                    for (int c = 0; c < copies; ++c)
+                        memcpy(t.data() + ((size_t)i * copies + c) * d, y.w_out + (size_t)i * d, (size_t)d * 4);
                 o[7] = sb.add(t.data(), t.size(), bf);
                 o[8] = sb.add(y.b_out, d, false);
             } else {

@@ -330,3 +330,89 @@ def test_head_layout_errors(srm):
         srm.Model(cfg, srm_synth.make_weights(cfg))            # mixed heads: even count
     cfg = srm_synth.tiny_config(vocab=64, d_model=96, n_layers=1, n_heads=3, n_ctx=8, head_layout="row")
     srm.Model(cfg, srm_synth.make_weights(cfg)).close()
+
+
+# ---- mixer with k filters along the hidden dimension (Eq. 11) ------------------------------------
+@pytest.mark.parametrize("H,k", [(1, 4), (2, 3), (1, 8)])
+def test_kernel_mixer_fp32_all_paths_match_oracle(srm, orc_mod, H, k):
+    d = 64
+    cfg = srm_synth.tiny_config(vocab=300, d_model=d, n_layers=3, n_heads=H, n_ctx=96, seed=75, head_layout="column",
+                                mixer_kernel=k)
+    w = srm_synth.make_weights(cfg, stress=True)
+    orc = orc_mod.Oracle(cfg, w, "f64")
+    model = srm.Model(cfg, w)
+    assert model.state_bytes(10) == cfg.n_layers * 10 * k * d * 4
+    B, P, G = 5, 12, 10
+    prompts = srm_synth.make_prompts(cfg, batch=B, length=P)
+    ref = orc.greedy(prompts, G, want_logits=True)
+    print(f"kernel mixer H={H} k={k}: prefill + generate", flush=True)
+    ws = model.new_workspace(B * 80)
+    st, tk = model.new_state(B), torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    model.prefill(to_dev(prompts), 1, st, tk, logits=lg, workspace=ws)
+    assert rel_err_rows(lg.cpu().numpy(), ref["logits"][:, 0]) <= 1e-4
+    out = torch.empty((G - 1, B), dtype=torch.int32, device="cuda")
+    first = tk.cpu().numpy().copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        model.generate(B, P, G - 1, tk, st, out, workspace=ws)
+    side.synchronize()
+    got = np.concatenate([first[:, None], out.cpu().numpy().T], axis=1)
+    assert check_tokens(got, ref["tokens"], ref["margin"], np.abs(ref["logits"]).max(axis=2)) == 0
+    s_got = st.permute(1, 0, 2).cpu().numpy()                  # [B][L][k*d], filter-major like the oracle's
+    assert np.abs(s_got - ref["state"]).max() <= 1e-4 * np.abs(ref["state"]).max()
+    T = 80
+    toks = srm_synth.make_prompts(cfg, batch=2, length=T)
+    rf = orc.recurrent_forward(toks)
+    st2 = model.new_state(2)
+    o2 = torch.empty(2, dtype=torch.int32, device="cuda")
+    l2 = torch.empty((2, cfg.vocab), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    for t in range(T):
+        model.decode_step(2, t, tc[t], st2, o2, logits=l2, workspace=ws)
+        if t % 9 == 0 or t == T - 1:
+            assert rel_err_rows(l2.cpu().numpy(), rf["logits"][:, t]) <= 1e-4
+    hid = torch.empty((2, T, d), dtype=torch.float32, device="cuda")
+    lgp = torch.empty((2, T, cfg.vocab), dtype=torch.float32, device="cuda")
+    model.parallel_forward(to_dev(toks), hid, logits=lgp, workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err_rows(hid.cpu().numpy().reshape(2 * T, -1), rf["hidden"].reshape(2 * T, -1)) <= 1e-4
+    assert rel_err_rows(lgp.cpu().numpy().reshape(2 * T, -1), rf["logits"].reshape(2 * T, -1)) <= 1e-4
+    st3, tk3 = model.new_state(2), torch.empty(2, dtype=torch.int32, device="cuda")
+    model.prefill(to_dev(toks), 1, st3, tk3, logits=l2, workspace=ws)          # the chunked scan
+    torch.cuda.synchronize()
+    assert rel_err_rows(l2.cpu().numpy(), rf["logits"][:, T - 1]) <= 1e-4
+    assert (st3 - st2).abs().max() <= 1e-4 * st2.abs().max()
+
+
+@pytest.mark.parametrize("B", [40, 5000])
+def test_kernel_mixer_bf16_matches_oracle(srm, orc_mod, B):
+    cfg = srm_synth.tiny_config(vocab=520, d_model=128, n_layers=2, n_heads=2, n_ctx=12, weight_dtype="bf16", seed=76,
+                                head_layout="column", mixer_kernel=4)
+    w = srm_synth.make_weights(cfg, stress=True)
+    T = 7
+    toks = srm_synth.make_prompts(cfg, batch=B, length=T)
+    rows = sorted({0, 1, B // 2, B - 1})
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks[rows])
+    model = srm.Model(cfg, w)
+    ws, st = model.new_workspace(B), model.new_state(B)
+    out = torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    print(f"kernel mixer bf16 B={B}", flush=True)
+    for t in range(T):
+        model.decode_step(B, t, tc[t], st, out, logits=lg, workspace=ws)
+        assert rel_err_rows(lg[rows].cpu().numpy(), ref["logits"][:, t]) <= 2e-2
+    s_got = st[:, rows].permute(1, 0, 2).cpu().numpy()
+    assert np.abs(s_got - ref["state"]).max() <= 2e-2 * np.abs(ref["state"]).max()
+
+
+def test_kernel_mixer_errors(srm):
+    cfg = srm_synth.tiny_config(vocab=64, d_model=64, n_layers=1, n_heads=2, n_ctx=8, mixer_kernel=2)
+    w = srm_synth.make_weights(dataclasses.replace(cfg, head_layout="column"))
+    with pytest.raises(srm.SrmError):
+        srm.Model(cfg, w)                                      # needs column-repeat heads
+    cfg = dataclasses.replace(cfg, head_layout="column", use_projections=False)
+    with pytest.raises(srm.SrmError):
+        srm.Model(cfg, w)                                      # needs the projections
