@@ -376,6 +376,20 @@ int srm_linear(int32_t dtype, int32_t epilogue, const void *d_A, const void *d_W
 size_t srm_linear_scratch_bytes(int64_t M, int32_t N);
 
 /*
+ * Work-groups of the one-kernel path that srm_generate / srm_generate_topp take
+ * for a batch of B samples, or 0 if such a call runs the ordinary step kernels.
+ * The one-kernel path ("MAX model details": per-call overhead dominates small
+ * batches) serves greedy and temperature sampling (no top-p) for fp32 models
+ * with fp32 state and head projections, B <= 8, d_model <= 1024 and at most
+ * 128 KB for the widest activation row of all samples: a small cooperative grid
+ * walks through all G steps, its phases separated by grid barriers, so a step
+ * costs 4L + 1 barriers instead of 6L + 7 kernel launches.  Same results up to
+ * the fp32 summation order.  Environment: SRM_MEGAKERNEL=0 switches it off,
+ * SRM_MEGA_BLOCKS=n sets the grid (default 16, at most 64).
+ */
+int32_t srm_generate_one_kernel_blocks(const srm_model *m, int64_t B);
+
+/*
  * Measuring tools (not part of the model's path): the chip's achievable rates,
  * which the benchmark reports beside the published peaks.
  *

@@ -94,6 +94,8 @@ def lib():
         L.srm_linear.argtypes = [i32, i32, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.srm_linear_scratch_bytes.restype = sz
         L.srm_linear_scratch_bytes.argtypes = [i64, i32]
+        L.srm_generate_one_kernel_blocks.restype = C.c_int32
+        L.srm_generate_one_kernel_blocks.argtypes = [vp, i64]
         L.srm_probe_copy.restype = C.c_int
         L.srm_probe_copy.argtypes = [vp, vp, sz, i32, vp]
         L.srm_probe_mfma.restype = C.c_int
@@ -205,6 +207,10 @@ class Model:
 
     def workspace_bytes(self, rows: int) -> int:
         return lib().srm_workspace_bytes(self._h, rows)
+
+    def one_kernel_blocks(self, batch: int) -> int:
+        """Grid size of the one-kernel path srm_generate takes for this batch (0: ordinary step kernels)."""
+        return int(lib().srm_generate_one_kernel_blocks(self._h, batch))
 
     def new_state(self, batch: int):
         torch = _torch()

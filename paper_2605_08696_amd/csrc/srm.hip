@@ -13,6 +13,7 @@
 
 #include "srm.h"
 #include "gemm.hpp"
+#include "mega.hpp"
 #include "mixer.hpp"
 #include "norm.hpp"
 #include "probe.hpp"
@@ -72,6 +73,7 @@ struct srm_model {
     size_t ssize;          // bytes per state element
     size_t wsize;          // bytes per matrix element
     void *slab;
+    MegaLayer *mega_layers;   // device copy of the layers' pointers for the one-kernel small-batch path, or null
     const void *embed, *head;
     const float *lnf_g, *lnf_b;
     std::vector<LayerDev> layers;
@@ -174,6 +176,7 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
     const bool bf = cfg->weight_dtype == SRM_BF16;
     m->wsize = bf ? 2 : 4;
     m->slab = nullptr;
+    m->mega_layers = nullptr;
     m->gexec = nullptr;
     m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, 1.0f, nullptr, 0, nullptr, 0};
 
@@ -265,6 +268,23 @@ extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w
         y.b_out = F(o[8]); y.ln2_g = F(o[9]); y.ln2_b = F(o[10]); y.w_up = base + o[11];
         y.b_up = F(o[12]); y.w_down = base + o[13]; y.b_down = F(o[14]);
     }
+    if (!bf && !m->noproj) {
+        std::vector<MegaLayer> ml(L);
+        for (int l = 0; l < L; ++l) {
+            const LayerDev &y = m->layers[l];
+            ml[l] = MegaLayer{y.ln1_g, y.ln1_b, static_cast<const float *>(y.w_in), y.b_in, y.alpha, y.beta, y.lam,
+                              static_cast<const float *>(y.w_out), y.b_out, y.ln2_g, y.ln2_b,
+                              static_cast<const float *>(y.w_up), y.b_up, static_cast<const float *>(y.w_down), y.b_down};
+        }
+        e = hipMalloc(reinterpret_cast<void **>(&m->mega_layers), sizeof(MegaLayer) * L);
+        if (e == hipSuccess) e = hipMemcpy(m->mega_layers, ml.data(), sizeof(MegaLayer) * L, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            if (m->mega_layers) (void)hipFree(m->mega_layers);
+            (void)hipFree(m->slab);
+            delete m;
+            return fail(SRM_EHIP, "srm_init_weights: layer table: %s", hipGetErrorString(e));
+        }
+    }
     *out = m;
     return SRM_OK;
 }
@@ -273,6 +293,7 @@ extern "C" void srm_free(srm_model *m)
 {
     if (!m) return;
     if (m->gexec) (void)hipGraphExecDestroy(m->gexec);
+    if (m->mega_layers) (void)hipFree(m->mega_layers);
     if (m->slab) (void)hipFree(m->slab);
     delete m;
 }
@@ -302,6 +323,7 @@ struct Workspace {
     int32_t *pi;       // [rows][nparts]
     int *ctr;          // [2] position and step counters of srm_generate
     int *slow;         // [64 + rows] nucleus pass: count, then (from slow + 64) the rows that need the search
+    unsigned char *mega;  // [kMegaScratch] one-kernel small-batch path: partial winners and the barrier words
     float *part;       // [kSplitK][rows][d] split-K slabs of the down projection (rows <= kSplitMaxRows), else null
     size_t bytes;
 };
@@ -316,6 +338,10 @@ constexpr int64_t kSplitMaxRows = 2048;
 // N / 64 blocks: the two residual projections are cut into up to kGemvSplitMax K slices the same way.
 constexpr int kGemvSplitMax = 8;
 constexpr int64_t kGemvRows = 32;
+
+// Scratch of the one-kernel path: [kMegaMaxBlocks][kMegaMaxB] floats, the same of ints, then 256 bytes of barrier words.
+constexpr int kMegaMaxBlocks = 64;
+constexpr size_t kMegaScratch = (size_t)kMegaMaxBlocks * kMegaMaxB * 8 + 256;
 
 static Workspace carve(const srm_model *m, void *base, int64_t rows)
 {
@@ -342,6 +368,7 @@ static Workspace carve(const srm_model *m, void *base, int64_t rows)
                                               (size_t)kGemvSplitMax * std::min<int64_t>(rows, kGemvRows));
     float *part = reinterpret_cast<float *>(take(part_rows * d * 4));
     w.part = rows <= kSplitMaxRows ? part : nullptr;
+    w.mega = take(kMegaScratch);
     w.ctr = reinterpret_cast<int *>(take(256));
     w.bytes = off;
     return w;
@@ -904,6 +931,77 @@ extern "C" int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, i
     return decode_batch(m, a, d_workspace, workspace_bytes, as_stream(hip_stream));
 }
 
+// ------------------------------------------------------------------ generate, few samples: one persistent kernel
+// Number of work-groups for the one-kernel path (see mega.hpp), or 0 if the call does not
+// qualify: fp32 weights and state, head projections, at most kMegaMaxB samples, d <= 1024,
+// the widest activation row of all samples within 128 KB of LDS, cooperative launches
+// supported.  SRM_MEGAKERNEL=0 in the environment switches the path off, SRM_MEGA_BLOCKS=n
+// sets the grid (default 16: a grid barrier costs about 1.4 us + 65 ns per work-group).
+static int mega_rows(int64_t B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : kMegaMaxB; }   // rows the kernel is unrolled for
+
+static int mega_blocks(const srm_model *m, int64_t B)
+{
+    if (!m->mega_layers || m->shalf || B > kMegaMaxB || m->L > kMegaMaxLayers) return 0;
+    const int widest = std::max(std::max(m->d, m->dm), m->ff);
+    if (m->d > 1024 || m->d % 4 || m->dm % 4 || m->ff % 4 || (size_t)mega_rows(B) * widest * 4 > 128 * 1024) return 0;
+    // The small grid has a fraction of the chip's arithmetic and cache bandwidth: measured, the path wins while
+    // rows x matrix elements stay below about 32 M (C1's model at B = 8: 128 against 148 us per step; a
+    // 25 M-element model wins at B = 1 by 8 % and loses at B = 8).
+    const double elems = (double)m->L * ((double)2 * m->d * m->dm + (double)2 * m->d * m->ff) + (double)m->V * m->d;
+    if (elems * mega_rows(B) > 32e6) return 0;
+    const char *sw = getenv("SRM_MEGAKERNEL");
+    if (sw && sw[0] == '0') return 0;
+    int coop = 0;
+    if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, m->device) != hipSuccess || !coop) return 0;
+    int nblk = 16;
+    if (const char *nb = getenv("SRM_MEGA_BLOCKS")) nblk = atoi(nb);
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device) != hipSuccess) return 0;
+    return std::max(1, std::min(std::min(nblk, kMegaMaxBlocks), cus));
+}
+
+extern "C" int32_t srm_generate_one_kernel_blocks(const srm_model *m, int64_t B)
+{
+    return m && B > 0 ? mega_blocks(m, B) : 0;
+}
+
+static int mega_generate(srm_model *m, int B, int pos0, int G, int32_t *tok, void *state, int32_t *store,
+                         float temperature, uint32_t seed, void *ws, int nblk, hipStream_t st)
+{
+    const Workspace w = carve(m, ws, B);
+    MegaArgs a;
+    a.layers = m->mega_layers;
+    a.embed = static_cast<const float *>(m->embed);
+    a.head = static_cast<const float *>(m->head);
+    a.lnf_g = m->lnf_g; a.lnf_b = m->lnf_b;
+    a.V = m->V; a.d = m->d; a.dm = m->dm; a.ff = m->ff; a.L = m->L; a.Hs = m->Hs; a.hrow = m->hrow;
+    a.n_ctx = m->cfg.n_ctx; a.eps = m->cfg.ln_eps;
+    a.B = B; a.pos0 = pos0; a.G = G;
+    a.tok = tok; a.state = static_cast<float *>(state); a.store = store;
+    a.temp = temperature; a.seed = seed;
+    a.x = w.x; a.mbuf = static_cast<float *>(w.mx); a.gbuf = static_cast<float *>(w.g);
+    a.pv = reinterpret_cast<float *>(w.mega);
+    a.pi = reinterpret_cast<int32_t *>(w.mega + (size_t)kMegaMaxBlocks * kMegaMaxB * 4);
+    a.bar = reinterpret_cast<unsigned *>(w.mega + (size_t)kMegaMaxBlocks * kMegaMaxB * 8);
+    const int mb = mega_rows(B);
+    const size_t lds = (size_t)mb * std::max(std::max(m->d, m->dm), m->ff) * 4;
+    const void *kern = mb == 1 ? reinterpret_cast<const void *>(mega_generate_kernel<1>)
+                       : mb == 2 ? reinterpret_cast<const void *>(mega_generate_kernel<2>)
+                       : mb == 4 ? reinterpret_cast<const void *>(mega_generate_kernel<4>)
+                                 : reinterpret_cast<const void *>(mega_generate_kernel<kMegaMaxB>);
+    static bool attr_set[4] = {false, false, false, false};
+    const int slot = mb == 1 ? 0 : mb == 2 ? 1 : mb == 4 ? 2 : 3;
+    if (!attr_set[slot]) {
+        HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+        attr_set[slot] = true;
+    }
+    hipLaunchKernelGGL(mega_reset_kernel, dim3(1), dim3(64), 0, st, a.bar);
+    HIP_TRY(hipGetLastError());
+    void *args[] = {&a};
+    HIP_TRY(hipLaunchCooperativeKernel(kern, dim3((unsigned)nblk), dim3(kMegaThreads), args, (unsigned)lds, st));
+    return SRM_OK;
+}
+
 // ------------------------------------------------------------------ generate (G steps in one call)
 static int generate_step(srm_model *m, int64_t B, int32_t *tok, void *state, void *ws, size_t ws_bytes, int *ctr,
                          TokenStore ts, hipStream_t st, float temperature, uint32_t seed, float top_p, float *logits,
@@ -942,6 +1040,11 @@ static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int
                     (long long)std::min<int64_t>(B, 256));
     SRM_TRY(check_device(m));
     hipStream_t st = as_stream(hip_stream);
+    if (!topp && !d_pos && !eos_plus1 && srm_workspace_bytes(m, B) <= ws_bytes) {
+        const int nblk = mega_blocks(m, B);
+        if (nblk > 0)
+            return mega_generate(m, (int)B, pos0, G, d_tok, d_state, d_tokens_out, temperature, seed, d_workspace, nblk, st);
+    }
     int *ctr = reinterpret_cast<int *>(static_cast<unsigned char *>(d_workspace) + ws_bytes - 256);
     const TokenStore ts{d_tokens_out, ctr + 1, B};
     hipLaunchKernelGGL(counters_set_kernel, dim3(1), dim3(1), 0, st, ctr, pos0, 0);
