@@ -47,29 +47,42 @@ struct MegaArgs {
     float *x, *mbuf, *gbuf;      // [B][d], [B][dm], [B][ff]
     float *pv;                   // [gridDim.x][kMegaMaxB] partial winners
     int32_t *pi;
-    unsigned *bar;               // bar[0] arrivals (starts at 0), bar[32] give-up flag
+    unsigned *bar;               // barrier slots and give-up flag (see mega_barrier), all zero at the start
 };
 
 
+// Grid barrier without read-modify-write traffic: work-group i publishes the number of the barrier it
+// has reached in its own 64-byte slot, and the first wavefront of every work-group polls all slots at
+// once (lane i reads slot i) until none is behind.  bar[i * 16] = slot of work-group i (all start at 0),
+// bar[kMegaMaxBlocks * 16] = give-up flag.  The wait is bounded: a work-group that gives up raises the
+// flag, which ends every other wait.
+constexpr int kMegaMaxBlocks = 64;
 __device__ __forceinline__ bool mega_barrier(unsigned *bar, unsigned &epoch, int *ok_lds)
 {
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < 64) {
+        ++epoch;
+        if (threadIdx.x == 0) {
+            __threadfence();                   // this work-group's writes first
+            __hip_atomic_store(bar + blockIdx.x * 16, epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        unsigned *flag = bar + kMegaMaxBlocks * 16;
+        const unsigned *slot = bar + (threadIdx.x < gridDim.x ? threadIdx.x : 0) * 16;
         bool ok = true;
-        epoch += gridDim.x;
-        __threadfence();
-        __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         unsigned spins = 0;
-        while (__hip_atomic_load(bar, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < epoch) {
-            if (++spins > (1u << 22) || __hip_atomic_load(bar + 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
-                __hip_atomic_store(bar + 32, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (;;) {
+            const unsigned seen = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // unsigned distance, so that the comparison survives a wrap of the counter
+            if (__all((int)(seen - epoch) >= 0)) break;
+            if (++spins > (1u << 22) || __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 ok = false;
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
         }
-        __threadfence();
-        *ok_lds = ok;
+        __threadfence();                       // acquire: drop what the caches hold of the others' data
+        if (threadIdx.x == 0) *ok_lds = ok;
     }
     __syncthreads();
     return *ok_lds != 0;
@@ -464,8 +477,8 @@ give_up:
     if (threadIdx.x < B) p.tok[threadIdx.x] = -1;
 }
 
-// bar[0] = arrivals, bar[32] = give-up flag: both start at zero.
+// The barrier slots and the give-up flag start at zero.
 __global__ void mega_reset_kernel(unsigned *bar)
 {
-    if (threadIdx.x == 0) { bar[0] = 0u; bar[32] = 0u; }
+    for (int i = threadIdx.x; i <= kMegaMaxBlocks * 16; i += blockDim.x) bar[i] = 0u;
 }

@@ -339,9 +339,9 @@ constexpr int64_t kSplitMaxRows = 2048;
 constexpr int kGemvSplitMax = 8;
 constexpr int64_t kGemvRows = 32;
 
-// Scratch of the one-kernel path: [kMegaMaxBlocks][kMegaMaxB] floats, the same of ints, then 256 bytes of barrier words.
-constexpr int kMegaMaxBlocks = 64;
-constexpr size_t kMegaScratch = (size_t)kMegaMaxBlocks * kMegaMaxB * 8 + 256;
+// Scratch of the one-kernel path: [kMegaMaxBlocks][kMegaMaxB] floats, the same of ints, then the barrier's
+// 64-byte slots (one per work-group) and its give-up flag.
+constexpr size_t kMegaScratch = (size_t)kMegaMaxBlocks * kMegaMaxB * 8 + (size_t)kMegaMaxBlocks * 64 + 256;
 
 static Workspace carve(const srm_model *m, void *base, int64_t rows)
 {
