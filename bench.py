@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--mixer-kernel", type=int, default=1,
                     help="k > 1: k column-repeat filters along the hidden dimension per mixer layer (a model variant; "
                          "implies --head-layout column)")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="decode batch instead of the workload's own (e.g. C4's model at a small batch: the "
+                         "weight-streaming regime)")
     ap.add_argument("--top-p", type=float, default=1.0,
                     help="with --temperature: nucleus truncation (the paper's rollouts use 0.9 at temperature 0.7)")
     ap.add_argument("--per-step-calls", action="store_true",
@@ -265,6 +268,9 @@ def main():
         import dataclasses
         cfg = dataclasses.replace(cfg, use_projections=not args.no_projections, state_dtype=args.state_dtype,
                                   head_layout=args.head_layout, mixer_kernel=args.mixer_kernel)
+    if args.batch > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, batch=args.batch)
     B, P = cfg.batch, cfg.prompt_len
     t0 = time.perf_counter()
     w = srm_synth.make_weights(cfg)

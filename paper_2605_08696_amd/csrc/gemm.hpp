@@ -414,11 +414,12 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
     }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, typename TAct>
+template <int BM, int BN, int WM, int WN, int EPI, typename TAct, int NS = 2>
 __global__ void __launch_bounds__(WM *WN * 64)
 gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, int N, int K, GemmEpi ep)
 {
     constexpr int BK = 64;
+    static_assert(NS >= 2 && (NS & (NS - 1)) == 0, "the LDS ring holds a power-of-two number of k tiles");
     constexpr int NW = WM * WN, NTHR = NW * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -426,11 +427,11 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     constexpr int STG = WTN + 4;                     // stage row stride in floats: 16 B * odd
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
     static_assert((BM * BK / 8) % NTHR == 0 && (BN * BK / 8) % NTHR == 0, "tile/threads mismatch");
-    static_assert(NW * 32 * STG * 4 + BM * WN * 8 <= 2 * (BM + BN) * BK * 2, "epilogue stage exceeds the tile LDS");
+    static_assert(NW * 32 * STG * 4 + BM * WN * 8 <= NS * (BM + BN) * BK * 2, "epilogue stage exceeds the tile LDS");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);   // [2][BM*BK]
-    bf16 *Bs = As + 2 * BM * BK;                     // [2][BN*BK]
+    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);   // [NS][BM*BK]
+    bf16 *Bs = As + NS * BM * BK;                    // [NS][BN*BK]
 
     // Split K (gridDim.y > 1, EPI_F32 only): block row y of the grid contracts k in
     // [y * K / gridDim.y, (y + 1) * K / gridDim.y) and writes its own output slab
@@ -519,8 +520,10 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     }                                                                                            \
     __builtin_amdgcn_sched_barrier(0);
 
-    // Software pipeline over K tiles (four k-substeps of 16 each), two LDS
-    // buffers, MFMA operands read two substeps ahead (four register sets):
+    // Software pipeline over K tiles (four k-substeps of 16 each), a ring of NS LDS
+    // buffers (NS = 2 below; with few blocks on the chip a k loop is bound by the
+    // latency of its tile loads, and a deeper ring keeps NS - 1 tiles in flight),
+    // MFMA operands read two substeps ahead (four register sets):
     //   substep 0: read operands of substep 2                  | MFMAs of substep 0
     //   substep 1: read operands of substep 3                  | MFMAs of substep 1
     //              wait for tile kt+1's loads, barrier: buffer `cur` is now free
@@ -532,29 +535,30 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     // the LDS pipe.  Loads for tiles past the end are issued like any other
     // (range check: zeros nobody reads), which keeps the loop branch-free.
     const int KT = K / ksplit / BK;
-    SRM_DMA_TILE(0, 0)
-    SRM_DMA_TILE(BK, 1)
-    SRM_WAIT_VM(A_IT + B_IT);
+    static_assert((NS - 1) * (A_IT + B_IT) <= 63, "more tile loads in flight than the counter holds");
+#pragma unroll
+    for (int stage = 0; stage < NS; ++stage) { SRM_DMA_TILE(stage * BK, stage) }   // (the macro's own loops use `i`)
+    SRM_WAIT_VM((NS - 1) * (A_IT + B_IT));
     __syncthreads();
     SRM_READ_FRAGS(0, 0, 0)
     SRM_READ_FRAGS(0, 1, 1)
     __builtin_amdgcn_sched_barrier(0);
 
     for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
+        const int cur = kt & (NS - 1), nxt = (kt + 1) & (NS - 1);
         SRM_READ_FRAGS(cur, 2, 2)
         SRM_MFMA_STEP(0)
         SRM_INTERLEAVE(0)
         SRM_READ_FRAGS(cur, 3, 3)
         SRM_MFMA_STEP(1)
         SRM_INTERLEAVE(0)
-        SRM_WAIT_VM(0);
+        SRM_WAIT_VM((NS - 2) * (A_IT + B_IT));           // tile kt+1 has landed; later tiles may still be in flight
         __syncthreads();
-        SRM_READ_FRAGS(cur ^ 1, 0, 0)
-        SRM_DMA_TILE((kt + 2) * BK, cur)
+        SRM_READ_FRAGS(nxt, 0, 0)
+        SRM_DMA_TILE((kt + NS) * BK, cur)
         SRM_MFMA_STEP(2)
         SRM_INTERLEAVE(A_IT + B_IT)
-        SRM_READ_FRAGS(cur ^ 1, 1, 1)
+        SRM_READ_FRAGS(nxt, 1, 1)
         SRM_MFMA_STEP(3)
         SRM_INTERLEAVE(0)
     }

@@ -50,9 +50,16 @@ ln_kernel(const float *x_in, int64_t in_stride, const int32_t *__restrict__ tok,
             } else {
                 v[i] = load4(x_in + src * in_stride + c);
                 if (part) {
-                    for (int sp = 0; sp < nsplit; ++sp) {
-                        const float4 t = load4(part + sp * part_stride + row * d + c);
-                        v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
+                    // four slabs requested at a time (a load per iteration would serialise their latencies);
+                    // the sums are still formed in slab order
+                    for (int s0 = 0; s0 < nsplit; s0 += 4) {
+                        float4 t[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            t[j] = load4(part + (int64_t)min(s0 + j, nsplit - 1) * part_stride + row * d + c);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (s0 + j < nsplit) { v[i].x += t[j].x; v[i].y += t[j].y; v[i].z += t[j].z; v[i].w += t[j].w; }
                     }
                     store4(x_out + row * d + c, v[i]);
                 }

@@ -324,7 +324,7 @@ struct Workspace {
     int *ctr;          // [2] position and step counters of srm_generate
     int *slow;         // [64 + rows] nucleus pass: count, then (from slow + 64) the rows that need the search
     unsigned char *mega;  // [kMegaScratch] one-kernel small-batch path: partial winners and the barrier words
-    float *part;       // [kSplitK][rows][d] split-K slabs of the down projection (rows <= kSplitMaxRows), else null
+    float *part;       // [slices][rows][d] split-K slabs of a residual projection (rows <= kSplitMaxRows), else null
     size_t bytes;
 };
 
@@ -381,12 +381,12 @@ extern "C" size_t srm_workspace_bytes(const srm_model *m, int64_t rows)
 }
 
 // ------------------------------------------------------------------ launchers
-template <int BM, int BN, int WM, int WN, int EPI, typename TAct>
+template <int BM, int BN, int WM, int WN, int EPI, typename TAct, int NS = 2>
 static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, const GemmEpi &ep, hipStream_t st,
                             int ksplit = 1)
 {
-    constexpr size_t smem = (size_t)2 * (BM + BN) * 64 * sizeof(bf16);
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI, TAct>;
+    constexpr size_t smem = (size_t)NS * (BM + BN) * 64 * sizeof(bf16);
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI, TAct, NS>;
     static bool attr_set = false;
     if (!attr_set) {
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -397,6 +397,20 @@ static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, c
     hipLaunchKernelGGL(kern, dim3((unsigned)nb, (unsigned)ksplit), dim3(WM * WN * 64), smem, st, A, W, M, N, K, ep);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
+}
+
+// The 64x64 tile with few blocks on the chip: its k loop is bound by the latency of the tile loads, so
+// the LDS ring is deepened as far as the blocks per CU allow (8 stages = 128 KB: one block per CU;
+// 4 stages = 64 KB: two).
+template <int EPI, typename TAct>
+static int launch_bf16_small(const bf16 *A, const bf16 *W, int M, int N, int K, const GemmEpi &ep, hipStream_t st,
+                             int ksplit)
+{
+    const int64_t blocks = cdiv(M, 64) * cdiv(N, 64) * ksplit;
+    const int kt = K / ksplit / 64;
+    if (blocks <= 256 && kt > 4) return launch_bf16_tile<64, 64, 2, 2, EPI, TAct, 8>(A, W, M, N, K, ep, st, ksplit);
+    if (blocks <= 512 && kt > 2) return launch_bf16_tile<64, 64, 2, 2, EPI, TAct, 4>(A, W, M, N, K, ep, st, ksplit);
+    return launch_bf16_tile<64, 64, 2, 2, EPI, TAct>(A, W, M, N, K, ep, st, ksplit);
 }
 
 // Tile codes of the bf16 GEMM: 0 = 256x256 (8 waves), 1 = 128x128 (4 waves),
@@ -427,7 +441,7 @@ static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, Ge
         if (EPI != EPI_F32 || K % (64 * ksplit)) return fail(SRM_EINVAL, "bf16 GEMM: bad split of K = %d", K);
         if (M <= 0 || M >= (1 << 30) || N <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
         ep.nparts = 0;
-        return launch_bf16_tile<64, 64, 2, 2, EPI, TAct>(A, W, (int)M, N, K, ep, st, ksplit);
+        return launch_bf16_small<EPI, TAct>(A, W, (int)M, N, K, ep, st, ksplit);
     }
     if (M <= 0 || M >= (1 << 30) || N <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
     if ((int64_t)K * 256 * 2 >= (1LL << 31)) return fail(SRM_EINVAL, "bf16 GEMM: K = %d too large", K);
@@ -438,7 +452,7 @@ static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, Ge
     switch (tile) {
     case 0: return launch_bf16_tile<256, 256, 2, 4, EPI, TAct>(A, W, m, N, K, ep, st);
     case 1: return launch_bf16_tile<128, 128, 2, 2, EPI, TAct>(A, W, m, N, K, ep, st);
-    case 2: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct>(A, W, m, N, K, ep, st);
+    case 2: return launch_bf16_small<EPI, TAct>(A, W, m, N, K, ep, st, 1);
     case 3: return launch_bf16_tile<128, 128, 2, 4, EPI, TAct>(A, W, m, N, K, ep, st);
     case 4: return launch_bf16_tile<256, 128, 4, 2, EPI, TAct>(A, W, m, N, K, ep, st);
     default: return fail(SRM_EINVAL, "unknown GEMM tile code %d", tile);
@@ -635,10 +649,20 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
 {
     const LayerDev &y = m->layers[l];
     const int d = m->d, dm = m->dm, ff = m->ff;
-    // split-K down projection (decode with few rows, bf16): see kSplitK
-    // (not with the fused non-projected layer: no LayerNorm kernel follows there to add the slabs)
-    const bool split = allow_split && norm_next && sizeof(T) == 2 && w.part && ff >= 1024 &&
-                       ff % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 256 && !(m->noproj && np_state);
+    // K slices of a residual projection (decode with few rows; see kSplitK).  bf16: the MLP down projection in
+    // kSplitK slices while the 64x64 tiles number at most 256 (measured: more slices, or slicing the
+    // out-projection too, costs more in the LayerNorm that adds the slabs than the shorter k loops save).
+    // fp32 with at most kGemvRows rows (GEMVs): both projections, slices of at least 64 k.
+    auto resid_split = [&](int K, bool down) {
+        if (!allow_split || !w.part) return 1;
+        if (sizeof(T) == 4) {
+            if (rows > kGemvRows) return 1;
+            int sp = kGemvSplitMax;
+            while (sp > 1 && (K % (16 * sp) || K / sp < 64)) sp >>= 1;
+            return sp;
+        }
+        return down && K >= 1024 && K % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 256 ? kSplitK : 1;
+    };
     if (m->noproj && np_state) {
         // non-projected layer, decode: LayerNorm1, state update, residual add and LayerNorm2 in one kernel
         const unsigned nb = (unsigned)cdiv(rows, 4);
@@ -674,15 +698,8 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
         SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, dm, d, w.u, st)));
         SRM_TRY(mix(l));
     }
-    // fp32, few rows: K slices of the residual GEMVs, chosen so that a slice keeps at least 64 k
-    auto gemv_split = [&](int K) {
-        if (!(allow_split && sizeof(T) == 4 && rows <= kGemvRows && w.part)) return 1;
-        int sp = kGemvSplitMax;
-        while (sp > 1 && (K % (16 * sp) || K / sp < 64)) sp >>= 1;
-        return sp;
-    };
     if (!m->noproj) {
-        const int sp = gemv_split(dm);
+        const int sp = resid_split(dm, false);
         if (sp > 1) {
             SRM_TRY((linear<EPI_F32, T>(w.mx, y.w_out, y.b_out, rows, d, dm, w.part, st, nullptr, nullptr, 64, nullptr,
                                         Sampling(), sp)));
@@ -694,11 +711,9 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
         }
     }
     SRM_TRY((linear<EPI_GELU, T>(w.a, y.w_up, y.b_up, rows, ff, d, w.g, st)));
-    const int spd = (norm_next && !(m->noproj && np_state)) ? gemv_split(ff) : 1;
-    if (split)
-        SRM_TRY((linear<EPI_F32, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.part, st, nullptr, nullptr, 64, nullptr,
-                                    Sampling(), kSplitK)));
-    else if (spd > 1)
+    // (not with the fused non-projected layer: no LayerNorm kernel follows there to add the slabs)
+    const int spd = (norm_next && !(m->noproj && np_state)) ? resid_split(ff, true) : 1;
+    if (spd > 1)
         SRM_TRY((linear<EPI_F32, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.part, st, nullptr, nullptr, 64, nullptr,
                                     Sampling(), spd)));
     else
@@ -706,9 +721,8 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
     if (norm_next && !(m->noproj && np_state && l + 1 < m->L)) {   // the fused kernel does its own LayerNorm1
         const float *g = l + 1 < m->L ? m->layers[l + 1].ln1_g : m->lnf_g;
         const float *b = l + 1 < m->L ? m->layers[l + 1].ln1_b : m->lnf_b;
-        if (split || spd > 1)      // x += slabs, then normalise
-            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, g, b, w.a, rows, st, nullptr, 0, 0, w.part,
-                                         split ? kSplitK : spd)));
+        if (spd > 1)               // x += slabs, then normalise
+            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, g, b, w.a, rows, st, nullptr, 0, 0, w.part, spd)));
         else
             SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, g, b, w.a, rows, st)));
     }
