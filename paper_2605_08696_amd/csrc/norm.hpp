@@ -31,6 +31,10 @@ ln_kernel(const float *x_in, int64_t in_stride, const int32_t *__restrict__ tok,
     if (row >= rows) return;
 
     float4 v[VPL];
+    // up to 4 vectors per lane the gain and bias are requested together with the row, so that their latency
+    // does not follow the two reductions (wider rows would need too many registers for that)
+    constexpr bool kEarlyParams = VPL <= 4;
+    float4 pg[kEarlyParams ? VPL : 1], pb[kEarlyParams ? VPL : 1];
     float sum = 0.0f;
     const TW *erow = nullptr;
     int64_t src = row;
@@ -44,6 +48,10 @@ ln_kernel(const float *x_in, int64_t in_stride, const int32_t *__restrict__ tok,
     for (int i = 0; i < VPL; ++i) {
         const int c = (i * 64 + lane) * 4;
         if (c < d) {
+            if constexpr (kEarlyParams) {
+                pg[i] = load4(g + c);
+                pb[i] = load4(b + c);
+            }
             if constexpr (GATHER) {
                 v[i] = load4(erow + c);
                 store4(x_out + row * d + c, v[i]);
@@ -90,7 +98,9 @@ ln_kernel(const float *x_in, int64_t in_stride, const int32_t *__restrict__ tok,
     for (int i = 0; i < VPL; ++i) {
         const int c = (i * 64 + lane) * 4;
         if (c < d) {
-            const float4 gg = load4(g + c), bb = load4(b + c);
+            float4 gg, bb;
+            if constexpr (kEarlyParams) { gg = pg[i]; bb = pb[i]; }
+            else { gg = load4(g + c); bb = load4(b + c); }
             float4 o;
             o.x = (v[i].x - mean) * rstd * gg.x + bb.x;
             o.y = (v[i].y - mean) * rstd * gg.y + bb.y;
