@@ -204,7 +204,12 @@ int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, const int32_t 
  * stay the same.  On the legacy default stream (NULL), which cannot be
  * captured, the steps are launched one by one instead.  temperature = 0 is
  * greedy; temperature > 0 samples as srm_decode_step_sampled does.  Results are
- * identical to G srm_decode_step(_sampled) calls.  Not thread-safe per model.
+ * identical to G srm_decode_step(_sampled) calls, except that a call which
+ * qualifies for the one-kernel path (see srm_generate_one_kernel_blocks) runs
+ * all G steps in one cooperative launch, with fp32 sums in another order: equal
+ * to the step calls up to fp32 rounding, token-exact unless two scores tie
+ * within that rounding.  Such a call must not be made under stream capture.
+ * Not thread-safe per model.
  * Errors: SRM_EINVAL (null pointer, B or G <= 0, pos0 + G > n_ctx), SRM_ENOMEM
  * (workspace smaller than srm_workspace_bytes(m, B)), SRM_EHIP.
  */
