@@ -164,7 +164,7 @@ def cpu_baseline(cfg, w, rows, T):
     orc.recurrent_forward(toks, pos0=cfg.prompt_len, want_hidden=False, want_logits=False, want_greedy=True)
     dt = time.perf_counter() - t0
     threads = min(rows, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
-    return {"value": rows * T / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+    return {"value": rows * T / dt, "unit": "tokens/s", "cores": threads, "per_core": rows * T / dt / threads, "kind": "oracle",
             "sample": f"{rows} samples x {T} decode positions of {cfg.name} (fp32 build, OpenMP over samples), {dt:.1f} s"}
 
 
