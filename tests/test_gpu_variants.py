@@ -416,3 +416,30 @@ def test_kernel_mixer_errors(srm):
     cfg = dataclasses.replace(cfg, head_layout="column", use_projections=False)
     with pytest.raises(srm.SrmError):
         srm.Model(cfg, w)                                      # needs the projections
+
+
+@pytest.mark.parametrize("variant", [dict(head_layout="combined"), dict(head_layout="column", mixer_kernel=2),
+                                     dict(head_layout="row")])
+def test_variants_at_the_large_configuration_shape(srm, orc_mod, variant):
+    """C4's shape and batch (the launch configuration bench.py times: 256x256 tiles, separate state update,
+    mixer rows of 2d for the combined / two-filter models): teacher-forced steps from a zero state, the oracle
+    on two rows."""
+    cfg = dataclasses.replace(srm_synth.CONFIGS["C4"], n_ctx_fixed=64, **variant)
+    w = srm_synth.make_weights(cfg)
+    B, T = cfg.batch, 4
+    toks = srm_synth.make_prompts(cfg, batch=B, length=T)
+    rows = [0, B - 1]
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks[rows])
+    model = srm.Model(cfg, w)
+    assert model.state_bytes(B) == cfg.n_layers * B * cfg.state_width * 4
+    ws, st = model.new_workspace(B), model.new_state(B)
+    out = torch.empty(B, dtype=torch.int32, device="cuda")
+    lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+    tc = to_dev(toks).t().contiguous()
+    print(f"large shape, {variant}", flush=True)
+    for t in range(T):
+        model.decode_step(B, t, tc[t], st, out, logits=lg, workspace=ws)
+        assert rel_err_rows(lg[rows].cpu().numpy(), ref["logits"][:, t]) <= 2e-2
+    s_got = st[:, rows].permute(1, 0, 2).cpu().numpy()
+    assert np.abs(s_got - ref["state"]).max() <= 2e-2 * np.abs(ref["state"]).max()
+    assert bool(torch.isfinite(st).all()) and bool(((out >= 0) & (out < cfg.vocab)).all())
