@@ -385,12 +385,14 @@ size_t srm_linear_scratch_bytes(int64_t M, int32_t N);
  * for a batch of B samples, or 0 if such a call runs the ordinary step kernels.
  * The one-kernel path ("MAX model details": per-call overhead dominates small
  * batches) serves greedy and temperature sampling (no top-p) for fp32 models
- * with fp32 state and head projections, B <= 8, d_model <= 1024 and at most
- * 128 KB for the widest activation row of all samples: a small cooperative grid
+ * with fp32 state and head projections, B <= 8, d_model <= 1024, at most
+ * 128 KB for the widest activation row of all samples, and rows x matrix
+ * elements below about 16 M (beyond, the step kernels are faster): a small cooperative grid
  * walks through all G steps, its phases separated by grid barriers, so a step
  * costs 4L + 1 barriers instead of 6L + 7 kernel launches.  Same results up to
  * the fp32 summation order.  Environment: SRM_MEGAKERNEL=0 switches it off,
- * SRM_MEGA_BLOCKS=n sets the grid (default 16, at most 64).
+ * SRM_MEGAKERNEL=2 takes it whatever the model's size, SRM_MEGA_BLOCKS=n sets
+ * the grid (default 16, at most 64).
  */
 int32_t srm_generate_one_kernel_blocks(const srm_model *m, int64_t B);
 

@@ -651,83 +651,166 @@ gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
     }
 }
 
-// ------------------------------------------------------------------ fp32, few rows
-// M <= a few dozen rows (small-batch decode): the work is streaming W once.  A
-// block of 256 threads owns 64 output columns; thread (c = tid & 63, q = tid >> 6)
-// accumulates, for MR rows at a time, the dot products of column c over the q-th
-// quarter of K.  The MR activation rows sit in LDS (every lane reads the same
-// address: a broadcast), each lane streams its own W row with 16-byte loads, and
-// the four K-quarters are added through LDS in a fixed order.  One argmax partial
-// per block, the layout gemm_f32_kernel uses.  Needs (K / gridDim.y) % 16 == 0.
-// Dynamic LDS: (MR * K / gridDim.y + 4 * MR * 64) floats.
-template <int EPI, int MR>
-__global__ void __launch_bounds__(256)
-gemv_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M, int N, int K, GemmEpi ep)
+// ------------------------------------------------------------------ few rows: streaming GEMV
+// out = epilogue(A W^T + bias) for at most a few dozen rows (fp32 models; with bf16 weights the 64x64
+// MFMA tile is faster even for one row: measured 2.7 us + 3.4 us per 1024 k against 5.5 + 6.9 for this
+// kernel reading bf16, whose eight rows of activations per weight vector make it LDS-bound).  The
+// product is bound by streaming W once, so the grid is made of
+// many small column slices (16 * CPG columns per block) and the loads are coalesced: 16 lanes
+// share CPG columns (4 such groups per wavefront), lane l16 reading every 16th 16-byte vector of
+// a weight row; MB rows of A sit in LDS as fp32 and are read by every column; after the 16-lane
+// reduction lane l16 == b owns row b of the group's columns.  Weight vectors are requested one
+// batch ahead, the first batch before A is staged.  Rows are processed MB at a time (W is streamed
+// again per group of MB rows).  Split K as in gemm_bf16_kernel (gridDim.y slabs, EPI_F32 only).
+// Dynamic LDS: MB * (K / gridDim.y) floats.
+__device__ __forceinline__ float row16_sum_dpp(float v)
 {
-    extern __shared__ __align__(16) float gemv_sm[];
-    // Split K (gridDim.y > 1, EPI_F32 only), as in gemm_bf16_kernel: block row y contracts
-    // k in [y * Kp, (y + 1) * Kp) into its own output slab; slab 0 carries the bias.
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
+    return v;
+}
+
+template <typename TW> struct GemvVec;
+template <> struct GemvVec<float> {
+    static constexpr int VW = 4;
+    __device__ static void unpack(const u32x4_t &r, float (&f)[4])
+    {
+        const f32x4_t t = __builtin_bit_cast(f32x4_t, r);
+        f[0] = t[0]; f[1] = t[1]; f[2] = t[2]; f[3] = t[3];
+    }
+};
+template <typename TW, typename TAct, int EPI, int MB, int CPG>
+__global__ void __launch_bounds__(256)
+gemv_rows_kernel(const TAct *__restrict__ A, const TW *__restrict__ W, int M, int N, int K, GemmEpi ep)
+{
+    extern __shared__ __align__(16) float gr_sm[];      // [MB][Kp]
+    __shared__ float red_v[16][MB];
+    __shared__ int red_i[16][MB];
+    constexpr int VW = GemvVec<TW>::VW;
+    constexpr int JB = 8 / CPG;                          // 16-byte vectors per lane, column and batch
+    static_assert(MB <= 16 && CPG * JB == 8, "one owner lane per row; eight vectors per lane and batch");
     const int Kp = K / (int)gridDim.y, kb = blockIdx.y * Kp;
     if (gridDim.y > 1) {
         ep.out = reinterpret_cast<float *>(ep.out) + (int64_t)blockIdx.y * M * ep.ldo;
         if (blockIdx.y) ep.bias = nullptr;
     }
-    float *xs = gemv_sm;                   // [MR][Kp]
-    float *part = gemv_sm + MR * Kp;       // [4][MR][64]
-    const int tid = threadIdx.x, c = tid & 63, q = tid >> 6;
-    const int n = blockIdx.x * 64 + c;
-    const int Ks = Kp >> 2;
-    const float *wrow = W + (size_t)min(n, N - 1) * K + kb + q * Ks;
-    for (int mg = 0; mg < M; mg += MR) {
-        __syncthreads();
-        for (int i = tid; i < MR * Kp / 4; i += 256) {
-            const int m = (i * 4) / Kp, k = (i * 4) - m * Kp;
-            const float4 v = mg + m < M ? load4(A + (size_t)(mg + m) * K + kb + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-            store4(xs + m * Kp + k, v);
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15;
+    const int grp = (tid >> 6) * 4 + (lane >> 4);        // 0..15
+    const int KV = Kp / VW;                              // 16-byte vectors per row slice
+    const int nbatch = (KV + 16 * JB - 1) / (16 * JB);
+    int n[CPG];
+    const u32x4_t *wr[CPG];
+#pragma unroll
+    for (int c = 0; c < CPG; ++c) {
+        n[c] = (blockIdx.x * 16 + grp) * CPG + c;
+        wr[c] = reinterpret_cast<const u32x4_t *>(W + (size_t)min(n[c], N - 1) * K + kb);
+    }
+    auto load_batch = [&](u32x4_t (&w)[CPG][JB], int jb) {
+#pragma unroll
+        for (int c = 0; c < CPG; ++c)
+#pragma unroll
+            for (int j = 0; j < JB; ++j) {
+                const int kv = (jb * JB + j) * 16 + l16;
+                const u32x4_t v = wr[c][min(kv, KV - 1)];          // clamped address, zeroed by a mask: no branches between loads
+                const uint32_t keep = (n[c] < N && kv < KV) ? 0xffffffffu : 0u;
+                w[c][j] = v & keep;
+            }
+    };
+    u32x4_t w[CPG][JB];
+    load_batch(w, 0);
+    float bias[CPG];
+#pragma unroll
+    for (int c = 0; c < CPG; ++c) bias[c] = (ep.bias && n[c] < N) ? ep.bias[n[c]] : 0.0f;
+
+    for (int mg = 0; mg < M; mg += MB) {
+        __syncthreads();                                 // the previous group's products are done with the stage
+        // stage the group's rows as fp32: a thread takes the same four k of every row, all MB loads in flight
+        const int rows_here = min(MB, M - mg);
+        for (int k = tid * 4; k < Kp; k += 256 * 4) {
+            float4 v[MB];
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                v[m] = load4(A + (size_t)(mg + min(m, rows_here - 1)) * K + kb + k);
+                if (m >= rows_here) v[m] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int m = 0; m < MB; ++m) *reinterpret_cast<float4 *>(gr_sm + m * Kp + k) = v[m];
         }
         __syncthreads();
-        float acc[MR];
+        if (mg > 0) load_batch(w, 0);
+        float acc[CPG][MB];
 #pragma unroll
-        for (int m = 0; m < MR; ++m) acc[m] = 0.0f;
-        for (int k = 0; k < Ks; k += 4) {
-            const float4 w4 = load4(wrow + k);
+        for (int c = 0; c < CPG; ++c)
 #pragma unroll
-            for (int m = 0; m < MR; ++m) {
-                const float4 x4 = load4(xs + m * Kp + q * Ks + k);
-                acc[m] = fmaf(w4.x, x4.x, acc[m]);
-                acc[m] = fmaf(w4.y, x4.y, acc[m]);
-                acc[m] = fmaf(w4.z, x4.z, acc[m]);
-                acc[m] = fmaf(w4.w, x4.w, acc[m]);
+            for (int b = 0; b < MB; ++b) acc[c][b] = 0.0f;
+#pragma unroll 1
+        for (int jb = 0; jb < nbatch; ++jb) {
+            u32x4_t wn[CPG][JB];
+            if (jb + 1 < nbatch) load_batch(wn, jb + 1);
+#pragma unroll
+            for (int j = 0; j < JB; ++j) {
+                const int kv = min((jb * JB + j) * 16 + l16, KV - 1);
+                float wf[CPG][VW];
+#pragma unroll
+                for (int c = 0; c < CPG; ++c) GemvVec<TW>::unpack(w[c][j], wf[c]);
+                // all rows' activations for this k position first (one batch of LDS reads), then the products
+                float4 av[MB][VW / 4];
+#pragma unroll
+                for (int b = 0; b < MB; ++b)
+#pragma unroll
+                    for (int q = 0; q < VW / 4; ++q)
+                        av[b][q] = *reinterpret_cast<const float4 *>(gr_sm + b * Kp + kv * VW + q * 4);
+#pragma unroll
+                for (int b = 0; b < MB; ++b)
+#pragma unroll
+                    for (int q = 0; q < VW / 4; ++q)
+#pragma unroll
+                        for (int c = 0; c < CPG; ++c) {
+                            acc[c][b] = fmaf(wf[c][q * 4], av[b][q].x, acc[c][b]);
+                            acc[c][b] = fmaf(wf[c][q * 4 + 1], av[b][q].y, acc[c][b]);
+                            acc[c][b] = fmaf(wf[c][q * 4 + 2], av[b][q].z, acc[c][b]);
+                            acc[c][b] = fmaf(wf[c][q * 4 + 3], av[b][q].w, acc[c][b]);
+                        }
+            }
+#pragma unroll
+            for (int c = 0; c < CPG; ++c)
+#pragma unroll
+                for (int j = 0; j < JB; ++j) w[c][j] = wn[c][j];
+        }
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int c = 0; c < CPG; ++c) {
+            float mine = 0.0f;
+#pragma unroll
+            for (int b = 0; b < MB; ++b) {
+                const float v = row16_sum_dpp(acc[c][b]);
+                if (l16 == b) mine = v;
+            }
+            const int row = mg + l16;
+            if (l16 < MB && row < M && n[c] < N) {
+                float v = mine + bias[c];
+                epi_store1p<EPI, TAct>(ep, row, n[c], v);
+                if constexpr (EPI == EPI_ARGMAX) {
+                    if (ep.temp > 0.0f)
+                        v += ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep, row, M), (uint32_t)row + ep.row_base), (uint32_t)n[c]);
+                    if (arg_better(v, n[c], bv, bi)) { bv = v; bi = n[c]; }
+                }
             }
         }
-#pragma unroll
-        for (int m = 0; m < MR; ++m) part[(q * MR + m) * 64 + c] = acc[m];
-        __syncthreads();
-        // thread (c, q) finishes rows q, q + 4, ...; the lanes of wave q are the 64 columns
-        for (int m = q; m < MR; m += 4) {
-            const int row = mg + m;
-            float v = ((part[m * 64 + c] + part[(MR + m) * 64 + c]) + part[(2 * MR + m) * 64 + c]) +
-                      part[(3 * MR + m) * 64 + c];
-            const bool live = n < N && row < M;
-            if (live) {
-                v += ep.bias ? ep.bias[n] : 0.0f;
-                epi_store<EPI, float>(ep, row, n, v);
-            }
-            if constexpr (EPI == EPI_ARGMAX) {
-                if (live && ep.temp > 0.0f)
-                    v += ep.temp * srm_gumbel(srm_rowkey(ep.seed, epi_pos(ep, row, M), (uint32_t)row + ep.row_base), (uint32_t)n);
-                float bv = live ? v : -INFINITY;
-                int bi = live ? n : 0x7fffffff;
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    const float ov = __shfl_xor(bv, off, kWave);
-                    const int oi = __shfl_xor(bi, off, kWave);
-                    if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-                }
-                if (c == 0 && row < M) {
-                    ep.part_val[(int64_t)row * ep.nparts + blockIdx.x] = bv;
-                    ep.part_idx[(int64_t)row * ep.nparts + blockIdx.x] = bi;
-                }
+        if constexpr (EPI == EPI_ARGMAX) {
+            // best (score, index) of this block's columns per row: 16 lane groups -> one partial
+            if (l16 < MB) { red_v[grp][l16] = bv; red_i[grp][l16] = bi; }
+            __syncthreads();
+            if (tid < MB && mg + tid < M) {
+                float v = red_v[0][tid];
+                int i = red_i[0][tid];
+                for (int g = 1; g < 16; ++g)
+                    if (arg_better(red_v[g][tid], red_i[g][tid], v, i)) { v = red_v[g][tid]; i = red_i[g][tid]; }
+                ep.part_val[(int64_t)(mg + tid) * ep.nparts + blockIdx.x] = v;
+                ep.part_idx[(int64_t)(mg + tid) * ep.nparts + blockIdx.x] = i;
             }
         }
     }

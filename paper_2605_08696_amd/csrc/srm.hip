@@ -399,6 +399,35 @@ static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, c
     return SRM_OK;
 }
 
+// Few rows: the streaming GEMV (gemv_rows_kernel), 16 * CPG columns per block.
+constexpr int kGemvMB = 8;                 // rows per pass over W
+constexpr size_t kGemvMaxLds = 128 * 1024;
+template <typename TW, typename TAct, int EPI, int CPG>
+static int launch_gemv_rows(const TAct *A, const TW *W, int M, int N, int K, GemmEpi ep, hipStream_t st, int ksplit,
+                            int *nparts_out)
+{
+    const size_t lds = (size_t)kGemvMB * (K / ksplit) * sizeof(float);
+    auto kern = gemv_rows_kernel<TW, TAct, EPI, kGemvMB, CPG>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)kGemvMaxLds));
+        attr_set = true;
+    }
+    ep.nparts = (int)cdiv(N, 16 * CPG);
+    if (nparts_out) *nparts_out = ep.nparts;
+    hipLaunchKernelGGL(kern, dim3((unsigned)ep.nparts, (unsigned)ksplit), dim3(256), lds, st, A, W, M, N, K, ep);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+// whether the streaming GEMV applies: few rows, whole 16-byte weight vectors per K slice, the rows' stage within LDS
+template <typename TW>
+static bool gemv_rows_ok(int64_t M, int K, int ksplit, int64_t max_rows)
+{
+    const int vw = 16 / (int)sizeof(TW);
+    return M <= max_rows && K % (vw * ksplit) == 0 && (size_t)kGemvMB * (K / ksplit) * sizeof(float) <= kGemvMaxLds;
+}
+
 // The 64x64 tile with few blocks on the chip: its k loop is bound by the latency of the tile loads, so
 // the LDS ring is deepened as far as the blocks per CU allow (8 stages = 128 KB: one block per CU;
 // 4 stages = 64 KB: two).
@@ -466,14 +495,13 @@ static int launch_f32(const float *A, const float *W, int64_t M, int N, int K, G
     if (M <= 0 || M >= (1 << 30) || N <= 0 || K <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
     ep.nparts = (int)cdiv(N, 64);
     if (nparts_out) *nparts_out = ep.nparts;
-    constexpr int MR = 8;
-    const size_t gemv_lds = ((size_t)MR * (K / ksplit) + 4 * MR * 64) * sizeof(float);
-    if (ksplit > 1 && !(EPI == EPI_F32 && M <= 32 && K % (16 * ksplit) == 0 && gemv_lds <= 64 * 1024))
-        return fail(SRM_EINVAL, "fp32 GEMM: bad split of K = %d", K);
-    if (M <= 32 && K % 16 == 0 && gemv_lds <= 64 * 1024) {
-        // few rows: stream W once per group of MR rows
-        hipLaunchKernelGGL((gemv_f32_kernel<EPI, MR>), dim3((unsigned)cdiv(N, 64), (unsigned)ksplit), dim3(256),
-                           gemv_lds, st, A, W, (int)M, N, K, ep);
+    const bool rows_ok = gemv_rows_ok<float>(M, K, ksplit, 32);
+    if (ksplit > 1 && !(EPI == EPI_F32 && rows_ok)) return fail(SRM_EINVAL, "fp32 GEMM: bad split of K = %d", K);
+    if (rows_ok) {
+        // few rows: stream W once per group of kGemvMB rows (64 columns per block where the partial winners of the
+        // LM head are counted per 64 columns, or where 16 would make too many blocks)
+        if (EPI == EPI_ARGMAX || N >= 16384) return launch_gemv_rows<float, float, EPI, 4>(A, W, (int)M, N, K, ep, st, ksplit, nparts_out);
+        return launch_gemv_rows<float, float, EPI, 1>(A, W, (int)M, N, K, ep, st, ksplit, nparts_out);
     } else {
         const int64_t nb = cdiv(M, 64) * cdiv(N, 64);
         hipLaunchKernelGGL(gemm_f32_kernel<EPI>, dim3((unsigned)nb), dim3(256), 0, st, A, W, (int)M, N, K, ep);
@@ -949,8 +977,10 @@ extern "C" int srm_decode_step_ragged(srm_model *m, int64_t B, int32_t *d_pos, i
 // Number of work-groups for the one-kernel path (see mega.hpp), or 0 if the call does not
 // qualify: fp32 weights and state, head projections, at most kMegaMaxB samples, d <= 1024,
 // the widest activation row of all samples within 128 KB of LDS, cooperative launches
-// supported.  SRM_MEGAKERNEL=0 in the environment switches the path off, SRM_MEGA_BLOCKS=n
-// sets the grid (default 16: a grid barrier costs about 1.4 us + 65 ns per work-group).
+// supported, and a model small enough for the small grid to win (see below).  SRM_MEGAKERNEL=0
+// in the environment switches the path off, =2 takes it whatever the model's size,
+// SRM_MEGA_BLOCKS=n sets the grid (default 16: a grid barrier costs about 1.4 us + 65 ns per
+// work-group).
 static int mega_rows(int64_t B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : kMegaMaxB; }   // rows the kernel is unrolled for
 
 static int mega_blocks(const srm_model *m, int64_t B)
@@ -958,13 +988,13 @@ static int mega_blocks(const srm_model *m, int64_t B)
     if (!m->mega_layers || m->shalf || B > kMegaMaxB || m->L > kMegaMaxLayers) return 0;
     const int widest = std::max(std::max(m->d, m->dm), m->ff);
     if (m->d > 1024 || m->d % 4 || m->dm % 4 || m->ff % 4 || (size_t)mega_rows(B) * widest * 4 > 128 * 1024) return 0;
-    // The small grid has a fraction of the chip's arithmetic and cache bandwidth: measured, the path wins while
-    // rows x matrix elements stay below about 32 M (C1's model at B = 8: 128 against 148 us per step; a
-    // 25 M-element model wins at B = 1 by 8 % and loses at B = 8).
-    const double elems = (double)m->L * ((double)2 * m->d * m->dm + (double)2 * m->d * m->ff) + (double)m->V * m->d;
-    if (elems * mega_rows(B) > 32e6) return 0;
+    // The small grid has a fraction of the chip's arithmetic and cache bandwidth: measured against the step
+    // kernels, the path wins while rows x matrix elements stay below about 16 M (C1's model: 93 against 132 us
+    // per step at B = 1, 112 against 132 at B = 4, 130 against 126 at B = 8; a 25 M-element model loses at B = 1).
     const char *sw = getenv("SRM_MEGAKERNEL");
     if (sw && sw[0] == '0') return 0;
+    const double elems = (double)m->L * ((double)2 * m->d * m->dm + (double)2 * m->d * m->ff) + (double)m->V * m->d;
+    if (elems * mega_rows(B) > 16e6 && !(sw && sw[0] == '2')) return 0;      // SRM_MEGAKERNEL=2: whatever the size
     int coop = 0;
     if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, m->device) != hipSuccess || !coop) return 0;
     int nblk = 16;

@@ -200,3 +200,20 @@ def test_probe_mfma_counts_every_product(srm):
     assert (out == 1024.0 * iters).all()          # 64 accumulator registers per lane, each 16 * iters
     with pytest.raises(srm.SrmError):
         srm.probe_mfma(out, 0, iters)
+
+
+@pytest.mark.parametrize("dtype_name", ["fp32", "bf16"])
+@pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("shape", [(1, 16, 64), (3, 70, 128), (8, 1000, 1024), (16, 130, 4096), (11, 32000, 512)])
+def test_linear_few_rows_streaming_gemv(srm, dtype_name, epi, shape):
+    """A handful of rows: fp32 takes the streaming GEMV (every epilogue, ragged column counts, one and two
+    passes of eight rows, the widest K its LDS stage holds, 16- and 64-column blocks), bf16 the 64x64 MFMA tile
+    with mostly empty rows."""
+    M, N, K = shape
+    dtype = srm.SRM_BF16 if dtype_name == "bf16" else srm.SRM_FP32
+    _linear_case(srm, dtype, M, N, K, epi, None, seed=1000 + M + epi)
+
+
+def test_linear_fp32_more_rows_than_one_pass(srm):
+    for M in (9, 24, 32):
+        _linear_case(srm, srm.SRM_FP32, M, 200, 256, 2, None, seed=M)

@@ -42,7 +42,7 @@ def _generate(model, prompts, G, one_kernel, temperature=None, seed=0):
         first, pos0, steps = None, P - 1, G
     out = torch.full((steps, B), -7, dtype=torch.int32, device="cuda")
     old = os.environ.get("SRM_MEGAKERNEL")
-    os.environ["SRM_MEGAKERNEL"] = "1" if one_kernel else "0"
+    os.environ["SRM_MEGAKERNEL"] = "2" if one_kernel else "0"      # 2: the path whatever the model's size
     try:
         assert (model.one_kernel_blocks(B) > 0) == one_kernel
         side = torch.cuda.Stream()
@@ -102,7 +102,7 @@ def test_one_kernel_sampling_matches_oracle(srm, orc_mod):
 def test_one_kernel_generation_variants_and_odd_sizes(srm, orc_mod, variant):
     kw = dict(vocab=333, d_model=64, n_layers=3, n_heads=2, n_ctx=48, seed=91)
     kw.update(variant)
-    B = kw.pop("B", 4)                     # the widest model only qualifies with one sample (size rule of the path)
+    B = kw.pop("B", 4)
     cfg = srm_synth.tiny_config(**kw)
     w = srm_synth.make_weights(cfg, stress=True)
     P, G = 6, 24
@@ -120,10 +120,13 @@ def test_one_kernel_path_is_taken_only_where_it_applies(srm):
     cfg = srm_synth.CONFIGS["C1"]
     w = srm_synth.make_weights(cfg)
     model = srm.Model(cfg, w)
-    assert model.one_kernel_blocks(8) > 0 and model.one_kernel_blocks(9) == 0
-    wide = srm_synth.tiny_config(vocab=333, d_model=1024, n_layers=3, n_heads=4, n_ctx=16, mlp_expansion=2)
-    mw = srm.Model(wide, srm_synth.make_weights(wide))
-    assert mw.one_kernel_blocks(1) > 0 and mw.one_kernel_blocks(4) == 0          # rows x matrix elements too many
+    # by default only while rows x matrix elements stay small; never above 8 rows
+    assert model.one_kernel_blocks(4) > 0 and model.one_kernel_blocks(8) == 0
+    os.environ["SRM_MEGAKERNEL"] = "2"
+    try:
+        assert model.one_kernel_blocks(8) > 0 and model.one_kernel_blocks(9) == 0
+    finally:
+        del os.environ["SRM_MEGAKERNEL"]
     for other in (dataclasses.replace(cfg, state_dtype="fp16"), dataclasses.replace(cfg, use_projections=False)):
         assert srm.Model(other, w).one_kernel_blocks(4) == 0
     cb = srm_synth.tiny_config(vocab=256, d_model=64, n_layers=1, n_heads=2, n_ctx=8, weight_dtype="bf16")
