@@ -368,7 +368,10 @@ def main():
         "next_token": "greedy argmax" if args.temperature == 0 else
                       f"sampled, temperature {args.temperature} (fused Gumbel-max)" +
                       (f", top-p {args.top_p} (nucleus pass over materialised logits)" if args.top_p < 1.0 else ""),
-        "driver": "K srm_decode_step calls" if args.per_step_calls else "one srm_generate call (HIP-graph replay of the step)",
+        "driver": "K srm_decode_step calls" if args.per_step_calls else
+                  ("one srm_generate call (all steps in one persistent kernel)"
+                   if model.one_kernel_blocks(B) > 0 and not (args.temperature > 0 and args.top_p < 1.0)
+                   else "one srm_generate call (HIP-graph replay of the step)"),
         "setup_seconds": t_setup,
     }
     if not args.no_kernel_legs:
