@@ -4,8 +4,10 @@
 #include <stdint.h>
 
 typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
@@ -25,9 +27,10 @@ __device__ __forceinline__ float4 load4(const bf16 *p)
 __device__ __forceinline__ void store4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
 __device__ __forceinline__ void store4(bf16 *p, float4 v)
 {
-    bf16x4_t o;
-    o[0] = (bf16)v.x; o[1] = (bf16)v.y; o[2] = (bf16)v.z; o[3] = (bf16)v.w;   // round to nearest even
-    *reinterpret_cast<bf16x4_t *>(p) = o;
+    // round to nearest even; converted in pairs so that each pair is one packed conversion
+    const bf16x2_t lo = __builtin_convertvector(f32x2_t{v.x, v.y}, bf16x2_t);
+    const bf16x2_t hi = __builtin_convertvector(f32x2_t{v.z, v.w}, bf16x2_t);
+    *reinterpret_cast<bf16x4_t *>(p) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
 }
 __device__ __forceinline__ void store1(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store1(bf16 *p, float v) { *p = (bf16)v; }

@@ -126,23 +126,25 @@ __device__ __forceinline__ void epi_store(const GemmEpi &ep, int64_t row, int co
 // conflict-free (measured: SQ_LDS_BANK_CONFLICT ~1% of SQ_LDS_IDX_ACTIVE).
 __device__ __forceinline__ int swz_of_row(int r) { return (r >> 1) & 7; }
 
-// Exact (erf) GELU for bf16 outputs: x * Phi(x) with erfc(z) / 2 = 2^-P(z),
-// z = |x| / sqrt(2) clamped to 4.3 (beyond it Phi is 0 or 1 to 1e-9), P a degree-6
-// polynomial fitted to -log2(erfc(z) / 2) (minimax in the absolute error of
-// erfc: 2.2e-7; |error| of the GELU value <= 6.5e-7 in fp32 evaluation), so one
-// exp2 and six FMAs, no reciprocal.  The result is rounded to bf16 (relative
-// 2^-9) right after, so the approximation error is invisible there.
+// Exact (erf) GELU for bf16 outputs: x * Phi(x) with erfc(|x| / sqrt(2)) / 2 = 2^-P(|x|), |x| clamped to
+// 4.3 * sqrt(2) (beyond it Phi is 0 or 1 to 1e-9), P a degree-6 polynomial fitted to
+// -log2(erfc(z) / 2), z = |x| / sqrt(2) (minimax in the absolute error of erfc: 2.2e-7; |error| of the
+// GELU value <= 6.5e-7 in fp32 evaluation; the 1 / sqrt(2) is folded into the coefficients), so one exp2
+// and six FMAs, no reciprocal.  With q = 2^-P: x * (1 - q) for x >= 0 and x * q for x < 0 are both
+// max(x, 0) - |x| * q, one max and one FMA instead of a subtraction, a compare, a select and a
+// product.  The result is rounded to bf16 (relative 2^-9) right after, so the approximation error is
+// invisible there.
 __device__ __forceinline__ float gelu_bf16out(float x)
 {
-    const float z = fminf(fabsf(x) * 0.70710678118654752440f, 4.3f);
-    float p = fmaf(z, -0.00015339720622212807f, 0.003725629992140978f);
-    p = fmaf(z, p, -0.031017635167076434f);
-    p = fmaf(z, p, 0.1498087523043019f);
-    p = fmaf(z, p, 0.9181205081101346f);
-    p = fmaf(z, p, 1.6279324177979881f);
-    p = fmaf(z, p, 0.9999996936263803f);
-    const float q = __builtin_amdgcn_exp2f(-p);                  // erfc(z) / 2
-    return x * (x >= 0.0f ? 1.0f - q : q);
+    const float w = fminf(fabsf(x), 6.081118318204308f);
+    float p = fmaf(w, -1.917465077776602e-05f, 0.0006586045579087176f);
+    p = fmaf(w, p, -0.00775440879176911f);
+    p = fmaf(w, p, 0.05296539231773387f);
+    p = fmaf(w, p, 0.4590602540550674f);
+    p = fmaf(w, p, 1.1511220519383694f);
+    p = fmaf(w, p, 0.9999996936263803f);
+    const float q = __builtin_amdgcn_exp2f(-p);                  // erfc(|x| / sqrt(2)) / 2
+    return fmaf(-fabsf(x), q, fmaxf(x, 0.0f));
 }
 
 template <int EPI, typename TAct>
@@ -450,7 +452,7 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     const int m0 = bm * BM, n0 = bn * BN;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: LDS targets of the tile loads
     const int wm = wave / WN, wn = wave % WN;
     const int lr = lane & 31, lk = lane >> 5;
 
@@ -468,15 +470,18 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
         const_cast<bf16 *>(W + (size_t)n0 * K), 0, min(BN, N - n0) * K * 2, 0x00020000);
     const int ld_voff = (ld_r * K + ((ld_c ^ swz_of_row(ld_r)) << 3)) * 2;       // bytes
     typedef __attribute__((address_space(3))) void lds_void;
+    // tile load number i of a k tile: the first A_IT fetch A, the rest W
+#define SRM_DMA_ONE(i, k0, buf)                                                                  \
+    if ((i) < A_IT)                                                                              \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
+            rs_a, (lds_void *)(As + (buf) * BM * BK + ((i) * ROWS_PER_IT + wave * 8) * BK), 16,  \
+            ld_voff, ((i) * ROWS_PER_IT * K + kbeg + (k0)) * 2, 0, 0);                           \
+    else                                                                                         \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
+            rs_w, (lds_void *)(Bs + (buf) * BN * BK + (((i) - A_IT) * ROWS_PER_IT + wave * 8) * BK), 16, \
+            ld_voff, (((i) - A_IT) * ROWS_PER_IT * K + kbeg + (k0)) * 2, 0, 0);
 #define SRM_DMA_TILE(k0, buf)                                                                    \
-    _Pragma("unroll") for (int i = 0; i < A_IT; ++i)                                             \
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
-            rs_a, (lds_void *)(As + (buf) * BM * BK + (i * ROWS_PER_IT + wave * 8) * BK), 16,    \
-            ld_voff, (i * ROWS_PER_IT * K + kbeg + (k0)) * 2, 0, 0);                             \
-    _Pragma("unroll") for (int i = 0; i < B_IT; ++i)                                             \
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
-            rs_w, (lds_void *)(Bs + (buf) * BN * BK + (i * ROWS_PER_IT + wave * 8) * BK), 16,    \
-            ld_voff, (i * ROWS_PER_IT * K + kbeg + (k0)) * 2, 0, 0);
+    _Pragma("unroll") for (int i = 0; i < A_IT + B_IT; ++i) { SRM_DMA_ONE(i, k0, buf) }
     // s_waitcnt immediate: vmcnt = n, expcnt and lgkmcnt unconstrained
 #define SRM_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
@@ -554,10 +559,29 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
         SRM_INTERLEAVE(0)
         SRM_WAIT_VM((NS - 2) * (A_IT + B_IT));           // tile kt+1 has landed; later tiles may still be in flight
         __syncthreads();
-        SRM_READ_FRAGS(nxt, 0, 0)
-        SRM_DMA_TILE((kt + NS) * BK, cur)
-        SRM_MFMA_STEP(2)
-        SRM_INTERLEAVE(A_IT + B_IT)
+        // substep 2 in issue order, pinned: behind each MFMA its share of the operand reads of the next
+        // tile's substep 0 and of the tile loads (left to the scheduler, the reads and loads all went in
+        // front of the second MFMA in one burst)
+        {
+            const int ch_ = ((lk ^ sw) << 3);
+            const bf16 *as_ = As + nxt * BM * BK + a_row_off + ch_;
+            const bf16 *bs_ = Bs + nxt * BN * BK + b_row_off + ch_;
+            constexpr int S_ = TM * TN;
+            constexpr int RPM = (TM + TN + S_ - 1) / S_, LPM = (A_IT + B_IT + S_ - 1) / S_;
+#pragma unroll
+            for (int q = 0; q < S_; ++q) {
+                acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[2][q % TN], fa[2][q / TN],
+                                                                              acc[q / TN][q % TN], 0, 0, 0);
+#pragma unroll
+                for (int r = q * RPM; r < (q + 1) * RPM && r < TM + TN; ++r) {
+                    if (r < TM) fa[0][r] = *reinterpret_cast<const bf16x8_t *>(as_ + r * 32 * BK);
+                    else fb[0][r - TM] = *reinterpret_cast<const bf16x8_t *>(bs_ + (r - TM) * 32 * BK);
+                }
+#pragma unroll
+                for (int l = q * LPM; l < (q + 1) * LPM && l < A_IT + B_IT; ++l) { SRM_DMA_ONE(l, (kt + NS) * BK, cur) }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
         SRM_READ_FRAGS(nxt, 1, 1)
         SRM_MFMA_STEP(3)
         SRM_INTERLEAVE(0)
@@ -567,6 +591,7 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
 #undef SRM_MFMA_STEP
 #undef SRM_INTERLEAVE
 #undef SRM_DMA_TILE
+#undef SRM_DMA_ONE
 #undef SRM_WAIT_VM
 #undef SRM_READ_FRAGS
 
