@@ -124,6 +124,18 @@ def kernel_legs(torch, srm, model, cfg, B, iters):
     t = time_launches(torch, su, max(iters, 2 * L), warm=L)
     nbytes = B * sd * ((4 if half else 8) + 2 * esz)
     legs["state_update"] = {"ms": t * 1e3, "gbs": nbytes / t * 1e-9, "bytes": nbytes}
+    if getattr(cfg, "use_projections", True):
+        # the form the step runs with bf16 weights: in-projection with the update in its epilogue (u never in memory)
+        def pu():
+            model.mixer_project_update(it[0] % L, 5, B, a, state[it[0] % L], m)
+            it[0] += 1
+
+        t = time_launches(torch, pu, max(iters, 2 * L), warm=L)
+        fused_bytes = B * sd * ((4 if half else 8) + esz) + B * d * esz + sd * d * esz
+        legs["gemm_in_with_state_update"] = {"ms": t * 1e3, "tflops": 2.0 * B * sd * d / t * 1e-12,
+                                             "gbs": fused_bytes / t * 1e-9, "bytes": fused_bytes,
+                                             "two_launch_ms": legs["gemm_in"]["ms"] + legs["state_update"]["ms"]
+                                             if sd == d else None}
     return legs
 
 
@@ -394,6 +406,9 @@ def main():
                                "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": up["tflops"] / PEAK_FP32_TFLOPS,
                                "traffic": None, "avg_launch_ms": up["ms"]}
         su = legs["state_update"]
+        # the update as a kernel of its own: the HBM-bound form of the path's defining step.  The timed step
+        # of a bf16 model runs it inside the in-projection's epilogue (leg gemm_in_with_state_update), which
+        # saves writing and re-reading u; the stand-alone kernel is what srm_mixer_update launches.
         out["roofline_state_update"] = {"kernel": "state_update_kernel", "bound": "hbm", "achieved": su["gbs"],
                                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": su["gbs"] / PEAK_HBM_GBS,
                                         "traffic": measured_traffic("state_update_kernel<bf16,2>") if cfg.name == "C4" else None,

@@ -367,6 +367,20 @@ int srm_mixer_update(srm_model *m, int32_t layer, int32_t pos, int64_t B, const 
                      void *d_state_layer, void *d_m, void *hip_stream);
 
 /*
+ * srm_mixer_project_update: the stacked head in-projection of one layer (Eq. 10:
+ * u = a W_in^T + b_in) and the recurrent state update (Eq. 2 / Eq. 3) of its
+ * result in ONE launch, the form a decode step uses: u stays in registers, the
+ * state slab is read and written once, d_m [B][state width] receives the mixer
+ * output.  d_a is the layer's LayerNorm1 output [B][d_model] in the activation
+ * type; d_state_layer and d_m as for srm_mixer_update.  Same values as
+ * srm_linear(epilogue 0) with the layer's W_in followed by srm_mixer_update
+ * (u is rounded to the activation type before the update, as the two-launch
+ * form stores it).  Models without head projections: SRM_EINVAL.
+ */
+int srm_mixer_project_update(srm_model *m, int32_t layer, int32_t pos, int64_t B, const void *d_a,
+                             void *d_state_layer, void *d_m, void *hip_stream);
+
+/*
  * srm_linear: out = epilogue(A W^T + bias) with A [M][K] and W [N][K] device
  * arrays of type `dtype` (SRM_BF16: bf16 operands on the matrix cores with fp32
  * accumulation, K % 64 == 0; SRM_FP32: fp32).  d_bias [N] fp32 or NULL.

@@ -90,6 +90,8 @@ def lib():
         L.srm_parallel_forward.argtypes = [vp, vp, i32, i32, vp, vp, vp, sz, vp]
         L.srm_mixer_update.restype = C.c_int
         L.srm_mixer_update.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp]
+        L.srm_mixer_project_update.restype = C.c_int
+        L.srm_mixer_project_update.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp]
         L.srm_linear.restype = C.c_int
         L.srm_linear.argtypes = [i32, i32, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.srm_linear_scratch_bytes.restype = sz
@@ -347,6 +349,13 @@ class Model:
         p_s = _dev(state_layer, self.state_torch_dtype, n, "state_layer")
         p_m = _dev(m, self.act_dtype, n, "m")
         _check(lib().srm_mixer_update(self._h, layer, pos, B, p_u, p_s, p_m, _stream(stream)))
+
+    def mixer_project_update(self, layer, pos, B, a, state_layer, m, stream=None):
+        n = B * self.sd
+        p_a = _dev(a, self.act_dtype, B * self.d, "a")
+        p_s = _dev(state_layer, self.state_torch_dtype, n, "state_layer")
+        p_m = _dev(m, self.act_dtype, n, "m")
+        _check(lib().srm_mixer_project_update(self._h, layer, pos, B, p_a, p_s, p_m, _stream(stream)))
 
 
 def sample_logits(logits, temperature, top_p, seed, pos, tok_out, stream=None):

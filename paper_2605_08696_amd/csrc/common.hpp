@@ -61,7 +61,15 @@ __device__ __forceinline__ void store_state4(f16 *S, int64_t j, float4 v)
     __builtin_nontemporal_store(o, reinterpret_cast<f16x4_t *>(S) + j);
 }
 __device__ __forceinline__ float to_state(float v, const float *) { return v; }
-__device__ __forceinline__ float to_state(float v, const f16 *) { return (float)(f16)v; }   // nearest, ties to even
+__device__ __forceinline__ float to_state(float v, const f16 *)
+{
+    // The update is formed in fp32 first and then rounded to binary16 (nearest, ties to even).  The empty
+    // statement pins that: left alone, the compiler folds the conversion into a mixed-precision FMA with a
+    // binary16 result for some elements of a kernel and not for others (one rounding against two), so the
+    // same update could differ in the last bit from kernel to kernel.
+    asm volatile("" : "+v"(v));
+    return (float)(f16)v;
+}
 
 // ---- wavefront reductions ------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v)

@@ -13,6 +13,7 @@
 // be written at all.
 #pragma once
 #include "common.hpp"
+#include <type_traits>
 
 enum { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_ARGMAX = 3, EPI_F32 = 4, EPI_MIX = 5 };
 
@@ -125,6 +126,16 @@ __device__ __forceinline__ void epi_store(const GemmEpi &ep, int64_t row, int co
 // with 64 banks this makes both the tile writes and the fragment reads
 // conflict-free (measured: SQ_LDS_BANK_CONFLICT ~1% of SQ_LDS_IDX_ACTIVE).
 __device__ __forceinline__ int swz_of_row(int r) { return (r >> 1) & 7; }
+
+// f(integral_constant<int, I>) for I = FIRST .. LAST-1, unrolled by construction
+template <int FIRST, int LAST, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (FIRST < LAST) {
+        f(std::integral_constant<int, FIRST>{});
+        static_for<FIRST + 1, LAST>(f);
+    }
+}
 
 // Exact (erf) GELU for bf16 outputs: x * Phi(x) with erfc(|x| / sqrt(2)) / 2 = 2^-P(|x|), |x| clamped to
 // 4.3 * sqrt(2) (beyond it Phi is 0 or 1 to 1e-9), P a degree-6 polynomial fitted to
@@ -245,8 +256,10 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
     const bool n_edge = wcol0 + WTN > N;              // wave-uniform
     const bool interior = vec_ok && m0 + BM <= M && n0 + BN <= N;      // block-uniform
 
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    // (a compile-time loop: with the largest epilogue the compiler kept `#pragma unroll` rolled, which indexes
+    // the accumulators with a variable and so moves all of them, main loop included, to scratch memory)
+    static_for<0, TM>([&](auto ic_) {
+        constexpr int i = decltype(ic_)::value;
         if constexpr (EPI == EPI_ARGMAX) {
             // in-lane over this lane's TN*16 columns in ascending order (strict >
             // keeps the lowest index), then one exchange with the lane holding
@@ -376,7 +389,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                         epi_store4<EPI, TAct>(ep, row0 + it * RPI, gcol, v[it]);
                     }
                 }
-                continue;
+                return;
             }
 #pragma unroll
             for (int it = 0; it < 32 / RPI; ++it) {
@@ -396,7 +409,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                 }
             }
         }
-    }
+    });
     if constexpr (EPI == EPI_ARGMAX) {
         __syncthreads();
         for (int lrow = tid; lrow < BM; lrow += NTHR) {

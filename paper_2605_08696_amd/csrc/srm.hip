@@ -660,11 +660,19 @@ static int check_device(const srm_model *m)
     return SRM_OK;
 }
 
-// Decode with few rows is bound by the number of dependent kernels, not by their
-// work: below this many state elements per layer the state update is fused into
-// the in-projection.  Above it the separate streaming kernel (HBM-bound, two
-// state vectors per thread) is the faster arrangement.
-static bool fuse_mixer(const srm_model *m, int64_t rows) { return !m->noproj && rows * m->dm <= (1 << 20); }
+// Whether the state update rides in the in-projection's epilogue (EPI_MIX) instead of running as a
+// kernel of its own.  bf16 models: always (few rows: one dependent kernel less per layer; many rows: the
+// head input u is never written to memory and read back, 66 MB per layer at 16384 x 1024, measured
+// 7.35 -> 7.15 ms per step there).  fp32 models: below 2^20 state elements per layer, where the step is
+// bound by its number of kernels; the fp32 tile kernel has not been measured beyond.
+// SRM_FUSE_MIXER=0 in the environment keeps the two kernels apart (tests, measurements).
+static bool fuse_mixer(const srm_model *m, int64_t rows)
+{
+    if (m->noproj) return false;
+    const char *e = getenv("SRM_FUSE_MIXER");
+    if (e && e[0] == '0') return false;
+    return m->wsize == 2 || rows * m->dm <= (1 << 20);
+}
 
 // One block (token mixing + channel mixing) on `rows` token rows.  On entry
 // w.a holds LayerNorm1(x) of this layer; mix(l) turns w.u into w.mx.  With
@@ -1427,6 +1435,28 @@ extern "C" int srm_mixer_update(srm_model *m, int32_t layer, int32_t pos, int64_
     hipStream_t st = as_stream(hip_stream);
     return m->wsize == 2 ? state_update<bf16>(m, layer, pos, B, d_u, d_state_layer, d_m, st)
                          : state_update<float>(m, layer, pos, B, d_u, d_state_layer, d_m, st);
+}
+
+extern "C" int srm_mixer_project_update(srm_model *m, int32_t layer, int32_t pos, int64_t B, const void *d_a,
+                                        void *d_state_layer, void *d_m, void *hip_stream)
+{
+    if (!m || !d_a || !d_state_layer || !d_m) return fail(SRM_EINVAL, "srm_mixer_project_update: null argument");
+    if (m->noproj) return fail(SRM_EINVAL, "srm_mixer_project_update: the model has no head projections");
+    if (layer < 0 || layer >= m->L)
+        return fail(SRM_EINVAL, "srm_mixer_project_update: layer %d outside [0, %d)", layer, m->L);
+    if (pos < 0 || pos >= m->cfg.n_ctx)
+        return fail(SRM_EINVAL, "srm_mixer_project_update: pos %d outside [0, %d)", pos, m->cfg.n_ctx);
+    if (B <= 0 || B >= (1 << 30)) return fail(SRM_EINVAL, "srm_mixer_project_update: batch out of range");
+    SRM_TRY(check_device(m));
+    hipStream_t st = as_stream(hip_stream);
+    const LayerDev &y = m->layers[layer];
+    const MixArgs mx{d_state_layer, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->hrow, m->dm / m->Hs, m->shalf ? 1 : 0};
+    Sampling where;
+    where.pos = pos;
+    return m->wsize == 2 ? linear<EPI_MIX, bf16>(d_a, y.w_in, y.b_in, B, m->dm, m->d, d_m, st, nullptr, nullptr, 64,
+                                                 nullptr, where, 1, mx)
+                         : linear<EPI_MIX, float>(d_a, y.w_in, y.b_in, B, m->dm, m->d, d_m, st, nullptr, nullptr, 64,
+                                                  nullptr, where, 1, mx);
 }
 
 extern "C" int srm_sample_logits(const float *d_logits, int64_t rows, int32_t vocab, float temperature, float top_p,

@@ -145,6 +145,55 @@ def test_state_update_matches_oracle_step(srm, dtype_name, B):
     assert np.abs(dS.cpu().numpy() - S_ref).max() <= 8e-7 * np.abs(S_ref).max()
 
 
+@pytest.mark.parametrize("dtype_name,d,B", [("fp32", 48, 5), ("fp32", 64, 700), ("bf16", 128, 5), ("bf16", 512, 1000),
+                                            ("bf16", 1024, 4099), ("bf16", 1024, 13000)])
+@pytest.mark.parametrize("half_state", [False, True])
+def test_project_update_equals_projection_then_update(srm, dtype_name, d, B, half_state):
+    """srm_mixer_project_update (in-projection with the state update in its epilogue, every tile shape up to the
+    256x256 one at 13000 rows) against srm_linear with the same W_in followed by srm_mixer_update: the same bits
+    in the state and in the mixer output, and both against the oracle's step on sampled rows."""
+    from oracle import srm_oracle
+    if half_state and dtype_name == "fp32" and B > 100:
+        pytest.skip("one binary16 case per weight type is enough")
+    cfg = srm_synth.tiny_config(vocab=16, d_model=d, n_layers=2, n_heads=4, n_ctx=8, weight_dtype=dtype_name, seed=77,
+                                state_dtype="fp16" if half_state else "fp32")
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    rng = np.random.default_rng(B + d)
+    a = rng.standard_normal((B, d)).astype(np.float32)
+    if dtype_name == "bf16":
+        a = srm_synth.round_to_bf16(a)
+    S0 = rng.standard_normal((B, d)).astype(np.float32)
+    layer, pos = 1, 6
+    lw = w["layers"][layer]
+    st_t = torch.float16 if half_state else torch.float32
+    da = to_dev(a, model.act_dtype)
+    S_f = to_dev(S0).to(st_t)
+    S_s = S_f.clone()
+    m_f = torch.empty((B, d), dtype=model.act_dtype, device="cuda")
+    m_s = torch.empty_like(m_f)
+    u = torch.empty_like(m_f)
+    print(f"project_update {dtype_name} d={d} B={B} half={half_state}", flush=True)
+    model.mixer_project_update(layer, pos, B, da, S_f, m_f)
+    dt = srm.SRM_BF16 if dtype_name == "bf16" else srm.SRM_FP32
+    srm.linear(dt, 0, da, to_dev(lw["w_in"], model.act_dtype), to_dev(lw["b_in"]), out=u)
+    model.mixer_update(layer, pos, B, u, S_s, m_s)
+    torch.cuda.synchronize()
+    if dtype_name == "bf16":
+        assert torch.equal(S_f, S_s) and torch.equal(m_f, m_s)
+    else:       # fp32: the few-row GEMV and the tile kernel may sum k in different orders
+        assert (S_f.float() - S_s.float()).abs().max() <= 2e-6 * S_s.float().abs().max()
+        assert (m_f - m_s).abs().max() <= 2e-6 * m_s.abs().max()
+    orc = srm_oracle.Oracle(cfg, w, "f64")
+    for b in sorted({0, B // 3, B - 1}):
+        S_ref = S0[b].astype(np.float16 if half_state else np.float32).astype(np.float64)
+        u_ref = lw["w_in"].astype(np.float64) @ a[b].astype(np.float64) + lw["b_in"]
+        m_ref = orc.mixer_step(S_ref, u_ref, lw["alpha"][:, pos], lw["beta"][:, pos], lw["lam"])
+        tol = 2e-2 if dtype_name == "bf16" or half_state else 1e-5
+        assert np.abs(S_f[b].float().cpu().numpy() - S_ref).max() <= tol * np.abs(S_ref).max()
+        assert np.abs(m_f[b].float().cpu().numpy() - m_ref).max() <= tol * np.abs(m_ref).max()
+
+
 def test_error_codes_on_the_gpu(srm):
     cfg = srm_synth.tiny_config(vocab=32, d_model=16, n_layers=1, n_heads=2, n_ctx=16)
     model = srm.Model(cfg, srm_synth.make_weights(cfg))

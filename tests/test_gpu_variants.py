@@ -167,9 +167,13 @@ def test_half_state_fp32_weights_all_paths_match_oracle(srm, orc_mod):
     assert torch.equal(st_b, st_c) and torch.equal(tk_b, tk_c)
 
 
-@pytest.mark.parametrize("use_projections,B", [(True, 300), (False, 300), (True, 3000)])
-def test_half_state_bf16_weights_match_oracle(srm, orc_mod, use_projections, B):
-    """bf16 weights with a binary16 cache; B = 3000 takes the separate state-update kernel, 300 the fused ones."""
+@pytest.mark.parametrize("use_projections,B,fuse", [(True, 300, True), (False, 300, True), (True, 3000, True),
+                                                    (True, 3000, False)])
+def test_half_state_bf16_weights_match_oracle(srm, orc_mod, use_projections, B, fuse, monkeypatch):
+    """bf16 weights with a binary16 cache; the state update in the in-projection's epilogue, and (fuse False: the
+    library's switch for it) as a kernel of its own."""
+    if not fuse:
+        monkeypatch.setenv("SRM_FUSE_MIXER", "0")
     cfg = srm_synth.tiny_config(vocab=400, d_model=512, n_layers=2, n_heads=4, n_ctx=12, weight_dtype="bf16", seed=62,
                                 use_projections=use_projections, state_dtype="fp16")
     w = srm_synth.make_weights(cfg, stress=True)
