@@ -276,9 +276,12 @@ def test_head_layouts_fp32_all_paths_match_oracle(srm, orc_mod, layout, H):
 
 
 @pytest.mark.parametrize("layout", ["row", "column", "combined"])
-@pytest.mark.parametrize("B", [40, 9000])
-def test_head_layouts_bf16_decode_and_prefill_match_oracle(srm, orc_mod, layout, B):
-    """bf16 weights; B = 9000 takes the separate streaming state update (rows x width above the fusion limit)."""
+@pytest.mark.parametrize("B,fuse", [(40, True), (9000, True), (9000, False)])
+def test_head_layouts_bf16_decode_and_prefill_match_oracle(srm, orc_mod, layout, B, fuse, monkeypatch):
+    """bf16 weights; the state update in the in-projection's epilogue (small tile, large tile) and, through the
+    library's switch, as the separate streaming kernel."""
+    if not fuse:
+        monkeypatch.setenv("SRM_FUSE_MIXER", "0")
     cfg = srm_synth.tiny_config(vocab=520, d_model=128, n_layers=2, n_heads=4, n_ctx=12, weight_dtype="bf16", seed=72,
                                 head_layout=layout)
     w = srm_synth.make_weights(cfg, stress=True)
