@@ -43,11 +43,20 @@ struct GemmEpi {
     int32_t n_ctx, hrow, dh, state_half;   // heads 0..hrow-1 row-repeat, the rest column-repeat
 };
 
+// The position all rows share: ep.pos, or *ep.pos_dev if that is set.  (Written as a conditional load with a
+// scalar result: from `pos_dev ? *pos_dev : pos` the compiler made a load through a selected pointer, which
+// needs ep.pos in scratch memory and a flat load per use.)
+__device__ __forceinline__ uint32_t epi_shared_pos(const GemmEpi &ep)
+{
+    int p = ep.pos;
+    if (ep.pos_dev) p = __builtin_amdgcn_readfirstlane(*ep.pos_dev);
+    return (uint32_t)p;
+}
 // Position that keys the random numbers of output row `row` (rows >= M read nothing).
 __device__ __forceinline__ uint32_t epi_pos(const GemmEpi &ep, int64_t row, int M)
 {
     if (ep.pos_rows) return row < M ? (uint32_t)ep.pos_rows[row] : 0u;
-    return (uint32_t)(ep.pos_dev ? *ep.pos_dev : ep.pos);
+    return epi_shared_pos(ep);
 }
 
 // Block -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs, each
@@ -82,7 +91,7 @@ __device__ __forceinline__ void epi_store(const GemmEpi &ep, int64_t row, int co
     } else if constexpr (EPI == EPI_F32) {
         reinterpret_cast<float *>(ep.out)[row * ep.ldo + col] = v;
     } else if constexpr (EPI == EPI_MIX) {
-        const int pos = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row] : (ep.pos_dev ? (uint32_t)*ep.pos_dev : (uint32_t)ep.pos));
+        const int pos = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row] : epi_shared_pos(ep));
         TAct *o = reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + col;
         if (pos < 0 || pos >= ep.n_ctx) { store1(o, 0.0f); return; }
         const int h = col / ep.dh;
@@ -174,7 +183,7 @@ __device__ __forceinline__ void epi_store4(const GemmEpi &ep, int64_t row, int c
         store4(reinterpret_cast<float *>(ep.out) + row * ep.ldo + col, v);
     } else if constexpr (EPI == EPI_MIX) {
         // four consecutive channels lie in one head (dh is a multiple of 4)
-        const int pos = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row] : (ep.pos_dev ? (uint32_t)*ep.pos_dev : (uint32_t)ep.pos));
+        const int pos = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row] : epi_shared_pos(ep));
         TAct *o = reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + col;
         if (pos < 0 || pos >= ep.n_ctx) { store4(o, make_float4(0.f, 0.f, 0.f, 0.f)); return; }
         const int h = col / ep.dh;
@@ -347,8 +356,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
                         const int64_t row = row0 + it * RPI;
-                        ps[it] = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row]
-                                                   : (ep.pos_dev ? (uint32_t)*ep.pos_dev : (uint32_t)ep.pos));
+                        ps[it] = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row] : epi_shared_pos(ep));
                     }
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
