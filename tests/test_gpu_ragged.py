@@ -244,6 +244,40 @@ def test_ragged_bf16_logits_against_oracle(srm, orc_mod):
     assert ((t >= 0) & (t < cfg.vocab)).all() and bool(torch.isfinite(st).all())
 
 
+def test_ragged_decode_large_batch_fused_equals_separate(srm, monkeypatch):
+    """13 000 samples of width 1024 (the in-projection takes the 256x256 tile, the state update rides in its
+    epilogue) at per-sample positions, idle slots (-1) included: the same states, tokens and positions as with the
+    separate ragged state-update kernel, and idle samples untouched."""
+    cfg = srm_synth.tiny_config(vocab=300, d_model=1024, n_layers=1, n_heads=4, n_ctx=8, weight_dtype="bf16", seed=9)
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    B = 13000
+    rng = np.random.default_rng(12)
+    pos0 = rng.integers(-1, cfg.n_ctx - 2, B).astype(np.int32)
+    tok0 = rng.integers(0, cfg.vocab, B).astype(np.int32)
+    S0 = rng.standard_normal((cfg.n_layers, B, cfg.d_model)).astype(np.float32)
+    ws = model.new_workspace(B)
+    res = []
+    for fuse in (True, False):
+        if not fuse:
+            monkeypatch.setenv("SRM_FUSE_MIXER", "0")
+        st, tk, pos = to_dev(S0), to_dev(tok0), to_dev(pos0)
+        print(f"ragged large batch B={B} fuse={fuse}", flush=True)
+        for _ in range(2):
+            model.decode_step_ragged(B, pos, tk, st, tk, advance=True, workspace=ws)
+        torch.cuda.synchronize()
+        res.append((st.cpu().numpy(), tk.cpu().numpy(), pos.cpu().numpy()))
+    for a, b in zip(res[0], res[1]):
+        np.testing.assert_array_equal(a, b)
+    st, tk, pos = res[0]
+    idle = pos0 < 0
+    assert idle.any() and (~idle).any()
+    np.testing.assert_array_equal(st[:, idle], S0[:, idle])
+    np.testing.assert_array_equal(pos[idle], pos0[idle])
+    np.testing.assert_array_equal(pos[~idle], pos0[~idle] + 2)
+    assert not np.array_equal(st[:, ~idle], S0[:, ~idle])
+
+
 def test_ragged_errors(c1, srm):
     cfg, w, model, orc = c1
     ws = model.new_workspace(32)
