@@ -160,9 +160,16 @@ def achievable_rates(torch, srm):
 
     t = time_launches(torch, run, 5, warm=2)
     assert bool((out == 1024.0 * iters).all())
+
+    def run_random():      # operands with random bits: more power per product, a lower clock
+        srm.probe_mfma(out, blocks, iters, random_operands=True)
+
+    t_rand = time_launches(torch, run_random, 5, warm=2)
+    assert bool(torch.isfinite(out).all())
     return {"copy_gbs": max(rates.values()), **rates, "copy_bytes": 2 << 30,
-            "mfma_bf16_tflops": flop[0] / t * 1e-12, "mfma_probe": f"{blocks} work-groups x 4 wavefronts x {iters} x 4 "
-            "independent 32x32x16 bf16 products, operands in registers"}
+            "mfma_bf16_tflops": flop[0] / t * 1e-12, "mfma_bf16_tflops_random_operands": flop[0] / t_rand * 1e-12,
+            "mfma_probe": f"{blocks} work-groups x 4 wavefronts x {iters} x 4 "
+            "independent 32x32x16 bf16 products, operands in registers (all ones; and pseudo-random in (-1, 1))"}
 
 
 def cpu_baseline(cfg, w, rows, T):
@@ -398,6 +405,7 @@ def main():
                                "frac": up["tflops"] / PEAK_BF16_TFLOPS,
                                "traffic": measured_traffic("gemm_bf16_kernel<256,256,2,4,EPI=GELU>") if cfg.name == "C4" else None,
                                "frac_of_achievable": up["tflops"] / ach["mfma_bf16_tflops"],
+                               "frac_of_achievable_random_operands": up["tflops"] / ach["mfma_bf16_tflops_random_operands"],
                                "avg_launch_ms": up["ms"], "flop_per_launch": 2.0 * B * ff * d,
                                "algorithmic_bytes_per_launch": (B * d + ff * d + B * ff) * 2.0}
         else:

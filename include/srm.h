@@ -420,12 +420,17 @@ int32_t srm_generate_one_kernel_blocks(const srm_model *m, int64_t B);
  *
  * srm_probe_mfma: `blocks` work-groups of four wavefronts each issue `iters`
  * rounds of four independent 32x32x16 bf16 matrix-core products on register
- * operands (A = B = 1) and write one fp32 sum per lane to d_out[blocks * 256]
- * (= 1024 * iters each).  *flop (host pointer, may be NULL) receives the
- * floating-point operations of the launch.
+ * operands and write one fp32 sum per lane to d_out[blocks * 256].
+ * random_operands == 0: A = B = 1, every sum is 1024 * iters (checkable).
+ * random_operands != 0: operand elements pseudo-random in (-1, 1), which costs
+ * the matrix cores more power than constants do and so shows the rate at the
+ * clock the chip holds on real data; the sums are finite, not predictable.
+ * *flop (host pointer, may be NULL) receives the floating-point operations of
+ * the launch.
  */
 int srm_probe_copy(void *d_dst, const void *d_src, size_t bytes, int32_t streaming, void *hip_stream);
-int srm_probe_mfma(float *d_out, int32_t blocks, int32_t iters, double *flop, void *hip_stream);
+int srm_probe_mfma(float *d_out, int32_t blocks, int32_t iters, int32_t random_operands, double *flop,
+                   void *hip_stream);
 
 /* Message for the last failure on the calling thread ("" if none). */
 const char *srm_last_error(void);

@@ -101,7 +101,7 @@ def lib():
         L.srm_probe_copy.restype = C.c_int
         L.srm_probe_copy.argtypes = [vp, vp, sz, i32, vp]
         L.srm_probe_mfma.restype = C.c_int
-        L.srm_probe_mfma.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
+        L.srm_probe_mfma.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_double), vp]
         L.srm_last_error.restype = C.c_char_p
         L.srm_last_error.argtypes = []
         _lib = L
@@ -378,11 +378,11 @@ def probe_copy(dst, src, streaming=True, stream=None):
     return 2 * nbytes
 
 
-def probe_mfma(out, blocks: int, iters: int, stream=None) -> float:
+def probe_mfma(out, blocks: int, iters: int, random_operands: bool = False, stream=None) -> float:
     """srm_probe_mfma into out (fp32, blocks * 256 elements); returns the launch's flop count."""
     flop = C.c_double(0.0)
     _check(lib().srm_probe_mfma(_dev(out, _torch().float32, blocks * 256, "out"), int(blocks), int(iters),
-                                C.byref(flop), _stream(stream)))
+                                1 if random_operands else 0, C.byref(flop), _stream(stream)))
     return flop.value
 
 

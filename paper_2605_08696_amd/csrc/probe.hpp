@@ -31,14 +31,25 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4_t *__restri
 // Every wavefront issues `iters` rounds of four independent 32x32x16 bf16 products into four fp32
 // accumulator tiles held in registers (no memory traffic inside the loop), then writes one sum per
 // lane.  With A = 1 and B = 1 every accumulator element ends at 16 * iters, so the written value is
-// 4 * 16 * 16 * iters per lane (16 accumulator registers per tile): checkable on the host.
-__global__ __launch_bounds__(256) void probe_mfma_kernel(float *__restrict__ out, int iters, float a_val)
+// 4 * 16 * 16 * iters per lane (16 accumulator registers per tile): checkable on the host.  With
+// random_operands the operand elements are pseudo-random values in (-1, 1), different per lane and
+// element: the matrix cores draw more power on such data than on constants, and the clock the chip
+// holds (hence the rate) is lower; the sums are then only finite, not predictable.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float *__restrict__ out, int iters, float a_val,
+                                                         int random_operands)
 {
     bf16x8_t a, b;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         a[i] = (bf16)a_val;
         b[i] = (bf16)1.0f;
+        if (random_operands) {
+            uint32_t h = (threadIdx.x * 2654435761u) ^ (uint32_t)(i * 40503 + 12345);
+            h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+            a[i] = (bf16)((float)(int32_t)h * (1.0f / 2147483648.0f));
+            h *= 3266489917u; h ^= h >> 16;
+            b[i] = (bf16)((float)(int32_t)h * (1.0f / 2147483648.0f));
+        }
     }
     f32x16_t c0 = {}, c1 = {}, c2 = {}, c3 = {};
     for (int it = 0; it < iters; ++it) {

@@ -1492,12 +1492,14 @@ extern "C" int srm_probe_copy(void *d_dst, const void *d_src, size_t bytes, int3
     return SRM_OK;
 }
 
-extern "C" int srm_probe_mfma(float *d_out, int32_t blocks, int32_t iters, double *flop, void *hip_stream)
+extern "C" int srm_probe_mfma(float *d_out, int32_t blocks, int32_t iters, int32_t random_operands, double *flop,
+                              void *hip_stream)
 {
     if (!d_out) return fail(SRM_EINVAL, "srm_probe_mfma: null argument");
     if (blocks <= 0 || blocks > (1 << 20) || iters <= 0 || iters > (1 << 20))
         return fail(SRM_EINVAL, "srm_probe_mfma: blocks and iters must lie in [1, 2^20]");
-    hipLaunchKernelGGL(probe_mfma_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), d_out, iters, 1.0f);
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), d_out, iters, 1.0f,
+                       random_operands ? 1 : 0);
     HIP_TRY(hipGetLastError());
     if (flop) *flop = (double)blocks * 4 /*wavefronts*/ * iters * 4 /*tiles*/ * (2.0 * 32 * 32 * 16);
     return SRM_OK;

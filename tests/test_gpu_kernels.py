@@ -247,6 +247,9 @@ def test_probe_mfma_counts_every_product(srm):
     torch.cuda.synchronize()
     assert flop == blocks * 4 * iters * 4 * 2.0 * 32 * 32 * 16
     assert (out == 1024.0 * iters).all()          # 64 accumulator registers per lane, each 16 * iters
+    assert srm.probe_mfma(out, blocks, iters, random_operands=True) == flop
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all() and not (out == 1024.0 * iters).all()
     with pytest.raises(srm.SrmError):
         srm.probe_mfma(out, 0, iters)
 
