@@ -533,16 +533,15 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     _Pragma("unroll") for (int i = 0; i < TM; ++i)                                               \
         _Pragma("unroll") for (int j = 0; j < TN; ++j) /* transposed: MFMA rows run over N */    \
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
-    // Issue order inside one k-substep: one LDS read (and, in substep 1, one LDS
-    // write and one global load) behind each MFMA, so that memory instructions
-    // issue while the matrix pipe works instead of in a burst in front of it.
-#define SRM_INTERLEAVE(n_vmem)                                                                   \
+    // Issue order inside the k-substeps that only read operands (0, 1 and 3): one LDS read behind
+    // each MFMA, so that the reads issue while the matrix pipe works instead of in a burst in front
+    // of it.  (Substep 2, which also issues the tile loads, is written out in issue order below.)
+#define SRM_INTERLEAVE()                                                                         \
     _Pragma("unroll") for (int q = 0; q < TM * TN; ++q) {                                        \
         constexpr int S_ = TM * TN;                                                              \
-        constexpr int R_ = (TM + TN + S_ - 1) / S_, V_ = ((n_vmem) + S_ - 1) / S_;               \
+        constexpr int R_ = (TM + TN + S_ - 1) / S_;                                              \
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                       \
         if (q * R_ < TM + TN) __builtin_amdgcn_sched_group_barrier(0x100, R_, 0);                \
-        if (q * V_ < (n_vmem)) __builtin_amdgcn_sched_group_barrier(0x020, V_, 0);               \
     }                                                                                            \
     __builtin_amdgcn_sched_barrier(0);
 
@@ -574,10 +573,10 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
         const int cur = kt & (NS - 1), nxt = (kt + 1) & (NS - 1);
         SRM_READ_FRAGS(cur, 2, 2)
         SRM_MFMA_STEP(0)
-        SRM_INTERLEAVE(0)
+        SRM_INTERLEAVE()
         SRM_READ_FRAGS(cur, 3, 3)
         SRM_MFMA_STEP(1)
-        SRM_INTERLEAVE(0)
+        SRM_INTERLEAVE()
         SRM_WAIT_VM((NS - 2) * (A_IT + B_IT));           // tile kt+1 has landed; later tiles may still be in flight
         __syncthreads();
         // substep 2 in issue order, pinned: behind each MFMA its share of the operand reads of the next
@@ -605,7 +604,7 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
         }
         SRM_READ_FRAGS(nxt, 1, 1)
         SRM_MFMA_STEP(3)
-        SRM_INTERLEAVE(0)
+        SRM_INTERLEAVE()
     }
     SRM_WAIT_VM(0);
     __syncthreads();                                  // LDS is reused by the epilogue
