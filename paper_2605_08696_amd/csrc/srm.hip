@@ -443,20 +443,24 @@ static int launch_bf16_small(const bf16 *A, const bf16 *W, int M, int N, int K, 
 }
 
 // Tile codes of the bf16 GEMM: 0 = 256x256 (8 waves), 1 = 128x128 (4 waves),
-// 2 = 64x64 (4 waves), 3 = 128x128 (8 waves), 4 = 256x128 (8 waves).  The big
-// tile needs enough blocks to fill 256 CUs; min_bn > 64 rules out the 64-wide one
-// (the LM head's partial buffers are sized for column tiles >= 128).
-constexpr int kNumTiles = 5;
+// 2 = 64x64 (4 waves), 3 = 128x128 (8 waves), 4 = 256x128 (8 waves); 5 .. 8 pin the
+// ring depth of a tile for sweeps.  min_bn > 64 rules out the 64-wide tile (the LM
+// head's partial buffers are sized for column tiles >= 128).  Measured on C4's
+// shapes over 512 .. 16384 rows: the big tile wins once it fills most of the chip in
+// whole rounds (one block per CU: 384 tiles are two rounds at 75 %, and lose to 1536
+// tiles of 128x128); 128x128 wins over 64x64 from about 144 blocks on.
+constexpr int kNumTiles = 9;
 static int choose_tile(int64_t M, int N, int min_bn)
 {
+    const int64_t t256 = cdiv(M, 256) * cdiv(N, 256), t128 = cdiv(M, 128) * cdiv(N, 128);
     int tile;
-    if (cdiv(M, 256) * cdiv(N, 256) >= 200) tile = 0;
-    else if (cdiv(M, 128) * cdiv(N, 128) >= 256) tile = 1;   // measured: below a full wave of 128x128 tiles, 64x64 wins
+    if (t256 >= 200 && (t256 >= 1024 || (double)t256 / (double)(cdiv(t256, 256) * 256) >= 0.8)) tile = 0;
+    else if (t128 >= 144) tile = 1;
     else tile = 2;
     if (tile == 2 && min_bn > 64) tile = 1;
     return tile;
 }
-static int tile_bn(int tile) { return tile == 0 ? 256 : tile == 2 ? 64 : 128; }
+static int tile_bn(int tile) { return tile == 0 ? 256 : (tile == 2 || tile >= 6) ? 64 : 128; }
 
 static thread_local int g_force_tile = -1;   // test/bench hook of srm_linear only
 
@@ -480,10 +484,20 @@ static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, Ge
     const int m = (int)M;
     switch (tile) {
     case 0: return launch_bf16_tile<256, 256, 2, 4, EPI, TAct>(A, W, m, N, K, ep, st);
-    case 1: return launch_bf16_tile<128, 128, 2, 2, EPI, TAct>(A, W, m, N, K, ep, st);
+    case 1:
+        // at most one block per CU: the k loop is bound by the latency of its tile loads (a 128x128x64 tile is
+        // 0.27 us of MFMAs, a load about 1 us), so the LDS ring is deepened to keep three tiles in flight
+        if (cdiv(M, 128) * cdiv(N, 128) <= 256 && K / 64 > 4)
+            return launch_bf16_tile<128, 128, 2, 2, EPI, TAct, 4>(A, W, m, N, K, ep, st);
+        return launch_bf16_tile<128, 128, 2, 2, EPI, TAct>(A, W, m, N, K, ep, st);
     case 2: return launch_bf16_small<EPI, TAct>(A, W, m, N, K, ep, st, 1);
     case 3: return launch_bf16_tile<128, 128, 2, 4, EPI, TAct>(A, W, m, N, K, ep, st);
     case 4: return launch_bf16_tile<256, 128, 4, 2, EPI, TAct>(A, W, m, N, K, ep, st);
+    // sweeps only: a fixed ring depth
+    case 5: return launch_bf16_tile<128, 128, 2, 2, EPI, TAct, 4>(A, W, m, N, K, ep, st);
+    case 6: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct, 2>(A, W, m, N, K, ep, st);
+    case 7: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct, 4>(A, W, m, N, K, ep, st);
+    case 8: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct, 8>(A, W, m, N, K, ep, st);
     default: return fail(SRM_EINVAL, "unknown GEMM tile code %d", tile);
     }
 }
