@@ -700,8 +700,10 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
     const LayerDev &y = m->layers[l];
     const int d = m->d, dm = m->dm, ff = m->ff;
     // K slices of a residual projection (decode with few rows; see kSplitK).  bf16: the MLP down projection in
-    // kSplitK slices while the 64x64 tiles number at most 256 (measured: more slices, or slicing the
-    // out-projection too, costs more in the LayerNorm that adds the slabs than the shorter k loops save).
+    // kSplitK slices while the 64x64 tiles number at most 192 (measured: more slices, or slicing the
+    // out-projection too, costs more in the LayerNorm that adds the slabs than the shorter k loops save;
+    // since the unsplit tile runs on a deep LDS ring the two arrangements time the same at 192 tiles and
+    // the unsplit one is 5 % faster per step at 256, for d = 512 and for d = 1024).
     // fp32 with at most kGemvRows rows (GEMVs): both projections, slices of at least 64 k.
     auto resid_split = [&](int K, bool down) {
         if (!allow_split || !w.part) return 1;
@@ -711,7 +713,7 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
             while (sp > 1 && (K % (16 * sp) || K / sp < 64)) sp >>= 1;
             return sp;
         }
-        return down && K >= 1024 && K % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 256 ? kSplitK : 1;
+        return down && K >= 1024 && K % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 192 ? kSplitK : 1;
     };
     if (m->noproj && np_state) {
         // non-projected layer, decode: LayerNorm1, state update, residual add and LayerNorm2 in one kernel
