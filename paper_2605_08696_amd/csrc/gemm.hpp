@@ -41,6 +41,17 @@ struct GemmEpi {
     void *state;
     const float *alpha, *beta, *lam;
     int32_t n_ctx, hrow, dh, state_half;   // heads 0..hrow-1 row-repeat, the rest column-repeat
+    // EPI_RESID: add_nsplit slabs [M][ldo] (slab stride add_stride floats) are added to the old value first, in
+    // slab order: the pending result of a K-sliced projection, which no kernel has folded into the stream yet.
+    const float *add_part;
+    int32_t add_nsplit;
+    int64_t add_stride;
+    // LNA kernels (A operand = LayerNorm of ln_x rows, computed by the block): ln_x [M][K] fp32 (+ ln_nsplit slabs
+    // of a K-sliced projection, added first in slab order, stride ln_stride floats), gain, bias, epsilon.
+    const float *ln_x, *ln_g, *ln_b, *ln_part;
+    int32_t ln_nsplit;
+    int64_t ln_stride;
+    float ln_eps;
 };
 
 // The position all rows share: ep.pos, or *ep.pos_dev if that is set.  (Written as a conditional load with a
@@ -87,7 +98,9 @@ __device__ __forceinline__ void epi_store(const GemmEpi &ep, int64_t row, int co
         store1(reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + col, gelu_erf(v));
     } else if constexpr (EPI == EPI_RESID) {
         float *p = reinterpret_cast<float *>(ep.out) + row * ep.ldo + col;
-        *p += v;
+        float o = *p;
+        for (int s_ = 0; s_ < ep.add_nsplit; ++s_) o += ep.add_part[(int64_t)s_ * ep.add_stride + row * ep.ldo + col];
+        *p = o + v;
     } else if constexpr (EPI == EPI_F32) {
         reinterpret_cast<float *>(ep.out)[row * ep.ldo + col] = v;
     } else if constexpr (EPI == EPI_MIX) {
@@ -177,7 +190,11 @@ __device__ __forceinline__ void epi_store4(const GemmEpi &ep, int64_t row, int c
                make_float4(gelu_bf16out(v.x), gelu_bf16out(v.y), gelu_bf16out(v.z), gelu_bf16out(v.w)));
     } else if constexpr (EPI == EPI_RESID) {
         float *p = reinterpret_cast<float *>(ep.out) + row * ep.ldo + col;
-        const float4 o = load4(p);
+        float4 o = load4(p);
+        for (int s_ = 0; s_ < ep.add_nsplit; ++s_) {
+            const float4 t = load4(ep.add_part + (int64_t)s_ * ep.add_stride + row * ep.ldo + col);
+            o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+        }
         store4(p, make_float4(o.x + v.x, o.y + v.y, o.z + v.z, o.w + v.w));
     } else if constexpr (EPI == EPI_F32) {
         store4(reinterpret_cast<float *>(ep.out) + row * ep.ldo + col, v);
@@ -339,6 +356,14 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                     float4 o[NIT];
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) o[it] = load4(p + (int64_t)it * RPI * ep.ldo);
+                    for (int s_ = 0; s_ < ep.add_nsplit; ++s_) {
+                        const float *q = ep.add_part + (int64_t)s_ * ep.add_stride + row0 * ep.ldo + gcol;
+#pragma unroll
+                        for (int it = 0; it < NIT; ++it) {
+                            const float4 t = load4(q + (int64_t)it * RPI * ep.ldo);
+                            o[it].x += t.x; o[it].y += t.y; o[it].z += t.z; o[it].w += t.w;
+                        }
+                    }
 #pragma unroll
                     for (int it = 0; it < NIT; ++it)
                         store4(p + (int64_t)it * RPI * ep.ldo,
@@ -437,11 +462,20 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
     }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, typename TAct, int NS = 2>
+// LNA (a handful of rows, M <= kLnaRows, one row tile, K <= 1024, no split): the A operand is not read
+// from memory but made by the block itself, A = LayerNorm(ep.ln_x rows [+ slabs]) in the arithmetic of
+// ln_kernel, written once as a panel [K / 64][32 rows][64] into LDS in the layout the tile loads would have
+// produced; only W then travels through the ring.  Every column block normalises the few rows again,
+// which is cheaper than the LayerNorm launch it replaces.  Rows >= M of the panel are never written: they
+// feed accumulator rows that no epilogue stores.
+constexpr int kLnaRows = 8;
+template <int BM, int BN, int WM, int WN, int EPI, typename TAct, int NS = 2, bool LNA = false>
 __global__ void __launch_bounds__(WM *WN * 64)
 gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, int N, int K, GemmEpi ep)
 {
     constexpr int BK = 64;
+    constexpr int PANEL_ROWS = 32;                   // rows per k tile of the LNA panel
+    static_assert(!LNA || (BM == 64 && WM == 2 && WN == 2), "the LNA panel is laid out for the 64x64 tile");
     static_assert(NS >= 2 && (NS & (NS - 1)) == 0, "the LDS ring holds a power-of-two number of k tiles");
     constexpr int NW = WM * WN, NTHR = NW * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -453,8 +487,10 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     static_assert(NW * 32 * STG * 4 + BM * WN * 8 <= NS * (BM + BN) * BK * 2, "epilogue stage exceeds the tile LDS");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);   // [NS][BM*BK]
-    bf16 *Bs = As + NS * BM * BK;                    // [NS][BN*BK]
+    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);   // [NS][BM*BK]; LNA: [K / BK][PANEL_ROWS*BK]
+    bf16 *Bs = As + (LNA ? (K / BK) * PANEL_ROWS * BK : NS * BM * BK);   // [NS][BN*BK]
+    constexpr int A_TILE = LNA ? PANEL_ROWS * BK : BM * BK;            // elements between k tiles of A in LDS
+    constexpr int A_LD = LNA ? 0 : A_IT;                               // tile loads of A per thread and k tile
 
     // Split K (gridDim.y > 1, EPI_F32 only): block row y of the grid contracts k in
     // [y * K / gridDim.y, (y + 1) * K / gridDim.y) and writes its own output slab
@@ -491,18 +527,18 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
         const_cast<bf16 *>(W + (size_t)n0 * K), 0, min(BN, N - n0) * K * 2, 0x00020000);
     const int ld_voff = (ld_r * K + ((ld_c ^ swz_of_row(ld_r)) << 3)) * 2;       // bytes
     typedef __attribute__((address_space(3))) void lds_void;
-    // tile load number i of a k tile: the first A_IT fetch A, the rest W
+    // tile load number i of a k tile: the first A_LD fetch A, the rest W
 #define SRM_DMA_ONE(i, k0, buf)                                                                  \
-    if ((i) < A_IT)                                                                              \
+    if ((i) < A_LD)                                                                              \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
             rs_a, (lds_void *)(As + (buf) * BM * BK + ((i) * ROWS_PER_IT + wave * 8) * BK), 16,  \
             ld_voff, ((i) * ROWS_PER_IT * K + kbeg + (k0)) * 2, 0, 0);                           \
     else                                                                                         \
         __builtin_amdgcn_raw_ptr_buffer_load_lds(                                                \
-            rs_w, (lds_void *)(Bs + (buf) * BN * BK + (((i) - A_IT) * ROWS_PER_IT + wave * 8) * BK), 16, \
-            ld_voff, (((i) - A_IT) * ROWS_PER_IT * K + kbeg + (k0)) * 2, 0, 0);
+            rs_w, (lds_void *)(Bs + (buf) * BN * BK + (((i) - A_LD) * ROWS_PER_IT + wave * 8) * BK), 16, \
+            ld_voff, (((i) - A_LD) * ROWS_PER_IT * K + kbeg + (k0)) * 2, 0, 0);
 #define SRM_DMA_TILE(k0, buf)                                                                    \
-    _Pragma("unroll") for (int i = 0; i < A_IT + B_IT; ++i) { SRM_DMA_ONE(i, k0, buf) }
+    _Pragma("unroll") for (int i = 0; i < A_LD + B_IT; ++i) { SRM_DMA_ONE(i, k0, buf) }
     // s_waitcnt immediate: vmcnt = n, expcnt and lgkmcnt unconstrained
 #define SRM_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
@@ -518,11 +554,12 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     const int a_row_off = (wm * WTM + lr) * BK;
     const int b_row_off = (wn * WTN + lr) * BK;
     bf16x8_t fa[4][TM], fb[4][TN];                   // one operand set per k-substep
-#define SRM_READ_FRAGS(buf, kk, set)                                                             \
+    // abuf: the k tile's place in the A area (its ring slot; LNA: the k tile's own number), bbuf: its ring slot
+#define SRM_READ_FRAGS(abuf, bbuf, kk, set)                                                      \
     {                                                                                            \
         const int ch_ = ((((kk) * 2 + lk) ^ sw) << 3);                                           \
-        const bf16 *as_ = As + (buf) * BM * BK + a_row_off + ch_;                                \
-        const bf16 *bs_ = Bs + (buf) * BN * BK + b_row_off + ch_;                                \
+        const bf16 *as_ = As + (abuf) * A_TILE + a_row_off + ch_;                                \
+        const bf16 *bs_ = Bs + (bbuf) * BN * BK + b_row_off + ch_;                               \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
             fa[set][i] = *reinterpret_cast<const bf16x8_t *>(as_ + i * 32 * BK);                 \
         _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
@@ -561,33 +598,116 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     // (range check: zeros nobody reads), which keeps the loop branch-free.
     const int KT = K / ksplit / BK;
     static_assert((NS - 1) * (A_IT + B_IT) <= 63, "more tile loads in flight than the counter holds");
+    constexpr int LD_IT = A_LD + B_IT;
+    if constexpr (LNA) {
+        // Two rows per wavefront.  Their values (and the first four slabs) are requested before the ring's tile
+        // loads, so that they return first and the normalisation runs while the W tiles travel.
+        constexpr int RW = kLnaRows / NW, VPL = 4;
+        const int d = K;
+        float4 v[RW][VPL], t[RW][VPL][4], pg[VPL], pb[VPL];
+        const int ns0 = ep.ln_part ? ep.ln_nsplit : 0;
 #pragma unroll
-    for (int stage = 0; stage < NS; ++stage) { SRM_DMA_TILE(stage * BK, stage) }   // (the macro's own loops use `i`)
-    SRM_WAIT_VM((NS - 1) * (A_IT + B_IT));
+        for (int i = 0; i < VPL; ++i) {
+            const int c = (i * 64 + lane) * 4;
+            pg[i] = pb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c < d) { pg[i] = load4(ep.ln_g + c); pb[i] = load4(ep.ln_b + c); }
+#pragma unroll
+            for (int j = 0; j < RW; ++j) {
+                const int r = wave * RW + j;
+                v[j][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (r < M && c < d) {
+                    v[j][i] = load4(ep.ln_x + (int64_t)r * d + c);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (ns0 > 0) t[j][i][q] = load4(ep.ln_part + (int64_t)min(q, ns0 - 1) * ep.ln_stride + (int64_t)r * d + c);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int stage = 0; stage < NS; ++stage) { SRM_DMA_TILE(stage * BK, stage) }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < RW; ++j) {
+            const int r = wave * RW + j;
+            if (r >= M) continue;                    // wave-uniform
+            float sum = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) {
+                const int c = (i * 64 + lane) * 4;
+                if (c < d) {
+                    // the slabs, in slab order (the first four were requested above)
+                    for (int s0 = 0; s0 < ns0; s0 += 4) {
+                        if (s0 > 0) {
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                t[j][i][q] = load4(ep.ln_part + (int64_t)min(s0 + q, ns0 - 1) * ep.ln_stride + (int64_t)r * d + c);
+                        }
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            if (s0 + q < ns0) {
+                                v[j][i].x += t[j][i][q].x; v[j][i].y += t[j][i][q].y;
+                                v[j][i].z += t[j][i][q].z; v[j][i].w += t[j][i][q].w;
+                            }
+                    }
+                    sum += (v[j][i].x + v[j][i].y) + (v[j][i].z + v[j][i].w);
+                }
+            }
+            const float mean = wave_sum(sum) / (float)d;
+            float sq = 0.0f;
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) {
+                const int c = (i * 64 + lane) * 4;
+                if (c < d) {
+                    const float a = v[j][i].x - mean, bb = v[j][i].y - mean, cc = v[j][i].z - mean, dd = v[j][i].w - mean;
+                    sq += (a * a + bb * bb) + (cc * cc + dd * dd);
+                }
+            }
+            const float var = wave_sum(sq) / (float)d;
+            const float rstd = 1.0f / sqrtf(var + ep.ln_eps);
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) {
+                const int c = (i * 64 + lane) * 4;
+                if (c < d) {
+                    float4 o;
+                    o.x = (v[j][i].x - mean) * rstd * pg[i].x + pb[i].x;
+                    o.y = (v[j][i].y - mean) * rstd * pg[i].y + pb[i].y;
+                    o.z = (v[j][i].z - mean) * rstd * pg[i].z + pb[i].z;
+                    o.w = (v[j][i].w - mean) * rstd * pg[i].w + pb[i].w;
+                    store4(As + (c >> 6) * A_TILE + r * BK + ((((c & 63) >> 3) ^ swz_of_row(r)) << 3) + (c & 7), o);
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int stage = 0; stage < NS; ++stage) { SRM_DMA_TILE(stage * BK, stage) }   // (the macro's own loops use `i`)
+    }
+    SRM_WAIT_VM((NS - 1) * LD_IT);
     __syncthreads();
-    SRM_READ_FRAGS(0, 0, 0)
-    SRM_READ_FRAGS(0, 1, 1)
+    SRM_READ_FRAGS(0, 0, 0, 0)
+    SRM_READ_FRAGS(0, 0, 1, 1)
     __builtin_amdgcn_sched_barrier(0);
 
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & (NS - 1), nxt = (kt + 1) & (NS - 1);
-        SRM_READ_FRAGS(cur, 2, 2)
+        const int acur = LNA ? kt : cur, anxt = LNA ? kt + 1 : nxt;
+        SRM_READ_FRAGS(acur, cur, 2, 2)
         SRM_MFMA_STEP(0)
         SRM_INTERLEAVE()
-        SRM_READ_FRAGS(cur, 3, 3)
+        SRM_READ_FRAGS(acur, cur, 3, 3)
         SRM_MFMA_STEP(1)
         SRM_INTERLEAVE()
-        SRM_WAIT_VM((NS - 2) * (A_IT + B_IT));           // tile kt+1 has landed; later tiles may still be in flight
+        SRM_WAIT_VM((NS - 2) * LD_IT);                   // tile kt+1 has landed; later tiles may still be in flight
         __syncthreads();
         // substep 2 in issue order, pinned: behind each MFMA its share of the operand reads of the next
         // tile's substep 0 and of the tile loads (left to the scheduler, the reads and loads all went in
         // front of the second MFMA in one burst)
         {
             const int ch_ = ((lk ^ sw) << 3);
-            const bf16 *as_ = As + nxt * BM * BK + a_row_off + ch_;
+            const bf16 *as_ = As + anxt * A_TILE + a_row_off + ch_;
             const bf16 *bs_ = Bs + nxt * BN * BK + b_row_off + ch_;
             constexpr int S_ = TM * TN;
-            constexpr int RPM = (TM + TN + S_ - 1) / S_, LPM = (A_IT + B_IT + S_ - 1) / S_;
+            constexpr int RPM = (TM + TN + S_ - 1) / S_, LPM = (LD_IT + S_ - 1) / S_;
 #pragma unroll
             for (int q = 0; q < S_; ++q) {
                 acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[2][q % TN], fa[2][q / TN],
@@ -598,11 +718,11 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
                     else fb[0][r - TM] = *reinterpret_cast<const bf16x8_t *>(bs_ + (r - TM) * 32 * BK);
                 }
 #pragma unroll
-                for (int l = q * LPM; l < (q + 1) * LPM && l < A_IT + B_IT; ++l) { SRM_DMA_ONE(l, (kt + NS) * BK, cur) }
+                for (int l = q * LPM; l < (q + 1) * LPM && l < LD_IT; ++l) { SRM_DMA_ONE(l, (kt + NS) * BK, cur) }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        SRM_READ_FRAGS(nxt, 1, 1)
+        SRM_READ_FRAGS(anxt, nxt, 1, 1)
         SRM_MFMA_STEP(3)
         SRM_INTERLEAVE()
     }

@@ -399,6 +399,26 @@ static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, c
     return SRM_OK;
 }
 
+// A handful of rows, LayerNorm made by the GEMM itself (see the LNA note in gemm.hpp): one row tile of 64x64
+// blocks, the normalised rows as a [K / 64][32][64] bf16 panel in LDS next to an eight-tile ring for W.
+template <int EPI>
+static int launch_bf16_lna(const bf16 *W, int M, int N, int K, const GemmEpi &ep, hipStream_t st)
+{
+    constexpr int NS = 8;
+    const size_t smem = (size_t)K * 64 + (size_t)NS * 64 * 64 * sizeof(bf16);
+    auto kern = gemm_bf16_kernel<64, 64, 2, 2, EPI, bf16, NS, true>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    1024 * 64 + NS * 64 * 64 * (int)sizeof(bf16)));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)cdiv(N, 64), 1), dim3(256), smem, st, W /*A: unused*/, W, M, N, K, ep);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+static bool lna_ok(int64_t M, int K) { return M <= kLnaRows && K <= 1024 && K % 64 == 0; }
+
 // Few rows: the streaming GEMV (gemv_rows_kernel), 16 * CPG columns per block.
 constexpr int kGemvMB = 8;                 // rows per pass over W
 constexpr size_t kGemvMaxLds = 128 * 1024;
@@ -567,14 +587,39 @@ struct MixArgs {           // EPI_MIX: state slab of the layer and its coefficie
     int n_ctx = 0, hrow = 0, dh = 0, state_half = 0;
 };
 
+struct SlabArgs {          // slabs of a K-sliced projection that no kernel has added to the residual stream yet
+    const float *part = nullptr;
+    int nsplit = 0;
+    int64_t stride = 0;
+};
+struct LnArgs {            // A = LayerNorm(x [+ slabs]) made by the GEMM itself (bf16, a handful of rows)
+    const float *x = nullptr, *g = nullptr, *b = nullptr;
+    SlabArgs slabs;
+    float eps = 0.0f;
+};
+
 // out = epilogue(A W^T + bias) with operands of type T (float or bf16)
 template <int EPI, typename T>
 static int linear(const void *A, const void *W, const float *bias, int64_t M, int N, int K, void *out,
                   hipStream_t st, float *pv = nullptr, int32_t *pi = nullptr, int min_bn = 64,
-                  int *nparts_out = nullptr, Sampling sm = Sampling(), int ksplit = 1, MixArgs mx = MixArgs())
+                  int *nparts_out = nullptr, Sampling sm = Sampling(), int ksplit = 1, MixArgs mx = MixArgs(),
+                  SlabArgs add = SlabArgs(), LnArgs ln = LnArgs())
 {
     GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, sm.row_base,
                mx.state, mx.alpha, mx.beta, mx.lam, mx.n_ctx, mx.hrow, mx.dh, mx.state_half};
+    ep.add_part = add.part; ep.add_nsplit = add.part ? add.nsplit : 0; ep.add_stride = add.stride;
+    if (add.part && EPI != EPI_RESID) return fail(SRM_EINVAL, "linear: pending slabs need the residual epilogue");
+    if (ln.x) {
+        if constexpr (sizeof(T) == 2 && (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_MIX)) {
+            if (!lna_ok(M, K) || ksplit != 1) return fail(SRM_EINVAL, "linear: LayerNorm-on-load needs M <= %d, K <= 1024", kLnaRows);
+            ep.ln_x = ln.x; ep.ln_g = ln.g; ep.ln_b = ln.b; ep.ln_eps = ln.eps;
+            ep.ln_part = ln.slabs.part; ep.ln_nsplit = ln.slabs.part ? ln.slabs.nsplit : 0; ep.ln_stride = ln.slabs.stride;
+            ep.nparts = 0;
+            return launch_bf16_lna<EPI>(static_cast<const bf16 *>(W), (int)M, N, K, ep, st);
+        } else {
+            return fail(SRM_EINVAL, "linear: LayerNorm-on-load exists for bf16 store / GELU / mixer epilogues only");
+        }
+    }
     if constexpr (sizeof(T) == 2)
         return launch_bf16<EPI, bf16>(static_cast<const bf16 *>(A), static_cast<const bf16 *>(W), M, N, K, ep,
                                       st, min_bn, nparts_out, ksplit);
@@ -688,17 +733,37 @@ static bool fuse_mixer(const srm_model *m, int64_t rows)
     return m->wsize == 2 || rows * m->dm <= (1 << 20);
 }
 
+// A handful of samples of a bf16 model: every LayerNorm between two GEMMs of the step is made by the GEMM
+// that consumes it (gemm_bf16_kernel's LNA form) instead of a launch of its own - with one row the
+// LayerNorm launches are a quarter of the step's time.  SRM_LN_ON_LOAD=0 in the environment keeps the
+// separate kernels.
+static bool ln_on_load(const srm_model *m, int64_t rows)
+{
+    if (m->wsize != 2 || m->noproj || !lna_ok(rows, m->d)) return false;
+    const char *e = getenv("SRM_LN_ON_LOAD");
+    return !(e && e[0] == '0');
+}
+
 // One block (token mixing + channel mixing) on `rows` token rows.  On entry
 // w.a holds LayerNorm1(x) of this layer; mix(l) turns w.u into w.mx.  With
 // norm_next, w.a leaves holding the next layer's LayerNorm1(x), or the final
 // LayerNorm after the last layer.
+// With pend (decode of a handful of rows, see ln_on_load): no LayerNorm kernels between the GEMMs.  From
+// layer 1 on w.a is not used: the in- and up-projection normalise the rows of w.x themselves, *pend says how
+// many slabs of the previous layer's K-sliced MLP-down projection still wait in w.part (the in-projection
+// adds them for its LayerNorm, the out-projection's residual epilogue adds them to w.x), and on return it
+// holds this layer's count.  Layer 0 enters with w.a from the embedding kernel as usual.
 template <typename T, typename MIX>
 static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hipStream_t st, MIX &&mix,
                  bool norm_next, bool allow_split = false, void *fuse_state = nullptr, Sampling fuse_pos = Sampling(),
-                 void *np_state = nullptr)
+                 void *np_state = nullptr, int *pend = nullptr)
 {
     const LayerDev &y = m->layers[l];
     const int d = m->d, dm = m->dm, ff = m->ff;
+    const bool lnf = pend != nullptr;
+    const SlabArgs waiting = lnf && *pend > 0 ? SlabArgs{w.part, *pend, (int64_t)rows * d} : SlabArgs();
+    const LnArgs ln1 = lnf && l > 0 ? LnArgs{w.x, y.ln1_g, y.ln1_b, waiting, m->cfg.ln_eps} : LnArgs();
+    const LnArgs ln2 = lnf ? LnArgs{w.x, y.ln2_g, y.ln2_b, SlabArgs(), m->cfg.ln_eps} : LnArgs();
     // K slices of a residual projection (decode with few rows; see kSplitK).  bf16: the MLP down projection in
     // kSplitK slices while the 64x64 tiles number at most 192 (measured: more slices, or slicing the
     // out-projection too, costs more in the LayerNorm that adds the slabs than the shorter k loops save;
@@ -745,9 +810,10 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
         // few rows: the state update rides in the in-projection's epilogue (one kernel less per layer)
         const MixArgs mx{fuse_state, y.alpha, y.beta, y.lam, m->cfg.n_ctx, m->hrow, dm / m->Hs, m->shalf ? 1 : 0};
         SRM_TRY((linear<EPI_MIX, T>(w.a, y.w_in, y.b_in, rows, dm, d, w.mx, st, nullptr, nullptr, 64, nullptr, fuse_pos,
-                                    1, mx)));
+                                    1, mx, SlabArgs(), ln1)));
     } else {
-        SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, dm, d, w.u, st)));
+        SRM_TRY((linear<EPI_STORE, T>(w.a, y.w_in, y.b_in, rows, dm, d, w.u, st, nullptr, nullptr, 64, nullptr, Sampling(),
+                                      1, MixArgs(), SlabArgs(), ln1)));
         SRM_TRY(mix(l));
     }
     if (!m->noproj) {
@@ -758,11 +824,13 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
             SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, y.ln2_g, y.ln2_b, w.a, rows, st, nullptr, 0, 0, w.part,
                                          sp)));
         } else {
-            SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, dm, w.x, st)));
-            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
+            SRM_TRY((linear<EPI_RESID, T>(w.mx, y.w_out, y.b_out, rows, d, dm, w.x, st, nullptr, nullptr, 64, nullptr,
+                                          Sampling(), 1, MixArgs(), l > 0 ? waiting : SlabArgs())));
+            if (!lnf) SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, nullptr, y.ln2_g, y.ln2_b, w.a, rows, st)));
         }
     }
-    SRM_TRY((linear<EPI_GELU, T>(w.a, y.w_up, y.b_up, rows, ff, d, w.g, st)));
+    SRM_TRY((linear<EPI_GELU, T>(w.a, y.w_up, y.b_up, rows, ff, d, w.g, st, nullptr, nullptr, 64, nullptr, Sampling(), 1,
+                                 MixArgs(), SlabArgs(), ln2)));
     // (not with the fused non-projected layer: no LayerNorm kernel follows there to add the slabs)
     const int spd = (norm_next && !(m->noproj && np_state)) ? resid_split(ff, true) : 1;
     if (spd > 1)
@@ -770,6 +838,8 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
                                     Sampling(), spd)));
     else
         SRM_TRY((linear<EPI_RESID, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.x, st)));
+    if (lnf) *pend = spd > 1 ? spd : 0;
+    if (lnf && l + 1 < m->L) return SRM_OK;                        // the next layer's in-projection normalises
     if (norm_next && !(m->noproj && np_state && l + 1 < m->L)) {   // the fused kernel does its own LayerNorm1
         const float *g = l + 1 < m->L ? m->layers[l + 1].ln1_g : m->lnf_g;
         const float *b = l + 1 < m->L ? m->layers[l + 1].ln1_b : m->lnf_b;
@@ -843,8 +913,11 @@ static int decode_rows(srm_model *m, const DecodeArgs &a, int64_t b0, int64_t nb
     };
     const bool fuse = fuse_mixer(m, nb);
     const Sampling where{0.0f, 0, a.pos, a.pos_dev, pos_rows, 1.0f, 0};
+    int pend = 0;
+    const bool lnf = ln_on_load(m, nb);
     for (int l = 0; l < m->L; ++l)
-        SRM_TRY((block<T>(m, l, w, nb, st, mix, true, true, fuse ? slab(l) : nullptr, where, slab(l))));
+        SRM_TRY((block<T>(m, l, w, nb, st, mix, true, true, fuse ? slab(l) : nullptr, where, slab(l),
+                          lnf ? &pend : nullptr)));
     if (a.hidden)
         HIP_TRY(hipMemcpyAsync(a.hidden + (size_t)b0 * d, w.x, (size_t)nb * d * 4, hipMemcpyDeviceToDevice, st));
     const Sampling sm{a.temperature, a.seed, a.pos, a.pos_dev, pos_rows, a.top_p, (uint32_t)b0, a.eos_plus1};
@@ -962,9 +1035,11 @@ static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int ad
     };
     const bool fuse = fuse_mixer(m, B);
     const Sampling where{0.0f, 0, 0, nullptr, pos_rows, 1.0f};
+    int pend = 0;
+    const bool lnf = ln_on_load(m, B);
     for (int l = 0; l < m->L; ++l)
         SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? layer_state(m, state, l, B) : nullptr, where,
-                          layer_state(m, state, l, B))));
+                          layer_state(m, state, l, B), lnf ? &pend : nullptr)));
     const bool topp = temperature > 0.0f && top_p < 1.0f;
     FinalizeRagged rg{};
     rg.pos_rows = pos_rows;

@@ -198,6 +198,42 @@ def test_half_state_bf16_weights_match_oracle(srm, orc_mod, use_projections, B, 
     assert np.abs(s_got - ref["state"]).max() <= 2e-2 * np.abs(ref["state"]).max()
 
 
+@pytest.mark.parametrize("d,B", [(256, 1), (512, 5), (1024, 8), (1024, 1), (320, 3)])
+@pytest.mark.parametrize("fuse_mixer", [True, False])
+def test_layernorm_made_by_the_consuming_gemm_equals_the_separate_kernel(srm, orc_mod, d, B, fuse_mixer, monkeypatch):
+    """A handful of samples of a bf16 model: the step without LayerNorm launches (every LayerNorm made by the
+    GEMM that consumes it, pending K-slice slabs added by the in-projection and by the out-projection's residual
+    epilogue) against the step with them (the library's switch): the same logits, tokens and states bit for bit
+    over four steps, and the logits against the oracle."""
+    cfg = srm_synth.tiny_config(vocab=333, d_model=d, n_layers=3, n_heads=4, n_ctx=8, weight_dtype="bf16", seed=91)
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    T = 4
+    toks = srm_synth.make_prompts(cfg, batch=B, length=T)
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks)
+    if not fuse_mixer:
+        monkeypatch.setenv("SRM_FUSE_MIXER", "0")
+    res = []
+    for on_load in (True, False):
+        if not on_load:
+            monkeypatch.setenv("SRM_LN_ON_LOAD", "0")
+        ws, st = model.new_workspace(B), model.new_state(B)
+        out = torch.empty(B, dtype=torch.int32, device="cuda")
+        lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+        tc = to_dev(toks).t().contiguous()
+        steps = []
+        print(f"LayerNorm on load d={d} B={B} fused mixer={fuse_mixer} on_load={on_load}", flush=True)
+        for t in range(T):
+            model.decode_step(B, t, tc[t], st, out, logits=lg, workspace=ws)
+            steps.append((lg.clone(), out.clone()))
+        torch.cuda.synchronize()
+        res.append((steps, st.clone()))
+    for t in range(T):
+        assert torch.equal(res[0][0][t][0], res[1][0][t][0]) and torch.equal(res[0][0][t][1], res[1][0][t][1])
+        assert rel_err_rows(res[0][0][t][0].cpu().numpy(), ref["logits"][:, t]) <= 2e-2
+    assert torch.equal(res[0][1], res[1][1])
+
+
 # ---- head layouts: row-only, column-only, combined ("Method", after Eq. 2; Table S0) ------------
 @pytest.mark.parametrize("layout,H", [("row", 4), ("column", 4), ("combined", 4), ("row", 1), ("combined", 1),
                                       ("column", 3)])
