@@ -280,7 +280,8 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
     }
     const bool want_store = EPI != EPI_ARGMAX || ep.out != nullptr;
     const bool n_edge = wcol0 + WTN > N;              // wave-uniform
-    const bool interior = vec_ok && m0 + BM <= M && n0 + BN <= N;      // block-uniform
+    const bool cols_inside = vec_ok && n0 + BN <= N;                   // block-uniform
+    const bool rows_inside = m0 + BM <= M;                             // block-uniform
 
     // (a compile-time loop: with the largest epilogue the compiler kept `#pragma unroll` rolled, which indexes
     // the accumulators with a variable and so moves all of them, main loop included, to scratch memory)
@@ -341,34 +342,47 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                 for (int g = 0; g < 4; ++g)
                     *reinterpret_cast<float4 *>(stage + lr * STG + j * 32 + 8 * g + 4 * lk) =
                         make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-            if (interior) {
-                // tile inside the matrix: no edge tests, all staged reads (and, for the residual
-                // add, all loads of the old values) issued before the first use, so their
-                // latencies overlap instead of adding up once per 128-byte row segment
+            // All columns of the tile inside the matrix: no column tests, all staged reads (and, for the
+            // residual add and the state update, all loads of the old values) issued before the first use,
+            // so their latencies overlap instead of adding up once per 128-byte row segment.  Compiled
+            // twice: for tiles with all rows inside too (no tests at all; the hot path of large batches),
+            // and for the last row tile (a handful of rows), where rows past M load from row M - 1
+            // instead and store nothing.
+            auto whole_columns = [&](auto rows_inside_c) {
+                constexpr bool RI = decltype(rows_inside_c)::value;
                 constexpr int NIT = 32 / RPI;
                 const int64_t row0 = m0 + wm * WTM + i * 32 + s_row;
+                auto row_of = [&](int it) {
+                    if constexpr (RI) return row0 + it * RPI;
+                    else return min(row0 + it * RPI, (int64_t)M - 1);
+                };
+                auto exists = [&](int it) {
+                    if constexpr (RI) return true;
+                    else return row0 + it * RPI < M;
+                };
                 float4 v[NIT];
 #pragma unroll
                 for (int it = 0; it < NIT; ++it)
                     v[it] = *reinterpret_cast<const float4 *>(stage + (it * RPI + s_row) * STG + s_col);
                 if constexpr (EPI == EPI_RESID) {
-                    float *p = reinterpret_cast<float *>(ep.out) + row0 * ep.ldo + gcol;
+                    float *p = reinterpret_cast<float *>(ep.out) + gcol;
                     float4 o[NIT];
 #pragma unroll
-                    for (int it = 0; it < NIT; ++it) o[it] = load4(p + (int64_t)it * RPI * ep.ldo);
+                    for (int it = 0; it < NIT; ++it) o[it] = load4(p + row_of(it) * ep.ldo);
                     for (int s_ = 0; s_ < ep.add_nsplit; ++s_) {
-                        const float *q = ep.add_part + (int64_t)s_ * ep.add_stride + row0 * ep.ldo + gcol;
+                        const float *q = ep.add_part + (int64_t)s_ * ep.add_stride + gcol;
 #pragma unroll
                         for (int it = 0; it < NIT; ++it) {
-                            const float4 t = load4(q + (int64_t)it * RPI * ep.ldo);
+                            const float4 t = load4(q + row_of(it) * ep.ldo);
                             o[it].x += t.x; o[it].y += t.y; o[it].z += t.z; o[it].w += t.w;
                         }
                     }
 #pragma unroll
                     for (int it = 0; it < NIT; ++it)
-                        store4(p + (int64_t)it * RPI * ep.ldo,
-                               make_float4(o[it].x + (v[it].x + bias4.x), o[it].y + (v[it].y + bias4.y),
-                                           o[it].z + (v[it].z + bias4.z), o[it].w + (v[it].w + bias4.w)));
+                        if (exists(it))
+                            store4(p + row_of(it) * ep.ldo,
+                                   make_float4(o[it].x + (v[it].x + bias4.x), o[it].y + (v[it].y + bias4.y),
+                                               o[it].z + (v[it].z + bias4.z), o[it].w + (v[it].w + bias4.w)));
                 } else if constexpr (EPI == EPI_MIX) {
                     // the state update of NIT rows: positions, coefficients and old states are all
                     // requested before the first is used
@@ -380,12 +394,12 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                     float4 s0[NIT];
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
-                        const int64_t row = row0 + it * RPI;
+                        const int64_t row = row_of(it);
                         ps[it] = (int)(ep.pos_rows ? (uint32_t)ep.pos_rows[row] : epi_shared_pos(ep));
                     }
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
-                        const int64_t sj = ((row0 + it * RPI) * ep.ldo + gcol) >> 2;
+                        const int64_t sj = (row_of(it) * ep.ldo + gcol) >> 2;
                         const bool act = ps[it] >= 0 && ps[it] < ep.n_ctx;
                         const int pc = act ? ps[it] : 0;
                         al[it] = ep.alpha[(size_t)h * ep.n_ctx + pc];
@@ -395,6 +409,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                     }
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
+                        if (!exists(it)) continue;
                         const int64_t row = row0 + it * RPI;
                         const int64_t sj = (row * ep.ldo + gcol) >> 2;
                         TAct *o = reinterpret_cast<TAct *>(ep.out) + row * ep.ldo + gcol;
@@ -419,9 +434,13 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
                         v[it].x += bias4.x; v[it].y += bias4.y; v[it].z += bias4.z; v[it].w += bias4.w;
-                        epi_store4<EPI, TAct>(ep, row0 + it * RPI, gcol, v[it]);
+                        if (exists(it)) epi_store4<EPI, TAct>(ep, row0 + it * RPI, gcol, v[it]);
                     }
                 }
+            };
+            if (cols_inside) {
+                if (rows_inside) whole_columns(std::true_type{});
+                else if (m0 + wm * WTM + i * 32 < M) whole_columns(std::false_type{});   // else: nothing of this slice exists
                 return;
             }
 #pragma unroll
