@@ -278,6 +278,35 @@ def test_ragged_decode_large_batch_fused_equals_separate(srm, monkeypatch):
     assert not np.array_equal(st[:, ~idle], S0[:, ~idle])
 
 
+def test_ragged_decode_of_a_handful_of_samples_without_layernorm_launches(srm, monkeypatch):
+    """bf16 model, 6 slots at their own positions (one idle): the ragged step whose LayerNorms are made by the
+    consuming GEMMs equals the ragged step with LayerNorm launches (the library's switch) bit for bit."""
+    cfg = srm_synth.tiny_config(vocab=200, d_model=256, n_layers=3, n_heads=4, n_ctx=12, weight_dtype="bf16", seed=10)
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    B = 6
+    rng = np.random.default_rng(13)
+    pos0 = np.array([0, 3, -1, 7, 2, 5], np.int32)
+    tok0 = rng.integers(0, cfg.vocab, B).astype(np.int32)
+    S0 = rng.standard_normal((cfg.n_layers, B, cfg.d_model)).astype(np.float32)
+    ws = model.new_workspace(B)
+    res = []
+    for on_load in (True, False):
+        if not on_load:
+            monkeypatch.setenv("SRM_LN_ON_LOAD", "0")
+        st, tk, pos = to_dev(S0), to_dev(tok0), to_dev(pos0)
+        lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+        print(f"ragged handful B={B} on_load={on_load}", flush=True)
+        for _ in range(3):
+            model.decode_step_ragged(B, pos, tk, st, tk, advance=True, logits=lg, workspace=ws)
+        torch.cuda.synchronize()
+        res.append((st.cpu().numpy(), tk.cpu().numpy(), pos.cpu().numpy(), lg.cpu().numpy()[pos0 >= 0]))
+    for a, b in zip(res[0], res[1]):
+        np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(res[0][0][:, 2], S0[:, 2])          # the idle slot's state is untouched
+    assert np.isfinite(res[0][3]).all()
+
+
 def test_ragged_errors(c1, srm):
     cfg, w, model, orc = c1
     ws = model.new_workspace(32)
