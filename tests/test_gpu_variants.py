@@ -198,7 +198,7 @@ def test_half_state_bf16_weights_match_oracle(srm, orc_mod, use_projections, B, 
     assert np.abs(s_got - ref["state"]).max() <= 2e-2 * np.abs(ref["state"]).max()
 
 
-@pytest.mark.parametrize("d,B", [(256, 1), (512, 5), (1024, 8), (1024, 1), (320, 3), (1024, 9)])
+@pytest.mark.parametrize("d,B", [(64, 2), (128, 8), (256, 1), (512, 5), (1024, 8), (1024, 1), (320, 3), (1024, 9)])
 @pytest.mark.parametrize("fuse_mixer", [True, False])
 def test_layernorm_made_by_the_consuming_gemm_equals_the_separate_kernel(srm, orc_mod, d, B, fuse_mixer, monkeypatch):
     """A handful of samples of a bf16 model: the step without LayerNorm launches (every LayerNorm made by the
