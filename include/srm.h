@@ -36,6 +36,14 @@
  *     mixer state and logits are fp32.  Requires d_model % 64 == 0.
  *     weight_dtype SRM_FP32: everything fp32.  Both need d_model % (4*n_heads) == 0
  *     and d_model <= 4096.
+ *   - Environment switches (read at each call; they select between arrangements
+ *     of the same arithmetic and exist for tests and measurements):
+ *     SRM_FUSE_MIXER=0   the recurrent state update as a kernel of its own instead
+ *                        of inside the in-projection's epilogue (same bits);
+ *     SRM_LN_ON_LOAD=0   bf16 models, at most 8 samples: LayerNorm launches
+ *                        between the GEMMs instead of LayerNorm made by the
+ *                        consuming GEMM (same bits);
+ *     SRM_MEGAKERNEL, SRM_MEGA_BLOCKS   see srm_generate_one_kernel_blocks.
  */
 #ifndef SRM_H
 #define SRM_H
