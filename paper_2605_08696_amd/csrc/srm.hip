@@ -470,11 +470,13 @@ static int launch_bf16_small(const bf16 *A, const bf16 *W, int M, int N, int K, 
 // whole rounds (one block per CU: 384 tiles are two rounds at 75 %, and lose to 1536
 // tiles of 128x128); 128x128 wins over 64x64 from about 144 blocks on.
 constexpr int kNumTiles = 9;
-static int choose_tile(int64_t M, int N, int min_bn)
+static int choose_tile(int64_t M, int N, int K, int min_bn)
 {
     const int64_t t256 = cdiv(M, 256) * cdiv(N, 256), t128 = cdiv(M, 128) * cdiv(N, 128);
     int tile;
-    if (t256 >= 200 && (t256 >= 1024 || (double)t256 / (double)(cdiv(t256, 256) * 256) >= 0.8)) tile = 0;
+    // (a long k loop makes up for CUs left idle: with K >= 2048 the big tile wins from 160 tiles on)
+    const int64_t t256_min = K >= 2048 ? 160 : 200;
+    if (t256 >= t256_min && (t256 >= 1024 || t256 < 256 || (double)t256 / (double)(cdiv(t256, 256) * 256) >= 0.8)) tile = 0;
     else if (t128 >= 144) tile = 1;
     else tile = 2;
     if (tile == 2 && min_bn > 64) tile = 1;
@@ -498,7 +500,7 @@ static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, Ge
     }
     if (M <= 0 || M >= (1 << 30) || N <= 0) return fail(SRM_EINVAL, "GEMM shape out of range");
     if ((int64_t)K * 256 * 2 >= (1LL << 31)) return fail(SRM_EINVAL, "bf16 GEMM: K = %d too large", K);
-    const int tile = g_force_tile >= 0 ? g_force_tile : choose_tile(M, N, min_bn);
+    const int tile = g_force_tile >= 0 ? g_force_tile : choose_tile(M, N, K, min_bn);
     ep.nparts = (int)cdiv(N, tile_bn(tile));
     if (nparts_out) *nparts_out = ep.nparts;
     const int m = (int)M;
