@@ -520,6 +520,6 @@ mixer_parallel_kernel(const TAct *__restrict__ U, TAct *__restrict__ Y,
 }
 
 // Step counters of a multi-step generate call, kept in device memory so that the
-// captured step needs no host-side update: ctr[0] = position, ctr[1] = step.
+// captured step needs no host-side update: ctr[0] = position, ctr[1] = step.  (Every step after the
+// first advances them in its first kernel, the embedding LayerNorm.)
 __global__ void counters_set_kernel(int *ctr, int pos, int step) { ctr[0] = pos; ctr[1] = step; }
-__global__ void counters_advance_kernel(int *ctr) { ctr[0] += 1; ctr[1] += 1; }

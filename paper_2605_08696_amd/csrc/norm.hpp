@@ -17,6 +17,10 @@
 //           back to x_out: the residual add of that GEMM, done here.
 //   add_act: [rows][d] in the activation type, added to x first (x_out gets the
 //           sum): the residual add of a non-projected mixer layer.
+//   advance_ctr (GATHER only): the two step counters of a multi-step generate call
+//           (position, step), advanced by one here, in the first kernel of a step,
+//           instead of by a launch of their own behind the previous step; no block
+//           of this kernel reads them.
 template <typename TW, typename TAct, int VPL, bool GATHER>
 __global__ void __launch_bounds__(256)
 ln_kernel(const float *x_in, int64_t in_stride, const int32_t *__restrict__ tok,
@@ -24,8 +28,12 @@ ln_kernel(const float *x_in, int64_t in_stride, const int32_t *__restrict__ tok,
           const float *__restrict__ g, const float *__restrict__ b, TAct *__restrict__ out,
           int64_t rows, int d, float eps, const int32_t *__restrict__ seq_end = nullptr, int64_t base = 0,
           int64_t src_rows = 0, const float *__restrict__ part = nullptr, int nsplit = 0, int64_t part_stride = 0,
-          const TAct *__restrict__ add_act = nullptr)
+          const TAct *__restrict__ add_act = nullptr, int *advance_ctr = nullptr)
 {
+    if (GATHER && advance_ctr && blockIdx.x == 0 && threadIdx.x == 0) {
+        advance_ctr[0] += 1;
+        advance_ctr[1] += 1;
+    }
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;

@@ -650,7 +650,8 @@ template <typename T, bool GATHER>
 static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, const int32_t *tok,
                      float *x_out, const float *g, const float *b, void *out, int64_t rows, hipStream_t st,
                      const int32_t *seq_end = nullptr, int64_t base = 0, int64_t src_rows = 0,
-                     const float *part = nullptr, int nsplit = 0, const void *add_act = nullptr)
+                     const float *part = nullptr, int nsplit = 0, const void *add_act = nullptr,
+                     int *advance_ctr = nullptr)
 {
     const int d = m->d;
     T *o = static_cast<T *>(out);
@@ -670,7 +671,7 @@ static int layernorm(const srm_model *m, const float *x_in, int64_t in_stride, c
 #define LN_CASE(VPL)                                                                                     \
     hipLaunchKernelGGL((ln_kernel<T, T, VPL, GATHER>), dim3(nb), dim3(256), 0, st, x_in, in_stride, tok, \
                        emb, m->V, x_out, g, b, o, rows, d, m->cfg.ln_eps, seq_end, base, src_rows, part, nsplit,       \
-                       (int64_t)rows * d, static_cast<const T *>(add_act))
+                       (int64_t)rows * d, static_cast<const T *>(add_act), advance_ctr)
     if (d <= 256) LN_CASE(1);
     else if (d <= 512) LN_CASE(2);
     else if (d <= 1024) LN_CASE(4);
@@ -884,6 +885,7 @@ struct DecodeArgs {
     uint32_t seed;
     float top_p;
     int eos_plus1 = 0;
+    int *advance_ctr = nullptr;     // step counters of srm_generate, advanced by the first kernel of the step
 };
 
 template <typename T>
@@ -897,7 +899,7 @@ static int decode_rows(srm_model *m, const DecodeArgs &a, int64_t b0, int64_t nb
                                    (size_t)b0 * dm * m->ssize);
     };
     SRM_TRY((layernorm<T, true>(m, nullptr, 0, a.tok_in + b0, w.x, m->layers[0].ln1_g, m->layers[0].ln1_b, w.a, nb,
-                                st)));
+                                st, nullptr, 0, 0, nullptr, 0, nullptr, b0 == 0 ? a.advance_ctr : nullptr)));
     auto mix = [&](int l) {
         if (!pos_rows) return state_update<T>(m, l, a.pos, nb, w.u, slab(l), w.mx, st, a.pos_dev);
         const LayerDev &y = m->layers[l];
@@ -1150,15 +1152,13 @@ static int mega_generate(srm_model *m, int B, int pos0, int G, int32_t *tok, voi
 // ------------------------------------------------------------------ generate (G steps in one call)
 static int generate_step(srm_model *m, int64_t B, int32_t *tok, void *state, void *ws, size_t ws_bytes, int *ctr,
                          TokenStore ts, hipStream_t st, float temperature, uint32_t seed, float top_p, float *logits,
-                         int32_t *pos_rows = nullptr, int eos_plus1 = 0)
+                         int32_t *pos_rows, int eos_plus1, bool advance_first)
 {
-    // uniform position: read from the device counter; ragged: one position per sample, advanced on the device
+    // uniform position: read from the device counter; ragged: one position per sample, advanced on the device.
+    // Every step but the first of a call advances the counters in its first kernel.
     const DecodeArgs a{B, 0, pos_rows ? nullptr : ctr, pos_rows, pos_rows ? 1 : 0, tok, state, tok, logits, nullptr, ts,
-                       temperature, seed, top_p, eos_plus1};
-    SRM_TRY(decode_batch(m, a, ws, ws_bytes, st));
-    hipLaunchKernelGGL(counters_advance_kernel, dim3(1), dim3(1), 0, st, ctr);
-    HIP_TRY(hipGetLastError());
-    return SRM_OK;
+                       temperature, seed, top_p, eos_plus1, advance_first ? ctr : nullptr};
+    return decode_batch(m, a, ws, ws_bytes, st);
 }
 
 static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int32_t *d_tok, void *d_state,
@@ -1196,13 +1196,13 @@ static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int
     HIP_TRY(hipGetLastError());
     // first step eagerly (it also performs every one-time kernel attribute set-up)
     SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p, d_logits,
-                          d_pos, eos_plus1));
+                          d_pos, eos_plus1, false));
     if (G == 1) return SRM_OK;
     // The legacy default stream cannot be captured: loop eagerly there.
     if (st == nullptr) {
         for (int g = 1; g < G; ++g)
             SRM_TRY(generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p,
-                                  d_logits, d_pos, eos_plus1));
+                                  d_logits, d_pos, eos_plus1, true));
         return SRM_OK;
     }
     const bool hit = m->gexec && m->gkey.B == B && m->gkey.tok == d_tok && m->gkey.state == d_state &&
@@ -1214,7 +1214,7 @@ static int generate_common(srm_model *m, int64_t B, int32_t pos0, int32_t G, int
         hipGraph_t graph = nullptr;
         HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
         const int rc = generate_step(m, B, d_tok, d_state, d_workspace, ws_bytes, ctr, ts, st, temperature, seed, top_p,
-                                     d_logits, d_pos, eos_plus1);
+                                     d_logits, d_pos, eos_plus1, true);
         const hipError_t e = hipStreamEndCapture(st, &graph);
         if (rc != SRM_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
         if (e != hipSuccess) return fail(SRM_EHIP, "srm_generate: stream capture failed: %s", hipGetErrorString(e));
