@@ -220,17 +220,20 @@ def test_layernorm_made_by_the_consuming_gemm_equals_the_separate_kernel(srm, or
         ws, st = model.new_workspace(B), model.new_state(B)
         out = torch.empty(B, dtype=torch.int32, device="cuda")
         lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+        hd = torch.empty((B, cfg.d_model), dtype=torch.float32, device="cuda")
         tc = to_dev(toks).t().contiguous()
         steps = []
         print(f"LayerNorm on load d={d} B={B} fused mixer={fuse_mixer} on_load={on_load}", flush=True)
         for t in range(T):
-            model.decode_step(B, t, tc[t], st, out, logits=lg, workspace=ws)
-            steps.append((lg.clone(), out.clone()))
+            model.decode_step(B, t, tc[t], st, out, logits=lg, hidden=hd, workspace=ws)
+            steps.append((lg.clone(), out.clone(), hd.clone()))
         torch.cuda.synchronize()
         res.append((steps, st.clone()))
     for t in range(T):
         assert torch.equal(res[0][0][t][0], res[1][0][t][0]) and torch.equal(res[0][0][t][1], res[1][0][t][1])
+        assert torch.equal(res[0][0][t][2], res[1][0][t][2])          # the residual stream after the last block
         assert rel_err_rows(res[0][0][t][0].cpu().numpy(), ref["logits"][:, t]) <= 2e-2
+        assert rel_err_rows(res[0][0][t][2].cpu().numpy(), ref["hidden"][:, t]) <= 2e-2
     assert torch.equal(res[0][1], res[1][1])
 
 
