@@ -249,6 +249,8 @@ def concurrency_sweep(torch, srm, srm_synth, steps, state_dtype="fp32"):
         B = int(B * 0.95) // 4096 * 4096
     out["max_resident"] = best
     out["value"] = max(r["tokens_per_s"] for r in out["sweep"])
+    torch.cuda.synchronize()
+    model.close()
     print(json.dumps(out))
 
 
@@ -310,6 +312,7 @@ def main():
             dst.copy_(src)
         kernel_legs(torch, srm, model, cfg, B, 4)
         torch.cuda.synchronize()
+        model.close()
         print(json.dumps({"pmc_probe": "done", "copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
         return
     e0.record()
@@ -426,6 +429,11 @@ def main():
         rows = min(16, os.cpu_count() or 1)
         T = {"C4": 200, "C3": 256, "C1": 240}[cfg.name]      # about 10-20 s of host work
         out["cpu_baseline"] = cpu_baseline(cfg, w, rows, min(T, cfg.n_ctx - P))
+    # explicit, ordered teardown: drain the device, free the model (its cached step graph and weights), then
+    # the tensors - nothing is left to interpreter finalisation, when a profiler's tool may already be gone
+    torch.cuda.synchronize()
+    model.close()
+    del state, ws, tok, dprompts, store
     print(json.dumps(out))
 
 

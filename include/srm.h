@@ -162,6 +162,9 @@ size_t srm_state_bytes(const srm_model *m, int64_t batch);
  * in bf16 models a different slice size may select another GEMM tile shape.
  */
 size_t srm_workspace_bytes(const srm_model *m, int64_t rows);
+/* The same number from a configuration alone (host only, no GPU call), for sizing buffers before a model
+ * exists; 0 for a null or invalid configuration or rows <= 0. */
+size_t srm_workspace_bytes_config(const srm_config *cfg, int64_t rows);
 
 /*
  * One decode step for B samples that all sit at absolute position `pos`
@@ -217,7 +220,12 @@ int srm_decode_step_sampled(srm_model *m, int64_t B, int32_t pos, const int32_t 
  * all G steps in one cooperative launch, with fp32 sums in another order: equal
  * to the step calls up to fp32 rounding, token-exact unless two scores tie
  * within that rounding.  Such a call must not be made under stream capture.
- * Not thread-safe per model.
+ * The one-kernel path synchronises its work-groups with bounded waits; should a
+ * wait ever give up (a work-group that is not resident: never observed), the
+ * kernel ends early, d_tok and the rows of d_tokens_out from that step on hold
+ * -1, the state is undefined and the call has already returned SRM_OK (it is
+ * asynchronous): a caller that cannot rule this out checks d_tokens_out for -1
+ * after synchronising.  Not thread-safe per model.
  * Errors: SRM_EINVAL (null pointer, B or G <= 0, pos0 + G > n_ctx), SRM_ENOMEM
  * (workspace smaller than srm_workspace_bytes(m, B)), SRM_EHIP.
  */
@@ -346,6 +354,34 @@ int srm_prefill_ragged(srm_model *m, const int32_t *d_tokens, const int32_t *h_o
                        float *d_logits, void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Host-only planning query (no GPU call, no model): how srm_prefill_ragged would
+ * take the packed prompts h_offsets[N + 1] of a model with configuration cfg
+ * through a workspace of workspace_bytes.  The mixer of a prefill pass is either
+ * one sequential scan per prompt or a chunked scan ("MAX model details" names a
+ * parallel scan for recurrent prefill as unexplored; the recurrence of Eq. 2 /
+ * Eq. 3 is linear, so the state entering chunk j is lambda^c times the state
+ * entering chunk j-1 plus what chunk j-1 reaches from zero).  The chunked scan
+ * keeps one fp32 partial state per (prompt, chunk, channel) in the MLP buffer of
+ * the pass; it is taken when the call's shape (N, longest prompt) asks for it AND
+ * those partial states fit that buffer in every pass - many short prompts next
+ * to one long prompt do not fit, and the whole call then takes the sequential
+ * scan.  Reports the passes, the chunk length taken (0: sequential) and the one
+ * the shape alone would choose, and for the tightest pass under that choice the
+ * bytes of partial states and the bytes of the buffer they would live in.
+ * Errors: as srm_prefill_ragged for cfg, the lengths and the workspace size.
+ */
+typedef struct {
+    int32_t passes;              /* passes of whole prompts                                */
+    int32_t chunk_len;           /* chunk length of the scan taken, 0 = sequential scan     */
+    int32_t chunk_len_by_shape;  /* what (N, longest prompt) alone would choose             */
+    int32_t n_chunks;            /* chunks per prompt under chunk_len_by_shape              */
+    size_t scratch_need;         /* tightest pass under chunk_len_by_shape: partial states  */
+    size_t scratch_room;         /* ... and the room of that pass's MLP buffer, in bytes    */
+} srm_prefill_plan;
+int srm_prefill_ragged_plan(const srm_config *cfg, const int32_t *h_offsets, int32_t N,
+                            size_t workspace_bytes, srm_prefill_plan *out);
+
+/*
  * Parallel (sequence) form over d_tok[B][T], positions 0..T-1: identical model,
  * but the mixer is the explicit structured triangular product Y = U M + beta
  * with M built from alpha and lambda as in Eq. 1 (row-repeat heads) and Eq. 3
@@ -395,7 +431,16 @@ int srm_mixer_project_update(srm_model *m, int32_t layer, int32_t pos, int64_t B
  * epilogue: 0 = store (type `dtype`), 1 = exact GELU then store (type `dtype`),
  * 2 = add into fp32 d_out (residual), 3 = store fp32 and also write the
  * row-wise argmax (lowest index on ties) to d_argmax[M] (needs d_scratch of
- * srm_linear_scratch_bytes(M, N) bytes); d_out may be NULL for epilogue 3.
+ * srm_linear_scratch_bytes(M, N) bytes); d_out may be NULL for epilogue 3;
+ * 4 = store fp32 (the form the parallel pass uses for its logits).
+ * Test and measurement hook: with SRM_BF16, epilogue = (tile + 1) * 100 + e runs
+ * epilogue e on a pinned tile shape instead of the one the library would choose:
+ * tile 0 = 256x256 (8 wavefronts), 1 = 128x128 (4), 2 = 64x64 (4), 3 = 128x128 (8),
+ * 4 = 256x128 (8), 5 = 128x128 on a four-stage LDS ring, 6 / 7 / 8 = 64x64 on a
+ * ring of 2 / 4 / 8 stages.  Same values for every tile up to the fp32 summation
+ * order inside a k tile (none: all tiles accumulate k in the same order).
+ * Errors: SRM_EINVAL (null operand or output, sizes <= 0, K % 64 with SRM_BF16,
+ * unknown dtype, epilogue or tile code).
  */
 int srm_linear(int32_t dtype, int32_t epilogue, const void *d_A, const void *d_W,
                const float *d_bias, int64_t M, int32_t N, int32_t K, void *d_out,

@@ -5,4 +5,5 @@ arguments.  PyTorch is used for device memory and streams.  There is no CPU
 fallback: if the library is missing, loading fails.
 """
 from .binding import (SRM_BF16, SRM_FP32, Model, SrmError, lib, linear, linear_scratch_bytes,
-                      probe_copy, probe_mfma, sample_logits)  # noqa: F401
+                      prefill_ragged_plan, probe_copy, probe_mfma, sample_logits,
+                      workspace_bytes_config)  # noqa: F401

@@ -6,8 +6,11 @@ handed to the library.
 """
 from __future__ import annotations
 
+import atexit
 import ctypes as C
 import os
+import sys
+import weakref
 from typing import Optional
 
 import numpy as np
@@ -16,6 +19,16 @@ SRM_FP32, SRM_BF16, SRM_FP16 = 0, 1, 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsrm.so")
 _lib = None
+# Models that still own device memory.  They are closed by an exit handler, i.e. before the interpreter
+# starts tearing modules down: srm_free then runs while the HIP runtime, torch and any profiler tool
+# loaded into the process are still intact.  A destructor that fires later, during finalisation, frees nothing.
+_live_models: "weakref.WeakSet" = weakref.WeakSet()
+
+
+@atexit.register
+def _close_live_models():
+    for m in list(_live_models):
+        m.close()
 
 _LAYER_FIELDS = ("ln1_g", "ln1_b", "w_in", "b_in", "alpha", "beta", "lambda", "w_out", "b_out",
                  "ln2_g", "ln2_b", "w_up", "b_up", "w_down", "b_down")
@@ -68,6 +81,10 @@ def lib():
         L.srm_generate.argtypes = [vp, i64, i32, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, sz, vp]
         L.srm_decode_step_sampled.restype = C.c_int
         L.srm_decode_step_sampled.argtypes = [vp, i64, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, vp, vp, sz, vp]
+        L.srm_workspace_bytes_config.restype = sz
+        L.srm_workspace_bytes_config.argtypes = [vp, i64]
+        L.srm_prefill_ragged_plan.restype = C.c_int
+        L.srm_prefill_ragged_plan.argtypes = [vp, vp, i32, sz, vp]
         L.srm_prefill.restype = C.c_int
         L.srm_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
         L.srm_decode_step_ragged.restype = C.c_int
@@ -140,6 +157,35 @@ def _stream(stream) -> Optional[int]:
 HEAD_LAYOUTS = {"mixed": 0, "row": 1, "column": 2, "combined": 3}
 
 
+def c_config(cfg) -> "srm_config":
+    """The srm_config of a srm_synth-style configuration object."""
+    return srm_config(cfg.vocab, cfg.d_model, cfg.n_layers, cfg.n_heads, cfg.mlp_expansion, cfg.n_ctx,
+                      SRM_BF16 if cfg.weight_dtype == "bf16" else SRM_FP32, cfg.ln_eps,
+                      SRM_FP16 if getattr(cfg, "state_dtype", "fp32") == "fp16" else SRM_FP32,
+                      0 if getattr(cfg, "use_projections", True) else 1,
+                      HEAD_LAYOUTS[getattr(cfg, "head_layout", "mixed")], int(getattr(cfg, "mixer_kernel", 1)))
+
+
+class srm_prefill_plan(C.Structure):
+    _fields_ = [("passes", C.c_int32), ("chunk_len", C.c_int32), ("chunk_len_by_shape", C.c_int32),
+                ("n_chunks", C.c_int32), ("scratch_need", C.c_size_t), ("scratch_room", C.c_size_t)]
+
+
+def workspace_bytes_config(cfg, rows: int) -> int:
+    c = c_config(cfg)
+    return lib().srm_workspace_bytes_config(C.byref(c), int(rows))
+
+
+def prefill_ragged_plan(cfg, offsets, workspace_bytes: int) -> dict:
+    """srm_prefill_ragged_plan (host only): how a ragged prefill of these prompts would be cut and scanned."""
+    off = np.ascontiguousarray(offsets, dtype=np.int32)
+    c = c_config(cfg)
+    plan = srm_prefill_plan()
+    _check(lib().srm_prefill_ragged_plan(C.byref(c), off.ctypes.data_as(C.POINTER(C.c_int32)), len(off) - 1,
+                                         int(workspace_bytes), C.byref(plan)))
+    return {n: getattr(plan, n) for n, _ in srm_prefill_plan._fields_}
+
+
 class Model:
     """Owns one srm_model.  cfg needs vocab, d_model, n_layers, n_heads,
     mlp_expansion, n_ctx, weight_dtype ("fp32"|"bf16") and ln_eps; weights is
@@ -152,11 +198,7 @@ class Model:
         self.ff = cfg.d_model * cfg.mlp_expansion
         self.n_ctx = cfg.n_ctx
         self.dtype = SRM_BF16 if cfg.weight_dtype == "bf16" else SRM_FP32
-        c = srm_config(cfg.vocab, cfg.d_model, cfg.n_layers, cfg.n_heads, cfg.mlp_expansion,
-                       cfg.n_ctx, self.dtype, cfg.ln_eps,
-                       SRM_FP16 if getattr(cfg, "state_dtype", "fp32") == "fp16" else SRM_FP32,
-                       0 if getattr(cfg, "use_projections", True) else 1,
-                       HEAD_LAYOUTS[getattr(cfg, "head_layout", "mixed")], int(getattr(cfg, "mixer_kernel", 1)))
+        c = c_config(cfg)
         kmix = int(getattr(cfg, "mixer_kernel", 1))
         copies = kmix if kmix > 1 else 2 if getattr(cfg, "head_layout", "mixed") == "combined" else 1
         self.sd = self.d * copies                          # state (and mixer) width per sample and layer
@@ -186,13 +228,21 @@ class Model:
         h = C.c_void_p()
         _check(L.srm_init_weights(C.byref(c), C.byref(hw), C.byref(h)))
         self._h = h
+        _live_models.add(self)
 
     def close(self):
-        if getattr(self, "_h", None):
-            lib().srm_free(self._h)
-            self._h = None
+        """Free the device copies of the weights and the cached step graph (idempotent).  Work of this
+        model that is still queued on a stream must have completed: synchronise first."""
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            lib().srm_free(h)
+        _live_models.discard(self)
 
-    __del__ = close
+    def __del__(self):
+        # During interpreter finalisation the runtime below may already be going down, and the
+        # process exit releases the device memory anyway.
+        if not sys.is_finalizing():
+            self.close()
 
     @property
     def act_dtype(self):

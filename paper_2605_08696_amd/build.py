@@ -1,6 +1,7 @@
 """Build libsrm.so (the HIP library behind include/srm.h) for gfx950 with hipcc."""
 from __future__ import annotations
 
+import glob
 import os
 import subprocess
 
@@ -8,8 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libsrm.so")
 SOURCES = [os.path.join(HERE, "csrc", "srm.hip")]
-HEADERS = [os.path.join(HERE, "csrc", n) for n in ("common.hpp", "gemm.hpp", "mixer.hpp", "norm.hpp")]
-HEADERS.append(os.path.join(ROOT, "include", "srm.h"))
+HEADERS = sorted(glob.glob(os.path.join(HERE, "csrc", "*.hpp"))) + [os.path.join(ROOT, "include", "srm.h")]
 
 
 def build_lib(verbose: bool = False) -> str:

@@ -847,15 +847,6 @@ gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
 // batch ahead, the first batch before A is staged.  Rows are processed MB at a time (W is streamed
 // again per group of MB rows).  Split K as in gemm_bf16_kernel (gridDim.y slabs, EPI_F32 only).
 // Dynamic LDS: MB * (K / gridDim.y) floats.
-__device__ __forceinline__ float row16_sum_dpp(float v)
-{
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
-    return v;
-}
-
 template <typename TW> struct GemvVec;
 template <> struct GemvVec<float> {
     static constexpr int VW = 4;
@@ -970,7 +961,7 @@ gemv_rows_kernel(const TAct *__restrict__ A, const TW *__restrict__ W, int M, in
             float mine = 0.0f;
 #pragma unroll
             for (int b = 0; b < MB; ++b) {
-                const float v = row16_sum_dpp(acc[c][b]);
+                const float v = row16_sum(acc[c][b]);
                 if (l16 == b) mine = v;
             }
             const int row = mg + l16;

@@ -91,15 +91,6 @@ __device__ __forceinline__ bool mega_barrier(unsigned *bar, unsigned &epoch, int
 constexpr int kMegaMaxLayers = 32;   // the layers' pointer tables are kept in LDS
 constexpr int kMegaPF = 8;       // float4 values per lane in one weight batch
 
-// Sum over the 16 lanes of a DPP row, result in every lane of the row (no LDS traffic).
-__device__ __forceinline__ float row16_sum(float v)
-{
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
-    return v;
-}
 __device__ __forceinline__ float wave64_sum(float v)
 {
     v = row16_sum(v);
@@ -477,8 +468,10 @@ give_up:
     if (threadIdx.x < B) p.tok[threadIdx.x] = -1;
 }
 
-// The barrier slots and the give-up flag start at zero.
-__global__ void mega_reset_kernel(unsigned *bar)
+// The barrier slots and the give-up flag start at zero; the token store starts at -1, so that the rows of
+// the steps a kernel that gave up never reached are recognisable.
+__global__ void mega_reset_kernel(unsigned *bar, int32_t *store, int n_store)
 {
     for (int i = threadIdx.x; i <= kMegaMaxBlocks * 16; i += blockDim.x) bar[i] = 0u;
+    for (int i = threadIdx.x; i < n_store; i += blockDim.x) store[i] = -1;
 }

@@ -26,8 +26,10 @@ constexpr int kMaxHeads = 64;
 // channels per thread.  The launch makes gridDim.x * 256 a multiple of d/4, so a
 // thread keeps one channel group, hence one head, for its whole loop; the per
 // head coefficients of this position are staged in LDS once per block.  If
-// pos_dev is not null the position is read from device memory (clamped to the
-// table), so that a captured graph of the step can be replayed as is.
+// pos_dev is not null the position is read from device memory, so that a captured
+// graph of the step can be replayed as is; a position outside [0, n_ctx) there
+// makes the whole batch inactive, as in the fused in-projection epilogue: the
+// state is left alone and m is written as zeros.
 template <typename TAct, int UNROLL, typename TState = float>
 __global__ void __launch_bounds__(256)
 state_update_kernel(const TAct *__restrict__ u, TState *__restrict__ S, TAct *__restrict__ m,
@@ -36,7 +38,12 @@ state_update_kernel(const TAct *__restrict__ u, TState *__restrict__ S, TAct *__
                     int d, int64_t nvec)
 {
     __shared__ float4 coef[kMaxHeads];      // (lam, p, q, beta) per head
-    if (pos_dev) pos = min(max(*pos_dev, 0), n_ctx - 1);
+    bool active = true;
+    if (pos_dev) {
+        const int pd = *pos_dev;
+        active = pd >= 0 && pd < n_ctx;
+        pos = active ? pd : 0;
+    }
     if (threadIdx.x < H) {
         const int h = threadIdx.x;
         const float a = alpha[(size_t)h * n_ctx + pos];
@@ -51,6 +58,10 @@ state_update_kernel(const TAct *__restrict__ u, TState *__restrict__ S, TAct *__
     const float4 cf = coef[(int)(gid % dv) / dhv];
     const float l = cf.x, p = cf.y, q = cf.z, be = cf.w;
 
+    if (!active) {
+        for (int64_t i = gid; i < nvec; i += nthreads) store4(m + i * 4, make_float4(0.f, 0.f, 0.f, 0.f));
+        return;
+    }
     for (int64_t i = gid; i < nvec; i += nthreads * UNROLL) {
         float4 s[UNROLL], x[UNROLL];
 #pragma unroll

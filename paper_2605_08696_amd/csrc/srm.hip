@@ -112,73 +112,93 @@ struct SlabBuilder {
 
 extern "C" const char *srm_last_error(void) { return g_err.c_str(); }
 
+// Checks a configuration and fills the sizes derived from it (no device work): what srm_init_weights
+// starts with, and all that the host-side planning queries need of a model.
+static int model_geometry(const char *who, const srm_config *cfg, srm_model *m)
+{
+    if (cfg->vocab <= 0 || cfg->d_model <= 0 || cfg->n_layers <= 0 || cfg->n_heads <= 0 ||
+        cfg->mlp_expansion <= 0 || cfg->n_ctx <= 0)
+        return fail(SRM_EINVAL, "%s: sizes must be positive", who);
+    const int layout = cfg->head_layout;
+    if (layout < SRM_HEADS_MIXED || layout > SRM_HEADS_COMBINED)
+        return fail(SRM_EINVAL, "%s: unknown head_layout %d", who, layout);
+    const int kmix = cfg->mixer_kernel > 1 ? cfg->mixer_kernel : 1;
+    if (cfg->mixer_kernel < 0 || kmix > cfg->d_model)
+        return fail(SRM_EINVAL, "%s: mixer_kernel %d outside [0, d_model]", who, cfg->mixer_kernel);
+    if (kmix > 1 && (layout != SRM_HEADS_COLUMN || cfg->no_projections))
+        return fail(SRM_EINVAL, "%s: mixer_kernel > 1 needs column-repeat heads and the head projections", who);
+    const int slots = cfg->n_heads * (kmix > 1 ? kmix : layout == SRM_HEADS_COMBINED ? 2 : 1);
+    if ((layout == SRM_HEADS_MIXED && cfg->n_heads % 2) || slots > kMaxHeads)
+        return fail(SRM_EINVAL, "%s: n_heads must be even for mixed heads, and at most %d "
+                                "coefficient rows per layer", who, kMaxHeads);
+    if (layout == SRM_HEADS_COMBINED && cfg->no_projections)
+        return fail(SRM_EINVAL, "%s: combined heads need the head projections", who);
+    if (cfg->d_model % (4 * cfg->n_heads))
+        return fail(SRM_EINVAL, "%s: d_model must be a multiple of 4*n_heads", who);
+    if (cfg->d_model > 4096) return fail(SRM_EINVAL, "%s: d_model > 4096 unsupported", who);
+    if (cfg->weight_dtype != SRM_FP32 && cfg->weight_dtype != SRM_BF16)
+        return fail(SRM_EINVAL, "%s: unknown weight_dtype %d", who, cfg->weight_dtype);
+    if (cfg->weight_dtype == SRM_BF16 && cfg->d_model % 64)
+        return fail(SRM_EINVAL, "%s: bf16 needs d_model %% 64 == 0", who);
+    if (!(cfg->ln_eps > 0.0f)) return fail(SRM_EINVAL, "%s: ln_eps must be > 0", who);
+    if (cfg->state_dtype != SRM_FP32 && cfg->state_dtype != SRM_FP16)
+        return fail(SRM_EINVAL, "%s: unknown state_dtype %d", who, cfg->state_dtype);
+    m->cfg = *cfg;
+    m->device = -1;
+    m->d = cfg->d_model; m->ff = cfg->mlp_expansion * cfg->d_model; m->V = cfg->vocab; m->L = cfg->n_layers;
+    m->H = cfg->n_heads;
+    const int copies = kmix > 1 ? kmix : layout == SRM_HEADS_COMBINED ? 2 : 1;   // times the mixer row repeats the head input
+    m->dm = copies * m->d;
+    m->Hs = slots;
+    m->hrow = layout == SRM_HEADS_MIXED ? m->H / 2 : layout == SRM_HEADS_COLUMN ? 0 : m->H;
+    m->noproj = cfg->no_projections != 0;
+    m->shalf = cfg->state_dtype == SRM_FP16;
+    m->ssize = m->shalf ? 2 : 4;
+    m->wsize = cfg->weight_dtype == SRM_BF16 ? 2 : 4;
+    m->slab = nullptr;
+    m->mega_layers = nullptr;
+    m->gexec = nullptr;
+    m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, 1.0f, nullptr, 0, nullptr, 0};
+    return SRM_OK;
+}
+
 extern "C" int srm_init_weights(const srm_config *cfg, const srm_host_weights *w, srm_model **out)
 {
     if (!cfg || !w || !out) return fail(SRM_EINVAL, "srm_init_weights: null argument");
     *out = nullptr;
-    if (cfg->vocab <= 0 || cfg->d_model <= 0 || cfg->n_layers <= 0 || cfg->n_heads <= 0 ||
-        cfg->mlp_expansion <= 0 || cfg->n_ctx <= 0)
-        return fail(SRM_EINVAL, "srm_init_weights: sizes must be positive");
-    const int layout = cfg->head_layout;
-    if (layout < SRM_HEADS_MIXED || layout > SRM_HEADS_COMBINED)
-        return fail(SRM_EINVAL, "srm_init_weights: unknown head_layout %d", layout);
-    const int kmix = cfg->mixer_kernel > 1 ? cfg->mixer_kernel : 1;
-    if (cfg->mixer_kernel < 0 || kmix > cfg->d_model)
-        return fail(SRM_EINVAL, "srm_init_weights: mixer_kernel %d outside [0, d_model]", cfg->mixer_kernel);
-    if (kmix > 1 && (layout != SRM_HEADS_COLUMN || cfg->no_projections))
-        return fail(SRM_EINVAL, "srm_init_weights: mixer_kernel > 1 needs column-repeat heads and the head projections");
-    const int slots = cfg->n_heads * (kmix > 1 ? kmix : layout == SRM_HEADS_COMBINED ? 2 : 1);
-    if ((layout == SRM_HEADS_MIXED && cfg->n_heads % 2) || slots > kMaxHeads)
-        return fail(SRM_EINVAL, "srm_init_weights: n_heads must be even for mixed heads, and at most %d "
-                                "coefficient rows per layer", kMaxHeads);
-    if (layout == SRM_HEADS_COMBINED && cfg->no_projections)
-        return fail(SRM_EINVAL, "srm_init_weights: combined heads need the head projections");
-    if (cfg->d_model % (4 * cfg->n_heads))
-        return fail(SRM_EINVAL, "srm_init_weights: d_model must be a multiple of 4*n_heads");
-    if (cfg->d_model > 4096) return fail(SRM_EINVAL, "srm_init_weights: d_model > 4096 unsupported");
-    if (cfg->weight_dtype != SRM_FP32 && cfg->weight_dtype != SRM_BF16)
-        return fail(SRM_EINVAL, "srm_init_weights: unknown weight_dtype %d", cfg->weight_dtype);
-    if (cfg->weight_dtype == SRM_BF16 && cfg->d_model % 64)
-        return fail(SRM_EINVAL, "srm_init_weights: bf16 needs d_model %% 64 == 0");
-    if (!(cfg->ln_eps > 0.0f)) return fail(SRM_EINVAL, "srm_init_weights: ln_eps must be > 0");
-    if (cfg->state_dtype != SRM_FP32 && cfg->state_dtype != SRM_FP16)
-        return fail(SRM_EINVAL, "srm_init_weights: unknown state_dtype %d", cfg->state_dtype);
-    if (!w->embed || !w->head || !w->lnf_g || !w->lnf_b || !w->layers)
+    srm_model *m = new (std::nothrow) srm_model();
+    if (!m) return fail(SRM_ENOMEM, "srm_init_weights: host allocation failed");
+    const int grc = model_geometry("srm_init_weights", cfg, m);
+    if (grc != SRM_OK) { delete m; return grc; }
+    if (!w->embed || !w->head || !w->lnf_g || !w->lnf_b || !w->layers) {
+        delete m;
         return fail(SRM_EINVAL, "srm_init_weights: null weight pointer");
-    const int d = cfg->d_model, L = cfg->n_layers, H = cfg->n_heads, V = cfg->vocab;
-    const size_t ff = (size_t)cfg->mlp_expansion * d, nc = cfg->n_ctx;
+    }
+    const int d = m->d, L = m->L, H = m->H, V = m->V;
+    const int layout = cfg->head_layout;
+    const int kmix = cfg->mixer_kernel > 1 ? cfg->mixer_kernel : 1;
+    const int slots = m->Hs, copies = m->dm / d;
+    const bool comb = layout == SRM_HEADS_COMBINED;
+    (void)comb;
+    const bool bf = cfg->weight_dtype == SRM_BF16;
+    const size_t ff = (size_t)m->ff, nc = cfg->n_ctx;
     for (int l = 0; l < L; ++l) {
         const srm_host_layer &y = w->layers[l];
         const float *ptrs[] = {y.ln1_g, y.ln1_b, y.alpha, y.beta, y.lambda, y.ln2_g, y.ln2_b, y.w_up, y.b_up,
                                y.w_down, y.b_down};
         for (const float *p : ptrs)
-            if (!p) return fail(SRM_EINVAL, "srm_init_weights: null weight pointer in layer %d", l);
-        if (!cfg->no_projections && (!y.w_in || !y.b_in || !y.w_out || !y.b_out))
+            if (!p) { delete m; return fail(SRM_EINVAL, "srm_init_weights: null weight pointer in layer %d", l); }
+        if (!cfg->no_projections && (!y.w_in || !y.b_in || !y.w_out || !y.b_out)) {
+            delete m;
             return fail(SRM_EINVAL, "srm_init_weights: null projection weights in layer %d", l);
+        }
         for (int h = 0; h < slots; ++h)
-            if (!(y.lambda[h] > 0.0f && y.lambda[h] <= 1.0f))
+            if (!(y.lambda[h] > 0.0f && y.lambda[h] <= 1.0f)) {
+                delete m;
                 return fail(SRM_EINVAL, "srm_init_weights: lambda[%d][%d] = %g outside (0, 1]", l, h,
                             (double)y.lambda[h]);
+            }
     }
-
-    srm_model *m = new (std::nothrow) srm_model();
-    if (!m) return fail(SRM_ENOMEM, "srm_init_weights: host allocation failed");
-    m->cfg = *cfg;
-    m->d = d; m->ff = (int)ff; m->V = V; m->L = L; m->H = H;
-    const bool comb = layout == SRM_HEADS_COMBINED;
-    const int copies = kmix > 1 ? kmix : comb ? 2 : 1;        // times the mixer row repeats the head input
-    m->dm = copies * d;
-    m->Hs = slots;
-    m->hrow = layout == SRM_HEADS_MIXED ? H / 2 : layout == SRM_HEADS_COLUMN ? 0 : H;
-    m->noproj = cfg->no_projections != 0;
-    m->shalf = cfg->state_dtype == SRM_FP16;
-    m->ssize = m->shalf ? 2 : 4;
-    const bool bf = cfg->weight_dtype == SRM_BF16;
-    m->wsize = bf ? 2 : 4;
-    m->slab = nullptr;
-    m->mega_layers = nullptr;
-    m->gexec = nullptr;
-    m->gkey = {0, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, 1.0f, nullptr, 0, nullptr, 0};
 
     struct Offs { size_t v[15]; };
     std::vector<Offs> lo(L);
@@ -1142,7 +1162,7 @@ static int mega_generate(srm_model *m, int B, int pos0, int G, int32_t *tok, voi
         HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
         attr_set[slot] = true;
     }
-    hipLaunchKernelGGL(mega_reset_kernel, dim3(1), dim3(64), 0, st, a.bar);
+    hipLaunchKernelGGL(mega_reset_kernel, dim3(1), dim3(256), 0, st, a.bar, store, G * B);
     HIP_TRY(hipGetLastError());
     void *args[] = {&a};
     HIP_TRY(hipLaunchCooperativeKernel(kern, dim3((unsigned)nblk), dim3(kMegaThreads), args, (unsigned)lds, st));
@@ -1286,6 +1306,48 @@ static int scan_chunk_len(const srm_model *m, int64_t nseq, int P)
     return 0;
 }
 
+// The chunked scan keeps its per-chunk partial states F [nc][nchunks][dm] fp32 in the pass's MLP buffer
+// w.g ([rows][ff] activation elements, free until the layer's MLP): whether they fit there.
+static bool scan_scratch_fits(const srm_model *m, int64_t nc, int nchunks, int64_t rows)
+{
+    return (size_t)nc * (size_t)nchunks * (size_t)m->dm * sizeof(float) <= (size_t)rows * (size_t)m->ff * m->wsize;
+}
+
+// How srm_prefill_ragged cuts packed prompts into passes of whole prompts that fit max_rows workspace rows,
+// and which mixer scan the call takes: the chunked one only if its partial states fit the MLP buffer in
+// EVERY pass (many short prompts next to a long one do not: the chunk count follows the longest prompt of
+// the call, the buffer the rows of the pass), so that one call uses one kind of scan whatever the workspace.
+struct RaggedPlan {
+    std::vector<int> first;        // first prompt of each pass, then N
+    int chunk = 0, nchunks = 1;    // the scan taken (chunk 0: sequential)
+    int chunk_by_shape = 0;        // what (N, longest prompt) alone would choose
+    size_t need = 0, room = 0;     // tightest pass under chunk_by_shape: bytes of F, bytes of w.g
+};
+static RaggedPlan plan_ragged(const srm_model *m, const int32_t *h_off, int N, int64_t max_rows, int pmax_call)
+{
+    RaggedPlan pl;
+    pl.chunk_by_shape = scan_chunk_len(m, N, pmax_call);
+    const int nch = pl.chunk_by_shape ? (int)cdiv(pmax_call, pl.chunk_by_shape) : 1;
+    bool fits = true;
+    int n0 = 0;
+    while (n0 < N) {
+        int n1 = n0;
+        while (n1 < N && (int64_t)h_off[n1 + 1] - h_off[n0] <= max_rows) ++n1;
+        if (n1 == n0) break;                          // a prompt longer than the workspace: rejected by the caller
+        pl.first.push_back(n0);
+        if (pl.chunk_by_shape) {
+            const int64_t nc = n1 - n0, rows = (int64_t)h_off[n1] - h_off[n0];
+            const size_t need = (size_t)nc * nch * m->dm * sizeof(float), room = (size_t)rows * m->ff * m->wsize;
+            if (!scan_scratch_fits(m, nc, nch, rows)) fits = false;
+            if (pl.room == 0 || (double)need * (double)pl.room > (double)pl.need * (double)room) { pl.need = need; pl.room = room; }
+        }
+        n0 = n1;
+    }
+    pl.first.push_back(N);
+    if (pl.chunk_by_shape && fits) { pl.chunk = pl.chunk_by_shape; pl.nchunks = nch; }
+    return pl;
+}
+
 // The mixer of one prefill pass: nc sequences in rows of w.u -> w.mx, final states to S_layer.
 template <typename T>
 static int prefill_mixer(const srm_model *m, int l, const Workspace &w, void *S_layer, int nc, int P, int chunk,
@@ -1329,11 +1391,10 @@ static int prefill_mixer(const srm_model *m, int l, const Workspace &w, void *S_
 
 template <typename T>
 static int prefill_impl(srm_model *m, const int32_t *prompts, int N, int P, int k, void *state,
-                        int32_t *next_tok, float *logits, void *ws, int64_t per_pass, hipStream_t st)
+                        int32_t *next_tok, float *logits, void *ws, int64_t per_pass, int chunk, hipStream_t st)
 {
     const int d = m->d;
     const int64_t Btot = (int64_t)N * k;
-    const int chunk = scan_chunk_len(m, N, P);
     const int nchunks = chunk ? (int)cdiv(P, chunk) : 1;
     for (int64_t n0 = 0; n0 < N; n0 += per_pass) {
         const int64_t nc = std::min<int64_t>(per_pass, N - n0);
@@ -1363,7 +1424,11 @@ extern "C" int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, in
     if (N <= 0 || P <= 0 || fanout_k <= 0) return fail(SRM_EINVAL, "srm_prefill: N, P and fanout_k must be positive");
     if (P > m->cfg.n_ctx) return fail(SRM_EINVAL, "srm_prefill: P = %d exceeds n_ctx = %d", P, m->cfg.n_ctx);
     if ((int64_t)N * fanout_k >= (1 << 30)) return fail(SRM_EINVAL, "srm_prefill: N * fanout_k too large");
-    if ((size_t)2 * m->Hs * P * sizeof(float) > 64 * 1024)
+    // the chunked scan where the call's shape asks for it and its partial states fit the MLP buffer of a pass
+    // (rows = prompts x P there, so the test does not depend on how many prompts a pass holds)
+    int chunk = scan_chunk_len(m, N, P);
+    if (chunk && !scan_scratch_fits(m, 1, (int)cdiv(P, chunk), P)) chunk = 0;
+    if (!chunk && (size_t)2 * m->Hs * P * sizeof(float) > 64 * 1024)   // the sequential scan stages its coefficients in LDS
         return fail(SRM_EINVAL, "srm_prefill: n_heads * P too large for the coefficient stage");
     const int64_t max_seqs = std::max<int64_t>(1, ((1 << 30) - 1) / P);
     int64_t per_pass = seqs_per_pass(m, workspace_bytes, P, std::min<int64_t>(N, max_seqs));
@@ -1373,30 +1438,25 @@ extern "C" int srm_prefill(srm_model *m, const int32_t *d_prompts, int32_t N, in
     SRM_TRY(check_device(m));
     hipStream_t st = as_stream(hip_stream);
     return m->wsize == 2 ? prefill_impl<bf16>(m, d_prompts, N, P, fanout_k, d_state, d_next_tok, d_logits,
-                                              d_workspace, per_pass, st)
+                                              d_workspace, per_pass, chunk, st)
                          : prefill_impl<float>(m, d_prompts, N, P, fanout_k, d_state, d_next_tok, d_logits,
-                                               d_workspace, per_pass, st);
+                                               d_workspace, per_pass, chunk, st);
 }
 
 // ------------------------------------------------------------------ prefill of packed ragged prompts
 template <typename T>
 static int prefill_ragged_impl(srm_model *m, const int32_t *tokens, const int32_t *h_off, const int32_t *d_off, int N,
                                int k, const int32_t *slot, int64_t state_batch, void *state, int32_t *next_tok,
-                               int32_t *pos_out, float *logits, void *ws, int64_t max_rows, int pmax_call,
+                               int32_t *pos_out, float *logits, void *ws, const RaggedPlan &plan, int pmax_call,
                                hipStream_t st)
 {
     const int d = m->d;
-    const int chunk = scan_chunk_len(m, N, pmax_call);
-    const int nchunks = chunk ? (int)cdiv(pmax_call, chunk) : 1;
-    int n0 = 0;
-    while (n0 < N) {
+    const int chunk = plan.chunk, nchunks = plan.nchunks;
+    for (size_t pass = 0; pass + 1 < plan.first.size(); ++pass) {
         // as many whole prompts as the workspace holds
-        int n1 = n0;
+        const int n0 = plan.first[pass], n1 = plan.first[pass + 1];
         int pmax = 0;
-        while (n1 < N && (int64_t)h_off[n1 + 1] - h_off[n0] <= max_rows) {
-            pmax = std::max(pmax, h_off[n1 + 1] - h_off[n1]);
-            ++n1;
-        }
+        for (int n = n0; n < n1; ++n) pmax = std::max(pmax, h_off[n + 1] - h_off[n]);
         const int nc = n1 - n0;
         const int64_t base = h_off[n0], rows = (int64_t)h_off[n1] - base;
         const Workspace w = carve(m, ws, rows);
@@ -1417,7 +1477,33 @@ static int prefill_ragged_impl(srm_model *m, const int32_t *tokens, const int32_
         rg.pos_set = pos_out;
         SRM_TRY((head_argmax<T>(m, w, w.a, nc, logits ? logits + (size_t)n0 * m->V : nullptr, next_tok, n0, k, st,
                                 TokenStore(), Sampling(), rg)));
-        n0 = n1;
+    }
+    return SRM_OK;
+}
+
+// Host-side checks of a packed prompt list against a model and a workspace size: every length within
+// [1, n_ctx] and within the rows the workspace holds; returns those rows and the longest prompt.
+static int ragged_lengths(const char *who, const srm_model *m, const int32_t *h_offsets, int N, size_t workspace_bytes,
+                          int64_t &max_rows, int &pmax)
+{
+    if (h_offsets[0] < 0) return fail(SRM_EINVAL, "%s: offsets[0] is negative", who);
+    // rows the workspace holds (largest r with srm_workspace_bytes(r) <= workspace_bytes)
+    int64_t lo = 0, hi = (1 << 30) - 1;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) / 2;
+        if (srm_workspace_bytes(m, mid) <= workspace_bytes) lo = mid; else hi = mid - 1;
+    }
+    max_rows = lo;
+    pmax = 0;
+    for (int n = 0; n < N; ++n) {
+        const int64_t len = (int64_t)h_offsets[n + 1] - h_offsets[n];
+        if (len < 1 || len > m->cfg.n_ctx)
+            return fail(SRM_EINVAL, "%s: prompt %d has length %lld outside [1, n_ctx = %d]", who, n, (long long)len,
+                        m->cfg.n_ctx);
+        if (len > max_rows)
+            return fail(SRM_ENOMEM, "%s: workspace %zu < %zu bytes (prompt %d of %lld tokens)", who, workspace_bytes,
+                        srm_workspace_bytes(m, len), n, (long long)len);
+        pmax = std::max(pmax, (int)len);
     }
     return SRM_OK;
 }
@@ -1436,35 +1522,49 @@ extern "C" int srm_prefill_ragged(srm_model *m, const int32_t *d_tokens, const i
     if (!d_slot && (int64_t)N * fanout_k > state_batch)
         return fail(SRM_EINVAL, "%s: N * fanout_k = %lld exceeds state_batch = %lld", who, (long long)N * fanout_k,
                     (long long)state_batch);
-    if (h_offsets[0] < 0) return fail(SRM_EINVAL, "%s: offsets[0] is negative", who);
-    // rows the workspace holds (largest r with srm_workspace_bytes(r) <= workspace_bytes)
-    int64_t lo = 0, hi = (1 << 30) - 1;
-    while (lo < hi) {
-        const int64_t mid = (lo + hi + 1) / 2;
-        if (srm_workspace_bytes(m, mid) <= workspace_bytes) lo = mid; else hi = mid - 1;
-    }
-    const int64_t max_rows = lo;
+    int64_t max_rows = 0;
     int pmax = 0;
-    for (int n = 0; n < N; ++n) {
-        const int64_t len = (int64_t)h_offsets[n + 1] - h_offsets[n];
-        if (len < 1 || len > m->cfg.n_ctx)
-            return fail(SRM_EINVAL, "%s: prompt %d has length %lld outside [1, n_ctx = %d]", who, n, (long long)len,
-                        m->cfg.n_ctx);
-        if (len > max_rows)
-            return fail(SRM_ENOMEM, "%s: workspace %zu < %zu bytes (prompt %d of %lld tokens)", who, workspace_bytes,
-                        srm_workspace_bytes(m, len), n, (long long)len);
-        pmax = std::max(pmax, (int)len);
-    }
-    if ((size_t)2 * m->Hs * pmax * sizeof(float) > 64 * 1024)
+    SRM_TRY(ragged_lengths(who, m, h_offsets, N, workspace_bytes, max_rows, pmax));
+    const RaggedPlan plan = plan_ragged(m, h_offsets, N, max_rows, pmax);
+    if (!plan.chunk && (size_t)2 * m->Hs * pmax * sizeof(float) > 64 * 1024)   // the sequential scan's coefficient stage
         return fail(SRM_EINVAL, "%s: n_heads * longest prompt too large for the coefficient stage", who);
     SRM_TRY(check_device(m));
     hipStream_t st = as_stream(hip_stream);
     return m->wsize == 2 ? prefill_ragged_impl<bf16>(m, d_tokens, h_offsets, d_offsets, N, fanout_k, d_slot,
                                                      state_batch, d_state, d_next_tok, d_pos, d_logits, d_workspace,
-                                                     max_rows, pmax, st)
+                                                     plan, pmax, st)
                          : prefill_ragged_impl<float>(m, d_tokens, h_offsets, d_offsets, N, fanout_k, d_slot,
                                                       state_batch, d_state, d_next_tok, d_pos, d_logits, d_workspace,
-                                                      max_rows, pmax, st);
+                                                      plan, pmax, st);
+}
+
+extern "C" size_t srm_workspace_bytes_config(const srm_config *cfg, int64_t rows)
+{
+    if (!cfg || rows <= 0) return 0;
+    srm_model m;
+    if (model_geometry("srm_workspace_bytes_config", cfg, &m) != SRM_OK) return 0;
+    return carve(&m, nullptr, rows).bytes;
+}
+
+extern "C" int srm_prefill_ragged_plan(const srm_config *cfg, const int32_t *h_offsets, int32_t N,
+                                       size_t workspace_bytes, srm_prefill_plan *out)
+{
+    const char *who = "srm_prefill_ragged_plan";
+    if (!cfg || !h_offsets || !out) return fail(SRM_EINVAL, "%s: null argument", who);
+    if (N <= 0) return fail(SRM_EINVAL, "%s: N must be positive", who);
+    srm_model m;
+    SRM_TRY(model_geometry(who, cfg, &m));
+    int64_t max_rows = 0;
+    int pmax = 0;
+    SRM_TRY(ragged_lengths(who, &m, h_offsets, N, workspace_bytes, max_rows, pmax));
+    const RaggedPlan plan = plan_ragged(&m, h_offsets, N, max_rows, pmax);
+    out->passes = (int32_t)plan.first.size() - 1;
+    out->chunk_len = plan.chunk;
+    out->chunk_len_by_shape = plan.chunk_by_shape;
+    out->n_chunks = plan.chunk_by_shape ? (int32_t)cdiv(pmax, plan.chunk_by_shape) : 1;
+    out->scratch_need = plan.need;
+    out->scratch_room = plan.room;
+    return SRM_OK;
 }
 
 // ------------------------------------------------------------------ parallel form

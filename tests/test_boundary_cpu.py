@@ -94,6 +94,77 @@ def test_null_arguments_are_rejected(srm):
     assert L.srm_linear(0, 0, None, None, None, 1, 1, 1, None, None, None, None) == -1
 
 
+def _plan_case(srm, cfg, lens, ws_rows):
+    """The library's plan for a ragged prefill, checked against the passes and buffer extents recomputed
+    here: partial states of the chunked scan are [prompts of the pass][chunks][state width] fp32 and live in
+    the pass's MLP buffer of rows x ff activation elements."""
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ws = srm.workspace_bytes_config(cfg, ws_rows)
+    plan = srm.prefill_ragged_plan(cfg, off, ws)
+    max_rows = ws_rows
+    while srm.workspace_bytes_config(cfg, max_rows + 1) <= ws:
+        max_rows += 1
+    passes, n0 = [], 0
+    while n0 < len(lens):
+        n1 = n0
+        while n1 < len(lens) and off[n1 + 1] - off[n0] <= max_rows:
+            n1 += 1
+        passes.append((n0, n1))
+        n0 = n1
+    assert plan["passes"] == len(passes)
+    wsize = 2 if cfg.weight_dtype == "bf16" else 4
+    ff = cfg.d_model * cfg.mlp_expansion
+    for c in (plan["chunk_len"],):
+        if c:
+            nch = -(-max(lens) // c)
+            for n0, n1 in passes:
+                need = (n1 - n0) * nch * cfg.state_width * 4
+                room = int(off[n1] - off[n0]) * ff * wsize
+                assert need <= room, (lens[:4], ws_rows, n0, n1, need, room)
+    if plan["chunk_len_by_shape"] and not plan["chunk_len"]:
+        assert plan["scratch_need"] > plan["scratch_room"]
+    return plan
+
+
+def test_chunked_scan_scratch_stays_inside_the_workspace(srm):
+    """Many short prompts next to one long one: the chunk count follows the longest prompt, the buffer the rows
+    of the pass; the partial states of the chunked scan would overrun it, so the call must fall back."""
+    cfg = srm_synth.tiny_config(vocab=64, d_model=256, n_layers=1, n_heads=4, n_ctx=512, weight_dtype="bf16")
+    skew = [1] * 199 + [256]
+    plan = _plan_case(srm, cfg, skew, ws_rows=sum(skew))
+    assert plan["chunk_len_by_shape"] == 16 and plan["chunk_len"] == 0
+    assert plan["scratch_need"] == 200 * 16 * 256 * 4 and plan["scratch_room"] == 455 * 1024 * 2
+    plan = _plan_case(srm, cfg, skew, ws_rows=256)                   # the documented minimum: several passes
+    assert plan["chunk_len"] == 0 and plan["passes"] >= 2
+    # a few long prompts: the chunked scan is taken and fits
+    plan = _plan_case(srm, cfg, [512] * 8, ws_rows=8 * 512)
+    assert plan["chunk_len"] > 0 and plan["scratch_need"] <= plan["scratch_room"]
+    plan = _plan_case(srm, cfg, [200, 77, 1, 130, 16], ws_rows=424)
+    assert plan["chunk_len"] > 0
+    rng = np.random.default_rng(5)
+    for trial in range(60):
+        n = int(rng.integers(1, 300))
+        lens = rng.integers(1, 3, size=n) if trial % 2 else rng.integers(1, 400, size=n)
+        lens[int(rng.integers(0, n))] = int(rng.integers(64, 512))
+        lens = [int(v) for v in lens]
+        rows = int(rng.integers(max(lens), sum(lens) + 1))
+        for c in (cfg, srm_synth.tiny_config(vocab=64, d_model=64, n_layers=1, n_heads=2, n_ctx=512,
+                                             head_layout="column", mixer_kernel=8)):
+            _plan_case(srm, c, lens, rows)
+
+
+def test_plan_rejects_what_the_prefill_rejects(srm):
+    cfg = srm_synth.tiny_config(vocab=64, d_model=64, n_layers=1, n_heads=2, n_ctx=32)
+    ws = srm.workspace_bytes_config(cfg, 64)
+    assert ws > 0 and srm.workspace_bytes_config(cfg, 0) == 0
+    with pytest.raises(srm.SrmError):
+        srm.prefill_ragged_plan(cfg, [0, 40], ws)            # longer than n_ctx
+    with pytest.raises(srm.SrmError):
+        srm.prefill_ragged_plan(cfg, [0, 0], ws)             # empty prompt
+    with pytest.raises(srm.SrmError):
+        srm.prefill_ragged_plan(cfg, [0, 20], srm.workspace_bytes_config(cfg, 8))   # workspace below one prompt
+
+
 def test_binding_shape_checks(srm):
     cfg = srm_synth.tiny_config(vocab=32, d_model=16, n_layers=1, n_heads=2, n_ctx=16)
     w = srm_synth.make_weights(cfg)

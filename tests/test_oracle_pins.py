@@ -754,6 +754,83 @@ def test_head_layout_half_precision_cache_values_are_representable(oracle_mod):
     assert np.abs(S).max() > 0
 
 
+def _f16(v):
+    return np.asarray(v, np.float64).astype(np.float16).astype(np.float64)
+
+
+@pytest.mark.parametrize("layout,H", [("row", 1), ("row", 4), ("column", 2), ("combined", 1), ("combined", 4), ("mixed", 4)])
+def test_head_layout_half_precision_cache_against_float16_emulation(tiny, layout, H):
+    """orc_mixer_step_layout(half = 1) against a numpy float16 emulation of the whole cache trajectory: the
+    stored cache and the decay constants are binary16 values, the update is formed from them in full precision and
+    rounded once, and the output is formed from the value as stored ("SRM architecture optimization")."""
+    _, _, orc = tiny
+    T, d = 40, 16
+    dh = d // H
+    slots = 2 * H if layout == "combined" else H
+    alpha, beta, lam = _coeffs(slots, T, seed=70 + H)
+    U = np.random.default_rng(71).standard_normal((T, d)) * 3.0
+    lam16 = _f16(lam)
+    assert (lam16 != lam).any()                           # the rounding of lambda is visible
+    S = np.zeros(2 * d if layout == "combined" else d)
+    Sr, Sc = np.zeros(d), np.zeros(d)                     # emulated caches, binary16 values held in float64
+    for t in range(T):
+        m = orc.mixer_step_layout(S, U[t], alpha[:, t], beta[:, t], lam, H, layout, half=True)
+        want = np.zeros(d)
+        for h in range(H):
+            sl = slice(h * dh, (h + 1) * dh)
+            row = layout in ("row", "combined") or (layout == "mixed" and h < H // 2)
+            col = layout in ("column", "combined") or (layout == "mixed" and h >= H // 2)
+            cs = H + h if layout == "combined" else h
+            if row:
+                Sr[sl] = _f16(lam16[h] * Sr[sl] + alpha[h, t] * U[t, sl])
+                want[sl] += Sr[sl] + beta[h, t]
+            if col:
+                Sc[sl] = _f16(lam16[cs] * Sc[sl] + U[t, sl])
+                want[sl] += alpha[cs, t] * Sc[sl] + beta[cs, t]
+        if layout == "combined":
+            np.testing.assert_array_equal(S, np.concatenate([Sr, Sc]))
+        else:
+            np.testing.assert_array_equal(S, Sr + Sc)     # each channel lives in exactly one of the two
+        np.testing.assert_allclose(m, want, rtol=1e-13, atol=1e-13)
+    # the rounding matters: the same trajectory with a full-precision cache ends elsewhere
+    S32 = np.zeros_like(S)
+    for t in range(T):
+        orc.mixer_step_layout(S32, U[t], alpha[:, t], beta[:, t], lam, H, layout, half=False)
+    assert np.abs(S32 - S).max() > 1e-4
+
+
+@pytest.mark.parametrize("H,k", [(1, 4), (2, 3)])
+def test_kernel_mixer_half_precision_cache_against_float16_emulation(tiny, H, k):
+    """orc_mixer_step_kernel(half = 1): one binary16 cache per filter, binary16 decay constants, output from the
+    stored values (Eq. 11 with the half-precision cache of "SRM architecture optimization")."""
+    _, _, orc = tiny
+    T, d = 40, 12
+    dh = d // H
+    alpha, beta, lam = _coeffs(k * H, T, seed=80 + k)
+    beta = beta[:H]
+    U = np.random.default_rng(81).standard_normal((T, d)) * 3.0
+    lam16 = _f16(lam)
+    S = np.zeros(k * d)
+    Sk = np.zeros((k, d))
+    for t in range(T):
+        m = orc.mixer_step_kernel(S, U[t], alpha[:, t], beta[:, t], lam, H, k, half=True)
+        want = np.zeros(d)
+        for c in range(d):
+            h = c // dh
+            y = beta[h, t]
+            for i in range(k):
+                x = U[t, c + i] if c + i < d else 0.0
+                Sk[i, c] = _f16(lam16[i * H + h] * Sk[i, c] + x)
+                y += alpha[i * H + h, t] * Sk[i, c]
+            want[c] = y
+        np.testing.assert_array_equal(S, Sk.reshape(-1))
+        np.testing.assert_allclose(m, want, rtol=1e-13, atol=1e-13)
+    S32 = np.zeros_like(S)
+    for t in range(T):
+        orc.mixer_step_kernel(S32, U[t], alpha[:, t], beta[:, t], lam, H, k, half=False)
+    assert np.abs(S32 - S).max() > 1e-4
+
+
 # ---- mixer with k filters along the hidden dimension (Eq. 11) ----------------------------------
 def _brute_kernel_mixer(U, alpha, beta, lam, H, k):
     """Eq. 11 in the paper's orientation: X is (d + k) x n, zero-padded after the last hidden
