@@ -59,6 +59,8 @@ def parse_args():
     ap.add_argument("--kernel-iters", type=int, default=20, help="launches per kernel leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-legs", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of C1, C3 and C5 (k = 1024) that the default C4 run appends")
     return ap.parse_args()
 
 
@@ -102,6 +104,17 @@ def kernel_legs(torch, srm, model, cfg, B, iters):
         t = time_launches(torch, lambda: srm.linear(dt, epi, A, W, bias, out=out), iters)
         fl = 2.0 * B * N * K
         legs[name] = {"ms": t * 1e3, "tflops": fl / t * 1e-12, "M": B, "N": N, "K": K}
+        if bf:
+            # the clock the chip holds while these launches run back to back: work-group 0 of the last launch
+            # stores the shader cycle counter and the 100 MHz wall clock at its start and end
+            clk = torch.zeros(4, dtype=torch.int64, device="cuda")
+            srm.linear_clock_probe(clk)
+            for _ in range(4):
+                srm.linear(dt, epi, A, W, bias, out=out)
+            srm.linear_clock_probe(None)
+            c0, c1, w0, w1 = (int(v) for v in clk.cpu())
+            if w1 > w0:
+                legs[name]["shader_clock_ghz"] = (c1 - c0) / (w1 - w0) * 0.1
         del W, out
     W = rnd(V, d, scale=0.02)
     am = torch.empty(B, dtype=torch.int32, device="cuda")
@@ -252,6 +265,46 @@ def concurrency_sweep(torch, srm, srm_synth, steps, state_dtype="fp32"):
     torch.cuda.synchronize()
     model.close()
     print(json.dumps(out))
+
+
+def quick_workload(torch, srm, srm_synth, name, steps, fanout=1, model=None, weights=None):
+    """A few graph-replayed decode steps of another configuration (prefilled state), for the one-line summary."""
+    cfg = srm_synth.CONFIGS[name]
+    w = weights if weights is not None else srm_synth.make_weights(cfg)
+    own = model is None
+    if own:
+        model = srm.Model(cfg, w)
+    prompts = torch.from_numpy(srm_synth.make_prompts(cfg)).cuda()
+    N, P = prompts.shape
+    B = N * fanout
+    state = model.new_state(B)
+    ws = model.new_workspace(max(B, min(N * P, 1 << 17)))
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    model.prefill(prompts, fanout, state, tok, workspace=ws)
+    store = torch.empty((steps, B), dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(side):
+        model.generate(B, P, 3, tok, state, store, workspace=ws, temperature=0.0, seed=1)      # warm-up + capture
+        side.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        model.generate(B, P + 3, steps, tok, state, store, workspace=ws, temperature=0.0, seed=1)
+        e1.record()
+        side.synchronize()
+        wall = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    t = max(wall, e0.elapsed_time(e1) * 1e-3) / steps
+    tk = tok.cpu().numpy()
+    assert ((tk >= 0) & (tk < cfg.vocab)).all()
+    res = {"batch": B, "steps": steps, "ms_per_step": t * 1e3, "tokens_per_s": B / t,
+           "state_gib": model.state_bytes(B) / 2**30}
+    if own:
+        model.close()
+    del state, ws, tok, store, prompts
+    torch.cuda.empty_cache()
+    return res
 
 
 def measured_traffic(kernel_key):
@@ -411,16 +464,41 @@ def main():
                                "frac_of_achievable_random_operands": up["tflops"] / ach["mfma_bf16_tflops_random_operands"],
                                "avg_launch_ms": up["ms"], "flop_per_launch": 2.0 * B * ff * d,
                                "algorithmic_bytes_per_launch": (B * d + ff * d + B * ff) * 2.0}
+            if "shader_clock_ghz" in up:
+                # the published peak is the rate at the maximum clock (2.4 GHz); under the power of this kernel
+                # the chip holds a lower clock, which scales the matrix cores' rate with it
+                ghz = up["shader_clock_ghz"]
+                out["roofline"].update(shader_clock_ghz=ghz, peak_at_that_clock=PEAK_BF16_TFLOPS * ghz / 2.4,
+                                       frac_of_peak_at_that_clock=up["tflops"] / (PEAK_BF16_TFLOPS * ghz / 2.4))
         else:
             up = legs["gemm_up"]
             out["roofline"] = {"kernel": "gemm_f32_kernel (MLP up)", "bound": "alu", "achieved": up["tflops"],
                                "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": up["tflops"] / PEAK_FP32_TFLOPS,
                                "traffic": None, "avg_launch_ms": up["ms"]}
         su = legs["state_update"]
+        sd_w = getattr(cfg, "state_width", d)
         # the update as a kernel of its own: the HBM-bound form of the path's defining step.  The timed step
         # of a bf16 model runs it inside the in-projection's epilogue (leg gemm_in_with_state_update), which
         # saves writing and re-reading u; the stand-alone kernel is what srm_mixer_update launches.
-        out["roofline_state_update"] = {"kernel": "state_update_kernel", "bound": "hbm", "achieved": su["gbs"],
+        fu = legs.get("gemm_in_with_state_update")
+        if fu and esz == 2:
+            # the form the timed step runs: in-projection GEMM with the state update in its epilogue.  HBM side:
+            # algorithmic bytes (state read + written, A read, W read, m written) over the launch time against
+            # 8 TB/s; the launch also carries 2*B*d*d flop on the matrix cores, which run first (k loop), then
+            # the epilogue streams the state - the two phases do not overlap inside one launch.
+            tr = measured_traffic("gemm_bf16_kernel<256,256,2,4,EPI=MIX>") if cfg.name == "C4" and B == 16384 else None
+            out["roofline_state_update_fused"] = {
+                "kernel": "gemm_bf16_kernel<EPI=MIX> (in-projection + state update, the launch the step runs)",
+                "bound": "hbm", "achieved": fu["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": fu["gbs"] / PEAK_HBM_GBS, "traffic": tr, "frac_of_achievable": fu["gbs"] / ach["copy_gbs"],
+                "avg_launch_ms": fu["ms"], "bytes_per_launch": fu["bytes"],
+                "measured_traffic_gbs": None if tr is None else tr / (fu["ms"] * 1e-3) * 1e-9,
+                "mfma_tflops": fu["tflops"], "mfma_frac": fu["tflops"] / PEAK_BF16_TFLOPS,
+                "time_at_hbm_roofline_ms": fu["bytes"] / (PEAK_HBM_GBS * 1e9) * 1e3,
+                "time_at_mfma_roofline_ms": 2.0 * B * sd_w * d / (PEAK_BF16_TFLOPS * 1e12) * 1e3}
+        out["roofline_state_update"] = {"kernel": "state_update_kernel (srm_mixer_update: the update as a launch of its own; "
+                                                  "the timed bf16 step runs it inside the in-projection instead, see "
+                                                  "roofline_state_update_fused)", "bound": "hbm", "achieved": su["gbs"],
                                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": su["gbs"] / PEAK_HBM_GBS,
                                         "traffic": measured_traffic("state_update_kernel<bf16,2>") if cfg.name == "C4" else None,
                                         "frac_of_achievable": su["gbs"] / ach["copy_gbs"],
@@ -429,6 +507,18 @@ def main():
         rows = min(16, os.cpu_count() or 1)
         T = {"C4": 200, "C3": 256, "C1": 240}[cfg.name]      # about 10-20 s of host work
         out["cpu_baseline"] = cpu_baseline(cfg, w, rows, min(T, cfg.n_ctx - P))
+    if not args.no_other_workloads and cfg.name == "C4" and args.batch == 0 and args.temperature == 0 \
+            and cfg.use_projections and cfg.state_dtype == "fp32" and cfg.head_layout == "mixed":
+        # the other configurations, a few steps each (greedy, graph replay of the step; C5 on this model's weights)
+        del state, ws, tok, dprompts, store
+        torch.cuda.empty_cache()
+        ow = {}
+        ow["C1 (fp32, B 8)"] = quick_workload(torch, srm, srm_synth, "C1", 64)
+        ow["C3 (bf16, B 1024)"] = quick_workload(torch, srm, srm_synth, "C3", 64)
+        ow["C5 k=1024 (bf16, B 262144, C4's model)"] = quick_workload(torch, srm, srm_synth, "C5", 8, fanout=1024,
+                                                                      model=model, weights=w)
+        out["other_workloads"] = ow
+        state = ws = tok = dprompts = store = None
     # explicit, ordered teardown: drain the device, free the model (its cached step graph and weights), then
     # the tensors - nothing is left to interpreter finalisation, when a profiler's tool may already be gone
     torch.cuda.synchronize()

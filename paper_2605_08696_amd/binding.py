@@ -81,6 +81,8 @@ def lib():
         L.srm_generate.argtypes = [vp, i64, i32, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, sz, vp]
         L.srm_decode_step_sampled.restype = C.c_int
         L.srm_decode_step_sampled.argtypes = [vp, i64, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, vp, vp, sz, vp]
+        L.srm_linear_clock_probe.restype = None
+        L.srm_linear_clock_probe.argtypes = [vp]
         L.srm_workspace_bytes_config.restype = sz
         L.srm_workspace_bytes_config.argtypes = [vp, i64]
         L.srm_prefill_ragged_plan.restype = C.c_int
@@ -434,6 +436,12 @@ def probe_mfma(out, blocks: int, iters: int, random_operands: bool = False, stre
     _check(lib().srm_probe_mfma(_dev(out, _torch().float32, blocks * 256, "out"), int(blocks), int(iters),
                                 1 if random_operands else 0, C.byref(flop), _stream(stream)))
     return flop.value
+
+
+def linear_clock_probe(buf) -> None:
+    """srm_linear_clock_probe: buf = int64 CUDA tensor of 4 elements, or None to clear."""
+    torch = _torch()
+    lib().srm_linear_clock_probe(None if buf is None else _dev(buf, torch.int64, 4, "clock probe"))
 
 
 def linear_scratch_bytes(M: int, N: int) -> int:

@@ -52,6 +52,9 @@ struct GemmEpi {
     int32_t ln_nsplit;
     int64_t ln_stride;
     float ln_eps;
+    // Measuring hook (srm_linear_clock_probe): if not null, work-group 0 of gemm_bf16_kernel writes the shader
+    // cycle counter and the 100 MHz wall clock at its start and at its end: clk[0..3] = cycles0, cycles1, wall0, wall1.
+    unsigned long long *clk;
 };
 
 // The position all rows share: ep.pos, or *ep.pos_dev if that is set.  (Written as a conditional load with a
@@ -506,6 +509,9 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     static_assert(NW * 32 * STG * 4 + BM * WN * 8 <= NS * (BM + BN) * BK * 2, "epilogue stage exceeds the tile LDS");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
+    const bool probe = ep.clk != nullptr && blockIdx.x == 0 && blockIdx.y == 0;
+    unsigned long long clk_c0 = 0, clk_t0 = 0;
+    if (probe) { clk_c0 = clock64(); clk_t0 = wall_clock64(); }
     bf16 *As = reinterpret_cast<bf16 *>(smem_raw);   // [NS][BM*BK]; LNA: [K / BK][PANEL_ROWS*BK]
     bf16 *Bs = As + (LNA ? (K / BK) * PANEL_ROWS * BK : NS * BM * BK);   // [NS][BN*BK]
     constexpr int A_TILE = LNA ? PANEL_ROWS * BK : BM * BK;            // elements between k tiles of A in LDS
@@ -755,6 +761,9 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
 #undef SRM_READ_FRAGS
 
     gemm_epilogue<BM, BN, WM, WN, EPI, TAct>(acc, smem_raw, ep, M, N, m0, n0, bn);
+    if (probe && tid == 0) {
+        ep.clk[0] = clk_c0; ep.clk[1] = clock64(); ep.clk[2] = clk_t0; ep.clk[3] = wall_clock64();
+    }
 }
 
 // ------------------------------------------------------------------ fp32 FMA

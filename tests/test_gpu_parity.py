@@ -108,81 +108,124 @@ def test_c2_parallel_equals_recurrent(srm, orc_mod):
 
 
 # ------------------------------------------------------------------ C3 / C4 (bf16 weights)
-def _bf16_config_parity(srm, orc_mod, cfg, n_rows, n_gen, tol=2e-2):
-    """Full batch on the GPU; rows 0..n_rows-1 are also run by the oracle and the
-    GPU is teacher-forced on the oracle's tokens for those rows."""
+def _check_step(got_logits, got_tok, ref_logits, ref_tok, tol, tag):
+    """One position of the oracle's rows: logits within tol * max|logit| per row; the GPU's token is the
+    argmax (lowest index) of the GPU's own logits; where it differs from the oracle's token, the oracle's own
+    margin between the two is within twice the row's logit error (a flip that the error explains, nothing
+    else).  Returns (max relative error, number of differing tokens)."""
+    ref = np.asarray(ref_logits, np.float64)
+    got = np.asarray(got_logits, np.float64)
+    scale = np.abs(ref).max(axis=1)
+    err = np.abs(got - ref).max(axis=1)
+    assert (err <= tol * scale).all(), f"{tag}: logit error {float((err / scale).max()):.3e}"
+    np.testing.assert_array_equal(got_tok, got.argmax(axis=1), err_msg=f"{tag}: token is not the argmax of the logits")
+    diff = np.nonzero(got_tok != ref_tok)[0]
+    for r in diff:
+        gap = ref[r, ref_tok[r]] - ref[r, got_tok[r]]
+        assert 0 <= gap <= 2 * err[r], f"{tag}: row {r} token {got_tok[r]} vs {ref_tok[r]}, oracle gap {gap:.3e}, error {err[r]:.3e}"
+    return float((err / scale).max()), len(diff)
+
+
+def _bf16_config_parity(srm, orc_mod, cfg, rows, n_gen, tol=2e-2):
+    """Full batch on the GPU in the launch configuration the benchmark times; the batch rows `rows` (spread
+    over the row tiles of the GEMMs, first and last row included) are also run by the oracle, and the GPU is
+    teacher-forced on the oracle's tokens for those rows."""
     w = srm_synth.make_weights(cfg)
     prompts = srm_synth.make_prompts(cfg)
     B, P, V = cfg.batch, cfg.prompt_len, cfg.vocab
-    ref = orc_mod.Oracle(cfg, w, "f64").greedy(prompts[:n_rows], n_gen, want_logits=True)
-    print(f"{cfg.name}: oracle done ({n_rows} rows x {P}+{n_gen})", flush=True)
+    rows = np.asarray(rows)
+    assert rows.min() == 0 and rows.max() == B - 1
+    ref = orc_mod.Oracle(cfg, w, "f64").greedy(prompts[rows], n_gen, want_logits=True)
+    print(f"{cfg.name}: oracle done ({len(rows)} rows x {P}+{n_gen})", flush=True)
     model = srm.Model(cfg, w)
     gen = Generator(model, B, min(B * P, 1 << 17))
     logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
-    plog = torch.empty((B, V), dtype=torch.float32, device="cuda")
-    gen.prefill(to_dev(prompts), logits=plog)
+    gen.prefill(to_dev(prompts), logits=logits)
     ref_tok = to_dev(ref["tokens"])
-    errs, agree, total = [], 0, 0
-    first = plog[:n_rows].cpu().numpy()
-    errs.append(rel_err_rows(first, ref["logits"][:, 0]))
-    agree += int((gen.tok[:n_rows].cpu().numpy() == ref["tokens"][:, 0]).sum()); total += n_rows
-    for g in range(1, n_gen):
-        gen.tok[:n_rows] = ref_tok[:, g - 1]                 # teacher forcing on the oracle's rows
-        gen.step(P + g - 1, logits=logits)
-        got = logits[:n_rows].cpu().numpy()
-        errs.append(rel_err_rows(got, ref["logits"][:, g]))
-        agree += int((gen.tok[:n_rows].cpu().numpy() == ref["tokens"][:, g]).sum()); total += n_rows
+    drows = to_dev(rows.astype(np.int64))
+    worst, flips = 0.0, 0
+    for g in range(n_gen):
+        if g > 0:
+            gen.tok[drows] = ref_tok[:, g - 1]                # teacher forcing on the oracle's rows
+            gen.step(P + g - 1, logits=logits)
+        e, f = _check_step(logits[drows].cpu().numpy(), gen.tok[drows].cpu().numpy(), ref["logits"][:, g],
+                           ref["tokens"][:, g], tol, f"{cfg.name} position {P + g - 1}")
+        worst, flips = max(worst, e), flips + f
     torch.cuda.synchronize()
-    print(f"{cfg.name}: max relative logit error {max(errs):.3e}; greedy agreement {agree}/{total}", flush=True)
-    assert max(errs) <= tol
-    assert agree >= 0.9 * total
+    print(f"{cfg.name}: max relative logit error {worst:.3e}; {flips} of {len(rows) * n_gen} tokens differ from "
+          f"the oracle's, each inside the logit error", flush=True)
+    assert flips <= 0.05 * len(rows) * n_gen
     # every row of the full batch produced a valid token and a finite state
     tk = gen.tok.cpu().numpy()
     assert ((tk >= 0) & (tk < V)).all()
     assert torch.isfinite(gen.state).all()
-    return gen, model, prompts
+    model.close()
 
 
 def test_c3_mid_bf16(srm, orc_mod):
+    # 8 rows x all 64 + 256 positions of the configuration; rows on both sides of 64-row tile borders
     cfg = srm_synth.CONFIGS["C3"]
-    _bf16_config_parity(srm, orc_mod, cfg, n_rows=8, n_gen=48)
+    _bf16_config_parity(srm, orc_mod, cfg, rows=[0, 63, 64, 511, 512, 960, 1022, 1023], n_gen=256)
 
 
 def test_c4_large_bf16(srm, orc_mod):
+    # 16 rows x (128 + 64) positions; rows on both sides of 256-row tile borders, in the middle of the
+    # XCD-remapped tile order, and the last row
     cfg = srm_synth.CONFIGS["C4"]
-    _bf16_config_parity(srm, orc_mod, cfg, n_rows=16, n_gen=12)
+    _bf16_config_parity(srm, orc_mod, cfg, rows=[0, 255, 256, 4095, 4096, 8191, 8192, 8193, 12287, 12288, 16127, 16128,
+                                                 16129, 16382, 16383, 777], n_gen=64)
 
 
 # ------------------------------------------------------------------ C5 (fan-out)
 def test_c5_fanout_replicas_and_max_batch(srm, orc_mod):
+    """256 prompts prefilled once, fanned out to k in {64, 256, 1024} samples (B up to 262144, 16 GiB of
+    state).  Four prompts (first, last, two between) are also run by the oracle: prefill logits, and the
+    logits of teacher-forced decode steps on the first and last replica of each, in the full-batch launch;
+    all k replicas of every prompt agree (greedy decoding of independent samples)."""
     cfg = srm_synth.CONFIGS["C5"]
     w = srm_synth.make_weights(cfg)
     prompts = srm_synth.make_prompts(cfg)                    # [256][128]
     N, P, V, d, L = cfg.batch, cfg.prompt_len, cfg.vocab, cfg.d_model, cfg.n_layers
-    n_or, n_gen = 4, 3
-    ref = orc_mod.Oracle(cfg, w, "f64").greedy(prompts[:n_or], n_gen, want_logits=True)
+    pr = np.array([0, 77, 200, N - 1])
+    n_gen = 5
+    ref = orc_mod.Oracle(cfg, w, "f64").greedy(prompts[pr], n_gen, want_logits=True)
     print("C5: oracle done", flush=True)
     model = srm.Model(cfg, w)
     dprompts = to_dev(prompts)
-    for k in (64, 1024):
+    ref_tok = to_dev(ref["tokens"])
+    for k in cfg.fanout:
         B = N * k
         print(f"C5: fanout {k}, batch {B}", flush=True)
         gen = Generator(model, B, N * P)
         plog = torch.empty((N, V), dtype=torch.float32, device="cuda")
+        logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
         gen.prefill(dprompts, fanout=k, logits=plog)
-        assert rel_err_rows(plog[:n_or].cpu().numpy(), ref["logits"][:, 0]) <= 2e-2
+        rows = np.concatenate([[p * k, p * k + k - 1] for p in pr])       # first and last replica
+        assert rows.max() == B - 1
+        drows = to_dev(rows.astype(np.int64))
+        rep = lambda a: np.repeat(a, 2, axis=0)
+        e, f = _check_step(plog[to_dev(pr.astype(np.int64))].cpu().numpy(), gen.tok.view(N, k)[:, 0][to_dev(pr.astype(np.int64))].cpu().numpy(),
+                           ref["logits"][:, 0], ref["tokens"][:, 0], 2e-2, f"C5 k={k} prefill")
+        worst, flips = e, f
         toks = [gen.tok.view(N, k).cpu().numpy().copy()]
         for g in range(1, n_gen):
-            gen.step(P + g - 1)
+            # every replica of the oracle's prompts continues on the oracle's token (so replicas stay equal)
+            gen.tok.view(N, k)[to_dev(pr.astype(np.int64))] = ref_tok[:, g - 1].unsqueeze(1)
+            gen.step(P + g - 1, logits=logits)
+            e, f = _check_step(logits[drows].cpu().numpy(), gen.tok[drows].cpu().numpy(), rep(ref["logits"][:, g]),
+                               rep(ref["tokens"][:, g]), 2e-2, f"C5 k={k} position {P + g - 1}")
+            worst, flips = max(worst, e), flips + f
             toks.append(gen.tok.view(N, k).cpu().numpy().copy())
         torch.cuda.synchronize()
+        print(f"C5 k={k}: max relative logit error {worst:.3e}; {flips} tokens differ inside the logit error", flush=True)
         for t in toks:                                        # replicas of one prompt agree (greedy)
             assert (t == t[:, :1]).all()
         st = gen.state.view(L, N, k, d)
         assert bool((st == st[:, :, :1]).all())
         assert model.state_bytes(B) == L * B * d * 4          # 64 KiB per sequence
-        del gen, st
+        del gen, st, logits, plog
         torch.cuda.empty_cache()
+    model.close()
 
 
 # ------------------------------------------------------------------ semantics and edges

@@ -390,6 +390,36 @@ def test_chunked_scan_ragged_prompts(c1):
         assert int(tk[b]) == int(ref["tokens"][0, 0])
 
 
+def test_skewed_lengths_fall_back_to_the_sequential_scan(c1, srm):
+    """Many one-token prompts next to a long one: the chunk count of the chunked scan follows the long prompt,
+    its scratch the few rows of the pass, so the call must take the sequential scan (and stay inside the
+    workspace).  Checked against the oracle on the long prompt and some short ones."""
+    cfg, w, model, orc = c1
+    lens = [1] * 120 + [200]
+    rng = np.random.default_rng(11)
+    prompts = rng.integers(0, cfg.vocab, (len(lens), 200)).astype(np.int32)
+    toks, off = _pack(prompts, lens)
+    N = len(lens)
+    ws = model.new_workspace(int(off[-1]))
+    plan = srm.prefill_ragged_plan(cfg, off, ws.numel())
+    assert plan["chunk_len_by_shape"] > 0 and plan["chunk_len"] == 0 and plan["scratch_need"] > plan["scratch_room"]
+    st, tk = model.new_state(N), torch.empty(N, dtype=torch.int32, device="cuda")
+    st.fill_(float("nan"))
+    lg = torch.empty((N, cfg.vocab), dtype=torch.float32, device="cuda")
+    guard = torch.full((1 << 20,), 7, dtype=torch.uint8, device="cuda")     # allocated right after the workspace
+    print(f"skewed ragged prefill, {N} prompts, plan {plan}", flush=True)
+    keep = model.prefill_ragged(to_dev(toks), off, st, tk, logits=lg, workspace=ws)
+    torch.cuda.synchronize()
+    del keep
+    assert bool((guard == 7).all())
+    sv = st.view(cfg.n_layers, N, cfg.d_model)
+    for b in (0, 1, 59, 119, 120):
+        ref = orc.greedy(prompts[b:b + 1, :lens[b]], 1, want_logits=True)
+        assert rel_err_rows(lg[b:b + 1].cpu().numpy(), ref["logits"][:, 0]) <= 1e-4
+        assert np.abs(sv[:, b].cpu().numpy() - ref["state"][0]).max() <= 1e-4 * np.abs(ref["state"][0]).max()
+        assert int(tk[b]) == int(ref["tokens"][0, 0])
+
+
 def test_chunked_scan_bf16(srm, orc_mod):
     cfg = srm_synth.tiny_config(vocab=300, d_model=128, n_layers=3, n_heads=4, n_ctx=160, weight_dtype="bf16", seed=13)
     w = srm_synth.make_weights(cfg, stress=True)

@@ -467,9 +467,9 @@ def test_kernel_mixer_errors(srm):
 @pytest.mark.parametrize("variant", [dict(head_layout="combined"), dict(head_layout="column", mixer_kernel=2),
                                      dict(head_layout="row")])
 def test_variants_at_the_large_configuration_shape(srm, orc_mod, variant):
-    """C4's shape and batch (the launch configuration bench.py times: 256x256 tiles, separate state update,
-    mixer rows of 2d for the combined / two-filter models): teacher-forced steps from a zero state, the oracle
-    on two rows."""
+    """C4's shape and batch (the launch configuration bench.py times: 256x256 tiles, the state update in the
+    in-projection's epilogue, mixer rows of 2d for the combined / two-filter models): teacher-forced steps
+    from a zero state, the oracle on the first and the last row."""
     cfg = dataclasses.replace(srm_synth.CONFIGS["C4"], n_ctx_fixed=64, **variant)
     w = srm_synth.make_weights(cfg)
     B, T = cfg.batch, 4
