@@ -448,6 +448,29 @@ int srm_linear(int32_t dtype, int32_t epilogue, const void *d_A, const void *d_W
 size_t srm_linear_scratch_bytes(int64_t M, int32_t N);
 
 /*
+ * srm_linear's epilogue 3 without logits and without a workspace, for callers
+ * that cannot allocate device memory or pass a scratch buffer along: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * d_argmax[M] = row-wise argmax of A W^T + bias (lowest index on ties), same
+ * kernels and same values as srm_linear(dtype, 3, ..., d_out = NULL, ...).  The
+ * per-column-tile partial results live in a device array built into the
+ * library (srm_linear_argmax_noalloc_max_bytes() = 8 MiB per GPU, held until
+ * the process ends); the call allocates and frees nothing.  A shape whose
+ * partials need more (srm_linear_scratch_bytes(M, N) > the maximum, e.g. more
+ * than 2097 rows at N = 32000) is rejected with SRM_EINVAL.  All calls on one
+ * GPU share that array: calls that overlap in time on one GPU (two streams, two
+ * threads) race; calls on one stream do not.  Nothing in the array needs
+ * clearing between calls (every partial a call reads, it has written).  The
+ * first call on a device looks up the array's address and must not be made
+ * under stream capture; later calls may be.
+ * Errors: SRM_EINVAL (null pointer, sizes <= 0, K % 64 with SRM_BF16, unknown
+ * dtype, shape beyond the built-in scratch), SRM_EHIP.
+ */
+int srm_linear_argmax_noalloc(int32_t dtype, const void *d_A, const void *d_W, const float *d_bias,
+                              int64_t M, int32_t N, int32_t K, int32_t *d_argmax, void *hip_stream);
+size_t srm_linear_argmax_noalloc_max_bytes(void);
+
+/*
  * Work-groups of the one-kernel path that srm_generate / srm_generate_topp take
  * for a batch of B samples, or 0 if such a call runs the ordinary step kernels.
  * The one-kernel path ("MAX model details": per-call overhead dominates small

@@ -81,6 +81,10 @@ def lib():
         L.srm_generate.argtypes = [vp, i64, i32, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, sz, vp]
         L.srm_decode_step_sampled.restype = C.c_int
         L.srm_decode_step_sampled.argtypes = [vp, i64, i32, vp, vp, vp, C.c_float, C.c_uint32, vp, vp, vp, sz, vp]
+        L.srm_linear_argmax_noalloc.restype = C.c_int
+        L.srm_linear_argmax_noalloc.argtypes = [i32, vp, vp, vp, i64, i32, i32, vp, vp]
+        L.srm_linear_argmax_noalloc_max_bytes.restype = sz
+        L.srm_linear_argmax_noalloc_max_bytes.argtypes = []
         L.srm_linear_clock_probe.restype = None
         L.srm_linear_clock_probe.argtypes = [vp]
         L.srm_workspace_bytes_config.restype = sz
@@ -442,6 +446,23 @@ def linear_clock_probe(buf) -> None:
     """srm_linear_clock_probe: buf = int64 CUDA tensor of 4 elements, or None to clear."""
     torch = _torch()
     lib().srm_linear_clock_probe(None if buf is None else _dev(buf, torch.int64, 4, "clock probe"))
+
+
+def linear_argmax_noalloc(dtype, A, W, bias, argmax, stream=None):
+    """srm_linear_argmax_noalloc on torch tensors A [M][K], W [N][K] -> argmax [M] int32."""
+    torch = _torch()
+    M, K = A.shape
+    N, K2 = W.shape
+    if K != K2:
+        raise ValueError("A and W disagree on K")
+    t = torch.bfloat16 if dtype == SRM_BF16 else torch.float32
+    _check(lib().srm_linear_argmax_noalloc(dtype, _dev(A, t, M * K, "A"), _dev(W, t, N * K, "W"),
+                                           None if bias is None else _dev(bias, torch.float32, N, "bias"),
+                                           M, N, K, _dev(argmax, torch.int32, M, "argmax"), _stream(stream)))
+
+
+def linear_argmax_noalloc_max_bytes() -> int:
+    return lib().srm_linear_argmax_noalloc_max_bytes()
 
 
 def linear_scratch_bytes(M: int, N: int) -> int:

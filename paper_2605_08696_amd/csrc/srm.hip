@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -1730,6 +1731,54 @@ static int linear_entry(int epilogue, const void *A, const void *W, const float 
     case 4: return linear<EPI_F32, T>(A, W, bias, M, N, K, out, st);
     default: return fail(SRM_EINVAL, "srm_linear: unknown epilogue %d", epilogue);
     }
+}
+
+// ------------------------------------------------------------------ entry point that allocates nothing
+// Scratch of srm_linear_argmax_noalloc: the per-column-tile (max, index) partials of the LM-head form,
+// [M][ceil(N / 64)] fp32 then the same of int32, in a file-scope device array instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy until the process ends.  In host code the
+// array's name is only a handle: its device address is looked up once per device and used from then on.
+constexpr size_t kNoallocScratch = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoallocScratch];
+constexpr int kNoallocMaxDevices = 64;
+static void *g_noalloc_ptr[kNoallocMaxDevices];
+static std::mutex g_noalloc_mutex;
+
+static int noalloc_scratch(void **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kNoallocMaxDevices) return fail(SRM_EINVAL, "srm_linear_argmax_noalloc: device %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    if (!g_noalloc_ptr[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(SRM_EHIP, "srm_linear_argmax_noalloc: no address for the scratch array on device %d", dev);
+        g_noalloc_ptr[dev] = ptr;
+    }
+    *out = g_noalloc_ptr[dev];
+    return SRM_OK;
+}
+
+extern "C" size_t srm_linear_argmax_noalloc_max_bytes(void) { return kNoallocScratch; }
+
+extern "C" int srm_linear_argmax_noalloc(int32_t dtype, const void *d_A, const void *d_W, const float *d_bias,
+                                         int64_t M, int32_t N, int32_t K, int32_t *d_argmax, void *hip_stream)
+{
+    const char *who = "srm_linear_argmax_noalloc";
+    if (!d_A || !d_W || !d_argmax) return fail(SRM_EINVAL, "%s: null argument", who);
+    if (M <= 0 || N <= 0 || K <= 0) return fail(SRM_EINVAL, "%s: sizes must be positive", who);
+    const size_t need = srm_linear_scratch_bytes(M, N);
+    if (need > kNoallocScratch)
+        return fail(SRM_EINVAL, "%s: M = %lld rows x N = %d columns need %zu bytes of partial results, the built-in "
+                                "scratch holds %zu (use srm_linear with a workspace)", who, (long long)M, N, need,
+                    kNoallocScratch);
+    void *ptr = nullptr;
+    SRM_TRY(noalloc_scratch(&ptr));
+    hipStream_t st = as_stream(hip_stream);
+    if (dtype == SRM_BF16) return linear_entry<bf16>(3, d_A, d_W, d_bias, M, N, K, nullptr, d_argmax, ptr, st);
+    if (dtype == SRM_FP32) return linear_entry<float>(3, d_A, d_W, d_bias, M, N, K, nullptr, d_argmax, ptr, st);
+    return fail(SRM_EINVAL, "%s: unknown dtype %d", who, dtype);
 }
 
 extern "C" int srm_linear(int32_t dtype, int32_t epilogue, const void *d_A, const void *d_W, const float *d_bias,
