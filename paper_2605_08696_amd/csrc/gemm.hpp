@@ -22,8 +22,8 @@ struct GemmEpi {
     void *out;           // EPI_STORE/GELU: TAct [M][ldo]; EPI_RESID: float [M][ldo] (+=);
                          // EPI_F32: float [M][ldo]; EPI_ARGMAX: float [M][ldo] or nullptr
     int64_t ldo;
-    float *part_val;     // EPI_ARGMAX: [M][nparts]
-    int32_t *part_idx;   // EPI_ARGMAX: [M][nparts]
+    float *part_val;     // EPI_ARGMAX: [nparts][M] (part-major: the rows of a tile write consecutive words)
+    int32_t *part_idx;   // EPI_ARGMAX: [nparts][M]
     int32_t nparts;      // number of column tiles
     // EPI_ARGMAX with temp > 0: the decision is argmax_v(logit_v + temp * gumbel(seed, pos, row, v)),
     // i.e. a sample from softmax(logits / temp); stored logits stay the raw ones.
@@ -473,8 +473,8 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN /
                 const int oi = red_idx[lrow * WN + w];
                 if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
             }
-            ep.part_val[(int64_t)row * ep.nparts + bn] = bv;
-            ep.part_idx[(int64_t)row * ep.nparts + bn] = bi;
+            ep.part_val[(int64_t)bn * M + row] = bv;
+            ep.part_idx[(int64_t)bn * M + row] = bi;
         }
     }
 }
@@ -856,8 +856,8 @@ gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W, int M,
                 if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
             }
             if (tx == 0 && row < M) {
-                ep.part_val[(int64_t)row * ep.nparts + bn] = bv;
-                ep.part_idx[(int64_t)row * ep.nparts + bn] = bi;
+                ep.part_val[(int64_t)bn * M + row] = bv;
+                ep.part_idx[(int64_t)bn * M + row] = bi;
             }
         }
     }
@@ -1012,8 +1012,8 @@ gemv_rows_kernel(const TAct *__restrict__ A, const TW *__restrict__ W, int M, in
                 int i = red_i[0][tid];
                 for (int g = 1; g < 16; ++g)
                     if (arg_better(red_v[g][tid], red_i[g][tid], v, i)) { v = red_v[g][tid]; i = red_i[g][tid]; }
-                ep.part_val[(int64_t)(mg + tid) * ep.nparts + blockIdx.x] = v;
-                ep.part_idx[(int64_t)(mg + tid) * ep.nparts + blockIdx.x] = i;
+                ep.part_val[(int64_t)blockIdx.x * M + mg + tid] = v;
+                ep.part_idx[(int64_t)blockIdx.x * M + mg + tid] = i;
             }
         }
     }
@@ -1032,8 +1032,10 @@ struct FinalizeRagged {
     int32_t eos_plus1;        // decode with advance: eos token + 1 (0: none); a row that emits it goes idle (position -1)
 };
 
-// Reduce the per-tile partials of each row to one token; writes `rep`
-// consecutive copies starting at out[(row0 + row) * rep].  One wave per row.
+// Reduce the per-tile partials [nparts][rows] of each row to one token; writes `rep`
+// consecutive copies starting at out[(row0 + row) * rep].  One work-group per 64
+// rows: thread (r = tid & 63, q = tid >> 6) scans parts q, q + 4, ... of row r
+// (consecutive lanes read consecutive rows), the four scans of a row meet in LDS.
 // A row without any ordered value (all NaN) yields token 0, so that the id is
 // always a valid embedding row.  If store is not null the token also goes to
 // store[step * store_stride + (row0 + row) * rep + r] with step = *step_dev.
@@ -1043,44 +1045,53 @@ argmax_finalize_kernel(const float *__restrict__ part_val, const int32_t *__rest
                        int vocab, int32_t *__restrict__ store, const int *__restrict__ step_dev,
                        int64_t store_stride, FinalizeRagged rg)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    __shared__ float sv[4][64];
+    __shared__ int si[4][64];
+    const int r = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t blk0 = (int64_t)blockIdx.x * 64;
+    const int64_t row = blk0 + r;
     if (rg.zero_counter && blockIdx.x == 0 && threadIdx.x == 0) *rg.zero_counter = 0;
-    if (row >= rows) return;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
-    for (int p = lane; p < nparts; p += kWave) {
-        const float v = part_val[row * nparts + p];
-        const int i = part_idx[row * nparts + p];
-        if (arg_better(v, i, bv, bi)) { bv = v; bi = i; }
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const float ov = __shfl_xor(bv, off, kWave);
-        const int oi = __shfl_xor(bi, off, kWave);
-        if (arg_better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-    }
-    if (bi < 0 || bi >= vocab) bi = 0;
-    if (rg.pos_rows) {
-        const int p = rg.pos_rows[row0 + row];
-        const bool active = p >= 0 && p < rg.n_ctx;
-        if (!active) bi = -1;
-        else if (rg.advance && lane == 0) rg.pos_rows[row0 + row] = (rg.eos_plus1 && bi == rg.eos_plus1 - 1) ? -1 : p + 1;
-    }
-    if (rg.slot) {
-        const int64_t dst = rg.slot[row0 + row];
-        if (lane == 0 && dst >= 0 && dst < rg.nslots) {
-            out[dst] = bi;
-            if (rg.pos_set) rg.pos_set[dst] = rg.offsets[row0 + row + 1] - rg.offsets[row0 + row];
+    if (row < rows)
+        for (int p = q; p < nparts; p += 4) {
+            const float v = part_val[(int64_t)p * rows + row];
+            const int i = part_idx[(int64_t)p * rows + row];
+            if (arg_better(v, i, bv, bi)) { bv = v; bi = i; }
         }
-        return;
+    sv[q][r] = bv;
+    si[q][r] = bi;
+    __syncthreads();
+    if (q == 0 && row < rows) {
+#pragma unroll
+        for (int k = 1; k < 4; ++k)
+            if (arg_better(sv[k][r], si[k][r], bv, bi)) { bv = sv[k][r]; bi = si[k][r]; }
+        if (bi < 0 || bi >= vocab) bi = 0;
+        if (rg.pos_rows) {
+            const int p = rg.pos_rows[row0 + row];
+            const bool active = p >= 0 && p < rg.n_ctx;
+            if (!active) bi = -1;
+            else if (rg.advance) rg.pos_rows[row0 + row] = (rg.eos_plus1 && bi == rg.eos_plus1 - 1) ? -1 : p + 1;
+        }
+        if (rg.slot) {
+            const int64_t dst = rg.slot[row0 + row];
+            if (dst >= 0 && dst < rg.nslots) {
+                out[dst] = bi;
+                if (rg.pos_set) rg.pos_set[dst] = rg.offsets[row0 + row + 1] - rg.offsets[row0 + row];
+            }
+        }
+        si[0][r] = bi;
     }
-    for (int r = lane; r < rep; r += kWave) {
-        out[(row0 + row) * rep + r] = bi;
-        if (rg.pos_set) rg.pos_set[(row0 + row) * rep + r] = rg.offsets[row0 + row + 1] - rg.offsets[row0 + row];
-    }
-    if (store) {
-        int32_t *dst = store + (int64_t)(*step_dev) * store_stride;
-        for (int r = lane; r < rep; r += kWave) dst[(row0 + row) * rep + r] = bi;
+    if (rg.slot) return;
+    __syncthreads();
+    // the rep copies of the 64 tokens, consecutive threads writing consecutive words
+    const int64_t nrow = min((int64_t)64, rows - blk0);
+    int32_t *dst2 = store ? store + (int64_t)(*step_dev) * store_stride : nullptr;
+    for (int64_t e = threadIdx.x; e < nrow * rep; e += 256) {
+        const int rl = (int)(e / rep);
+        const int64_t o = (row0 + blk0) * rep + e;
+        out[o] = si[0][rl];
+        if (rg.pos_set) rg.pos_set[o] = rg.offsets[row0 + blk0 + rl + 1] - rg.offsets[row0 + blk0 + rl];
+        if (dst2) dst2[o] = si[0][rl];
     }
 }
