@@ -105,22 +105,16 @@ def kernel_legs(torch, srm, model, cfg, B, iters):
         fl = 2.0 * B * N * K
         legs[name] = {"ms": t * 1e3, "tflops": fl / t * 1e-12, "M": B, "N": N, "K": K}
         if bf:
-            # the clock the chip holds while these launches run back to back: work-group 0 of the last launch
-            # stores the shader cycle counter and the 100 MHz wall clock at its start and end
-            clk = torch.zeros(4, dtype=torch.int64, device="cuda")
-            srm.linear_clock_probe(clk)
-            for _ in range(4):
-                srm.linear(dt, epi, A, W, bias, out=out)
-            srm.linear_clock_probe(None)
-            c0, c1, w0, w1 = (int(v) for v in clk.cpu())
-            if w1 > w0:
-                legs[name]["shader_clock_ghz"] = (c1 - c0) / (w1 - w0) * 0.1
+            legs[name].update(gemm_timeline(torch, srm, lambda: srm.linear(dt, epi, A, W, bias, out=out), B, N, K))
         del W, out
     W = rnd(V, d, scale=0.02)
     am = torch.empty(B, dtype=torch.int32, device="cuda")
     scratch = torch.empty(srm.linear_scratch_bytes(B, V), dtype=torch.uint8, device="cuda")
     t = time_launches(torch, lambda: srm.linear(dt, 3, a, W, None, out=None, argmax=am, scratch=scratch), iters)
     legs["gemm_head_argmax"] = {"ms": t * 1e3, "tflops": 2.0 * B * V * d / t * 1e-12, "M": B, "N": V, "K": d}
+    if bf:
+        legs["gemm_head_argmax"].update(gemm_timeline(
+            torch, srm, lambda: srm.linear(dt, 3, a, W, None, out=None, argmax=am, scratch=scratch), B, V, d))
     del W, scratch
     # state update: cycle over the L layer slabs exactly as a step does
     half = getattr(cfg, "state_dtype", "fp32") == "fp16"
@@ -150,6 +144,46 @@ def kernel_legs(torch, srm, model, cfg, B, iters):
                                              "two_launch_ms": legs["gemm_in"]["ms"] + legs["state_update"]["ms"]
                                              if sd == d else None}
     return legs
+
+
+def gemm_timeline(torch, srm, launch, M, N, K):
+    """Where the time of a bf16 GEMM launch goes, from the kernel's own clocks (srm_linear_timeline_probe): every
+    work-group stores the 100 MHz wall clock at its start, k-loop start, k-loop end and after its last store,
+    and the shader cycle counter around the k loop.  Launches run back to back, the last one is read."""
+    import numpy as np
+    cap = 1 << 16
+    buf = torch.zeros(8 * cap, dtype=torch.int64, device="cuda")
+    srm.linear_timeline_probe(buf, cap)
+    for _ in range(4):
+        launch()
+    srm.linear_timeline_probe(None)
+    torch.cuda.synchronize()
+    tr = buf.cpu().numpy().reshape(cap, 8)
+    tr = tr[tr[:, 3] > 0]
+    if len(tr) == 0:
+        return {}
+    t0, t1, t2, t3, c1, c2, hw = (tr[:, i].astype(np.int64) for i in range(7))
+    us = 0.01                                       # one tick of the 100 MHz clock
+    ghz = float(((c2 - c1) / np.maximum(t2 - t1, 1)).mean() * 0.1)
+    cu = ((hw >> 32) << 16) | (hw & 0xFF00)         # XCC, shader engine / array, CU
+    gaps, per_cu = [], {}
+    for i in np.argsort(t0):
+        k = int(cu[i])
+        if k in per_cu:
+            gaps.append((t0[i] - per_cu[k]) * us)
+        per_cu[k] = t3[i]
+    loop_us = float((t2 - t1).mean() * us)
+    flop_per_wg = 2.0 * M * N * K / len(tr)
+    return {"shader_clock_ghz": ghz,
+            "timeline": {"work_groups": int(len(tr)), "cus": len(per_cu),
+                         "prologue_us": float((t1 - t0).mean() * us), "k_loop_us": loop_us,
+                         "epilogue_us": float((t3 - t2).mean() * us),
+                         "turnaround_us": float(np.mean(gaps)) if gaps else 0.0,
+                         "launch_span_us": float((t3.max() - t0.min()) * us),
+                         "k_loop_tflops_all_cus": flop_per_wg / (loop_us * 1e-6) * len(per_cu) * 1e-12,
+                         # cycles the four matrix pipes of a CU need for the work-group's flops (a 32x32x16 bf16
+                         # product, 32768 flop, occupies a SIMD's pipe for 32 cycles) over the cycles the loop took
+                         "k_loop_mfma_busy_frac": float(flop_per_wg / 4096.0 / (c2 - c1).mean())}}
 
 
 def achievable_rates(torch, srm):

@@ -504,14 +504,17 @@ int32_t srm_generate_one_kernel_blocks(const srm_model *m, int64_t B);
  * *flop (host pointer, may be NULL) receives the floating-point operations of
  * the launch.
  *
- * srm_linear_clock_probe: sets (NULL: clears) a device buffer of four uint64 for the calling thread; while
- * set, every bf16 srm_linear launch of this thread has its work-group 0 store the shader cycle counter at
- * its start and end and the 100 MHz wall clock at the same two moments (cycles0, cycles1, wall0, wall1):
- * (cycles1 - cycles0) / (wall1 - wall0) * 100 MHz is the clock the chip held during that launch.  The
- * matrix-core peak is quoted at the maximum clock; under the power of a GEMM on real data the chip holds
- * a lower one.  Only srm_linear honours it; the model's path never writes the buffer.
+ * srm_linear_timeline_probe: sets (d_u64 = NULL or blocks = 0: clears), for the calling thread, a device
+ * buffer of 8 * blocks uint64.  While set, every work-group b < blocks of a bf16 srm_linear launch of this
+ * thread stores at d_u64 + 8 b: the 100 MHz wall clock at its start, at the start of its k loop, at the end
+ * of its k loop and after its last store has completed; the shader cycle counter at the k loop's start and
+ * end; HW_ID | XCC_ID << 32 (the CU it ran on); the cycle counter at its start.  (cycles / wall ticks) x
+ * 100 MHz is the clock the chip held: the matrix-core peak is quoted at the maximum clock, and under the
+ * power of a GEMM on real data the chip holds a lower one.  The work-groups of one CU, ordered by start
+ * time, give that CU's timeline: prologue, k loop, epilogue and the turnaround to the next work-group.
+ * Only srm_linear honours it; the model's path never writes the buffer.
  */
-void srm_linear_clock_probe(void *d_u64x4);
+void srm_linear_timeline_probe(void *d_u64, int64_t blocks);
 int srm_probe_copy(void *d_dst, const void *d_src, size_t bytes, int32_t streaming, void *hip_stream);
 int srm_probe_mfma(float *d_out, int32_t blocks, int32_t iters, int32_t random_operands, double *flop,
                    void *hip_stream);

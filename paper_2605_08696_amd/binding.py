@@ -85,8 +85,8 @@ def lib():
         L.srm_linear_argmax_noalloc.argtypes = [i32, vp, vp, vp, i64, i32, i32, vp, vp]
         L.srm_linear_argmax_noalloc_max_bytes.restype = sz
         L.srm_linear_argmax_noalloc_max_bytes.argtypes = []
-        L.srm_linear_clock_probe.restype = None
-        L.srm_linear_clock_probe.argtypes = [vp]
+        L.srm_linear_timeline_probe.restype = None
+        L.srm_linear_timeline_probe.argtypes = [vp, i64]
         L.srm_workspace_bytes_config.restype = sz
         L.srm_workspace_bytes_config.argtypes = [vp, i64]
         L.srm_prefill_ragged_plan.restype = C.c_int
@@ -442,10 +442,13 @@ def probe_mfma(out, blocks: int, iters: int, random_operands: bool = False, stre
     return flop.value
 
 
-def linear_clock_probe(buf) -> None:
-    """srm_linear_clock_probe: buf = int64 CUDA tensor of 4 elements, or None to clear."""
+def linear_timeline_probe(buf, blocks: int = 0) -> None:
+    """srm_linear_timeline_probe: buf = int64 CUDA tensor of 8 * blocks elements, or None to clear."""
     torch = _torch()
-    lib().srm_linear_clock_probe(None if buf is None else _dev(buf, torch.int64, 4, "clock probe"))
+    if buf is None:
+        lib().srm_linear_timeline_probe(None, 0)
+    else:
+        lib().srm_linear_timeline_probe(_dev(buf, torch.int64, 8 * blocks, "timeline probe"), int(blocks))
 
 
 def linear_argmax_noalloc(dtype, A, W, bias, argmax, stream=None):

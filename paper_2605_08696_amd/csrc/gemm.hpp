@@ -52,9 +52,13 @@ struct GemmEpi {
     int32_t ln_nsplit;
     int64_t ln_stride;
     float ln_eps;
-    // Measuring hook (srm_linear_clock_probe): if not null, work-group 0 of gemm_bf16_kernel writes the shader
-    // cycle counter and the 100 MHz wall clock at its start and at its end: clk[0..3] = cycles0, cycles1, wall0, wall1.
+    // Measuring hook (srm_linear_timeline_probe): if not null, every work-group b < clk_blocks of
+    // gemm_bf16_kernel writes eight words at clk + 8 b: the 100 MHz wall clock at its start, at the start
+    // of its k loop, at the end of the k loop and after its last store has completed; the shader cycle
+    // counter at the k loop's start and end; HW_ID | XCC_ID << 32 (which CU it ran on); the cycle
+    // counter at its start.
     unsigned long long *clk;
+    int64_t clk_blocks;
 };
 
 // The position all rows share: ep.pos, or *ep.pos_dev if that is set.  (Written as a conditional load with a
@@ -504,8 +508,9 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     static_assert(NW * 32 * STG * 4 + BM * WN * 8 <= NS * (BM + BN) * BK * 2, "epilogue stage exceeds the tile LDS");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    const bool probe = ep.clk != nullptr && blockIdx.x == 0 && blockIdx.y == 0;
-    unsigned long long clk_c0 = 0, clk_t0 = 0;
+    const int64_t probe_id = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const bool probe = ep.clk != nullptr && probe_id < ep.clk_blocks;
+    unsigned long long clk_c0 = 0, clk_t0 = 0, clk_c1 = 0, clk_t1 = 0, clk_c2 = 0, clk_t2 = 0;
     if (probe) { clk_c0 = clock64(); clk_t0 = wall_clock64(); }
     bf16 *As = reinterpret_cast<bf16 *>(smem_raw);   // [NS][BM*BK]; LNA: [K / BK][PANEL_ROWS*BK]
     bf16 *Bs = As + (LNA ? (K / BK) * PANEL_ROWS * BK : NS * BM * BK);   // [NS][BN*BK]
@@ -731,6 +736,7 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
                 acc[i][j][4 * g + 2] = bq[j][g].z; acc[i][j][4 * g + 3] = bq[j][g].w;
             }
     __builtin_amdgcn_sched_barrier(0);
+    if (probe) { clk_c1 = clock64(); clk_t1 = wall_clock64(); }
 
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & (NS - 1), nxt = (kt + 1) & (NS - 1);
@@ -772,6 +778,7 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     }
     SRM_WAIT_VM(0);
     __syncthreads();                                  // LDS is reused by the epilogue
+    if (probe) { clk_c2 = clock64(); clk_t2 = wall_clock64(); }
 #undef SRM_MFMA_STEP
 #undef SRM_INTERLEAVE
 #undef SRM_DMA_TILE
@@ -780,8 +787,15 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
 #undef SRM_READ_FRAGS
 
     gemm_epilogue<BM, BN, WM, WN, EPI, TAct>(acc, smem_raw, ep, M, N, m0, n0, bn);
-    if (probe && tid == 0) {
-        ep.clk[0] = clk_c0; ep.clk[1] = clock64(); ep.clk[2] = clk_t0; ep.clk[3] = wall_clock64();
+    if (probe) {
+        __builtin_amdgcn_s_waitcnt(0);                // this wave's stores have completed
+        if (tid == 0) {
+            unsigned long long *p = ep.clk + 8 * probe_id;
+            p[0] = clk_t0; p[1] = clk_t1; p[2] = clk_t2; p[3] = wall_clock64(); p[4] = clk_c1; p[5] = clk_c2;
+            p[6] = (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |        // HW_ID
+                   ((unsigned long long)__builtin_amdgcn_s_getreg((3 << 11) | 20) << 32);  // XCC_ID
+            p[7] = clk_c0;
+        }
     }
 }
 

@@ -507,6 +507,7 @@ static int tile_bn(int tile) { return tile == 0 ? 256 : (tile == 2 || tile >= 6)
 
 static thread_local int g_force_tile = -1;   // test/bench hook of srm_linear only
 static thread_local unsigned long long *g_clock_probe = nullptr;   // measuring hook of srm_linear only
+static thread_local int64_t g_clock_blocks = 0;
 
 template <int EPI, typename TAct>
 static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, GemmEpi ep, hipStream_t st,
@@ -632,7 +633,7 @@ static int linear(const void *A, const void *W, const float *bias, int64_t M, in
     GemmEpi ep{bias, out, (int64_t)N, pv, pi, 0, sm.temp, sm.seed, sm.pos, sm.pos_dev, sm.pos_rows, sm.row_base,
                mx.state, mx.alpha, mx.beta, mx.lam, mx.n_ctx, mx.hrow, mx.dh, mx.state_half};
     ep.add_part = add.part; ep.add_nsplit = add.part ? add.nsplit : 0; ep.add_stride = add.stride;
-    ep.clk = g_clock_probe;
+    ep.clk = g_clock_probe; ep.clk_blocks = g_clock_blocks;
     if (add.part && EPI != EPI_RESID) return fail(SRM_EINVAL, "linear: pending slabs need the residual epilogue");
     if (ln.x) {
         if constexpr (sizeof(T) == 2 && (EPI == EPI_STORE || EPI == EPI_GELU || EPI == EPI_MIX)) {
@@ -1701,9 +1702,10 @@ extern "C" int srm_probe_mfma(float *d_out, int32_t blocks, int32_t iters, int32
     return SRM_OK;
 }
 
-extern "C" void srm_linear_clock_probe(void *d_u64x4)
+extern "C" void srm_linear_timeline_probe(void *d_u64, int64_t blocks)
 {
-    g_clock_probe = static_cast<unsigned long long *>(d_u64x4);
+    g_clock_probe = blocks > 0 ? static_cast<unsigned long long *>(d_u64) : nullptr;
+    g_clock_blocks = g_clock_probe ? blocks : 0;
 }
 
 extern "C" size_t srm_linear_scratch_bytes(int64_t M, int32_t N)
