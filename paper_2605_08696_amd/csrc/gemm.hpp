@@ -173,19 +173,32 @@ __device__ __forceinline__ void static_for(F &&f)
 // and six FMAs, no reciprocal.  With q = 2^-P: x * (1 - q) for x >= 0 and x * q for x < 0 are both
 // max(x, 0) - |x| * q, one max and one FMA instead of a subtraction, a compare, a select and a
 // product.  The result is rounded to bf16 (relative 2^-9) right after, so the approximation error is
-// invisible there.  (A degree-4 fit, error 2.3e-5, measured the same launch time on the MLP-up shape:
-// the launch is bound by the chip's power, not by this epilogue's instruction count.)
+// invisible there.
 __device__ __forceinline__ float gelu_bf16out(float x)
 {
-    const float w = fminf(fabsf(x), 6.081118318204308f);
-    float p = fmaf(w, -1.917465077776602e-05f, 0.0006586045579087176f);
-    p = fmaf(w, p, -0.00775440879176911f);
-    p = fmaf(w, p, 0.05296539231773387f);
-    p = fmaf(w, p, 0.4590602540550674f);
-    p = fmaf(w, p, 1.1511220519383694f);
-    p = fmaf(w, p, 0.9999996936263803f);
-    const float q = __builtin_amdgcn_exp2f(-p);                  // erfc(|x| / sqrt(2)) / 2
-    return fmaf(-fabsf(x), q, fmaxf(x, 0.0f));
+    // Eleven instructions, written out: from the C form the compiler made 14 to 18 per element (a
+    // NaN-quieting max in front of each min / max, whose inputs come straight from LDS, and a move per
+    // constant in every other Horner chain), and this epilogue is bound by its instruction count.
+    //   w = min(|x|, 6.0811183)                       P(w) by Horner, coefficients high to low:
+    //   -1.917465077776602e-05, 0.0006586045579087176, -0.00775440879176911, 0.05296539231773387,
+    //   0.4590602540550674, 1.1511220519383694, 0.9999996936263803
+    //   q = 2^-P ;  result = max(x, 0) - |x| * q
+    float w, p, q, r;
+    const float c5 = 0.0006586045579087176f;
+    asm("v_and_b32 %0, 0x7fffffff, %4\n\t"
+        "v_min_f32 %0, 0x40c29885, %0\n\t"
+        "v_fmamk_f32 %1, %0, 0xb7a0d940, %5\n\t"
+        "v_fmaak_f32 %1, %0, %1, 0xbbfe18b2\n\t"
+        "v_fmaak_f32 %1, %0, %1, 0x3d58f23d\n\t"
+        "v_fmaak_f32 %1, %0, %1, 0x3eeb09f2\n\t"
+        "v_fmaak_f32 %1, %0, %1, 0x3f9357f8\n\t"
+        "v_fmaak_f32 %1, %0, %1, 0x3f7ffffb\n\t"
+        "v_exp_f32_e64 %2, -%1\n\t"
+        "v_max_f32 %3, 0, %4\n\t"
+        "v_fma_f32 %3, -|%4|, %2, %3"
+        : "=&v"(w), "=&v"(p), "=&v"(q), "=&v"(r)
+        : "v"(x), "v"(c5));
+    return r;
 }
 
 // GELU in the precision of the output type: the fitted form for bf16 outputs, erf for fp32 ones.
@@ -572,22 +585,26 @@ gemm_bf16_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ W, int M, 
     // bias is requested here, in front of the first tile loads, and moved into the accumulators once the
     // first tile has landed (loads return in order): its latency hides under the first tile's.
     float4 bq[TN][4];
+    if (ep.bias && (N & 3) == 0 && n0 + BN <= N) {       // block-uniform: all of the tile's columns exist
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int col = n0 + wn * WTN + j * 32 + 8 * g + 4 * lk;
-            bq[j][g] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ep.bias) {
-                if ((N & 3) == 0 && col + 3 < N) bq[j][g] = load4(ep.bias + col);
-                else {
+            for (int g = 0; g < 4; ++g) bq[j][g] = load4(ep.bias + n0 + wn * WTN + j * 32 + 8 * g + 4 * lk);
+    } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = n0 + wn * WTN + j * 32 + 8 * g + 4 * lk;
+                bq[j][g] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (ep.bias) {
                     bq[j][g].x = col < N ? ep.bias[col] : 0.f;
                     bq[j][g].y = col + 1 < N ? ep.bias[col + 1] : 0.f;
                     bq[j][g].z = col + 2 < N ? ep.bias[col + 2] : 0.f;
                     bq[j][g].w = col + 3 < N ? ep.bias[col + 3] : 0.f;
                 }
             }
-        }
+    }
     f32x16_t acc[TM][TN];
 
     const int sw = swz_of_row(lr);                   // wave-tile rows are multiples of 32 apart
