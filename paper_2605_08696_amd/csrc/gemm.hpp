@@ -1064,38 +1064,48 @@ struct FinalizeRagged {
 };
 
 // Reduce the per-tile partials [nparts][rows] of each row to one token; writes `rep`
-// consecutive copies starting at out[(row0 + row) * rep].  One work-group per 64
-// rows: thread (r = tid & 63, q = tid >> 6) scans parts q, q + 4, ... of row r
-// (consecutive lanes read consecutive rows), the four scans of a row meet in LDS.
+// consecutive copies starting at out[(row0 + row) * rep].  One work-group per 16
+// rows: thread (r = tid & 15, q = tid >> 4) scans parts q, q + 16, ... of row r
+// (16 consecutive lanes read 16 consecutive rows; the loads of eight parts are in
+// flight together), the sixteen scans of a row meet in LDS.
 // A row without any ordered value (all NaN) yields token 0, so that the id is
 // always a valid embedding row.  If store is not null the token also goes to
 // store[step * store_stride + (row0 + row) * rep + r] with step = *step_dev.
+constexpr int kFinalRows = 16;
 __global__ void __launch_bounds__(256)
 argmax_finalize_kernel(const float *__restrict__ part_val, const int32_t *__restrict__ part_idx,
                        int64_t rows, int nparts, int32_t *__restrict__ out, int64_t row0, int rep,
                        int vocab, int32_t *__restrict__ store, const int *__restrict__ step_dev,
                        int64_t store_stride, FinalizeRagged rg)
 {
-    __shared__ float sv[4][64];
-    __shared__ int si[4][64];
-    const int r = threadIdx.x & 63, q = threadIdx.x >> 6;
-    const int64_t blk0 = (int64_t)blockIdx.x * 64;
+    constexpr int NQ = 256 / kFinalRows, U = 8;
+    __shared__ float sv[NQ][kFinalRows];
+    __shared__ int si[NQ][kFinalRows];
+    const int r = threadIdx.x % kFinalRows, q = threadIdx.x / kFinalRows;
+    const int64_t blk0 = (int64_t)blockIdx.x * kFinalRows;
     const int64_t row = blk0 + r;
     if (rg.zero_counter && blockIdx.x == 0 && threadIdx.x == 0) *rg.zero_counter = 0;
     float bv = -INFINITY;
     int bi = 0x7fffffff;
     if (row < rows)
-        for (int p = q; p < nparts; p += 4) {
-            const float v = part_val[(int64_t)p * rows + row];
-            const int i = part_idx[(int64_t)p * rows + row];
-            if (arg_better(v, i, bv, bi)) { bv = v; bi = i; }
+        for (int p0 = q; p0 < nparts; p0 += NQ * U) {
+            float v[U];
+            int i[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int p = min(p0 + u * NQ, nparts - 1);          // clamped address, masked below
+                v[u] = part_val[(int64_t)p * rows + row];
+                i[u] = part_idx[(int64_t)p * rows + row];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (p0 + u * NQ < nparts && arg_better(v[u], i[u], bv, bi)) { bv = v[u]; bi = i[u]; }
         }
     sv[q][r] = bv;
     si[q][r] = bi;
     __syncthreads();
     if (q == 0 && row < rows) {
-#pragma unroll
-        for (int k = 1; k < 4; ++k)
+        for (int k = 1; k < NQ; ++k)
             if (arg_better(sv[k][r], si[k][r], bv, bi)) { bv = sv[k][r]; bi = si[k][r]; }
         if (bi < 0 || bi >= vocab) bi = 0;
         if (rg.pos_rows) {
@@ -1115,8 +1125,8 @@ argmax_finalize_kernel(const float *__restrict__ part_val, const int32_t *__rest
     }
     if (rg.slot) return;
     __syncthreads();
-    // the rep copies of the 64 tokens, consecutive threads writing consecutive words
-    const int64_t nrow = min((int64_t)64, rows - blk0);
+    // the rep copies of the block's tokens, consecutive threads writing consecutive words
+    const int64_t nrow = min((int64_t)kFinalRows, rows - blk0);
     int32_t *dst2 = store ? store + (int64_t)(*step_dev) * store_stride : nullptr;
     for (int64_t e = threadIdx.x; e < nrow * rep; e += 256) {
         const int rl = (int)(e / rep);

@@ -664,7 +664,7 @@ static int argmax_finalize(const float *pv, const int32_t *pi, int64_t rows, int
                            int64_t row0, int rep, int vocab, hipStream_t st, TokenStore ts = TokenStore(),
                            FinalizeRagged rg = FinalizeRagged{})
 {
-    hipLaunchKernelGGL(argmax_finalize_kernel, dim3((unsigned)cdiv(rows, 64)), dim3(256), 0, st, pv, pi, rows,
+    hipLaunchKernelGGL(argmax_finalize_kernel, dim3((unsigned)cdiv(rows, kFinalRows)), dim3(256), 0, st, pv, pi, rows,
                        nparts, out, row0, rep, vocab, ts.store, ts.step_dev, ts.stride, rg);
     HIP_TRY(hipGetLastError());
     return SRM_OK;
