@@ -437,7 +437,10 @@ int srm_mixer_project_update(srm_model *m, int32_t layer, int32_t pos, int64_t B
  * epilogue e on a pinned tile shape instead of the one the library would choose:
  * tile 0 = 256x256 (8 wavefronts), 1 = 128x128 (4), 2 = 64x64 (4), 3 = 128x128 (8),
  * 4 = 256x128 (8), 5 = 128x128 on a four-stage LDS ring, 6 / 7 / 8 = 64x64 on a
- * ring of 2 / 4 / 8 stages.  Same values for every tile up to the fp32 summation
+ * ring of 2 / 4 / 8 stages, 9 / 10 = 256x256 as a persistent kernel (one work-group
+ * per compute unit walks several tiles; needs K % 128 == 0, K >= 256, N % 4 == 0) /
+ * as one work-group per tile (tile 0 takes the first form when there are more tiles
+ * than compute units and the shape allows it).  Same values for every tile up to the fp32 summation
  * order inside a k tile (none: all tiles accumulate k in the same order).
  * Errors: SRM_EINVAL (null operand or output, sizes <= 0, K % 64 with SRM_BF16,
  * unknown dtype, epilogue or tile code).
@@ -512,6 +515,9 @@ int32_t srm_generate_one_kernel_blocks(const srm_model *m, int64_t B);
  * 100 MHz is the clock the chip held: the matrix-core peak is quoted at the maximum clock, and under the
  * power of a GEMM on real data the chip holds a lower one.  The work-groups of one CU, ordered by start
  * time, give that CU's timeline: prologue, k loop, epilogue and the turnaround to the next work-group.
+ * The persistent form of the 256x256 tile writes one such record per output tile (tile number in place of b;
+ * "start" is the end of the work-group's previous tile), and waits for its stores once per tile to do so,
+ * which costs it more than it costs the one-tile work-groups: time the two forms with the probe cleared.
  * Only srm_linear honours it; the model's path never writes the buffer.
  */
 void srm_linear_timeline_probe(void *d_u64, int64_t blocks);

@@ -56,7 +56,7 @@ struct GemmEpi {
     // gemm_bf16_kernel writes eight words at clk + 8 b: the 100 MHz wall clock at its start, at the start
     // of its k loop, at the end of the k loop and after its last store has completed; the shader cycle
     // counter at the k loop's start and end; HW_ID | XCC_ID << 32 (which CU it ran on); the cycle
-    // counter at its start.
+    // counter at its start.  (gemm_bf16_persist_kernel: one record per output tile.)
     unsigned long long *clk;
     int64_t clk_blocks;
 };
@@ -81,10 +81,9 @@ __device__ __forceinline__ uint32_t epi_pos(const GemmEpi &ep, int64_t row, int 
 // with its own L2: give every XCD one contiguous run of tiles, and inside a run
 // walk groups of GM row-tiles column by column so the A rows of a group and the
 // W tile being shared stay L2-resident.
-__device__ __forceinline__ void tile_of_block(int nbm, int nbn, int &bm, int &bn)
+__device__ __forceinline__ void tile_of_pid(int pid, int nbm, int nbn, int &bm, int &bn)
 {
     constexpr int GM = 8;
-    int pid = blockIdx.x;
     const int nblk = nbm * nbn;
     if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
     const int gsz = GM * nbn;
@@ -94,6 +93,10 @@ __device__ __forceinline__ void tile_of_block(int nbm, int nbn, int &bm, int &bn
     const int in_g = pid - g * gsz;
     bm = first_m + in_g % gm;
     bn = in_g / gm;
+}
+__device__ __forceinline__ void tile_of_block(int nbm, int nbn, int &bm, int &bn)
+{
+    tile_of_pid(blockIdx.x, nbm, nbn, bm, bn);
 }
 
 template <int EPI, typename TAct>
@@ -278,13 +281,13 @@ __device__ __forceinline__ void epi_store1p(const GemmEpi &ep, int64_t row, int 
 // loads have completed and a barrier has been passed); lds_bytes its size.
 template <int BM, int BN, int WM, int WN, int EPI, typename TAct>
 __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[BM / WM / 32][BN / WN / 32], unsigned char *smem_raw,
-                                              const GemmEpi &ep, int M, int N, int m0, int n0, int bn)
+                                              const GemmEpi &ep, int M, int N, int m0, int n0, int bn,
+                                              const int tid = threadIdx.x)
 {
     constexpr int NW = WM * WN, NTHR = NW * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     constexpr int STG = WTN + 4;                     // stage row stride in floats: 16 B * odd
-    const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int lr = lane & 31, lk = lane >> 5;

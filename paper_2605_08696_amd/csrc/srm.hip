@@ -14,6 +14,7 @@
 
 #include "srm.h"
 #include "gemm.hpp"
+#include "gemm_persist.hpp"
 #include "mega.hpp"
 #include "mixer.hpp"
 #include "norm.hpp"
@@ -420,6 +421,46 @@ static int launch_bf16_tile(const bf16 *A, const bf16 *W, int M, int N, int K, c
     return SRM_OK;
 }
 
+// The 256x256 tile as a persistent kernel (gemm_persist.hpp): one work-group per CU, for launches of more
+// tiles than CUs.  It needs an even number >= 4 of k tiles and whole float4 groups of bias per column tile.
+static bool persist_ok(int64_t M, int N, int K)
+{
+    return K % 128 == 0 && K >= 256 && (N & 3) == 0 && cdiv(M, 256) * cdiv(N, 256) < (1 << 30);
+}
+static int device_cus()
+{
+    static thread_local int dev_of = -1, cus_of = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (dev != dev_of) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        dev_of = dev;
+        cus_of = cus;
+    }
+    return cus_of;
+}
+template <int EPI, typename TAct, bool RING = false>
+static int launch_bf16_persist(const bf16 *A, const bf16 *W, int M, int N, int K, const GemmEpi &ep, hipStream_t st)
+{
+    // (the argmax epilogue that stores no logits needs no stage in LDS: the ring runs through)
+    if constexpr (EPI == EPI_ARGMAX && !RING)
+        if (!ep.out) return launch_bf16_persist<EPI, TAct, true>(A, W, M, N, K, ep, st);
+    auto kern = gemm_bf16_persist_kernel<EPI, TAct, RING>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kPersistLds));
+        attr_set = true;
+    }
+    const int cus = device_cus();
+    if (cus <= 0) return fail(SRM_EHIP, "cannot read the number of compute units");
+    const int64_t nb = cdiv(M, 256) * cdiv(N, 256);
+    hipLaunchKernelGGL(kern, dim3((unsigned)std::min<int64_t>(nb, cus)), dim3(512), kPersistLds, st, A, W, M, N, K, ep);
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
 // A handful of rows, LayerNorm made by the GEMM itself (see the LNA note in gemm.hpp): one row tile of 64x64
 // blocks, the normalised rows as a [K / 64][32][64] bf16 panel in LDS next to an eight-tile ring for W.
 template <int EPI>
@@ -485,12 +526,12 @@ static int launch_bf16_small(const bf16 *A, const bf16 *W, int M, int N, int K, 
 
 // Tile codes of the bf16 GEMM: 0 = 256x256 (8 waves), 1 = 128x128 (4 waves),
 // 2 = 64x64 (4 waves), 3 = 128x128 (8 waves), 4 = 256x128 (8 waves); 5 .. 8 pin the
-// ring depth of a tile for sweeps.  min_bn > 64 rules out the 64-wide tile (the LM
+// ring depth of a tile for sweeps, 9 / 10 pin the persistent / one-tile-per-work-group form of 256x256.  min_bn > 64 rules out the 64-wide tile (the LM
 // head's partial buffers are sized for column tiles >= 128).  Measured on C4's
 // shapes over 512 .. 16384 rows: the big tile wins once it fills most of the chip in
 // whole rounds (one block per CU: 384 tiles are two rounds at 75 %, and lose to 1536
 // tiles of 128x128); 128x128 wins over 64x64 from about 144 blocks on.
-constexpr int kNumTiles = 9;
+constexpr int kNumTiles = 11;
 static int choose_tile(int64_t M, int N, int K, int min_bn)
 {
     const int64_t t256 = cdiv(M, 256) * cdiv(N, 256), t128 = cdiv(M, 128) * cdiv(N, 128);
@@ -503,7 +544,7 @@ static int choose_tile(int64_t M, int N, int K, int min_bn)
     if (tile == 2 && min_bn > 64) tile = 1;
     return tile;
 }
-static int tile_bn(int tile) { return tile == 0 ? 256 : (tile == 2 || tile >= 6) ? 64 : 128; }
+static int tile_bn(int tile) { return tile == 0 || tile >= 9 ? 256 : (tile == 2 || tile >= 6) ? 64 : 128; }
 
 static thread_local int g_force_tile = -1;   // test/bench hook of srm_linear only
 static thread_local unsigned long long *g_clock_probe = nullptr;   // measuring hook of srm_linear only
@@ -528,7 +569,12 @@ static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, Ge
     if (nparts_out) *nparts_out = ep.nparts;
     const int m = (int)M;
     switch (tile) {
-    case 0: return launch_bf16_tile<256, 256, 2, 4, EPI, TAct>(A, W, m, N, K, ep, st);
+    case 0:
+        // more tiles than CUs: the persistent form, whose tiles after a CU's first start without a launch and
+        // a cold first load (measured on C4's shapes: MLP-up -1 .. -4 %, LM head -2 %)
+        if (persist_ok(M, N, K) && cdiv(M, 256) * cdiv(N, 256) > device_cus())
+            return launch_bf16_persist<EPI, TAct>(A, W, m, N, K, ep, st);
+        return launch_bf16_tile<256, 256, 2, 4, EPI, TAct>(A, W, m, N, K, ep, st);
     case 1:
         // at most one block per CU: the k loop is bound by the latency of its tile loads (a 128x128x64 tile is
         // 0.27 us of MFMAs, a load about 1 us), so the LDS ring is deepened to keep three tiles in flight
@@ -543,6 +589,10 @@ static int launch_bf16(const bf16 *A, const bf16 *W, int64_t M, int N, int K, Ge
     case 6: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct, 2>(A, W, m, N, K, ep, st);
     case 7: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct, 4>(A, W, m, N, K, ep, st);
     case 8: return launch_bf16_tile<64, 64, 2, 2, EPI, TAct, 8>(A, W, m, N, K, ep, st);
+    case 9:
+        if (!persist_ok(M, N, K)) return fail(SRM_EINVAL, "the persistent GEMM does not take this shape");
+        return launch_bf16_persist<EPI, TAct>(A, W, m, N, K, ep, st);
+    case 10: return launch_bf16_tile<256, 256, 2, 4, EPI, TAct>(A, W, m, N, K, ep, st);
     default: return fail(SRM_EINVAL, "unknown GEMM tile code %d", tile);
     }
 }

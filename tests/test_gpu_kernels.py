@@ -269,3 +269,23 @@ def test_linear_few_rows_streaming_gemv(srm, dtype_name, epi, shape):
 def test_linear_fp32_more_rows_than_one_pass(srm):
     for M in (9, 24, 32):
         _linear_case(srm, srm.SRM_FP32, M, 200, 256, 2, None, seed=M)
+
+
+@pytest.mark.parametrize("shape", [(4400, 4000, 256), (700, 520, 384), (8200, 6000, 256)])
+@pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
+def test_linear_bf16_persistent_kernel(srm, shape, epi):
+    """The persistent 256x256 kernel (tile code 9): fewer tiles than CUs, a few more (some work-groups take two),
+    and three to four per work-group, ragged in M and N, four and six k tiles."""
+    M, N, K = shape
+    if M > 8000 and epi not in (1, 3):
+        pytest.skip("the largest shape runs the two epilogues that large batches take this kernel for")
+    _linear_case(srm, srm.SRM_BF16, M, N, K, epi, 9, seed=900 + epi)
+
+
+def test_linear_bf16_persistent_kernel_rejects_odd_k_tile_counts(srm):
+    A = torch.zeros((512, 192), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((512, 192), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros((512, 512), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(srm.SrmError) as e:
+        srm.linear(srm.SRM_BF16, 0, A, W, None, out=out, tile=9)
+    assert e.value.code == -1
