@@ -425,6 +425,26 @@ int srm_mixer_project_update(srm_model *m, int32_t layer, int32_t pos, int64_t B
                              void *d_state_layer, void *d_m, void *hip_stream);
 
 /*
+ * The token-mixing half of block `layer` in the form a decode step takes for a few dozen
+ * to a couple of thousand rows of a bf16 model (the block of Fig. 1: the mixer of
+ * Eq. 2 / Eq. 3 with the head projections of Eq. 10, between its LayerNorms):
+ *   a = LayerNorm1(x); u = a W_in^T + b_in; (S, m) = state update of Eq. 2 / 3 at `pos`;
+ *   x += m W_out^T + b_out; norm_out = LayerNorm2(x)
+ * as two kernels: one from LayerNorm1 to the out-projection, which it leaves as d / 128
+ * K slices in d_slabs, and the LayerNorm kernel that adds them to x.
+ * d_x [B][d] fp32 (device, read and written), d_state_layer [B][d] in the model's
+ * state type (device, updated in place), d_norm_out [B][d] bf16 (device, written),
+ * d_slabs (device, scratch, (d / 128) * B * d floats).
+ * d_pos_rows (device, [B], may be NULL) gives one position per row instead of `pos`;
+ * a row whose position is outside [0, n_ctx) keeps its state and mixes zeros.
+ * The caller owns all buffers.  Needs bf16 weights, use_projections with projection
+ * width d, and d = 256 or 512: SRM_EINVAL otherwise, and for a null pointer, a layer
+ * or (without d_pos_rows) a position out of range, B <= 0.  SRM_EHIP.
+ */
+int srm_mixer_block(srm_model *m, int32_t layer, int32_t pos, const int32_t *d_pos_rows, int64_t B,
+                    float *d_x, void *d_state_layer, void *d_norm_out, float *d_slabs, void *hip_stream);
+
+/*
  * srm_linear: out = epilogue(A W^T + bias) with A [M][K] and W [N][K] device
  * arrays of type `dtype` (SRM_BF16: bf16 operands on the matrix cores with fp32
  * accumulation, K % 64 == 0; SRM_FP32: fp32).  d_bias [N] fp32 or NULL.
@@ -518,7 +538,11 @@ int32_t srm_generate_one_kernel_blocks(const srm_model *m, int64_t B);
  * The persistent form of the 256x256 tile writes one such record per output tile (tile number in place of b;
  * "start" is the end of the work-group's previous tile), and waits for its stores once per tile to do so,
  * which costs it more than it costs the one-tile work-groups: time the two forms with the probe cleared.
- * Only srm_linear honours it; the model's path never writes the buffer.
+ * While it is set, every bf16 tile-GEMM launch of the calling thread writes such records (the model's own
+ * launches included, each overwriting the last), and srm_mixer_block's first kernel writes, per work-group:
+ * the wall clock at its start, when its first batch of loads has arrived, after LayerNorm1, after the
+ * in-projection, after the state update, after the out-projection's products and after its stores have
+ * completed; HW_ID | XCC_ID << 32.  Clear it before running a model.
  */
 void srm_linear_timeline_probe(void *d_u64, int64_t blocks);
 int srm_probe_copy(void *d_dst, const void *d_src, size_t bytes, int32_t streaming, void *hip_stream);

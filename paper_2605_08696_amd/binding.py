@@ -115,6 +115,8 @@ def lib():
         L.srm_mixer_update.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp]
         L.srm_mixer_project_update.restype = C.c_int
         L.srm_mixer_project_update.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp]
+        L.srm_mixer_block.restype = C.c_int
+        L.srm_mixer_block.argtypes = [vp, i32, i32, vp, i64, vp, vp, vp, vp, vp]
         L.srm_linear.restype = C.c_int
         L.srm_linear.argtypes = [i32, i32, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp]
         L.srm_linear_scratch_bytes.restype = sz
@@ -412,6 +414,21 @@ class Model:
         p_s = _dev(state_layer, self.state_torch_dtype, n, "state_layer")
         p_m = _dev(m, self.act_dtype, n, "m")
         _check(lib().srm_mixer_project_update(self._h, layer, pos, B, p_a, p_s, p_m, _stream(stream)))
+
+    def mixer_block(self, layer, pos, B, x, state_layer, norm_out, pos_rows=None, slabs=None, stream=None):
+        """srm_mixer_block: x [B][d] fp32 (updated), state_layer [B][d] (updated), norm_out [B][d] bf16 (written);
+        pos_rows: int32 [B] device tensor of per-row positions instead of `pos`; slabs: fp32 scratch of
+        (d / 128) * B * d elements (allocated here if not given)."""
+        torch = _torch()
+        n = B * self.d
+        if slabs is None:
+            slabs = torch.empty((self.d // 128) * n, dtype=torch.float32, device=x.device)
+        p_x = _dev(x, torch.float32, n, "x")
+        p_s = _dev(state_layer, self.state_torch_dtype, n, "state_layer")
+        p_o = _dev(norm_out, self.act_dtype, n, "norm_out")
+        p_l = _dev(slabs, torch.float32, (self.d // 128) * n, "slabs")
+        p_p = None if pos_rows is None else _dev(pos_rows, torch.int32, B, "pos_rows")
+        _check(lib().srm_mixer_block(self._h, layer, pos, p_p, B, p_x, p_s, p_o, p_l, _stream(stream)))
 
 
 def sample_logits(logits, temperature, top_p, seed, pos, tok_out, stream=None):

@@ -20,6 +20,7 @@
 #include "norm.hpp"
 #include "probe.hpp"
 #include "sample.hpp"
+#include "tokmix.hpp"
 
 // ------------------------------------------------------------------ errors
 static thread_local std::string g_err;
@@ -386,7 +387,8 @@ static Workspace carve(const srm_model *m, void *base, int64_t rows)
     w.pi = reinterpret_cast<int32_t *>(take(r * nparts * 4));
     w.slow = reinterpret_cast<int *>(take(256 + r * 4));
     // sized so that the workspace grows monotonically with the row count
-    const size_t part_rows = std::max<size_t>((size_t)kSplitK * std::min<int64_t>(rows, kSplitMaxRows),
+    // (twice kSplitK slabs: the one-kernel token mixing writes its out-projection slabs behind the MLP's)
+    const size_t part_rows = std::max<size_t>((size_t)2 * kSplitK * std::min<int64_t>(rows, kSplitMaxRows),
                                               (size_t)kGemvSplitMax * std::min<int64_t>(rows, kGemvRows));
     float *part = reinterpret_cast<float *>(take(part_rows * d * 4));
     w.part = rows <= kSplitMaxRows ? part : nullptr;
@@ -821,6 +823,73 @@ static bool ln_on_load(const srm_model *m, int64_t rows)
     return !(e && e[0] == '0');
 }
 
+// A dozen to about a thousand rows of a bf16 model with head projections: LayerNorm1, in-projection, state
+// update and out-projection of a layer are one kernel (tokmix.hpp), which leaves the out-projection as d / 128
+// slabs behind the slabs that the previous layer's K-sliced MLP-down projection may have left; the LayerNorm2
+// kernel adds all of them to x.  Taken while its work-groups (16 rows x 128 columns each) fit the chip in one
+// round: measured on C3's model (d 512, L 8) per step 0.282 -> 0.258 ms at 16 rows, 0.300 -> 0.270 at 64,
+// 0.318 -> 0.294 at 256, 0.344 -> 0.312 at 512, 0.366 -> 0.357 at 1024, and 0.453 -> 0.508 at 2048 (two rounds).
+// SRM_TOKEN_MIX=0 in the environment keeps the separate kernels, =1 takes the one kernel wherever it can run.
+constexpr int64_t kTokMixMinRows = 9;
+static bool token_mix_shape_ok(const srm_model *m)
+{
+    return m->wsize == 2 && !m->noproj && m->dm == m->d && (m->d == 256 || m->d == 512);
+}
+static bool token_mix_one_kernel(const srm_model *m, int64_t rows)
+{
+    if (!token_mix_shape_ok(m) || ln_on_load(m, rows) || rows > kSplitMaxRows) return false;   // (w.part: see carve)
+    const char *e = getenv("SRM_TOKEN_MIX");
+    if (e && e[0] == '0') return false;
+    if (e && e[0] == '1') return true;
+    return rows >= kTokMixMinRows && cdiv(rows, 16) * (m->d / kTokMixCols) <= device_cus();
+}
+struct TokMixCall {
+    const float *x;
+    SlabArgs pending;
+    void *state;
+    Sampling where;
+    float *slabs;          // [d / 128][rows][d]
+};
+static int token_mix(const srm_model *m, int l, const TokMixCall &c, int64_t rows, hipStream_t st)
+{
+    const LayerDev &y = m->layers[l];
+    TokMixArgs a{};
+    a.x = c.x;
+    a.pend = c.pending.nsplit > 0 ? c.pending.part : nullptr;
+    a.npend = c.pending.nsplit > 0 ? c.pending.nsplit : 0;
+    a.pend_stride = c.pending.stride;
+    a.ln1_g = y.ln1_g; a.ln1_b = y.ln1_b;
+    a.eps = m->cfg.ln_eps;
+    a.w_in = static_cast<const bf16 *>(y.w_in); a.w_out = static_cast<const bf16 *>(y.w_out);
+    a.b_in = y.b_in; a.b_out = y.b_out;
+    a.state = c.state;
+    a.alpha = y.alpha; a.beta = y.beta; a.lam = y.lam;
+    a.n_ctx = m->cfg.n_ctx; a.hrow = m->hrow; a.dh = m->dm / m->Hs;
+    a.pos = c.where.pos; a.pos_dev = c.where.pos_dev; a.pos_rows = c.where.pos_rows;
+    a.slabs = c.slabs;
+    a.rows = rows;
+    a.clk = g_clock_probe;
+    a.clk_blocks = g_clock_blocks;
+    const unsigned nb = (unsigned)(cdiv(rows, 16) * (m->d / kTokMixCols));
+#define TOKMIX_LAUNCH(D, TS)                                                                                   \
+    do {                                                                                                       \
+        auto kern = token_mix_kernel<D, TS>;                                                                   \
+        static bool attr_set = false;                                                                          \
+        if (!attr_set) {                                                                                       \
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                                  \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, tokmix_lds_bytes<D>()));   \
+            attr_set = true;                                                                                   \
+        }                                                                                                      \
+        hipLaunchKernelGGL(kern, dim3(nb), dim3(256), tokmix_lds_bytes<D>(), st, a);                           \
+    } while (0)
+    if (m->d == 256) { if (m->shalf) TOKMIX_LAUNCH(256, f16); else TOKMIX_LAUNCH(256, float); }
+    else if (m->d == 512) { if (m->shalf) TOKMIX_LAUNCH(512, f16); else TOKMIX_LAUNCH(512, float); }
+    else return fail(SRM_EINVAL, "token_mix: d = %d has no one-kernel form", m->d);
+#undef TOKMIX_LAUNCH
+    HIP_TRY(hipGetLastError());
+    return SRM_OK;
+}
+
 // One block (token mixing + channel mixing) on `rows` token rows.  On entry
 // w.a holds LayerNorm1(x) of this layer; mix(l) turns w.u into w.mx.  With
 // norm_next, w.a leaves holding the next layer's LayerNorm1(x), or the final
@@ -833,7 +902,7 @@ static bool ln_on_load(const srm_model *m, int64_t rows)
 template <typename T, typename MIX>
 static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hipStream_t st, MIX &&mix,
                  bool norm_next, bool allow_split = false, void *fuse_state = nullptr, Sampling fuse_pos = Sampling(),
-                 void *np_state = nullptr, int *pend = nullptr)
+                 void *np_state = nullptr, int *pend = nullptr, int *tm_pend = nullptr)
 {
     const LayerDev &y = m->layers[l];
     const int d = m->d, dm = m->dm, ff = m->ff;
@@ -857,6 +926,34 @@ static int block(const srm_model *m, int l, const Workspace &w, int64_t rows, hi
         }
         return down && K >= 1024 && K % (64 * kSplitK) == 0 && cdiv(rows, 64) * cdiv(d, 64) <= 192 ? kSplitK : 1;
     };
+    if constexpr (sizeof(T) == 2) {
+        if (tm_pend) {
+            // Token mixing in one kernel (see token_mix_one_kernel).  w.part holds 2 * kSplitK slabs: the first
+            // kSplitK are the MLP-down projection's (*tm_pend of them wait from the previous layer), the rest
+            // take this layer's out-projection.  w.a on entry is not used (the kernel normalises w.x + waiting
+            // slabs itself); LayerNorm2 adds everything to w.x.  On return *tm_pend is this layer's count.
+            const int64_t stride = (int64_t)rows * d;
+            const int nq = d / kTokMixCols;
+            float *mine = w.part + (size_t)*tm_pend * stride;      // directly behind the waiting slabs
+            const SlabArgs waiting_tm = *tm_pend > 0 ? SlabArgs{w.part, *tm_pend, stride} : SlabArgs();
+            SRM_TRY(token_mix(m, l, TokMixCall{w.x, waiting_tm, np_state, fuse_pos, mine}, rows, st));
+            SRM_TRY((layernorm<T, false>(m, w.x, d, nullptr, w.x, y.ln2_g, y.ln2_b, w.a, rows, st, nullptr, 0, 0, w.part,
+                                         *tm_pend + nq)));
+            SRM_TRY((linear<EPI_GELU, T>(w.a, y.w_up, y.b_up, rows, ff, d, w.g, st)));
+            const int spd = resid_split(ff, true);
+            if (spd > 1)
+                SRM_TRY((linear<EPI_F32, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.part, st, nullptr, nullptr, 64,
+                                            nullptr, Sampling(), spd)));
+            else
+                SRM_TRY((linear<EPI_RESID, T>(w.g, y.w_down, y.b_down, rows, d, ff, w.x, st)));
+            *tm_pend = spd > 1 ? spd : 0;
+            if (l + 1 < m->L) return SRM_OK;                       // the next layer's kernels add the slabs
+            if (spd > 1)
+                return layernorm<T, false>(m, w.x, d, nullptr, w.x, m->lnf_g, m->lnf_b, w.a, rows, st, nullptr, 0, 0,
+                                           w.part, spd);
+            return layernorm<T, false>(m, w.x, d, nullptr, nullptr, m->lnf_g, m->lnf_b, w.a, rows, st);
+        }
+    }
     if (m->noproj && np_state) {
         // non-projected layer, decode: LayerNorm1, state update, residual add and LayerNorm2 in one kernel
         const unsigned nb = (unsigned)cdiv(rows, 4);
@@ -991,11 +1088,12 @@ static int decode_rows(srm_model *m, const DecodeArgs &a, int64_t b0, int64_t nb
     };
     const bool fuse = fuse_mixer(m, nb);
     const Sampling where{0.0f, 0, a.pos, a.pos_dev, pos_rows, 1.0f, 0};
-    int pend = 0;
+    int pend = 0, tm_pend = 0;
     const bool lnf = ln_on_load(m, nb);
+    const bool tm = token_mix_one_kernel(m, nb);
     for (int l = 0; l < m->L; ++l)
         SRM_TRY((block<T>(m, l, w, nb, st, mix, true, true, fuse ? slab(l) : nullptr, where, slab(l),
-                          lnf ? &pend : nullptr)));
+                          lnf ? &pend : nullptr, tm ? &tm_pend : nullptr)));
     if (a.hidden)
         HIP_TRY(hipMemcpyAsync(a.hidden + (size_t)b0 * d, w.x, (size_t)nb * d * 4, hipMemcpyDeviceToDevice, st));
     const Sampling sm{a.temperature, a.seed, a.pos, a.pos_dev, pos_rows, a.top_p, (uint32_t)b0, a.eos_plus1};
@@ -1704,6 +1802,27 @@ extern "C" int srm_mixer_project_update(srm_model *m, int32_t layer, int32_t pos
                                                  nullptr, where, 1, mx)
                          : linear<EPI_MIX, float>(d_a, y.w_in, y.b_in, B, m->dm, m->d, d_m, st, nullptr, nullptr, 64,
                                                   nullptr, where, 1, mx);
+}
+
+extern "C" int srm_mixer_block(srm_model *m, int32_t layer, int32_t pos, const int32_t *d_pos_rows, int64_t B,
+                               float *d_x, void *d_state_layer, void *d_norm_out, float *d_slabs, void *hip_stream)
+{
+    if (!m || !d_x || !d_state_layer || !d_norm_out || !d_slabs) return fail(SRM_EINVAL, "srm_mixer_block: null argument");
+    if (!token_mix_shape_ok(m))
+        return fail(SRM_EINVAL, "srm_mixer_block: needs bf16 weights, head projections of width d and d = 256 or 512");
+    if (layer < 0 || layer >= m->L) return fail(SRM_EINVAL, "srm_mixer_block: layer %d outside [0, %d)", layer, m->L);
+    if (!d_pos_rows && (pos < 0 || pos >= m->cfg.n_ctx))
+        return fail(SRM_EINVAL, "srm_mixer_block: pos %d outside [0, %d)", pos, m->cfg.n_ctx);
+    if (B <= 0 || B >= (1 << 26)) return fail(SRM_EINVAL, "srm_mixer_block: batch out of range");
+    SRM_TRY(check_device(m));
+    hipStream_t st = as_stream(hip_stream);
+    Sampling where;
+    where.pos = pos;
+    where.pos_rows = d_pos_rows;
+    SRM_TRY(token_mix(m, layer, TokMixCall{d_x, SlabArgs(), d_state_layer, where, d_slabs}, B, st));
+    const LayerDev &y = m->layers[layer];
+    return layernorm<bf16, false>(m, d_x, m->d, nullptr, d_x, y.ln2_g, y.ln2_b, d_norm_out, B, st, nullptr, 0, 0, d_slabs,
+                                  m->d / kTokMixCols);
 }
 
 extern "C" int srm_sample_logits(const float *d_logits, int64_t rows, int32_t vocab, float temperature, float top_p,

@@ -91,6 +91,7 @@ def test_null_arguments_are_rejected(srm):
     assert L.srm_parallel_forward(None, None, 1, 1, None, None, None, 0, None) == -1
     assert L.srm_mixer_update(None, 0, 0, 1, None, None, None, None) == -1
     assert L.srm_mixer_project_update(None, 0, 0, 1, None, None, None, None) == -1
+    assert L.srm_mixer_block(None, 0, 0, None, 1, None, None, None, None, None) == -1
     assert L.srm_linear(0, 0, None, None, None, 1, 1, 1, None, None, None, None) == -1
 
 

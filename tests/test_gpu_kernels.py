@@ -289,3 +289,72 @@ def test_linear_bf16_persistent_kernel_rejects_odd_k_tile_counts(srm):
     with pytest.raises(srm.SrmError) as e:
         srm.linear(srm.SRM_BF16, 0, A, W, None, out=out, tile=9)
     assert e.value.code == -1
+
+
+@pytest.mark.parametrize("d,B", [(256, 5), (256, 100), (512, 16), (512, 333), (512, 1024)])
+@pytest.mark.parametrize("half_state", [False, True])
+def test_mixer_block_one_kernel(srm, d, B, half_state):
+    """srm_mixer_block (LayerNorm1, in-projection, state update, out-projection, residual add and LayerNorm2 of a
+    layer in one kernel) against the oracle's LayerNorm / linear / mixer step in fp64 on sampled rows, with one
+    shared position and with one position per row (some of them outside the context: state kept, zeros mixed)."""
+    from oracle import srm_oracle
+    if half_state and B > 400:
+        pytest.skip("one large binary16 case is enough")
+    n_ctx = 8
+    cfg = srm_synth.tiny_config(vocab=16, d_model=d, n_layers=2, n_heads=4, n_ctx=n_ctx, weight_dtype="bf16", seed=78,
+                                state_dtype="fp16" if half_state else "fp32")
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    orc = srm_oracle.Oracle(cfg, w, "f64")
+    rng = np.random.default_rng(B + d)
+    x0 = (rng.standard_normal((B, d)) * 1.5 + 0.3).astype(np.float32)
+    S0 = rng.standard_normal((B, d)).astype(np.float32)
+    layer = 1
+    lw = w["layers"][layer]
+    st_t = torch.float16 if half_state else torch.float32
+    pos_rows = rng.integers(-1, n_ctx + 1, size=B).astype(np.int32)      # -1 and n_ctx: inactive rows
+    rows = sorted({0, 1, B // 3, B - 2 if B > 1 else 0, B - 1})
+    for shared in (True, False):
+        print(f"mixer_block d={d} B={B} half={half_state} shared_pos={shared}", flush=True)
+        x = to_dev(x0)
+        S = to_dev(S0).to(st_t)
+        out = torch.full((B, d), 7.0, dtype=torch.bfloat16, device="cuda")
+        if shared:
+            model.mixer_block(layer, 6, B, x, S, out)
+        else:
+            model.mixer_block(layer, 0, B, x, S, out, pos_rows=to_dev(pos_rows, torch.int32))
+        torch.cuda.synchronize()
+        xg, Sg, og = x.cpu().numpy(), S.float().cpu().numpy(), out.float().cpu().numpy()
+        for b in rows:
+            pos = 6 if shared else int(pos_rows[b])
+            a = orc.layernorm(x0[b].astype(np.float64), lw["ln1_g"], lw["ln1_b"], cfg.ln_eps)
+            S_ref = S0[b].astype(np.float16 if half_state else np.float32).astype(np.float64)
+            if 0 <= pos < n_ctx:
+                u = orc.linear(lw["w_in"], lw["b_in"], a)
+                m = orc.mixer_step(S_ref, u, lw["alpha"][:, pos], lw["beta"][:, pos], lw["lam"])
+            else:
+                m = np.zeros(d)
+            x_ref = x0[b].astype(np.float64) + orc.linear(lw["w_out"], lw["b_out"], m)
+            o_ref = orc.layernorm(x_ref, lw["ln2_g"], lw["ln2_b"], cfg.ln_eps)
+            tol = 2e-2
+            assert np.abs(Sg[b] - S_ref).max() <= tol * max(1.0, np.abs(S_ref).max()), (b, pos)
+            assert np.abs(xg[b] - x_ref).max() <= tol * np.abs(x_ref).max(), (b, pos)
+            assert np.abs(og[b] - o_ref).max() <= 2 * tol * np.abs(o_ref).max(), (b, pos)
+        if not shared:
+            inactive = (pos_rows < 0) | (pos_rows >= n_ctx)
+            if inactive.any():
+                np.testing.assert_array_equal(Sg[inactive], S0[inactive].astype(np.float16 if half_state else np.float32)
+                                              .astype(np.float32))
+    model.close()
+
+
+def test_mixer_block_rejects_what_it_cannot_run(srm):
+    cfg = srm_synth.tiny_config(vocab=16, d_model=128, n_layers=1, n_heads=4, n_ctx=8, weight_dtype="bf16", seed=3)
+    model = srm.Model(cfg, srm_synth.make_weights(cfg))
+    x = torch.zeros((4, 128), device="cuda")
+    S = torch.zeros((4, 128), device="cuda")
+    out = torch.zeros((4, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(srm.SrmError) as e:
+        model.mixer_block(0, 0, 4, x, S, out)
+    assert e.value.code == -1
+    model.close()

@@ -237,6 +237,52 @@ def test_layernorm_made_by_the_consuming_gemm_equals_the_separate_kernel(srm, or
     assert torch.equal(res[0][1], res[1][1])
 
 
+@pytest.mark.parametrize("d,B,layers", [(256, 9, 3), (256, 100, 3), (512, 33, 2), (512, 700, 2)])
+@pytest.mark.parametrize("half_state", [False, True])
+def test_token_mixing_in_one_kernel_matches_the_separate_kernels(srm, orc_mod, d, B, layers, half_state, monkeypatch):
+    """A dozen to about a thousand rows of a bf16 model: the step whose token mixing is one kernel per layer
+    (LayerNorm1 to out-projection, its slabs added by LayerNorm2; pending MLP-down slabs in front of them) against
+    the step of separate kernels (the library's switch) over four steps: logits, residual stream and states agree
+    to bf16 rounding, both match the oracle, and the one-kernel step is the one the library takes by itself."""
+    cfg = srm_synth.tiny_config(vocab=333, d_model=d, n_layers=layers, n_heads=4, n_ctx=8, weight_dtype="bf16", seed=92,
+                                state_dtype="fp16" if half_state else "fp32")
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    T = 4
+    toks = srm_synth.make_prompts(cfg, batch=B, length=T)
+    rows = sorted({0, B // 2, B - 1})
+    ref = orc_mod.Oracle(cfg, w, "f64").recurrent_forward(toks[rows])
+    res = []
+    for mode in ("1", "0", None):
+        if mode is None:
+            monkeypatch.delenv("SRM_TOKEN_MIX", raising=False)
+        else:
+            monkeypatch.setenv("SRM_TOKEN_MIX", mode)
+        ws, st = model.new_workspace(B), model.new_state(B)
+        out = torch.empty(B, dtype=torch.int32, device="cuda")
+        lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+        hd = torch.empty((B, cfg.d_model), dtype=torch.float32, device="cuda")
+        tc = to_dev(toks).t().contiguous()
+        steps = []
+        print(f"token mixing in one kernel d={d} B={B} half={half_state} SRM_TOKEN_MIX={mode}", flush=True)
+        for t in range(T):
+            model.decode_step(B, t, tc[t], st, out, logits=lg, hidden=hd, workspace=ws)
+            steps.append((lg.clone(), out.clone(), hd.clone()))
+        torch.cuda.synchronize()
+        res.append((steps, st.clone()))
+    tol = 4e-2 if half_state else 2e-2
+    for t in range(T):
+        for k in (0, 1):
+            assert rel_err_rows(res[k][0][t][0][rows].cpu().numpy(), ref["logits"][:, t]) <= tol
+            assert rel_err_rows(res[k][0][t][2][rows].cpu().numpy(), ref["hidden"][:, t]) <= tol
+        assert rel_err_rows(res[0][0][t][0].cpu().numpy(), res[1][0][t][0].cpu().numpy()) <= tol
+        # the library's own choice at these row counts is the one-kernel step: the same bits
+        assert torch.equal(res[0][0][t][0], res[2][0][t][0]) and torch.equal(res[0][0][t][1], res[2][0][t][1])
+    assert torch.equal(res[0][1], res[2][1])
+    assert (res[0][1].float() - res[1][1].float()).abs().max() <= tol * res[1][1].float().abs().max()
+    model.close()
+
+
 # ---- head layouts: row-only, column-only, combined ("Method", after Eq. 2; Table S0) ------------
 @pytest.mark.parametrize("layout,H", [("row", 4), ("column", 4), ("combined", 4), ("row", 1), ("combined", 1),
                                       ("column", 3)])
