@@ -827,8 +827,8 @@ static bool ln_on_load(const srm_model *m, int64_t rows)
 // update and out-projection of a layer are one kernel (tokmix.hpp), which leaves the out-projection as d / 128
 // slabs behind the slabs that the previous layer's K-sliced MLP-down projection may have left; the LayerNorm2
 // kernel adds all of them to x.  Taken while its work-groups (16 rows x 128 columns each) fit the chip in one
-// round: measured on C3's model (d 512, L 8) per step 0.282 -> 0.258 ms at 16 rows, 0.300 -> 0.270 at 64,
-// 0.318 -> 0.294 at 256, 0.344 -> 0.312 at 512, 0.366 -> 0.357 at 1024, and 0.453 -> 0.508 at 2048 (two rounds).
+// round: measured on C3's model (d 512, L 8) per step 0.280 -> 0.248 ms at 16 rows, 0.298 -> 0.260 at 64,
+// 0.318 -> 0.285 at 256, 0.353 -> 0.310 at 512, 0.378 -> 0.361 at 1024, and 0.473 -> 0.512 at 2048 (two rounds).
 // SRM_TOKEN_MIX=0 in the environment keeps the separate kernels, =1 takes the one kernel wherever it can run.
 constexpr int64_t kTokMixMinRows = 9;
 static bool token_mix_shape_ok(const srm_model *m)

@@ -16,9 +16,10 @@
 // of both weight matrices: d^2 / 64 bytes each, requested once, at the start - no k loop waits for memory, the
 // kernel is one round trip deep.  The share of W_in goes global -> LDS (buffer_load ... lds, whole 128-byte row
 // segments per request, into the swizzled layout of gemm_bf16_kernel; each wavefront loads and reads only its
-// own rows, so no barrier guards them).  The share of W_out goes straight into registers as MFMA operand fragments
-// (128 registers at d = 512): such loads are slow - every lane's 16 bytes are a request of their own, measured
-// 8.6 us until both shares had arrived that way - but this one is not needed before the last phase.
+// own rows, so no barrier guards them).  The share of W_out is as large and follows into the same LDS once the
+// in-projection has read W_in: a second trip to memory, under the state update.  (Loaded straight into registers
+// as MFMA operand fragments instead, every lane's 16 bytes are a request of their own: 8.6 us until both shares
+// had arrived that way, and 2.5 us of stalled issue for W_out's alone.)
 //
 // Work-group: 4 wavefronts; the products are 16x16x32 bf16 MFMAs formed transposed (W rows as first operand), so
 // a lane holds 4 consecutive output columns of one row: lane l works on row l & 15, column quad l >> 4 of a
@@ -71,7 +72,7 @@ token_mix_kernel(TokMixArgs a)
     constexpr int NU = QC / NW / 16;                 // 16-column tiles of u per wavefront (2)
     constexpr int HK1 = D / 32, HK2 = QC / 32;       // 32-wide k steps of the two projections
     constexpr int PLD = D + 8, MLD = QC + 8;         // panel row strides: 16 bytes of padding, conflict-free reads
-    static_assert(D % 256 == 0 && D % QC == 0 && NL * HK2 <= 32, "a lane holds its share of W_out in registers");
+    static_assert(D % 256 == 0 && D % QC == 0, "whole LayerNorm vectors per lane, whole column blocks");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
     constexpr int BK = 64, KT = D / BK, WR = QC / NW;                       // k tiles of W_in; its rows per wavefront
@@ -107,33 +108,38 @@ token_mix_kernel(TokMixArgs a)
     // parameters, the waiting slabs - LayerNorm1 starts when these have arrived, one round trip into the kernel.
     // Second batch, requested in front of LayerNorm1 and arriving under it and the in-projection: the
     // coefficients at the position, and the share of W_out (whose registers the slabs used before).
-    {
-        // W_in rows ucol0 .. ucol0 + 31, all k: instruction i of k tile kt moves rows 8 i .. 8 i + 7 x 128 bytes;
-        // lane (r = l >> 3, slot = l & 7) fetches chunk slot ^ swz(8 i + r) of its row, swz(8 i + r) =
-        // (4 (i & 1) + (r >> 1)) & 7.  Issued from an asm statement (see gemm_persist.hpp); they are the oldest
-        // loads of the wavefront, so any later wait for a loaded value also waits for them.
-        typedef __attribute__((address_space(3))) unsigned char lds_byte;
-        const int wv = __builtin_amdgcn_readfirstlane(wave);
-        const unsigned dst0 = __builtin_amdgcn_readfirstlane(
-            (unsigned)reinterpret_cast<unsigned long long>((lds_byte *)smem_raw)) + wv * KT * STAGE * 2;
+    // ---- tile loads (buffer_load ... lds): one instruction moves rows 8 i .. 8 i + 7 x 128 bytes of a k tile of this
+    // wavefront's rows; lane (r = l >> 3, slot = l & 7) fetches chunk slot ^ swz(8 i + r) of its row, swz(8 i + r) =
+    // (4 (i & 1) + (r >> 1)) & 7.  Issued from an asm statement (see gemm_persist.hpp); all waits are explicit.
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned dst0 = __builtin_amdgcn_readfirstlane(
+        (unsigned)reinterpret_cast<unsigned long long>((lds_byte *)smem_raw)) + wv * KT * STAGE * 2;
+    auto descriptor = [](const void *base, int bytes) {
         u32x4_t rs;
-        const unsigned long long base = reinterpret_cast<unsigned long long>(a.w_in + (size_t)(q * QC + wv * WR) * D);
-        rs[0] = __builtin_amdgcn_readfirstlane((unsigned)base);
-        rs[1] = __builtin_amdgcn_readfirstlane((unsigned)(base >> 32));
-        rs[2] = WR * D * 2;
+        const unsigned long long p = reinterpret_cast<unsigned long long>(base);
+        rs[0] = __builtin_amdgcn_readfirstlane((unsigned)p);
+        rs[1] = __builtin_amdgcn_readfirstlane((unsigned)(p >> 32));
+        rs[2] = __builtin_amdgcn_readfirstlane((unsigned)bytes);
         rs[3] = 0x00020000u;
-        const int ld_r = lane >> 3, ld_c = lane & 7;
-        const int voff_even = (ld_r * D + ((ld_c ^ (ld_r >> 1)) << 3)) * 2;
-        const int voff_odd = (ld_r * D + ((ld_c ^ ((4 + (ld_r >> 1)) & 7)) << 3)) * 2;
-        auto dma = [&](unsigned lds_dst, int voff, int soff) {
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :
-                         : "s"(lds_dst), "v"(voff), "s"(rs), "s"(soff)
-                         : "memory");
-        };
+        return rs;
+    };
+    const int ld_r = lane >> 3, ld_c = lane & 7;
+    const int voff_even = (ld_r * D + ((ld_c ^ (ld_r >> 1)) << 3)) * 2;
+    const int voff_odd = (ld_r * D + ((ld_c ^ ((4 + (ld_r >> 1)) & 7)) << 3)) * 2;
+    auto dma = [&](const u32x4_t &rs, unsigned lds_dst, int voff, int soff) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_dst), "v"(voff), "s"(rs), "s"(soff)
+                     : "memory");
+    };
+    {
+        // W_in rows ucol0 .. ucol0 + 31, all k, as KT k tiles of 32 rows x 64.  They are the oldest loads of the
+        // wavefront, so the wait for x (LayerNorm1) also waits for them.
+        const u32x4_t rs = descriptor(a.w_in + (size_t)(q * QC + wv * WR) * D, WR * D * 2);
         static_for<0, KT * (WR / 8)>([&](auto n_) {
             constexpr int kt = decltype(n_)::value / (WR / 8), i = decltype(n_)::value % (WR / 8);
-            dma(dst0 + (kt * STAGE + i * 8 * BK) * 2, (i & 1) ? voff_odd : voff_even, (i * 8 * D + kt * BK) * 2);
+            dma(rs, dst0 + (kt * STAGE + i * 8 * BK) * 2, (i & 1) ? voff_odd : voff_even, (i * 8 * D + kt * BK) * 2);
         });
     }
     int p_dev = 0, p_row = 0;
@@ -200,15 +206,7 @@ token_mix_kernel(TokMixArgs a)
         be[t] = a.beta[(size_t)h * a.n_ctx + pc];
         la[t] = a.lam[h];
     }
-    __builtin_amdgcn_sched_barrier(0);               // (keeps the second batch behind the first)
-    bf16x8_t wout[HK2][NL];
-#pragma unroll
-    for (int hk = 0; hk < HK2; ++hk)
-#pragma unroll
-        for (int t = 0; t < NL; ++t)
-            wout[hk][t] = *reinterpret_cast<const bf16x8_t *>(a.w_out + (size_t)(ocol0 + t * 16 + j) * D + q * QC + hk * 32 + 8 * g);
-
-    constexpr int kSecond = 3 * NU + HK2 * NL;       // loads of the second batch
+    constexpr int kSecond = 3 * NU;                  // loads that may still be in flight: the coefficients
     if (probe) { __builtin_amdgcn_s_waitcnt(0x0F70 | (kSecond & 15) | ((kSecond >> 4) << 14)); ck[1] = wall_clock64(); }
 
     // ---- LayerNorm1 (the arithmetic of ln_kernel, in its order), normalised rows to the panel as bf16
@@ -243,9 +241,10 @@ token_mix_kernel(TokMixArgs a)
     f32x4_t accu[NU];
 #pragma unroll
     for (int t = 0; t < NU; ++t) { accu[t][0] = bi[t].x; accu[t][1] = bi[t].y; accu[t][2] = bi[t].z; accu[t][3] = bi[t].w; }
-    // (all of the wavefront's W_in rows have landed: the tile loads are older than x, which LayerNorm1 waited for;
-    // at most the second batch is still in flight)
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (kSecond & 15) | ((kSecond >> 4) << 14));
+    // (the wavefront's W_in rows have landed long ago: the tile loads are older than x, which LayerNorm1 waited
+    // for.  Waiting for everything here, the coefficients included, leaves the compiler no later wait that would
+    // also wait for the tile loads issued below.)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     {
         const bf16 *ws = wring + wave * KT * STAGE + j * BK;
         const int swz = (j >> 1) & 7;
@@ -263,23 +262,39 @@ token_mix_kernel(TokMixArgs a)
 
     if (probe) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_nop 0" :: "v"(accu[NU - 1][0])); ck[3] = wall_clock64(); }
 
+    // ---- the wavefront's share of W_out takes the place of its W_in rows in LDS (rows ocol0 .. + d / 4 - 1,
+    // k = 128 q .. + 127, as two k tiles of d / 4 rows x 64), requested now and travelling under the state update.
+    // Nothing else is issued to memory between here and the products that wait for it (the state is stored at
+    // the end), so the two waits below can count tile loads.
+    constexpr int WRO = D / NW, OSTAGE = WRO * BK, O_IT = WRO / 8;
+    static_assert(2 * OSTAGE == KT * STAGE && 2 * O_IT <= 63, "the share of W_out fits the ring and the counter");
+    __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): the W_in rows have been read
+    {
+        const u32x4_t rs = descriptor(a.w_out + (size_t)(wv * WRO) * D + q * QC, (WRO * D - q * QC) * 2);
+        static_for<0, 2 * O_IT>([&](auto n_) {
+            constexpr int kt = decltype(n_)::value / O_IT, i = decltype(n_)::value % O_IT;
+            dma(rs, dst0 + (kt * OSTAGE + i * 8 * BK) * 2, (i & 1) ? voff_odd : voff_even, (i * 8 * D + kt * BK) * 2);
+        });
+    }
+
     // ---- state update (u in the activation type, as the unfused path stores it); m goes to its panel
     TState *sq_ = static_cast<TState *>(a.state);
+    float4 nv[NU];
 #pragma unroll
     for (int t = 0; t < NU; ++t) {
         const int c = ucol0 + t * 16 + 4 * g;
         const bool row_repeat = c / a.dh < a.hrow;
         const float p = row_repeat ? al[t] : 1.0f, r = row_repeat ? 1.0f : al[t];
-        float4 n, m = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 n = make_float4(0.f, 0.f, 0.f, 0.f), m = n;
         if (act) {
             n.x = fmaf(la[t], sv[t].x, p * (float)(bf16)accu[t][0]);
             n.y = fmaf(la[t], sv[t].y, p * (float)(bf16)accu[t][1]);
             n.z = fmaf(la[t], sv[t].z, p * (float)(bf16)accu[t][2]);
             n.w = fmaf(la[t], sv[t].w, p * (float)(bf16)accu[t][3]);
             n = make_float4(to_state(n.x, sq_), to_state(n.y, sq_), to_state(n.z, sq_), to_state(n.w, sq_));
-            if (valid) store_state4(sq_, (row * D + c) >> 2, n);
             m = make_float4(fmaf(r, n.x, be[t]), fmaf(r, n.y, be[t]), fmaf(r, n.z, be[t]), fmaf(r, n.w, be[t]));
         }
+        nv[t] = n;
         store4(mpanel + j * MLD + (c - q * QC), m);
     }
     SRM_LDS_BARRIER()                                // the panel of m is complete
@@ -292,13 +307,27 @@ token_mix_kernel(TokMixArgs a)
         const float on = q == 0 ? 1.0f : 0.0f;
         acco[t][0] = on * bo[t].x; acco[t][1] = on * bo[t].y; acco[t][2] = on * bo[t].z; acco[t][3] = on * bo[t].w;
     }
+    {
+        const bf16 *ws = wring + wave * KT * STAGE + j * BK;
+        const int swz = (j >> 1) & 7;
 #pragma unroll
-    for (int hk = 0; hk < HK2; ++hk) {
-        const bf16x8_t fa = *reinterpret_cast<const bf16x8_t *>(mpanel + j * MLD + hk * 32 + 8 * g);
+        for (int hk = 0; hk < HK2; ++hk) {
+            if (hk == 0) __builtin_amdgcn_s_waitcnt(0x0F70 | (O_IT & 15) | ((O_IT >> 4) << 14));   // k tile 0 has landed
+            if (hk == 2) __builtin_amdgcn_s_waitcnt(0x0F70);                                        // vmcnt(0): k tile 1
+            const bf16x8_t fa = *reinterpret_cast<const bf16x8_t *>(mpanel + j * MLD + hk * 32 + 8 * g);
 #pragma unroll
-        for (int t = 0; t < NL; ++t) acco[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wout[hk][t], fa, acco[t], 0, 0, 0);
+            for (int t = 0; t < NL; ++t) {
+                const bf16x8_t fw = *reinterpret_cast<const bf16x8_t *>(ws + (hk >> 1) * OSTAGE + t * 16 * BK +
+                                                                        ((((hk & 1) * 4 + g) ^ swz) << 3));
+                acco[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw, fa, acco[t], 0, 0, 0);
+            }
+        }
     }
     if (probe) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_nop 0" :: "v"(acco[NL - 1][0])); ck[5] = wall_clock64(); }
+    if (valid && act) {
+#pragma unroll
+        for (int t = 0; t < NU; ++t) store_state4(sq_, (row * D + ucol0 + t * 16 + 4 * g) >> 2, nv[t]);
+    }
     if (valid) {
         float *dst = a.slabs + ((int64_t)q * a.rows + row) * D + ocol0 + 4 * g;
 #pragma unroll
