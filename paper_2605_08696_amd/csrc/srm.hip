@@ -838,6 +838,7 @@ static bool token_mix_shape_ok(const srm_model *m)
 static bool token_mix_one_kernel(const srm_model *m, int64_t rows)
 {
     if (!token_mix_shape_ok(m) || ln_on_load(m, rows) || rows > kSplitMaxRows) return false;   // (w.part: see carve)
+    if (!fuse_mixer(m, rows)) return false;          // (SRM_FUSE_MIXER=0 asks for the state update as a kernel of its own)
     const char *e = getenv("SRM_TOKEN_MIX");
     if (e && e[0] == '0') return false;
     if (e && e[0] == '1') return true;
@@ -1211,11 +1212,12 @@ static int decode_ragged_impl(srm_model *m, int64_t B, int32_t *pos_rows, int ad
     };
     const bool fuse = fuse_mixer(m, B);
     const Sampling where{0.0f, 0, 0, nullptr, pos_rows, 1.0f};
-    int pend = 0;
+    int pend = 0, tm_pend = 0;
     const bool lnf = ln_on_load(m, B);
+    const bool tm = token_mix_one_kernel(m, B);
     for (int l = 0; l < m->L; ++l)
         SRM_TRY((block<T>(m, l, w, B, st, mix, true, true, fuse ? layer_state(m, state, l, B) : nullptr, where,
-                          layer_state(m, state, l, B), lnf ? &pend : nullptr)));
+                          layer_state(m, state, l, B), lnf ? &pend : nullptr, tm ? &tm_pend : nullptr)));
     const bool topp = temperature > 0.0f && top_p < 1.0f;
     FinalizeRagged rg{};
     rg.pos_rows = pos_rows;
