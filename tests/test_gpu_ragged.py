@@ -278,6 +278,42 @@ def test_ragged_decode_large_batch_fused_equals_separate(srm, monkeypatch):
     assert not np.array_equal(st[:, ~idle], S0[:, ~idle])
 
 
+@pytest.mark.parametrize("d,B", [(256, 40), (512, 300)])
+def test_ragged_decode_with_token_mixing_in_one_kernel(srm, d, B, monkeypatch):
+    """bf16 model, a few dozen to a few hundred slots at their own positions (idle ones included): the ragged step
+    whose token mixing is one kernel per layer against the ragged step of separate kernels (the library's switch):
+    the same positions, states and logits to bf16 rounding, idle slots untouched bit for bit."""
+    cfg = srm_synth.tiny_config(vocab=200, d_model=d, n_layers=3, n_heads=4, n_ctx=12, weight_dtype="bf16", seed=14)
+    w = srm_synth.make_weights(cfg, stress=True)
+    model = srm.Model(cfg, w)
+    rng = np.random.default_rng(15 + B)
+    pos0 = rng.integers(-1, cfg.n_ctx - 3, B).astype(np.int32)
+    tok0 = rng.integers(0, cfg.vocab, B).astype(np.int32)
+    S0 = rng.standard_normal((cfg.n_layers, B, cfg.d_model)).astype(np.float32)
+    ws = model.new_workspace(B)
+    res = []
+    for mode in ("1", "0"):
+        monkeypatch.setenv("SRM_TOKEN_MIX", mode)
+        st, tk, pos = to_dev(S0), to_dev(tok0), to_dev(pos0)
+        lg = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+        print(f"ragged token mixing d={d} B={B} SRM_TOKEN_MIX={mode}", flush=True)
+        steps = []
+        for _ in range(3):
+            # (teacher-forced on tok0: a token that flips between the two forms would make the later steps incomparable)
+            model.decode_step_ragged(B, pos, to_dev(tok0), st, tk, advance=True, logits=lg, workspace=ws)
+            steps.append(lg.clone())
+        torch.cuda.synchronize()
+        res.append((st.cpu().numpy(), pos.cpu().numpy(), [x.cpu().numpy() for x in steps]))
+    idle = pos0 < 0
+    assert idle.any() and (~idle).any()
+    np.testing.assert_array_equal(res[0][1], res[1][1])
+    np.testing.assert_array_equal(res[0][0][:, idle], S0[:, idle])
+    assert np.abs(res[0][0] - res[1][0]).max() <= 2e-2 * np.abs(res[1][0]).max()
+    for a, b in zip(res[0][2], res[1][2]):
+        assert rel_err_rows(a[~idle], b[~idle]) <= 2e-2
+    model.close()
+
+
 def test_ragged_decode_of_a_handful_of_samples_without_layernorm_launches(srm, monkeypatch):
     """bf16 model, 6 slots at their own positions (one idle): the ragged step whose LayerNorms are made by the
     consuming GEMMs equals the ragged step with LayerNorm launches (the library's switch) bit for bit."""
