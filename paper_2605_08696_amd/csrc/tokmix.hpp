@@ -1,4 +1,4 @@
-// Token mixing of an SRM block for decode steps of a few dozen to a couple of thousand rows of a bf16 model
+// Token mixing of an SRM block for decode steps of a dozen to about a thousand rows of a bf16 model
 // (Eq. 2 / Eq. 3 with the head projections of Eq. 10, behind the block's first LayerNorm), as ONE kernel:
 //
 //   a = LN1(x + pending slabs);  u = a W_in^T + b_in;  S, m = state update(S, u);  slab_q = m_q W_out[:, q]^T
@@ -13,8 +13,8 @@
 // go on to form that slice's contribution to all d output columns, which it writes as fp32 slab q; the slabs
 // are added in slab order by the next kernel, so the sum does not depend on scheduling.  u and m never
 // leave the CU, and the d / 128 work-groups of a row group run on different CUs, each reading only 1 / (d / 128)
-// of both weight matrices: d^2 / 64 bytes each, requested once, at the start - no k loop waits for memory, the
-// kernel is one round trip deep.  The share of W_in goes global -> LDS (buffer_load ... lds, whole 128-byte row
+// of both weight matrices (256 d bytes of each), each requested whole, in one go - no k loop waits for memory.
+// The share of W_in is requested at the start and goes global -> LDS (buffer_load ... lds, whole 128-byte row
 // segments per request, into the swizzled layout of gemm_bf16_kernel; each wavefront loads and reads only its
 // own rows, so no barrier guards them).  The share of W_out is as large and follows into the same LDS once the
 // in-projection has read W_in: a second trip to memory, under the state update.  (Loaded straight into registers
@@ -103,11 +103,10 @@ token_mix_kernel(TokMixArgs a)
     unsigned long long ck[7] = {0, 0, 0, 0, 0, 0, 0};
     if (probe) ck[0] = wall_clock64();
 
-    // ---- everything this lane will need from memory, requested up front.  First batch: the position, its share
-    // of W_in (operand fragments: 16 bytes of row tile * 16 + j at k = 32 step + 8 g), its row of x, the
-    // parameters, the waiting slabs - LayerNorm1 starts when these have arrived, one round trip into the kernel.
-    // Second batch, requested in front of LayerNorm1 and arriving under it and the in-projection: the
-    // coefficients at the position, and the share of W_out (whose registers the slabs used before).
+    // ---- everything the first phases need from memory is requested up front: the wavefront's rows of W_in, the
+    // position, the rows of x with the waiting slabs, the parameters, the old state - LayerNorm1 starts when these
+    // have arrived, one round trip into the kernel.  The coefficients at the position follow (they need the
+    // position) and arrive under LayerNorm1.
     // ---- tile loads (buffer_load ... lds): one instruction moves rows 8 i .. 8 i + 7 x 128 bytes of a k tile of this
     // wavefront's rows; lane (r = l >> 3, slot = l & 7) fetches chunk slot ^ swz(8 i + r) of its row, swz(8 i + r) =
     // (4 (i & 1) + (r >> 1)) & 7.  Issued from an asm statement (see gemm_persist.hpp); all waits are explicit.
