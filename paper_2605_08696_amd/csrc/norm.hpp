@@ -6,6 +6,7 @@
 // with wavefront shuffles.
 #pragma once
 #include "common.hpp"
+#include <type_traits>
 
 // VPL = float4 vectors per lane: covers d <= 256 * VPL.
 //   GATHER: x = embed[tok[row]] is fetched, stored to x_out (fp32) and normalised.
@@ -66,17 +67,23 @@ ln_kernel(const float *x_in, int64_t in_stride, const int32_t *__restrict__ tok,
             } else {
                 v[i] = load4(x_in + src * in_stride + c);
                 if (part) {
-                    // four slabs requested at a time (a load per iteration would serialise their latencies);
+                    // four slabs requested at a time (a load per iteration would serialise their latencies), eight
+                    // when there are more than four (the slabs of two projections: a second round trip saved);
                     // the sums are still formed in slab order
-                    for (int s0 = 0; s0 < nsplit; s0 += 4) {
-                        float4 t[4];
+                    auto add_slabs = [&](auto width) {
+                        constexpr int W = decltype(width)::value;
+                        for (int s0 = 0; s0 < nsplit; s0 += W) {
+                            float4 t[W];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            t[j] = load4(part + (int64_t)min(s0 + j, nsplit - 1) * part_stride + row * d + c);
+                            for (int j = 0; j < W; ++j)
+                                t[j] = load4(part + (int64_t)min(s0 + j, nsplit - 1) * part_stride + row * d + c);
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            if (s0 + j < nsplit) { v[i].x += t[j].x; v[i].y += t[j].y; v[i].z += t[j].z; v[i].w += t[j].w; }
-                    }
+                            for (int j = 0; j < W; ++j)
+                                if (s0 + j < nsplit) { v[i].x += t[j].x; v[i].y += t[j].y; v[i].z += t[j].z; v[i].w += t[j].w; }
+                        }
+                    };
+                    if (nsplit > 4) add_slabs(std::integral_constant<int, 8>{});
+                    else add_slabs(std::integral_constant<int, 4>{});
                     store4(x_out + row * d + c, v[i]);
                 }
                 if (add_act) {
