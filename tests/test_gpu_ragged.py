@@ -244,14 +244,15 @@ def test_ragged_bf16_logits_against_oracle(srm, orc_mod):
     assert ((t >= 0) & (t < cfg.vocab)).all() and bool(torch.isfinite(st).all())
 
 
-def test_ragged_decode_large_batch_fused_equals_separate(srm, monkeypatch):
+@pytest.mark.parametrize("B", [13000, 66000])
+def test_ragged_decode_large_batch_fused_equals_separate(srm, B, monkeypatch):
     """13 000 samples of width 1024 (the in-projection takes the 256x256 tile, the state update rides in its
-    epilogue) at per-sample positions, idle slots (-1) included: the same states, tokens and positions as with the
-    separate ragged state-update kernel, and idle samples untouched."""
+    epilogue) and 66 000 (more tiles than compute units: the persistent form of that tile) at per-sample
+    positions, idle slots (-1) included: the same states, tokens and positions as with the separate ragged
+    state-update kernel, and idle samples untouched."""
     cfg = srm_synth.tiny_config(vocab=300, d_model=1024, n_layers=1, n_heads=4, n_ctx=8, weight_dtype="bf16", seed=9)
     w = srm_synth.make_weights(cfg, stress=True)
     model = srm.Model(cfg, w)
-    B = 13000
     rng = np.random.default_rng(12)
     pos0 = rng.integers(-1, cfg.n_ctx - 2, B).astype(np.int32)
     tok0 = rng.integers(0, cfg.vocab, B).astype(np.int32)
