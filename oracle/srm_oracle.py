@@ -12,6 +12,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import sys
 import subprocess
 from typing import Optional
 
@@ -173,7 +174,10 @@ class Oracle:
             self.lib.orc_destroy(C.c_void_p(self.h))
             self.h = None
 
-    __del__ = close
+    def __del__(self):
+        if sys.is_finalizing():      # module globals are going away: the process frees the handle
+            return
+        self.close()
 
     # -- pieces -----------------------------------------------------------
     def _r(self, a):
